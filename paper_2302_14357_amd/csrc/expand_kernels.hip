@@ -1,0 +1,168 @@
+// Expansion scores of token-wise RNN-T beam search (Eq. 3-7) for every live
+// hypothesis of a joiner call, and its N best non-blank expansions.
+//
+// One workgroup owns one (utterance, hypothesis) pair, i.e. the S' logit rows
+// of that hypothesis.  Softmax probabilities are never formed: with row
+// maximum m_t, row sum Z_t = sum_k exp(l[t,k]-m_t) and blank probability b_t,
+// the blank products of Eq. 3 collapse into a forward variable
+//     alpha_1 = d_old[1],  alpha_t = alpha_{t-1} b_{t-1} + d_old[t]
+// (alpha_t = sum_{t1<=t} d_old[t1] Bl(t1,t)), so that
+//     delta_blank   = alpha_S' b_S'                                  (Eq. 7)
+//     d[k][t]       = alpha_t exp(l[t,k]-m_t) / Z_t                   (Eq. 4-5)
+//     delta_nb[k]   = sum_t d[k][t] = sum_t exp(l[t,k] + lc_t)        (Eq. 6)
+// with lc_t = log(alpha_t / Z_t) - m_t.  The [S+1,S+1] table, the [V,S] tensor
+// d and the normalised J are never built; the logits are streamed from memory
+// and each costs one exp and one add.
+#include "tbs_internal.h"
+
+#define EXP_THREADS 256
+#define EXP_WAVES (EXP_THREADS / 64)
+
+__device__ __forceinline__ void ms_combine(float &m, float &z, float m2, float z2) {
+    float mn = fmaxf(m, m2);
+    // exp(-inf - finite) = 0; guard the -inf - -inf case of two empty parts
+    float a = (m == -INFINITY) ? 0.f : z * __expf(m - mn);
+    float b = (m2 == -INFINITY) ? 0.f : z2 * __expf(m2 - mn);
+    m = mn;
+    z = a + b;
+}
+
+template <bool VEC4>
+__global__ void __launch_bounds__(EXP_THREADS)
+k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
+         float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
+         float *__restrict__ row_stats, float *__restrict__ delta_nb) {
+    extern __shared__ float s_dnb[];  // [V]
+    __shared__ float s_m[TBS_MAX_SEG], s_z[TBS_MAX_SEG], s_b[TBS_MAX_SEG], s_lc[TBS_MAX_SEG];
+    __shared__ float s_rv[EXP_WAVES];
+    __shared__ int s_rk[EXP_WAVES];
+    const int pair = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int u = rv.pair_u[pair], h = rv.pair_h[pair];
+    const int row0 = rv.pair_row0[pair], sp = rv.pair_len[pair];
+    const int V = d.V;
+    const float *L = logits + (long)row0 * V;
+
+    // ---- softmax statistics of each row: one wave per row, no barriers inside
+    for (int t = wave; t < sp; t += EXP_WAVES) {
+        const float *row = L + (long)t * V;
+        float m = -INFINITY, z = 0.f;
+        if (VEC4) {
+            const float4 *r4 = reinterpret_cast<const float4 *>(row);
+            for (int i = lane; i < V / 4; i += 64) {
+                float4 x = r4[i];
+                float mx = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+                float mn = fmaxf(m, mx);
+                z = z * __expf(m - mn) + __expf(x.x - mn) + __expf(x.y - mn) + __expf(x.z - mn) + __expf(x.w - mn);
+                m = mn;
+            }
+        } else {
+            for (int i = lane; i < V; i += 64) {
+                float x = row[i];
+                float mn = fmaxf(m, x);
+                z = z * __expf(m - mn) + __expf(x - mn);
+                m = mn;
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            float m2 = __shfl_xor(m, off), z2 = __shfl_xor(z, off);
+            ms_combine(m, z, m2, z2);
+        }
+        if (lane == 0) {
+            s_m[t] = m;
+            s_z[t] = z;
+            s_b[t] = __expf(row[d.blank] - m) / z;
+        }
+    }
+    __syncthreads();
+
+    // ---- forward variable over the segment (Eq. 3 folded into a scan) and Eq. 7
+    if (tid == 0) {
+        const float *dold = A.dhat + ((long)u * d.N + h) * d.S;
+        float alpha = 0.f;
+        for (int t = 0; t < sp; ++t) {
+            alpha = (t == 0 ? 0.f : alpha * s_b[t - 1]) + dold[t];
+            float c = alpha / s_z[t];
+            float lc = c > 0.f ? __logf(c) - s_m[t] : -INFINITY;
+            s_lc[t] = lc;
+            row_lc[row0 + t] = lc;
+            if (row_stats) {
+                row_stats[(long)(row0 + t) * 3 + 0] = s_m[t];
+                row_stats[(long)(row0 + t) * 3 + 1] = s_z[t];
+                row_stats[(long)(row0 + t) * 3 + 2] = s_b[t];
+            }
+        }
+        dphi[pair] = alpha * s_b[sp - 1];
+    }
+    __syncthreads();
+
+    // ---- Eq. 4-6: delta_nb[k] = sum_t exp(l[t,k] + lc_t), streamed
+    if (VEC4) {
+        for (int i = tid; i < V / 4; i += EXP_THREADS) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int t = 0; t < sp; ++t) {
+                float4 x = reinterpret_cast<const float4 *>(L + (long)t * V)[i];
+                float lc = s_lc[t];
+                acc.x += __expf(x.x + lc);
+                acc.y += __expf(x.y + lc);
+                acc.z += __expf(x.z + lc);
+                acc.w += __expf(x.w + lc);
+            }
+            reinterpret_cast<float4 *>(s_dnb)[i] = acc;
+        }
+    } else {
+        for (int k = tid; k < V; k += EXP_THREADS) {
+            float acc = 0.f;
+            for (int t = 0; t < sp; ++t) acc += __expf(L[(long)t * V + k] + s_lc[t]);
+            s_dnb[k] = acc;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) s_dnb[d.blank] = 0.f;  // blank is not a non-blank expansion
+    __syncthreads();
+    if (delta_nb)
+        for (int k = tid; k < V; k += EXP_THREADS) delta_nb[(long)pair * V + k] = s_dnb[k];
+
+    // ---- the N best expansions of this hypothesis: N rounds of workgroup arg-max
+    for (int n = 0; n < d.N; ++n) {
+        float bv = 0.f;  // only strictly positive scores are candidates
+        int bk = 0x7fffffff;
+        for (int k = tid; k < V; k += EXP_THREADS) {
+            float v = s_dnb[k];
+            if (v > bv) { bv = v; bk = k; }  // ascending k: the smallest token wins a tie
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            float ov = __shfl_xor(bv, off);
+            int ok = __shfl_xor(bk, off);
+            if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
+        }
+        if (lane == 0) { s_rv[wave] = bv; s_rk[wave] = bk; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < EXP_WAVES; ++w)
+                if (s_rv[w] > bv || (s_rv[w] == bv && s_rk[w] < bk)) { bv = s_rv[w]; bk = s_rk[w]; }
+            if (bk != 0x7fffffff) {
+                cand_score[(long)pair * d.N + n] = __logf(bv);
+                cand_tok[(long)pair * d.N + n] = bk;
+                s_dnb[bk] = -1.f;
+            } else {
+                cand_score[(long)pair * d.N + n] = -INFINITY;
+                cand_tok[(long)pair * d.N + n] = -1;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
+                         float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
+                         float *delta_nb) {
+    if (pairs <= 0) return hipSuccess;
+    size_t shm = (size_t)d.V * sizeof(float);
+    if (d.V % 4 == 0)
+        hipLaunchKernelGGL(k_expand<true>, dim3(pairs), dim3(EXP_THREADS), shm, st, d, logits, A, rv, row_lc, dphi,
+                           cand_score, cand_tok, row_stats, delta_nb);
+    else
+        hipLaunchKernelGGL(k_expand<false>, dim3(pairs), dim3(EXP_THREADS), shm, st, d, logits, A, rv, row_lc, dphi,
+                           cand_score, cand_tok, row_stats, delta_nb);
+    return hipGetLastError();
+}

@@ -1,0 +1,238 @@
+// Joiner of token-wise RNN-T beam search: for every live (utterance,
+// hypothesis, frame) row r, logits[r, :] = W_out * act(e[frame] + p[hyp]) + b_out
+// (Section 3.1: j(t,u,k) = joiner(h, g); Algorithm 1 batches it over the S
+// frames of a segment and all hypotheses).  It is a dense contraction
+// [rows, Dj] x [Dj, V], so it runs on the matrix cores: the activation rows are
+// formed once (add, tanh/relu, round to bf16) and the product is a bf16 MFMA
+// GEMM with fp32 accumulation whose epilogue adds the bias and stores the
+// logits once.  The same GEMM serves the LSTM gates and the predictor
+// projection.  A plain fp32 path exists for fp32 models.
+#include "tbs_internal.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest, ties to even
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((unsigned)b) << 16); }
+
+__device__ __forceinline__ float joiner_act(float x, int act) { return act == 0 ? tanhf(x) : fmaxf(x, 0.f); }
+
+// ------------------------------------------------------------------ activation rows
+// a[r, :] = act(e[row_enc[r], :] + p[row_slot[r], :]), 8 elements per thread.
+__global__ void k_joiner_prep_bf16(int rows, int Dj, int act, const bf16_t *__restrict__ enc,
+                                   const float *__restrict__ pool_p, const int *__restrict__ row_enc,
+                                   const int *__restrict__ row_slot, bf16_t *__restrict__ amat) {
+    int chunks = Dj / 8;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)rows * chunks) return;
+    int r = (int)(idx / chunks), c = (int)(idx % chunks);
+    const uint4 ev = *reinterpret_cast<const uint4 *>(enc + (long)row_enc[r] * Dj + c * 8);
+    const float4 p0 = *reinterpret_cast<const float4 *>(pool_p + (long)row_slot[r] * Dj + c * 8);
+    const float4 p1 = *reinterpret_cast<const float4 *>(pool_p + (long)row_slot[r] * Dj + c * 8 + 4);
+    float e[8] = {__uint_as_float(ev.x << 16), __uint_as_float(ev.x & 0xFFFF0000u),
+                  __uint_as_float(ev.y << 16), __uint_as_float(ev.y & 0xFFFF0000u),
+                  __uint_as_float(ev.z << 16), __uint_as_float(ev.z & 0xFFFF0000u),
+                  __uint_as_float(ev.w << 16), __uint_as_float(ev.w & 0xFFFF0000u)};
+    float p[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+    unsigned o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        unsigned lo = f2bf(joiner_act(e[2 * i] + p[2 * i], act));
+        unsigned hi = f2bf(joiner_act(e[2 * i + 1] + p[2 * i + 1], act));
+        o[i] = lo | (hi << 16);
+    }
+    *reinterpret_cast<uint4 *>(amat + (long)r * Dj + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+__global__ void k_joiner_prep_f32(int rows, int Dj, int act, const float *__restrict__ enc,
+                                  const float *__restrict__ pool_p, const int *__restrict__ row_enc,
+                                  const int *__restrict__ row_slot, float *__restrict__ amat) {
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)rows * Dj) return;
+    int r = (int)(idx / Dj), j = (int)(idx % Dj);
+    amat[idx] = joiner_act(enc[(long)row_enc[r] * Dj + j] + pool_p[(long)row_slot[r] * Dj + j], act);
+}
+
+hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
+                              const float *pool_p, RowView rv, void *amat) {
+    if (rows <= 0) return hipSuccess;
+    if (dtype == 1) {
+        long n = (long)rows * (d.Dj / 8);
+        hipLaunchKernelGGL(k_joiner_prep_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rows, d.Dj, act,
+                           (const bf16_t *)enc, pool_p, rv.row_enc, rv.row_slot, (bf16_t *)amat);
+    } else {
+        long n = (long)rows * d.Dj;
+        hipLaunchKernelGGL(k_joiner_prep_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rows, d.Dj, act,
+                           (const float *)enc, pool_p, rv.row_enc, rv.row_slot, (float *)amat);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fp32 GEMM (fp32 models)
+// C[M,N] = A[M,K] * B[N,K]^T + bias, 64x64 tile, 4x4 outputs per thread.
+__global__ void __launch_bounds__(256)
+k_gemm_f32(const float *__restrict__ A, const float *__restrict__ B, const float *__restrict__ bias,
+           float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc) {
+    __shared__ float sA[16][64 + 1], sB[16][64 + 1];
+    const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        for (int i = tid; i < 64 * 16; i += 256) {
+            int r = i / 16, k = i % 16;
+            int gm = m0 + r, gn = n0 + r, gk = k0 + k;
+            sA[k][r] = (gm < M && gk < K) ? A[(long)gm * K + gk] : 0.f;
+            sB[k][r] = (gn < N && gk < K) ? B[(long)gn * K + gk] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = sA[k][ty * 4 + i]; b[i] = sB[k][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i) {
+        int gm = m0 + ty * 4 + i;
+        if (gm >= M) continue;
+        long orow = out_row ? out_row[gm] : gm;
+        for (int j = 0; j < 4; ++j) {
+            int gn = n0 + tx * 4 + j;
+            if (gn < N) C[orow * ldc + gn] = acc[i][j] + (bias ? bias[gn] : 0.f);
+        }
+    }
+}
+
+hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
+                           int K, const int *out_row, long ldc) {
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gemm_f32, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, A, B, bias, C, M, N, K,
+                       out_row, ldc);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bf16 MFMA GEMM
+// C[M,N] = A[M,K] * B[N,K]^T + bias, bf16 inputs, fp32 accumulate and output.
+// Workgroup = 4 waves in a 2x2 grid; each wave owns TM x TN blocks of 32x32
+// computed with v_mfma_f32_32x32x16_bf16.  K is consumed in tiles of 64 held in
+// LDS (rows padded by 8 elements to spread banks); the next tile is fetched into
+// registers while the current one is multiplied.
+#define GEMM_BK 64
+#define GEMM_LDS_STRIDE (GEMM_BK + 8)
+
+template <int TM, int TN>
+__global__ void __launch_bounds__(256)
+k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
+            float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;  // 16-byte chunks per thread
+    __shared__ __attribute__((aligned(16))) bf16_t sA[BM * GEMM_LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) bf16_t sB[BN * GEMM_LDS_STRIDE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
+            int gm = min(m0 + row, M - 1);
+            ra[i] = (k0 + kc < K) ? *reinterpret_cast<const uint4 *>(A + (long)gm * K + k0 + kc)
+                                  : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
+            int gn = min(n0 + row, N - 1);
+            rb[i] = (k0 + kc < K) ? *reinterpret_cast<const uint4 *>(B + (long)gn * K + k0 + kc)
+                                  : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
+            *reinterpret_cast<uint4 *>(sA + row * GEMM_LDS_STRIDE + kc) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
+            *reinterpret_cast<uint4 *>(sB + row * GEMM_LDS_STRIDE + kc) = rb[i];
+        }
+    };
+
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += GEMM_BK) {
+        stage();
+        __syncthreads();
+        if (k0 + GEMM_BK < K) fetch(k0 + GEMM_BK);
+#pragma unroll
+        for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TN];
+            const int koff = kk * 16 + (lane >> 5) * 8;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const bf16x8 *>(
+                    sA + (wm * 32 * TM + i * 32 + (lane & 31)) * GEMM_LDS_STRIDE + koff);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8 *>(
+                    sB + (wn * 32 * TN + j * 32 + (lane & 31)) * GEMM_LDS_STRIDE + koff);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: lane holds column (lane%32); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int col = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+            float bv = (bias && col < N) ? bias[col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int row = m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                if (row < M && col < N) {
+                    long orow = out_row ? out_row[row] : row;
+                    C[orow * ldc + col] = acc[i][j][r] + bv;
+                }
+            }
+        }
+}
+
+hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
+                            int N, int K, const int *out_row, long ldc) {
+    if (M <= 0) return hipSuccess;
+    // small problems take the 64x64 tile so that the grid still covers the chip
+    long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (tiles128 >= 256)
+        hipLaunchKernelGGL((k_gemm_bf16<2, 2>), dim3((N + 127) / 128, (M + 127) / 128), dim3(256), 0, st, A, B, bias,
+                           C, M, N, K, out_row, ldc);
+    else
+        hipLaunchKernelGGL((k_gemm_bf16<1, 1>), dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, A, B, bias, C,
+                           M, N, K, out_row, ldc);
+    return hipGetLastError();
+}

@@ -1,0 +1,136 @@
+// UpdatePredictorOutput of Algorithm 1: for every hypothesis created in this
+// round, run the prediction network one step from its parent's recurrent state
+// (Section 3.1: g(u) = predictor(y)).  Embedding lookup and state gather build
+// the LSTM input rows, the gate pre-activations are one GEMM against the
+// concatenated [W_ih | W_hh] matrix, the cell update is a pointwise kernel, and
+// the projection to the joint space is a GEMM that scatters into the state pool.
+#include "tbs_internal.h"
+
+__device__ __forceinline__ bf16_t f2bf_p(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + expf(-x)); }
+
+// xh[j, :] = [ embed[token_j, 0:E] | h_parent_j(layer 0)[0:H] ]
+__global__ void k_pred_gather(Dims d, int dtype, AView A, RowView rv, const void *embed, const float *pool_h,
+                              void *xh) {
+    int j = blockIdx.x;
+    int u = rv.pair_u[j], h = rv.pair_h[j];
+    long a = (long)u * d.N + h;
+    int tok = A.token[a];
+    long ps = A.pslot[a];
+    int W = d.E + d.H;
+    if (dtype == 1) {
+        const bf16_t *em = (const bf16_t *)embed + (long)tok * d.E;
+        bf16_t *x = (bf16_t *)xh + (long)j * W;
+        for (int i = threadIdx.x; i < d.E; i += blockDim.x) x[i] = em[i];
+        for (int i = threadIdx.x; i < d.H; i += blockDim.x) x[d.E + i] = f2bf_p(pool_h[ps * d.H + i]);
+    } else {
+        const float *em = (const float *)embed + (long)tok * d.E;
+        float *x = (float *)xh + (long)j * W;
+        for (int i = threadIdx.x; i < d.E; i += blockDim.x) x[i] = em[i];
+        for (int i = threadIdx.x; i < d.H; i += blockDim.x) x[d.E + i] = pool_h[ps * d.H + i];
+    }
+}
+
+hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
+                              const void *embed, const float *pool_h, void *xh) {
+    if (pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_pred_gather, dim3(pairs), dim3(256), 0, st, d, dtype, A, rv, embed, pool_h, xh);
+    return hipGetLastError();
+}
+
+// LSTM cell, gate order i, f, g, o; gates already hold W x + W h + b.
+__global__ void k_lstm_pointwise(Dims d, int dtype, int layer, AView A, RowView rv, const float *gates,
+                                 float *pool_h, float *pool_c, long pool_rows, void *xh_next, void *htop) {
+    int j = blockIdx.x;
+    int u = rv.pair_u[j], hh = rv.pair_h[j];
+    long a = (long)u * d.N + hh;
+    long ps = A.pslot[a], ns = A.slot[a];
+    const float *g = gates + (long)j * 4 * d.H;
+    const float *c_par = pool_c + ((long)layer * pool_rows + ps) * d.H;
+    float *c_new = pool_c + ((long)layer * pool_rows + ns) * d.H;
+    float *h_new = pool_h + ((long)layer * pool_rows + ns) * d.H;
+    const bool last = layer + 1 == d.L;
+    const float *h_par_next = last ? nullptr : pool_h + ((long)(layer + 1) * pool_rows + ps) * d.H;
+    for (int i = threadIdx.x; i < d.H; i += blockDim.x) {
+        float ig = sigmoidf_(g[i]);
+        float fg = sigmoidf_(g[d.H + i]);
+        float gg = tanhf(g[2 * d.H + i]);
+        float og = sigmoidf_(g[3 * d.H + i]);
+        float c = fg * c_par[i] + ig * gg;
+        float hv = og * tanhf(c);
+        c_new[i] = c;
+        h_new[i] = hv;
+        if (dtype == 1) {
+            if (last) ((bf16_t *)htop)[(long)j * d.H + i] = f2bf_p(hv);
+            else {
+                bf16_t *x = (bf16_t *)xh_next + (long)j * 2 * d.H;
+                x[i] = f2bf_p(hv);
+                x[d.H + i] = f2bf_p(h_par_next[i]);
+            }
+        } else {
+            if (last) ((float *)htop)[(long)j * d.H + i] = hv;
+            else {
+                float *x = (float *)xh_next + (long)j * 2 * d.H;
+                x[i] = hv;
+                x[d.H + i] = h_par_next[i];
+            }
+        }
+    }
+}
+
+hipError_t launch_lstm_pointwise(hipStream_t st, const Dims &d, int dtype, int pairs, int layer, AView A, RowView rv,
+                                 const float *gates, float *pool_h, float *pool_c, long pool_rows, void *xh_next,
+                                 void *htop) {
+    if (pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_lstm_pointwise, dim3(pairs), dim3(256), 0, st, d, dtype, layer, A, rv, gates, pool_h,
+                       pool_c, pool_rows, xh_next, htop);
+    return hipGetLastError();
+}
+
+// out_row[j] = state slot of pair j (rows of the projection GEMM land there)
+__global__ void k_pair_slots(Dims d, int pairs, AView A, RowView rv, int *out_row) {
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < pairs) out_row[j] = A.slot[(long)rv.pair_u[j] * d.N + rv.pair_h[j]];
+}
+
+hipError_t launch_pair_slots(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, int *out_row) {
+    if (pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_pair_slots, dim3((pairs + 255) / 256), dim3(256), 0, st, d, pairs, A, rv, out_row);
+    return hipGetLastError();
+}
+
+// wcat[r, :] = [ w_ih[r, 0:in] | w_hh[r, 0:hid] ], elements of 2 bytes
+__global__ void k_concat16(const uint16_t *w_ih, const uint16_t *w_hh, uint16_t *wcat, int rows, int in_dim,
+                           int hid) {
+    long W = in_dim + hid;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * W) return;
+    long r = idx / W, c = idx % W;
+    wcat[idx] = c < in_dim ? w_ih[r * in_dim + c] : w_hh[r * hid + (c - in_dim)];
+}
+__global__ void k_concat32(const uint32_t *w_ih, const uint32_t *w_hh, uint32_t *wcat, int rows, int in_dim,
+                           int hid) {
+    long W = in_dim + hid;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * W) return;
+    long r = idx / W, c = idx % W;
+    wcat[idx] = c < in_dim ? w_ih[r * in_dim + c] : w_hh[r * hid + (c - in_dim)];
+}
+
+hipError_t launch_concat_weights(hipStream_t st, int elem_bytes, const void *w_ih, const void *w_hh, void *wcat,
+                                 int rows, int in_dim, int hid) {
+    long n = (long)rows * (in_dim + hid);
+    unsigned blocks = (unsigned)((n + 255) / 256);
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(k_concat16, dim3(blocks), dim3(256), 0, st, (const uint16_t *)w_ih, (const uint16_t *)w_hh,
+                           (uint16_t *)wcat, rows, in_dim, hid);
+    else
+        hipLaunchKernelGGL(k_concat32, dim3(blocks), dim3(256), 0, st, (const uint32_t *)w_ih, (const uint32_t *)w_hh,
+                           (uint32_t *)wcat, rows, in_dim, hid);
+    return hipGetLastError();
+}

@@ -1,0 +1,704 @@
+// Host side of libtbs: context, workspaces, the C ABI of include/tbs.h and the
+// lock-step driver of Algorithm 1 (outer loop over segments, inner loop over
+// token-emission rounds).  All arithmetic of the method runs in the kernels of
+// the other files; this file only sizes buffers, orders launches and moves
+// counts and results between device and host.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tbs_internal.h"
+
+namespace {
+
+enum State { ST_INIT = 0, ST_BEGUN, ST_READY, ST_JOINED, ST_EXPANDED, ST_SELECTED };
+
+struct EventPair {
+    hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct tbs_ctx {
+    tbs_config cfg;
+    tbs_weights w;
+    hipStream_t stream;
+    Dims d;       // capacities (U = max_utts)
+    Dims cur;     // current batch (U = bound utterances)
+    int state;
+    int last_hip;
+    std::vector<void *> allocs;
+
+    // batch
+    const void *enc;
+    int *utt_T, *utt_off;
+    std::vector<int> h_T;
+    int max_T;
+    int seg, round, parity, a_cur;
+
+    AView A[2];
+    BView B;
+    RowView rv;
+    int *h_counts;      // pinned host mirror of rv.counts
+    int *h_counts_dev;  // device view of the same memory
+    int2 *nodes;
+    long pool_rows;
+    float *pool_p, *pool_h, *pool_c;
+
+    void *amat;
+    float *logits, *row_lc, *row_stats, *dphi, *delta_nb, *cand_score;
+    int *cand_tok;
+
+    void *wcat[TBS_MAX_LAYERS];
+    void *xh[2];
+    void *htop;
+    float *gates;
+    int *out_row;
+
+    // results
+    int *res_count, *res_len, *res_tok, *res_ovf;
+    double *res_logs;
+    int res_max_len;
+
+    // counters
+    int64_t n_calls, n_joined, n_frames, n_launches;
+
+    // profiling
+    int prof_kernel;
+    std::vector<EventPair> events;
+    size_t ev_used;
+    int64_t prof_units;
+};
+
+#define HIPCHK(ctx, expr)                       \
+    do {                                        \
+        hipError_t e_ = (expr);                 \
+        if (e_ != hipSuccess) {                 \
+            (ctx)->last_hip = (int)e_;          \
+            return TBS_EHIP;                    \
+        }                                       \
+    } while (0)
+
+namespace {
+
+template <typename T>
+int dev_alloc(tbs_ctx *c, T **p, size_t n) {
+    void *q = nullptr;
+    size_t bytes = std::max<size_t>(n, 1) * sizeof(T);
+    hipError_t e = hipMalloc(&q, bytes);
+    if (e != hipSuccess) {
+        c->last_hip = (int)e;
+        (void)hipGetLastError();
+        return TBS_ENOMEM;
+    }
+    c->allocs.push_back(q);
+    *p = (T *)q;
+    return TBS_OK;
+}
+
+int alloc_aview(tbs_ctx *c, AView *a, long UN, int S, int U) {
+    int rc = 0;
+    rc |= dev_alloc(c, &a->count, U);
+    rc |= dev_alloc(c, &a->logs, UN);
+    rc |= dev_alloc(c, &a->node, UN);
+    rc |= dev_alloc(c, &a->hash, UN);
+    rc |= dev_alloc(c, &a->len, UN);
+    rc |= dev_alloc(c, &a->slot, UN);
+    rc |= dev_alloc(c, &a->pslot, UN);
+    rc |= dev_alloc(c, &a->pnode, UN);
+    rc |= dev_alloc(c, &a->token, UN);
+    rc |= dev_alloc(c, &a->dhat, UN * S);
+    return rc ? TBS_ENOMEM : TBS_OK;
+}
+
+struct ProfScope {
+    tbs_ctx *c;
+    bool on;
+    size_t idx;
+    ProfScope(tbs_ctx *ctx, int kernel, int64_t units) : c(ctx), on(false), idx(0) {
+        if (c->prof_kernel == kernel && c->ev_used < c->events.size()) {
+            on = true;
+            idx = c->ev_used++;
+            c->prof_units += units;
+            (void)hipEventRecord(c->events[idx].a, c->stream);
+        }
+    }
+    ~ProfScope() {
+        if (on) (void)hipEventRecord(c->events[idx].b, c->stream);
+    }
+};
+
+int check_err_flags(tbs_ctx *c) {
+    int err = c->h_counts[TBS_CNT_ERR];
+    if (err) return TBS_EOVERFLOW;
+    return TBS_OK;
+}
+
+int elem_bytes(const tbs_ctx *c) { return c->cfg.dtype == 1 ? 2 : 4; }
+
+hipError_t gemm(tbs_ctx *c, const void *A, const void *B, const float *bias, float *C, int M, int N, int K,
+                const int *out_row, long ldc) {
+    if (c->cfg.dtype == 1)
+        return launch_gemm_bf16(c->stream, (const bf16_t *)A, (const bf16_t *)B, bias, C, M, N, K, out_row, ldc);
+    return launch_gemm_f32(c->stream, (const float *)A, (const float *)B, bias, C, M, N, K, out_row, ldc);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *tbs_strerror(int code) {
+    switch (code) {
+        case TBS_OK: return "ok";
+        case TBS_EINVAL: return "invalid argument or unsupported shape";
+        case TBS_ESTATE: return "call out of order";
+        case TBS_ENOMEM: return "allocation failed";
+        case TBS_EHIP: return "HIP call failed";
+        case TBS_EOVERFLOW: return "capacity exceeded (rounds per segment, merged list, trie nodes or max_len)";
+        default: return "unknown error";
+    }
+}
+
+int tbs_last_hip_error(const tbs_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+void tbs_free(tbs_ctx *c) {
+    if (!c) return;
+    (void)hipSetDevice(c->cfg.device_id);
+    (void)hipStreamSynchronize(c->stream);
+    for (void *p : c->allocs) (void)hipFree(p);
+    if (c->h_counts) (void)hipHostFree(c->h_counts);
+    for (auto &e : c->events) {
+        (void)hipEventDestroy(e.a);
+        (void)hipEventDestroy(e.b);
+    }
+    delete c;
+}
+
+int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
+    if (!cfg || !w || !out) return TBS_EINVAL;
+    *out = nullptr;
+    if (cfg->d_joint < 1 || cfg->vocab < 2 || cfg->blank_id < 0 || cfg->blank_id >= cfg->vocab) return TBS_EINVAL;
+    if (cfg->beam_n < 1 || cfg->beam_n > TBS_MAX_BEAM || cfg->seg_s < 1 || cfg->seg_s > TBS_MAX_SEG)
+        return TBS_EINVAL;
+    if (cfg->max_utts < 1 || cfg->max_frames_total < 0) return TBS_EINVAL;
+    if (cfg->pred_layers < 1 || cfg->pred_layers > TBS_MAX_LAYERS || cfg->pred_hidden < 1 || cfg->pred_embed < 1)
+        return TBS_EINVAL;
+    if (cfg->act < 0 || cfg->act > 1 || cfg->dtype < 0 || cfg->dtype > 1) return TBS_EINVAL;
+    if (cfg->max_rounds_per_segment < 0 || cfg->rounds_capacity < 0 || cfg->max_nodes < 0) return TBS_EINVAL;
+    if (cfg->vocab > 16000) return TBS_EINVAL;  // the expansion kernel keeps one row of scores in LDS
+    if (cfg->dtype == 1 && (cfg->d_joint % 8 || cfg->pred_hidden % 8 || cfg->pred_embed % 8)) return TBS_EINVAL;
+    if (!w->w_out || !w->b_out || !w->embed || !w->w_proj || !w->b_proj || !w->pred_init) return TBS_EINVAL;
+    for (int l = 0; l < cfg->pred_layers; ++l)
+        if (!w->w_ih[l] || !w->w_hh[l] || !w->b_lstm[l]) return TBS_EINVAL;
+
+    tbs_ctx *c = new (std::nothrow) tbs_ctx();
+    if (!c) return TBS_ENOMEM;
+    c->cfg = *cfg;
+    c->w = *w;
+    c->stream = (hipStream_t)cfg->stream;
+    c->state = ST_INIT;
+    c->last_hip = 0;
+    c->h_counts = nullptr;
+    c->res_tok = nullptr;
+    c->res_max_len = 0;
+    c->prof_kernel = -1;
+    c->ev_used = 0;
+    c->prof_units = 0;
+    hipError_t e = hipSetDevice(cfg->device_id);
+    if (e != hipSuccess) {
+        c->last_hip = (int)e;
+        delete c;
+        return TBS_EHIP;
+    }
+
+    Dims &d = c->d;
+    d.U = cfg->max_utts;
+    d.N = cfg->beam_n;
+    d.S = cfg->seg_s;
+    d.V = cfg->vocab;
+    d.Dj = cfg->d_joint;
+    d.blank = cfg->blank_id;
+    d.R = cfg->rounds_capacity > 0 ? cfg->rounds_capacity : 32;
+    if (cfg->max_rounds_per_segment > 0) d.R = cfg->max_rounds_per_segment;
+    d.BCAP = d.N * d.R;
+    d.E = cfg->pred_embed;
+    d.H = cfg->pred_hidden;
+    d.L = cfg->pred_layers;
+    long dn = cfg->max_nodes > 0 ? (long)cfg->max_nodes
+                                 : 4L * d.N * ((long)cfg->max_frames_total + (long)d.U * d.S) + 16;
+    if (dn > 2000000000L) dn = 2000000000L;
+    d.max_nodes = (int)dn;
+
+    const long U = d.U, UN = U * d.N, M = UN * d.S;
+    int rc = 0;
+    rc |= alloc_aview(c, &c->A[0], UN, d.S, d.U);
+    rc |= alloc_aview(c, &c->A[1], UN, d.S, d.U);
+    rc |= dev_alloc(c, &c->B.count, U);
+    rc |= dev_alloc(c, &c->B.logs, U * d.BCAP);
+    rc |= dev_alloc(c, &c->B.node, U * d.BCAP);
+    rc |= dev_alloc(c, &c->B.hash, U * d.BCAP);
+    rc |= dev_alloc(c, &c->B.len, U * d.BCAP);
+    rc |= dev_alloc(c, &c->B.slot, U * d.BCAP);
+    rc |= dev_alloc(c, &c->rv.utt_pair0, U);
+    rc |= dev_alloc(c, &c->rv.utt_sp, U);
+    rc |= dev_alloc(c, &c->rv.pair_u, UN);
+    rc |= dev_alloc(c, &c->rv.pair_h, UN);
+    rc |= dev_alloc(c, &c->rv.pair_row0, UN);
+    rc |= dev_alloc(c, &c->rv.pair_len, UN);
+    rc |= dev_alloc(c, &c->rv.row_enc, M);
+    rc |= dev_alloc(c, &c->rv.row_slot, M);
+    rc |= dev_alloc(c, &c->rv.counts, TBS_CNT_SIZE);
+    rc |= dev_alloc(c, &c->utt_T, U);
+    rc |= dev_alloc(c, &c->utt_off, U + 1);
+    rc |= dev_alloc(c, &c->nodes, (size_t)d.max_nodes);
+    c->pool_rows = U * 2 * (d.R + 1) * d.N;
+    rc |= dev_alloc(c, &c->pool_p, (size_t)c->pool_rows * d.Dj);
+    rc |= dev_alloc(c, &c->pool_h, (size_t)c->pool_rows * d.H * d.L);
+    rc |= dev_alloc(c, &c->pool_c, (size_t)c->pool_rows * d.H * d.L);
+    {
+        char *p = nullptr;
+        rc |= dev_alloc(c, &p, (size_t)M * d.Dj * elem_bytes(c));
+        c->amat = p;
+    }
+    rc |= dev_alloc(c, &c->logits, (size_t)M * d.V);
+    rc |= dev_alloc(c, &c->row_lc, M);
+    rc |= dev_alloc(c, &c->dphi, UN);
+    rc |= dev_alloc(c, &c->cand_score, UN * d.N);
+    rc |= dev_alloc(c, &c->cand_tok, UN * d.N);
+    c->row_stats = nullptr;
+    c->delta_nb = nullptr;
+    if (cfg->debug) {
+        rc |= dev_alloc(c, &c->row_stats, (size_t)M * 3);
+        rc |= dev_alloc(c, &c->delta_nb, (size_t)UN * d.V);
+    }
+    const int xw = std::max(d.E + d.H, 2 * d.H);
+    for (int i = 0; i < 2; ++i) {
+        char *p = nullptr;
+        rc |= dev_alloc(c, &p, (size_t)UN * xw * elem_bytes(c));
+        c->xh[i] = p;
+    }
+    {
+        char *p = nullptr;
+        rc |= dev_alloc(c, &p, (size_t)UN * d.H * elem_bytes(c));
+        c->htop = p;
+    }
+    rc |= dev_alloc(c, &c->gates, (size_t)UN * 4 * d.H);
+    rc |= dev_alloc(c, &c->out_row, UN);
+    for (int l = 0; l < d.L; ++l) {
+        int in_dim = l == 0 ? d.E : d.H;
+        char *p = nullptr;
+        rc |= dev_alloc(c, &p, (size_t)4 * d.H * (in_dim + d.H) * elem_bytes(c));
+        c->wcat[l] = p;
+    }
+    rc |= dev_alloc(c, &c->res_count, U);
+    rc |= dev_alloc(c, &c->res_len, UN);
+    rc |= dev_alloc(c, &c->res_logs, UN);
+    rc |= dev_alloc(c, &c->res_ovf, 1);
+    if (rc) {
+        tbs_free(c);
+        return TBS_ENOMEM;
+    }
+    e = hipHostMalloc((void **)&c->h_counts, TBS_CNT_SIZE * sizeof(int), hipHostMallocMapped);
+    if (e != hipSuccess) {
+        c->last_hip = (int)e;
+        tbs_free(c);
+        return TBS_ENOMEM;
+    }
+    memset(c->h_counts, 0, TBS_CNT_SIZE * sizeof(int));
+    e = hipHostGetDevicePointer((void **)&c->h_counts_dev, c->h_counts, 0);
+    if (e != hipSuccess) {
+        c->last_hip = (int)e;
+        tbs_free(c);
+        return TBS_EHIP;
+    }
+    for (int l = 0; l < d.L; ++l) {
+        int in_dim = l == 0 ? d.E : d.H;
+        e = launch_concat_weights(c->stream, elem_bytes(c), w->w_ih[l], w->w_hh[l], c->wcat[l], 4 * d.H, in_dim,
+                                  d.H);
+        if (e != hipSuccess) {
+            c->last_hip = (int)e;
+            tbs_free(c);
+            return TBS_EHIP;
+        }
+    }
+    e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        c->last_hip = (int)e;
+        tbs_free(c);
+        return TBS_EHIP;
+    }
+    c->n_calls = c->n_joined = c->n_frames = c->n_launches = 0;
+    *out = c;
+    return TBS_OK;
+}
+
+int tbs_begin(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, int32_t U) {
+    if (!c || !frame_offsets || U < 1 || U > c->d.U) return TBS_EINVAL;
+    if (frame_offsets[0] != 0) return TBS_EINVAL;
+    int max_T = 0;
+    c->h_T.assign(U, 0);
+    for (int u = 0; u < U; ++u) {
+        int T = frame_offsets[u + 1] - frame_offsets[u];
+        if (T < 0) return TBS_EINVAL;
+        c->h_T[u] = T;
+        max_T = std::max(max_T, T);
+    }
+    if (frame_offsets[U] > c->cfg.max_frames_total) return TBS_EINVAL;
+    if (frame_offsets[U] > 0 && !enc_proj) return TBS_EINVAL;
+    HIPCHK(c, hipSetDevice(c->cfg.device_id));
+    c->cur = c->d;
+    c->cur.U = U;
+    c->enc = enc_proj;
+    c->max_T = max_T;
+    HIPCHK(c, hipMemcpyAsync(c->utt_T, c->h_T.data(), sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->utt_off, frame_offsets, sizeof(int) * (U + 1), hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, launch_init_batch(c->stream, c->cur, c->B, c->A[0], c->A[1], c->rv, c->nodes, c->pool_p, c->pool_h,
+                                c->pool_c, c->w.pred_init, c->pool_rows));
+    // the two host arrays above are read by the copies: finish them before returning
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->seg = -1;
+    c->round = 0;
+    c->parity = 1;
+    c->a_cur = 0;
+    memset(c->h_counts, 0, TBS_CNT_SIZE * sizeof(int));
+    c->h_counts[TBS_CNT_NODES] = 1;
+    c->n_calls = c->n_joined = c->n_launches = 0;
+    c->n_frames = frame_offsets[U];
+    c->state = ST_BEGUN;
+    return TBS_OK;
+}
+
+int tbs_segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
+    if (!c || seg_index < 0) return TBS_EINVAL;
+    if (c->state != ST_BEGUN && c->state != ST_READY && c->state != ST_SELECTED) return TBS_ESTATE;
+    if (c->state != ST_BEGUN && c->h_counts[TBS_CNT_PAIRS] != 0) return TBS_ESTATE;  // A not empty yet
+    c->seg = seg_index;
+    c->round = 0;
+    c->parity = seg_index & 1;
+    AView &A = c->A[c->a_cur];
+    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv));
+    HIPCHK(c, launch_state_copy(c->stream, c->cur, A, c->rv, c->pool_p, c->pool_h, c->pool_c, c->pool_rows));
+    HIPCHK(c, launch_rowlist(c->stream, c->cur, c->seg, c->utt_T, c->utt_off, A, c->rv, c->nodes, 0,
+                             c->h_counts_dev));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
+    c->state = ST_READY;
+    return TBS_OK;
+}
+
+int tbs_joiner_segment(tbs_ctx *c) {
+    if (!c) return TBS_EINVAL;
+    if (c->state != ST_READY) return TBS_ESTATE;
+    const int rows = c->h_counts[TBS_CNT_ROWS];
+    if (c->round + 1 > c->cur.R) return TBS_EOVERFLOW;
+    c->round += 1;
+    {
+        ProfScope ps(c, TBS_K_PREP, rows);
+        HIPCHK(c, launch_joiner_prep(c->stream, c->cur, c->cfg.dtype, c->cfg.act, rows, c->enc, c->pool_p, c->rv,
+                                     c->amat));
+    }
+    {
+        ProfScope ps(c, TBS_K_JOINER, rows);
+        HIPCHK(c, gemm(c, c->amat, c->w.w_out, c->w.b_out, c->logits, rows, c->cur.V, c->cur.Dj, nullptr,
+                       c->cur.V));
+    }
+    c->n_launches += 1;
+    c->n_calls += c->h_counts[TBS_CNT_UTTS];
+    c->n_joined += c->h_counts[TBS_CNT_FRAMES];
+    c->state = ST_JOINED;
+    return TBS_OK;
+}
+
+int tbs_expand(tbs_ctx *c) {
+    if (!c) return TBS_EINVAL;
+    if (c->state != ST_JOINED) return TBS_ESTATE;
+    const int pairs = c->h_counts[TBS_CNT_PAIRS];
+    {
+        ProfScope ps(c, TBS_K_EXPAND, c->h_counts[TBS_CNT_ROWS]);
+        HIPCHK(c, launch_expand(c->stream, c->cur, pairs, c->logits, c->A[c->a_cur], c->rv, c->row_lc, c->dphi,
+                                c->cand_score, c->cand_tok, c->row_stats, c->delta_nb));
+    }
+    c->state = ST_EXPANDED;
+    return TBS_OK;
+}
+
+int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
+    if (!c) return TBS_EINVAL;
+    if (c->state != ST_EXPANDED) return TBS_ESTATE;
+    AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];
+    const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
+    {
+        ProfScope ps(c, TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
+        HIPCHK(c, launch_select_merge(c->stream, c->cur, c->parity, c->round, drop, c->logits, c->row_lc, c->dphi,
+                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes));
+        HIPCHK(c, launch_rowlist(c->stream, c->cur, c->seg, c->utt_T, c->utt_off, An, c->rv, c->nodes, 1,
+                                 c->h_counts_dev));
+    }
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->a_cur ^= 1;
+    if (live_host) *live_host = c->h_counts[TBS_CNT_PAIRS];
+    c->state = ST_SELECTED;
+    return check_err_flags(c);
+}
+
+int tbs_predictor_step(tbs_ctx *c) {
+    if (!c) return TBS_EINVAL;
+    if (c->state != ST_SELECTED) return TBS_ESTATE;
+    const int pairs = c->h_counts[TBS_CNT_PAIRS];
+    const Dims &d = c->cur;
+    AView &A = c->A[c->a_cur];
+    if (pairs > 0) {
+        ProfScope ps(c, TBS_K_PREDICTOR, pairs);
+        HIPCHK(c, launch_pred_gather(c->stream, d, c->cfg.dtype, pairs, A, c->rv, c->w.embed, c->pool_h, c->xh[0]));
+        for (int l = 0; l < d.L; ++l) {
+            int in_dim = l == 0 ? d.E : d.H;
+            HIPCHK(c, gemm(c, c->xh[l & 1], c->wcat[l], c->w.b_lstm[l], c->gates, pairs, 4 * d.H, in_dim + d.H,
+                           nullptr, 4L * d.H));
+            HIPCHK(c, launch_lstm_pointwise(c->stream, d, c->cfg.dtype, pairs, l, A, c->rv, c->gates, c->pool_h,
+                                            c->pool_c, c->pool_rows, c->xh[(l + 1) & 1], c->htop));
+        }
+        HIPCHK(c, launch_pair_slots(c->stream, d, pairs, A, c->rv, c->out_row));
+        HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, pairs, d.Dj, d.H, c->out_row, d.Dj));
+    }
+    c->state = ST_READY;
+    return TBS_OK;
+}
+
+int tbs_result(tbs_ctx *c, int32_t *tokens, int32_t *lens, double *logscores, int32_t *nbest_count,
+               int32_t max_len) {
+    if (!c || !tokens || !lens || !logscores || !nbest_count || max_len < 1) return TBS_EINVAL;
+    if (c->state == ST_INIT) return TBS_ESTATE;
+    const Dims &d = c->cur;
+    const long UN = (long)d.U * d.N;
+    if (max_len > c->res_max_len) {  // grown on demand; the decode loop itself never allocates
+        int *p = nullptr;
+        if (dev_alloc(c, &p, (size_t)c->d.U * d.N * max_len) != TBS_OK) return TBS_ENOMEM;
+        c->res_tok = p;
+        c->res_max_len = max_len;
+    }
+    HIPCHK(c, hipMemsetAsync(c->res_ovf, 0, sizeof(int), c->stream));
+    HIPCHK(c, hipMemsetAsync(c->res_tok, 0xFF, sizeof(int) * UN * max_len, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->res_len, 0, sizeof(int) * UN, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->res_logs, 0, sizeof(double) * UN, c->stream));
+    HIPCHK(c, launch_finalize(c->stream, d, c->B, c->nodes, c->res_count, c->res_len, c->res_logs, c->res_tok,
+                              max_len, c->res_ovf));
+    int ovf = 0;
+    HIPCHK(c, hipMemcpyAsync(tokens, c->res_tok, sizeof(int) * UN * max_len, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(lens, c->res_len, sizeof(int) * UN, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(logscores, c->res_logs, sizeof(double) * UN, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(nbest_count, c->res_count, sizeof(int) * d.U, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(&ovf, c->res_ovf, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return ovf ? TBS_EOVERFLOW : TBS_OK;
+}
+
+int tbs_decode(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, int32_t U, int32_t *tokens,
+               int32_t *lens, double *logscores, int32_t *nbest_count, int32_t max_len) {
+    int rc = tbs_begin(c, enc_proj, frame_offsets, U);
+    if (rc) return rc;
+    const int S = c->cur.S;
+    const int nseg = (c->max_T + S - 1) / S;
+    for (int seg = 0; seg < nseg; ++seg) {          // while t <= Length(enc)
+        int rows = 0;
+        rc = tbs_segment_begin(c, seg, &rows);
+        if (rc) return rc;
+        while (rows > 0) {                           // while Length(A) > 0
+            int live = 0;
+            if ((rc = tbs_joiner_segment(c))) return rc;
+            if ((rc = tbs_expand(c))) return rc;
+            if ((rc = tbs_select_merge(c, &live))) return rc;
+            if ((rc = tbs_predictor_step(c))) return rc;
+            rows = c->h_counts[TBS_CNT_ROWS];
+        }
+    }
+    return tbs_result(c, tokens, lens, logscores, nbest_count, max_len);
+}
+
+int tbs_stats(const tbs_ctx *c, int64_t *joiner_calls, int64_t *joined_frames, int64_t *frames, int64_t *launches) {
+    if (!c) return TBS_EINVAL;
+    if (joiner_calls) *joiner_calls = c->n_calls;
+    if (joined_frames) *joined_frames = c->n_joined;
+    if (frames) *frames = c->n_frames;
+    if (launches) *launches = c->n_launches;
+    return TBS_OK;
+}
+
+// ------------------------------------------------------------------ inspection
+int tbs_debug_read(tbs_ctx *c, int32_t which, void *dst, size_t bytes) {
+    if (!c || !dst) return TBS_EINVAL;
+    if (c->state == ST_INIT) return TBS_ESTATE;
+    const Dims &d = c->cur;
+    const long UN = (long)d.U * d.N;
+    const long pairs = c->h_counts[TBS_CNT_PAIRS], rows = c->h_counts[TBS_CNT_ROWS];
+    const AView &A = c->A[c->a_cur];
+    const void *src = nullptr;
+    size_t have = 0;
+    float *tmp = nullptr;
+    switch (which) {
+        case TBS_BUF_A_COUNT: src = A.count; have = sizeof(int) * d.U; break;
+        case TBS_BUF_A_LOGS: src = A.logs; have = sizeof(double) * UN; break;
+        case TBS_BUF_A_DHAT: src = A.dhat; have = sizeof(float) * UN * d.S; break;
+        case TBS_BUF_A_PRED: {
+            HIPCHK(c, hipMalloc((void **)&tmp, sizeof(float) * UN * d.Dj));
+            HIPCHK(c, hipMemsetAsync(tmp, 0, sizeof(float) * UN * d.Dj, c->stream));
+            HIPCHK(c, launch_gather_pred(c->stream, d, A, c->pool_p, tmp, 0));
+            src = tmp;
+            have = sizeof(float) * UN * d.Dj;
+            break;
+        }
+        case TBS_BUF_LOGITS: src = c->logits; have = sizeof(float) * rows * d.V; break;
+        case TBS_BUF_ROW_STATS:
+            if (!c->row_stats) return TBS_ESTATE;
+            src = c->row_stats; have = sizeof(float) * rows * 3; break;
+        case TBS_BUF_DELTA_BLANK: src = c->dphi; have = sizeof(float) * pairs; break;
+        case TBS_BUF_DELTA_NB:
+            if (!c->delta_nb) return TBS_ESTATE;
+            src = c->delta_nb; have = sizeof(float) * pairs * d.V; break;
+        case TBS_BUF_CAND_SCORE: src = c->cand_score; have = sizeof(float) * pairs * d.N; break;
+        case TBS_BUF_CAND_TOKEN: src = c->cand_tok; have = sizeof(int) * pairs * d.N; break;
+        case TBS_BUF_PAIR_UTT: src = c->rv.pair_u; have = sizeof(int) * pairs; break;
+        case TBS_BUF_PAIR_HYP: src = c->rv.pair_h; have = sizeof(int) * pairs; break;
+        case TBS_BUF_PAIR_ROW0: src = c->rv.pair_row0; have = sizeof(int) * pairs; break;
+        case TBS_BUF_PAIR_LEN: src = c->rv.pair_len; have = sizeof(int) * pairs; break;
+        case TBS_BUF_COUNTS: src = c->rv.counts; have = sizeof(int) * 4; break;
+        default: return TBS_EINVAL;
+    }
+    size_t n = std::min(have, bytes);
+    hipError_t e = hipSuccess;
+    if (n) e = hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (tmp) (void)hipFree(tmp);
+    HIPCHK(c, e);
+    return TBS_OK;
+}
+
+int tbs_debug_write(tbs_ctx *c, int32_t which, const void *src, size_t bytes) {
+    if (!c || !src) return TBS_EINVAL;
+    if (c->state == ST_INIT) return TBS_ESTATE;
+    const Dims &d = c->cur;
+    const long UN = (long)d.U * d.N;
+    AView &A = c->A[c->a_cur];
+    switch (which) {
+        case TBS_BUF_A_COUNT:
+            if (bytes != sizeof(int) * d.U) return TBS_EINVAL;
+            HIPCHK(c, hipMemcpyAsync(A.count, src, bytes, hipMemcpyHostToDevice, c->stream));
+            HIPCHK(c, launch_debug_fill_a(c->stream, d, A));
+            break;
+        case TBS_BUF_A_LOGS:
+            if (bytes != sizeof(double) * UN) return TBS_EINVAL;
+            HIPCHK(c, hipMemcpyAsync(A.logs, src, bytes, hipMemcpyHostToDevice, c->stream));
+            break;
+        case TBS_BUF_A_DHAT:
+            if (bytes != sizeof(float) * UN * d.S) return TBS_EINVAL;
+            HIPCHK(c, hipMemcpyAsync(A.dhat, src, bytes, hipMemcpyHostToDevice, c->stream));
+            break;
+        case TBS_BUF_A_PRED: {
+            if (bytes != sizeof(float) * UN * d.Dj) return TBS_EINVAL;
+            float *tmp = nullptr;
+            HIPCHK(c, hipMalloc((void **)&tmp, bytes));
+            hipError_t e = hipMemcpyAsync(tmp, src, bytes, hipMemcpyHostToDevice, c->stream);
+            if (e == hipSuccess) e = launch_gather_pred(c->stream, d, A, c->pool_p, tmp, 1);
+            if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+            (void)hipFree(tmp);
+            HIPCHK(c, e);
+            break;
+        }
+        default: return TBS_EINVAL;
+    }
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return TBS_OK;
+}
+
+int tbs_debug_rebuild(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
+    if (!c || seg_index < 0) return TBS_EINVAL;
+    if (c->state == ST_INIT) return TBS_ESTATE;
+    c->seg = seg_index;
+    c->round = 0;
+    c->parity = 0;
+    HIPCHK(c, launch_set_sp(c->stream, c->cur, seg_index, c->utt_T, c->rv));
+    HIPCHK(c, launch_rowlist(c->stream, c->cur, c->seg, c->utt_T, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0,
+                             c->h_counts_dev));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
+    c->state = ST_READY;
+    return TBS_OK;
+}
+
+int tbs_debug_hyps(tbs_ctx *c, int32_t group, int32_t *tokens, int32_t *lens, double *logscores, int32_t *counts,
+                   int32_t cap, int32_t max_len) {
+    if (!c || !tokens || !lens || !logscores || !counts || cap < 1 || max_len < 1 || group < 0 || group > 1)
+        return TBS_EINVAL;
+    if (c->state == ST_INIT) return TBS_ESTATE;
+    const Dims &d = c->cur;
+    const size_t n = (size_t)d.U * cap;
+    int *dtok = nullptr, *dlen = nullptr, *dcnt = nullptr;
+    double *dlogs = nullptr;
+    hipError_t e = hipMalloc((void **)&dtok, sizeof(int) * n * max_len);
+    if (e == hipSuccess) e = hipMalloc((void **)&dlen, sizeof(int) * n);
+    if (e == hipSuccess) e = hipMalloc((void **)&dlogs, sizeof(double) * n);
+    if (e == hipSuccess) e = hipMalloc((void **)&dcnt, sizeof(int) * d.U);
+    if (e == hipSuccess) e = hipMemsetAsync(dtok, 0xFF, sizeof(int) * n * max_len, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(dlen, 0, sizeof(int) * n, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(dlogs, 0, sizeof(double) * n, c->stream);
+    if (e == hipSuccess)
+        e = launch_hyps_dump(c->stream, d, group, c->A[c->a_cur], c->B, c->nodes, cap, max_len, dtok, dlen, dlogs,
+                             dcnt);
+    if (e == hipSuccess) e = hipMemcpyAsync(tokens, dtok, sizeof(int) * n * max_len, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(lens, dlen, sizeof(int) * n, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(logscores, dlogs, sizeof(double) * n, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(counts, dcnt, sizeof(int) * d.U, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    (void)hipFree(dtok);
+    (void)hipFree(dlen);
+    (void)hipFree(dlogs);
+    (void)hipFree(dcnt);
+    HIPCHK(c, e);
+    return TBS_OK;
+}
+
+// ------------------------------------------------------------------ profiling
+int tbs_profile_select(tbs_ctx *c, int32_t kernel_id) {
+    if (!c || kernel_id < -1 || kernel_id >= TBS_K_COUNT) return TBS_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (kernel_id >= 0 && c->events.empty()) {
+        c->events.resize(8192);
+        for (auto &e : c->events) {
+            HIPCHK(c, hipEventCreate(&e.a));
+            HIPCHK(c, hipEventCreate(&e.b));
+        }
+    }
+    c->prof_kernel = kernel_id;
+    c->ev_used = 0;
+    c->prof_units = 0;
+    return TBS_OK;
+}
+
+int tbs_profile_read(tbs_ctx *c, int64_t *launches, double *total_ms, int64_t *units) {
+    if (!c) return TBS_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    double tot = 0.0;
+    for (size_t i = 0; i < c->ev_used; ++i) {
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, c->events[i].a, c->events[i].b));
+        tot += ms;
+    }
+    if (launches) *launches = (int64_t)c->ev_used;
+    if (total_ms) *total_ms = tot;
+    if (units) *units = c->prof_units;
+    c->ev_used = 0;
+    c->prof_units = 0;
+    return TBS_OK;
+}
+
+int tbs_gemm_bf16(const void *A, const void *B, const float *bias, float *C, int32_t M, int32_t N, int32_t K,
+                  void *stream) {
+    if (!A || !B || !C || M < 1 || N < 1 || K < 8 || K % 8) return TBS_EINVAL;
+    hipError_t e = launch_gemm_bf16((hipStream_t)stream, (const bf16_t *)A, (const bf16_t *)B, bias, C, M, N, K,
+                                    nullptr, N);
+    return e == hipSuccess ? TBS_OK : TBS_EHIP;
+}
+
+}  // extern "C"

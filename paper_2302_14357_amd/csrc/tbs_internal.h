@@ -1,0 +1,99 @@
+// Internal declarations shared by the host code and the kernel files of libtbs.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tbs.h"
+
+typedef unsigned long long u64;
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+// Group A (hypotheses still emitting in this segment), structure of arrays, [U, N].
+struct AView {
+    int *count;     // [U]
+    double *logs;   // log score
+    int *node;      // trie node of the token sequence
+    u64 *hash;      // hash of the token sequence
+    int *len;       // number of tokens
+    int *slot;      // predictor-state slot of this hypothesis
+    int *pslot;     // slot of the hypothesis it was made from (source of the recurrent state)
+    int *pnode;     // trie node of the hypothesis it was made from
+    int *token;     // last token (-1 for hypotheses carried into the segment)
+    float *dhat;    // [U, N, S] frame distribution of the last token, normalised
+};
+
+// Group B (hypotheses that took their blank for this segment), [U, BCAP].
+struct BView {
+    int *count;
+    double *logs;
+    int *node;
+    u64 *hash;
+    int *len;
+    int *slot;
+};
+
+// Row/pair lists of the current round.
+struct RowView {
+    int *utt_pair0;  // [U]  first pair of each utterance
+    int *utt_sp;     // [U]  frames of each utterance in this segment (0 = finished)
+    int *pair_u, *pair_h, *pair_row0, *pair_len;  // [pairs]
+    int *row_enc;    // [rows] frame row in enc_proj
+    int *row_slot;   // [rows] predictor-state slot
+    int *counts;     // [8]: 0 pairs, 1 rows, 2 trie nodes used, 3 error flags, 4 live utterances,
+                     //      5 frames joined (sum of S' over live utterances)
+};
+
+enum { TBS_CNT_PAIRS = 0, TBS_CNT_ROWS = 1, TBS_CNT_NODES = 2, TBS_CNT_ERR = 3, TBS_CNT_UTTS = 4, TBS_CNT_FRAMES = 5,
+       TBS_CNT_SIZE = 8 };
+enum { TBS_ERRF_BCAP = 1, TBS_ERRF_NODES = 2 };
+
+struct Dims {
+    int U, N, S, V, Dj, blank;
+    int R;      // rounds capacity
+    int BCAP;   // entries of B per utterance
+    int E, H, L;
+    int max_nodes;
+};
+
+__host__ __device__ inline int tbs_slot_id(int u, int parity, int r, int i, int R, int N) {
+    return ((u * 2 + parity) * (R + 1) + r) * N + i;
+}
+
+// ---- launchers (each enqueues on `st` and returns the HIP status) ----
+hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, AView A1, RowView rv, int2 *nodes,
+                             float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
+                             long pool_rows);
+hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
+                                AView A, RowView rv);
+hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv, float *pool_p, float *pool_h,
+                             float *pool_c, long pool_rows);
+hipError_t launch_rowlist(hipStream_t st, const Dims &d, int seg, const int *utt_T, const int *utt_off, AView A,
+                          RowView rv, int2 *nodes, int assign_nodes, int *host_counts);
+hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
+                              const float *pool_p, RowView rv, void *amat);
+hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
+                           int K, const int *out_row, long ldc);
+hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
+                            int N, int K, const int *out_row, long ldc);
+hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
+                         float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
+                         float *delta_nb);
+hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
+                               const float *row_lc, const float *dphi, const float *cand_score,
+                               const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes);
+hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
+                              const void *embed, const float *pool_h, void *xh);
+hipError_t launch_lstm_pointwise(hipStream_t st, const Dims &d, int dtype, int pairs, int layer, AView A, RowView rv,
+                                 const float *gates, float *pool_h, float *pool_c, long pool_rows, void *xh_next,
+                                 void *htop);
+hipError_t launch_pair_slots(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, int *out_row);
+hipError_t launch_finalize(hipStream_t st, const Dims &d, BView B, const int2 *nodes, int *res_count, int *res_len,
+                           double *res_logs, int *res_tok, int max_len, int *ovf);
+hipError_t launch_hyps_dump(hipStream_t st, const Dims &d, int group, AView A, BView B, const int2 *nodes, int cap,
+                            int max_len, int *tok, int *len, double *logs, int *count);
+hipError_t launch_gather_pred(hipStream_t st, const Dims &d, AView A, const float *pool_p, float *out, int scatter);
+hipError_t launch_concat_weights(hipStream_t st, int elem_bytes, const void *w_ih, const void *w_hh, void *wcat,
+                                 int rows, int in_dim, int hid);
+hipError_t launch_debug_fill_a(hipStream_t st, const Dims &d, AView A);
+hipError_t launch_set_sp(hipStream_t st, const Dims &d, int seg, const int *utt_T, RowView rv);

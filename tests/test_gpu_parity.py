@@ -1,0 +1,307 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element
+by element, on the same seeded inputs.
+
+Tolerances.  Expansion scores (spec bar): relative 1e-3 on scores
+relative to the hypothesis score, i.e. |log gpu - log oracle| <= 1e-3, for
+entries above 1e-30.  For bf16 models the oracle rounds act(e+p) and the
+recurrent inputs to bf16 at the same points as the kernels; what remains is
+fp32 accumulation order and exp/log/tanh rounding (~1e-6), plus rare bf16
+rounding flips.  fp32 models: the same checks at 1e-4.  Integer results
+(tokens, candidate sets, list sizes) must match exactly wherever the oracle's
+own decision margin exceeds the tolerance.
+"""
+
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from tbs_inputs import SHAPES, TbsShape, make_model, make_utterances
+from helpers import build_case, oracle_weights, make_tbs, compare_nbest, small_bf16_shape
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_values(rng, shape, scale=1.0):
+    import torch
+    x = (rng.standard_normal(shape) * scale).astype(np.float32)
+    return torch.from_numpy(x).to(torch.bfloat16)
+
+
+# ------------------------------------------------------------------ the MFMA GEMM on its own
+
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (200, 192, 128), (37, 100, 72), (1000, 1024, 512),
+                                   (4100, 4096, 1024)])
+def test_gemm_bf16_tiles(M, N, K):
+    import torch
+    from paper_2302_14357_amd import gemm_bf16
+    rng = np.random.default_rng(M + N + K)
+    a, b = _bf16_values(rng, (M, K)), _bf16_values(rng, (N, K), 0.1)
+    bias = torch.from_numpy(rng.standard_normal(N).astype(np.float32))
+    got = gemm_bf16(a.cuda(), b.cuda(), bias.cuda()).cpu().numpy()
+    want = a.to(torch.float64).numpy() @ b.to(torch.float64).numpy().T + bias.numpy().astype(np.float64)
+    np.testing.assert_allclose(got, want, rtol=1e-4, atol=1e-4 * math.sqrt(K))
+
+
+# ------------------------------------------------------------------ joiner + expansion on chosen inputs
+
+def _teacher_forced_state(rng, U, N, S, Dj):
+    counts = rng.integers(0, N + 1, size=U).astype(np.int32)
+    counts[0] = N
+    if U > 1:
+        counts[1] = 1
+    pred = (rng.standard_normal((U, N, Dj)) * 0.5).astype(np.float32)
+    dhat = rng.random((U, N, S)).astype(np.float32)
+    dhat[rng.random((U, N, S)) < 0.35] = 0.0
+    dhat[:, :, 0] += 0.05
+    logs = -rng.random((U, N)) * 50.0
+    return counts, pred, dhat, logs
+
+
+def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3):
+    model, offsets, enc = build_case(shape, n_utts=U)
+    W = oracle_weights(shape, model)
+    tbs = make_tbs(shape, model, offsets, N, S, debug=True)
+    enc_dev = tbs.upload_frames(enc)
+    rng = np.random.default_rng(11)
+    counts, pred, dhat, logs = _teacher_forced_state(rng, U, N, S, shape.d_joint)
+    tbs.begin(enc_dev, offsets)
+    from paper_2302_14357_amd import BUF
+    tbs.debug_write(BUF.A_COUNT, counts)
+    tbs.debug_write(BUF.A_LOGS, logs)
+    tbs.debug_write(BUF.A_PRED, pred)
+    tbs.debug_write(BUF.A_DHAT, dhat)
+    rows = tbs.debug_rebuild(seg)
+    lens = np.diff(offsets)
+    sp = np.clip(lens - seg * S, 0, S)
+    assert rows == int(np.sum(np.where(sp > 0, counts, 0) * sp))
+    np.testing.assert_array_equal(tbs.debug_read(BUF.A_PRED)[0, :N], pred[0, :N])
+    tbs.joiner_segment()
+    tbs.expand()
+    pu, ph = tbs.debug_read(BUF.PAIR_UTT), tbs.debug_read(BUF.PAIR_HYP)
+    row0, plen = tbs.debug_read(BUF.PAIR_ROW0), tbs.debug_read(BUF.PAIR_LEN)
+    logits = tbs.debug_read(BUF.LOGITS)
+    stats = tbs.debug_read(BUF.ROW_STATS)
+    dphi = tbs.debug_read(BUF.DELTA_BLANK)
+    dnb = tbs.debug_read(BUF.DELTA_NB)
+    cs, ct = tbs.debug_read(BUF.CAND_SCORE), tbs.debug_read(BUF.CAND_TOKEN)
+    pairs = len(pu)
+    # pair list: utterances in order, hypotheses in order, finished utterances absent
+    want_pairs = [(u, h) for u in range(U) if sp[u] > 0 for h in range(counts[u])]
+    assert list(zip(pu.tolist(), ph.tolist())) == want_pairs
+    which = range(pairs) if sample_pairs is None else rng.choice(pairs, size=min(sample_pairs, pairs), replace=False)
+    worst = 0.0
+    for j in which:
+        u, h, r0, L = int(pu[j]), int(ph[j]), int(row0[j]), int(plen[j])
+        assert L == sp[u]
+        ref_logits = np.stack([W.joiner_vec(enc[offsets[u] + seg * S + t], pred[u, h]) for t in range(L)])
+        np.testing.assert_allclose(logits[r0:r0 + L], ref_logits, rtol=0, atol=tol)
+        d_old = dhat[u, h, :L].astype(np.float64)
+        J, Bl, d, ref_nb, ref_phi = oracle.expansion_scores(ref_logits[None], d_old[None], shape.blank_id)
+        np.testing.assert_allclose(stats[r0:r0 + L, 2], J[0, :, shape.blank_id], rtol=tol)
+        assert abs(math.log(dphi[j]) - math.log(ref_phi[0])) <= tol
+        ref_nb = ref_nb[0]
+        big = ref_nb > 1e-30
+        err = np.abs(np.log(dnb[j][big]) - np.log(ref_nb[big]))
+        worst = max(worst, float(err.max()))
+        assert err.max() <= tol
+        assert dnb[j][shape.blank_id] == 0.0
+        # the N best expansions of this hypothesis: same set wherever the margin is clear
+        order = np.argsort(-ref_nb, kind="stable")
+        n_take = min(N, shape.vocab - 1)
+        margin = math.log(ref_nb[order[n_take - 1]]) - math.log(ref_nb[order[n_take]]) if n_take < shape.vocab - 1 else 1.0
+        if margin > 2 * tol:
+            assert set(ct[j][:n_take].tolist()) == set(order[:n_take].tolist())
+        got_sorted = cs[j][:n_take]
+        assert np.all(np.diff(got_sorted) <= 0)
+        np.testing.assert_allclose(got_sorted, np.log(ref_nb[ct[j][:n_take]]), rtol=0, atol=tol)
+    tbs.close()
+    return worst
+
+
+def test_joiner_expand_tiny_fp32():
+    _check_joiner_expand(SHAPES["tiny"], U=1, N=2, S=3, seg=2, tol=1e-4)
+    _check_joiner_expand(SHAPES["tiny"], U=1, N=2, S=3, seg=16, tol=1e-4)  # ragged last segment (2 frames)
+
+
+@pytest.mark.parametrize("N,S", [(5, 3), (2, 1), (10, 5), (3, 50)])
+def test_joiner_expand_small_bf16(N, S):
+    shape = small_bf16_shape(n_utts=5, vocab=200, d=128, hidden=64)
+    _check_joiner_expand(shape, U=5, N=N, S=S, seg=1 if S < 20 else 0)
+
+
+def test_joiner_expand_odd_vocab():
+    shape = small_bf16_shape(n_utts=3, vocab=77, d=64, hidden=64)
+    _check_joiner_expand(shape, U=3, N=4, S=3, seg=0)
+
+
+def test_joiner_expand_librispeech_full_size_sampled():
+    """Headline configuration at full size (64 utterances, V=1024, Dj=512,
+    N=5, S=3): sampled hypotheses against the oracle."""
+    _check_joiner_expand(SHAPES["librispeech"], U=64, N=5, S=3, seg=10, sample_pairs=12)
+
+
+def test_joiner_expand_assistant_full_width_sampled():
+    """Large-assistant widths (V=4096, Dj=1024, N=10, S=3) with a multi-tile row count."""
+    _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=6)
+
+
+# ------------------------------------------------------------------ whole decode
+
+def _oracle_decode(shape, model, offsets, enc, N, S, threads=16, **kw):
+    W = oracle_weights(shape, model)
+    res, _ = oracle.decode_lstm_batch(W, enc, offsets, N, S, threads=min(threads, oracle.max_threads()), **kw)
+    return res
+
+
+def _gpu_decode(shape, model, offsets, enc, N, S, **kw):
+    tbs = make_tbs(shape, model, offsets, N, S, **kw)
+    out = tbs.decode(tbs.upload_frames(enc), offsets)
+    st = tbs.stats()
+    tbs.close()
+    return out, st
+
+
+def test_decode_tiny_reference_config():
+    shape = SHAPES["tiny"]
+    model, offsets, enc = build_case(shape)
+    ref = _oracle_decode(shape, model, offsets, enc, 2, 3)
+    got, st = _gpu_decode(shape, model, offsets, enc, 2, 3)
+    same, amb, tot = compare_nbest(got, ref, score_tol=1e-3)
+    assert same == tot
+    assert st["joiner_calls"] == ref[0].joiner_calls and st["joined_frames"] == ref[0].joined_frames
+    assert st["frames"] == 50
+
+
+@pytest.mark.parametrize("N,S", [(1, 1), (2, 2), (5, 3), (3, 7), (4, 30)])
+def test_decode_small_bf16_and_edges(N, S):
+    """Ragged batch with an empty utterance, one shorter than a segment and
+    lengths that leave ragged last segments."""
+    shape = small_bf16_shape(n_utts=6, vocab=64, d=64, hidden=64, layers=2)
+    lengths = np.array([0, 1, 2, 7, 12, 23])
+    model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, N, S)
+    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    assert got[0] == [((), 0.0)]
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot and same >= tot - 1
+    assert st["joiner_calls"] == sum(r.joiner_calls for r in ref) or amb > 0
+
+
+def test_decode_step_by_step_matches_oracle_trace():
+    """Drive the step entry points and compare A and B with the oracle after every round."""
+    shape = small_bf16_shape(n_utts=1, vocab=48, d=64, hidden=64)
+    N, S = 3, 4
+    model, offsets, enc = build_case(shape, n_utts=1, lengths=np.array([14]))
+    W = oracle_weights(shape, model)
+    ref = oracle.decode(oracle.LstmModel(W, enc), 14, N, S, trace=True)
+    tbs = make_tbs(shape, model, offsets, N, S, debug=True)
+    tbs.begin(tbs.upload_frames(enc), offsets)
+    it = iter(ref.rounds)
+    nseg = (14 + S - 1) // S
+    for seg in range(nseg):
+        rows = tbs.segment_begin(seg)
+        while rows > 0:
+            r = next(it)
+            assert r.seg == seg
+            a_now = tbs.debug_hyps(0)[0]
+            assert [y for y, _ in a_now] == r.a_tokens
+            np.testing.assert_allclose([s for _, s in a_now], r.a_scores, atol=1e-3)
+            tbs.joiner_segment()
+            tbs.expand()
+            live = tbs.select_merge()
+            b_now = tbs.debug_hyps(1)[0]
+            assert [y for y, _ in b_now] == r.b_tokens
+            np.testing.assert_allclose([s for _, s in b_now], r.b_scores, atol=1e-3)
+            assert live == len(r.new_pairs)
+            from paper_2302_14357_amd import BUF
+            dh = tbs.debug_read(BUF.A_DHAT)[0]
+            for i, dref in enumerate(r.new_d):
+                np.testing.assert_allclose(dh[i, :r.S], dref, rtol=1e-3, atol=1e-7)
+            tbs.predictor_step()
+            rows = tbs.counts()["rows"]
+    assert next(it, None) is None
+    final = tbs.result()[0]
+    assert [y for y, _ in final] == [y for y, _ in ref.nbest]
+    tbs.close()
+
+
+def test_round_limit_matches_oracle():
+    shape = small_bf16_shape(n_utts=2, vocab=32, d=64, hidden=64)
+    model, offsets, enc = build_case(shape, n_utts=2, lengths=np.array([9, 6]))
+    ref = _oracle_decode(shape, model, offsets, enc, 4, 3, max_rounds=2)
+    got, _ = _gpu_decode(shape, model, offsets, enc, 4, 3, max_rounds_per_segment=2)
+    same, amb, tot = compare_nbest(got, ref)
+    assert same == tot
+
+
+def test_batch_equals_each_alone_and_is_deterministic():
+    shape = small_bf16_shape(n_utts=4, vocab=64, d=64, hidden=64)
+    model, offsets, enc = build_case(shape, n_utts=4, lengths=np.array([11, 4, 17, 8]))
+    together, _ = _gpu_decode(shape, model, offsets, enc, 3, 3)
+    again, _ = _gpu_decode(shape, model, offsets, enc, 3, 3)
+    assert together == again
+    for u in range(4):
+        o = np.array([0, offsets[u + 1] - offsets[u]], np.int32)
+        alone, _ = _gpu_decode(shape, model, o, enc[offsets[u]:offsets[u + 1]], 3, 3)
+        assert [y for y, _ in alone[0]] == [y for y, _ in together[u]]
+        np.testing.assert_allclose([s for _, s in alone[0]], [s for _, s in together[u]], atol=1e-5)
+
+
+def test_decode_librispeech_like_subset():
+    """Headline shapes (Dj=512, V=1024, LSTM 640, N=5, S=3) on the first 8
+    utterances of the benchmark batch, whole decode against the oracle."""
+    shape = SHAPES["librispeech"]
+    model = make_model(shape)
+    offsets_all, _ = None, None
+    full_off, full_enc = make_utterances(shape, model)
+    U = 8
+    offsets = full_off[:U + 1].copy()
+    enc = full_enc[:offsets[-1]]
+    ref = _oracle_decode(shape, model, offsets, enc, 5, 3)
+    got, st = _gpu_decode(shape, model, offsets, enc, 5, 3)
+    same, amb, tot = compare_nbest(got, ref)
+    print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
+    assert same + amb == tot and same >= tot - 2
+
+
+def test_decode_full_batch_contains_the_subset():
+    """Full benchmark batch (64 utterances) in the benchmark's launch
+    configuration: the first utterances must decode exactly as they do in the
+    8-utterance batch that is checked against the oracle above."""
+    shape = SHAPES["librispeech"]
+    model = make_model(shape)
+    full_off, full_enc = make_utterances(shape, model)
+    full, st = _gpu_decode(shape, model, full_off, full_enc, 5, 3)
+    offsets = full_off[:9].copy()
+    part, _ = _gpu_decode(shape, model, offsets, full_enc[:offsets[-1]], 5, 3)
+    for u in range(8):
+        assert [y for y, _ in part[u]] == [y for y, _ in full[u]]
+    assert st["frames"] == int(full_off[-1])
+    assert 0.3 < st["joiner_calls"] / st["frames"] < 2.0
+
+
+def test_errors_are_codes_not_crashes():
+    from paper_2302_14357_amd import TbsError
+    shape = small_bf16_shape(n_utts=2)
+    model, offsets, enc = build_case(shape, n_utts=2, lengths=np.array([5, 6]))
+    tbs = make_tbs(shape, model, offsets, 2, 2)
+    with pytest.raises(TbsError) as e:
+        tbs.expand()            # before begin / joiner
+    assert e.value.code == -2
+    enc_dev = tbs.upload_frames(enc)
+    tbs.begin(enc_dev, offsets)
+    with pytest.raises(TbsError) as e:
+        tbs.joiner_segment()    # before segment_begin
+    assert e.value.code == -2
+    with pytest.raises(TbsError) as e:
+        tbs.begin(enc_dev, np.array([0, 5, 11, 12], np.int32))   # more utterances than capacity
+    assert e.value.code == -1
+    tbs.close()
+    # rounds capacity of one: the second round of a segment overflows cleanly
+    tbs = make_tbs(shape, model, offsets, 2, 2, rounds_capacity=1)
+    with pytest.raises(TbsError) as e:
+        tbs.decode(tbs.upload_frames(enc), offsets)
+    assert e.value.code == -5
+    tbs.close()
