@@ -282,7 +282,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
         double key = A.logs[a] + log((double)dphi[pair0 + h]);
         u64 hs = A.hash[a];
         int ln = A.len[a], nd = A.node[a];
-        if (lane == 0) s_found = -1;
+        if (lane == 0) s_found = 0x7fffffff;
         __syncthreads();
         for (int base = 0; base < nB; base += WAVE) {
             int i = base + lane;
@@ -291,7 +291,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
             if (hit) atomicMin(&s_found, i);  // at most one entry can match; min keeps it deterministic
         }
         __syncthreads();
-        int f = s_found;
+        int f = s_found == 0x7fffffff ? -1 : s_found;
         if (lane == 0) {
             if (f >= 0) {
                 bl[f] = log_add(bl[f], key);

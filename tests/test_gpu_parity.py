@@ -192,14 +192,21 @@ def test_decode_small_bf16_and_edges(N, S):
 def test_decode_step_by_step_matches_oracle_trace():
     """Drive the step entry points and compare A and B with the oracle after every round."""
     shape = small_bf16_shape(n_utts=1, vocab=48, d=64, hidden=64)
-    N, S = 3, 4
-    model, offsets, enc = build_case(shape, n_utts=1, lengths=np.array([14]))
+    N, S, T = 3, 4, 38
+    model, offsets, enc = build_case(shape, n_utts=1, lengths=np.array([T]))
     W = oracle_weights(shape, model)
-    ref = oracle.decode(oracle.LstmModel(W, enc), 14, N, S, trace=True)
+    ref = oracle.decode(oracle.LstmModel(W, enc), T, N, S, trace=True)
+    # the run must exercise AddAndMerge: some round adds fewer entries to B than it has hypotheses
+    merges, prev = 0, {}
+    for r in ref.rounds:
+        before = prev.get(r.seg, 0)
+        merges += before + len(r.a_tokens) - len(r.b_tokens)
+        prev[r.seg] = len(r.b_tokens)
+    assert merges > 0
     tbs = make_tbs(shape, model, offsets, N, S, debug=True)
     tbs.begin(tbs.upload_frames(enc), offsets)
     it = iter(ref.rounds)
-    nseg = (14 + S - 1) // S
+    nseg = (T + S - 1) // S
     for seg in range(nseg):
         rows = tbs.segment_begin(seg)
         while rows > 0:
