@@ -60,6 +60,11 @@ def load_library():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2302_14357_amd.build` "
                           "(there is no CPU fallback)")
+    # PyTorch owns the device memory handed to the library, so both must share one
+    # HIP runtime: torch is imported first and libtbs then binds to the runtime
+    # torch has already loaded (two runtimes in one process do not see each
+    # other's allocations).
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64p = C.c_void_p, C.c_int32, C.POINTER(C.c_int64)
     L.tbs_init.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]
