@@ -1,0 +1,277 @@
+// bf16 MFMA GEMM of the joiner (and of the predictor's dense layers):
+//   C[M,N] = A[M,K] * B[N,K]^T + bias[N],  bf16 inputs, fp32 accumulate, fp32 output.
+//
+// Workgroup = WM x WN waves; each wave owns TM x TN blocks of 32x32 computed
+// with v_mfma_f32_32x32x16_bf16, so a workgroup tile is (32 TM WM) x (32 TN WN).
+// K is consumed in tiles of 64 through LDS.  LDS rows are 128 bytes (8 chunks
+// of 16 bytes) and chunk c of row r is stored at position c ^ (r & 7): the
+// 16-byte fragment reads of 8 consecutive rows then touch 8 different chunk
+// positions, i.e. all banks once, with no padding.  Two LDS buffers alternate,
+// the next K tile is fetched from global memory into registers while the
+// current one is multiplied, and one barrier per K tile separates them.
+// The grid is one-dimensional and maps workgroups to tiles so that the
+// workgroups resident on one XCD (ids equal modulo 8) work on a compact block of
+// tiles and share their operand rows in that XCD's L2.
+#include "tbs_internal.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+#define GEMM_BK 64
+#define GEMM_XCDS 8
+#define GEMM_GROUP_M 4   // M tiles per XCD block
+
+// Position idx of XCD xcd's tile sequence -> (tile_m, tile_n).  Tiles are ordered
+// in blocks of GEMM_GROUP_M rows of tiles (M fastest inside a block) and XCD x
+// owns the x-th contiguous eighth of that order, so the workgroups resident on
+// one XCD at any time work on neighbouring tiles.
+__device__ __forceinline__ bool gemm_tile_of(int xcd, int idx, int tiles_m, int tiles_n, int &tm, int &tn) {
+    const int total = tiles_m * tiles_n;
+    const int chunk = (total + GEMM_XCDS - 1) / GEMM_XCDS;
+    const int t = xcd * chunk + idx;
+    tm = 0;
+    tn = 0;
+    if (idx >= chunk || t >= total) return false;
+    const int per_block = GEMM_GROUP_M * tiles_n;
+    const int b = t / per_block, r = t % per_block;
+    const int gm = min(GEMM_GROUP_M, tiles_m - b * GEMM_GROUP_M);
+    tm = b * GEMM_GROUP_M + r % gm;
+    tn = r / gm;
+    return true;
+}
+
+// Persistent kernel: gridDim.x (a multiple of 8) workgroups each walk a strided
+// share of their XCD's tile sequence.  The first K tile of the next output tile
+// is prefetched during the last K tile of the current one and the epilogue's
+// stores are left in flight, so neither the load latency at the head of a tile
+// nor the store traffic at its tail stalls the matrix cores.
+template <int TM, int TN, int WM, int WN, bool KGUARD>
+__global__ void __launch_bounds__(64 * WM * WN)
+k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
+            float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
+            int tiles_n) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    constexpr int A_CHUNKS = BM * 8 / NT, B_CHUNKS = BN * 8 / NT;  // 16-byte chunks per thread per K tile
+    constexpr int ROWS_PER_PASS = NT / 8;
+    constexpr int TILE_ELEMS = (BM + BN) * GEMM_BK;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // 2 x [A tile | B tile]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int xcd = blockIdx.x % GEMM_XCDS, jstride = gridDim.x / GEMM_XCDS;
+    int idx = blockIdx.x / GEMM_XCDS;
+    int tile_m, tile_n;
+    if (!gemm_tile_of(xcd, idx, tiles_m, tiles_n, tile_m, tile_n)) return;
+
+    floatx16 acc[TM][TN];
+
+    // chunk (row, kc) this thread moves per pass, and where it lands in an LDS buffer
+    const int kc = (tid & 7), crow = tid >> 3;
+    int la[A_CHUNKS], lb[B_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+        int row = crow + ROWS_PER_PASS * i;
+        la[i] = row * GEMM_BK + ((kc ^ ((row >> 1) & 7)) * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+        int row = crow + ROWS_PER_PASS * i;
+        lb[i] = BM * GEMM_BK + row * GEMM_BK + ((kc ^ ((row >> 1) & 7)) * 8);
+    }
+    // global sources of the current tile (rows clamped, so reads stay in bounds)
+    const bf16_t *ga[A_CHUNKS], *gb[B_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i)
+        ga[i] = A + (long)min(tile_m * BM + crow + ROWS_PER_PASS * i, M - 1) * K + kc * 8;
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i)
+        gb[i] = B + (long)min(tile_n * BN + crow + ROWS_PER_PASS * i, N - 1) * K + kc * 8;
+
+    // fragment addresses: lane reads row (lane & 31) of a 32-row block, K chunk 2*kk + (lane >> 5)
+    const int frow = lane & 31, fsel = lane >> 5;
+    int fa[TM], fb[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i] = (wm * 32 * TM + i * 32 + frow) * GEMM_BK;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[j] = BM * GEMM_BK + (wn * 32 * TN + j * 32 + frow) * GEMM_BK;
+    const int fsw = (frow >> 1) & 7;
+
+    const int ktiles = (K + GEMM_BK - 1) / GEMM_BK;
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+    // prologue: K tile 0 of the first tile -> LDS buffer 0
+    {
+        const bool in = !KGUARD || (kc * 8 < K);
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) ra[i] = in ? *reinterpret_cast<const uint4 *>(ga[i]) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) rb[i] = in ? *reinterpret_cast<const uint4 *>(gb[i]) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<uint4 *>(smem + la[i]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<uint4 *>(smem + lb[i]) = rb[i];
+    }
+    __syncthreads();
+    int buf = 0;
+    for (;;) {
+        // accumulators start from the bias: a lane's column is the same for all 16 of its entries
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = tile_n * BN + wn * 32 * TN + j * 32 + (lane & 31);
+            const float bv = (bias && col < N) ? bias[col] : 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = bv;
+        }
+        // the tile after this one (if any): its first K tile is prefetched at the end of this one
+        int next_m, next_n;
+        const bool have_next = gemm_tile_of(xcd, idx + jstride, tiles_m, tiles_n, next_m, next_n);
+        const bf16_t *gan[A_CHUNKS], *gbn[B_CHUNKS];
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i)
+            gan[i] = have_next ? A + (long)min(next_m * BM + crow + ROWS_PER_PASS * i, M - 1) * K + kc * 8 : ga[i];
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i)
+            gbn[i] = have_next ? B + (long)min(next_n * BN + crow + ROWS_PER_PASS * i, N - 1) * K + kc * 8 : gb[i];
+
+        for (int kt = 0; kt < ktiles; ++kt) {
+            const bf16_t *cur = smem + buf * TILE_ELEMS;
+            bf16_t *nxt = smem + (buf ^ 1) * TILE_ELEMS;
+            const bool last = kt + 1 == ktiles;
+            const int kn = last ? 0 : (kt + 1) * GEMM_BK;
+            const bool in = !KGUARD || (kn + kc * 8 < K);
+#pragma unroll
+            for (int i = 0; i < A_CHUNKS; ++i) {
+                const bf16_t *src = (last ? gan[i] : ga[i]) + kn;
+                ra[i] = in ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < B_CHUNKS; ++i) {
+                const bf16_t *src = (last ? gbn[i] : gb[i]) + kn;
+                rb[i] = in ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
+            }
+            // keep the prefetch ahead of the multiply: without this fence the compiler sinks the
+            // loads down to their first use (the LDS stores below) and exposes their latency
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
+                bf16x8 af[TM], bfr[TN];
+                const int cpos = ((kk * 2 + fsel) ^ fsw) * 8;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(cur + fa[i] + cpos);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8 *>(cur + fb[j] + cpos);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            }
+            // the other buffer was last read one iteration ago, which every wave has left
+#pragma unroll
+            for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<uint4 *>(nxt + la[i]) = ra[i];
+#pragma unroll
+            for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<uint4 *>(nxt + lb[i]) = rb[i];
+            __syncthreads();
+            buf ^= 1;
+        }
+
+        // epilogue: lane holds column (lane & 31); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4
+        const int m0 = tile_m * BM, n0 = tile_n * BN;
+        if (out_row == nullptr && m0 + BM <= M && n0 + BN <= N) {
+            // interior tile: address = uniform row base (scalar registers) + one per-lane offset
+            // + a constant, so a store costs no vector address arithmetic
+            const unsigned offl = (unsigned)(wm * 32 * TM + (lane >> 5) * 4) * (unsigned)ldc +
+                                  (unsigned)(wn * 32 * TN + (lane & 31));
+            float *tb = C + (long)m0 * ldc + n0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float *tr = tb + (long)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc;   // uniform
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) tr[offl + j * 32] = acc[i][j][r];
+                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    int col = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int row = m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                        if (row < M && col < N) {
+                            long orow = out_row ? out_row[row] : row;
+                            C[orow * ldc + col] = acc[i][j][r];
+                        }
+                    }
+                }
+        }
+        if (!have_next) break;
+        idx += jstride;
+        tile_m = next_m;
+        tile_n = next_n;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) ga[i] = gan[i];
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) gb[i] = gbn[i];
+    }
+}
+
+template <int TM, int TN, int WM, int WN, int OCC>
+static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
+                              int N, int K, const int *out_row, long ldc) {
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const size_t shm = 2u * (BM + BN) * GEMM_BK * sizeof(bf16_t);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<TM, TN, WM, WN, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<TM, TN, WM, WN, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    // one wave of resident workgroups (256 CUs x OCC), a multiple of the 8 XCDs, no more than the tiles
+    const long total = (long)tiles_m * tiles_n;
+    long g = ((total + GEMM_XCDS - 1) / GEMM_XCDS) * GEMM_XCDS;
+    if (g > 256L * OCC) g = 256L * OCC;
+    const dim3 grid((unsigned)g), block(64 * WM * WN);
+    if (K % GEMM_BK == 0)
+        hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, false>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
+                           ldc, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, true>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
+                           ldc, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+// variant: 0 = choose by size; others force a tile shape (for tuning runs)
+int g_tbs_gemm_variant = 0;
+
+hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
+                            int N, int K, const int *out_row, long ldc) {
+    if (M <= 0) return hipSuccess;
+    int v = g_tbs_gemm_variant;
+    if (v == 0) {
+        // measured on MI355X: 256x256 tiles (8 waves) once they fill the chip 1.5 times over,
+        // 128x128 (two workgroups per CU) for mid sizes, 64x64 so that small problems still spread
+        long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+        long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+        v = t256 >= 384 ? 5 : (t128 >= 256 ? 2 : 1);
+    }
+    switch (v) {
+        case 1: return gemm_launch<1, 1, 2, 2, 4>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 64x64, 4 waves
+        case 2: return gemm_launch<2, 2, 2, 2, 2>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 128x128, 4 waves
+        case 3: return gemm_launch<2, 2, 4, 2, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x128, 8 waves
+        case 4: return gemm_launch<4, 4, 2, 2, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 4 waves
+        case 5: return gemm_launch<2, 4, 4, 2, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 8 waves
+        case 6: return gemm_launch<4, 2, 2, 4, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 8 waves
+        case 7: return gemm_launch<2, 2, 2, 4, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 128x256, 8 waves
+        default: return gemm_launch<2, 2, 4, 4, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);  // 256x256, 16 waves
+    }
+}

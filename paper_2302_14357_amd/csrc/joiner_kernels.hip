@@ -119,120 +119,3 @@ hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const
                        out_row, ldc);
     return hipGetLastError();
 }
-
-// ------------------------------------------------------------------ bf16 MFMA GEMM
-// C[M,N] = A[M,K] * B[N,K]^T + bias, bf16 inputs, fp32 accumulate and output.
-// Workgroup = 4 waves in a 2x2 grid; each wave owns TM x TN blocks of 32x32
-// computed with v_mfma_f32_32x32x16_bf16.  K is consumed in tiles of 64 held in
-// LDS (rows padded by 8 elements to spread banks); the next tile is fetched into
-// registers while the current one is multiplied.
-#define GEMM_BK 64
-#define GEMM_LDS_STRIDE (GEMM_BK + 8)
-
-template <int TM, int TN>
-__global__ void __launch_bounds__(256)
-k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
-            float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;  // 16-byte chunks per thread
-    __shared__ __attribute__((aligned(16))) bf16_t sA[BM * GEMM_LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) bf16_t sB[BN * GEMM_LDS_STRIDE];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-    auto fetch = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
-            int gm = min(m0 + row, M - 1);
-            ra[i] = (k0 + kc < K) ? *reinterpret_cast<const uint4 *>(A + (long)gm * K + k0 + kc)
-                                  : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
-            int gn = min(n0 + row, N - 1);
-            rb[i] = (k0 + kc < K) ? *reinterpret_cast<const uint4 *>(B + (long)gn * K + k0 + kc)
-                                  : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
-            *reinterpret_cast<uint4 *>(sA + row * GEMM_LDS_STRIDE + kc) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = (c & 7) * 8;
-            *reinterpret_cast<uint4 *>(sB + row * GEMM_LDS_STRIDE + kc) = rb[i];
-        }
-    };
-
-    fetch(0);
-    for (int k0 = 0; k0 < K; k0 += GEMM_BK) {
-        stage();
-        __syncthreads();
-        if (k0 + GEMM_BK < K) fetch(k0 + GEMM_BK);
-#pragma unroll
-        for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
-            bf16x8 af[TM], bfr[TN];
-            const int koff = kk * 16 + (lane >> 5) * 8;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(
-                    sA + (wm * 32 * TM + i * 32 + (lane & 31)) * GEMM_LDS_STRIDE + koff);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(
-                    sB + (wn * 32 * TN + j * 32 + (lane & 31)) * GEMM_LDS_STRIDE + koff);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        __syncthreads();
-    }
-
-    // epilogue: lane holds column (lane%32); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int col = n0 + wn * 32 * TN + j * 32 + (lane & 31);
-            float bv = (bias && col < N) ? bias[col] : 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                if (row < M && col < N) {
-                    long orow = out_row ? out_row[row] : row;
-                    C[orow * ldc + col] = acc[i][j][r] + bv;
-                }
-            }
-        }
-}
-
-hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc) {
-    if (M <= 0) return hipSuccess;
-    // small problems take the 64x64 tile so that the grid still covers the chip
-    long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (tiles128 >= 256)
-        hipLaunchKernelGGL((k_gemm_bf16<2, 2>), dim3((N + 127) / 128, (M + 127) / 128), dim3(256), 0, st, A, B, bias,
-                           C, M, N, K, out_row, ldc);
-    else
-        hipLaunchKernelGGL((k_gemm_bf16<1, 1>), dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, A, B, bias, C,
-                           M, N, K, out_row, ldc);
-    return hipGetLastError();
-}

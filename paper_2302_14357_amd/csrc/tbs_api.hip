@@ -12,6 +12,8 @@
 
 #include "tbs_internal.h"
 
+extern int g_tbs_gemm_variant;
+
 namespace {
 
 enum State { ST_INIT = 0, ST_BEGUN, ST_READY, ST_JOINED, ST_EXPANDED, ST_SELECTED };
@@ -696,8 +698,11 @@ int tbs_profile_read(tbs_ctx *c, int64_t *launches, double *total_ms, int64_t *u
 int tbs_gemm_bf16(const void *A, const void *B, const float *bias, float *C, int32_t M, int32_t N, int32_t K,
                   void *stream) {
     if (!A || !B || !C || M < 1 || N < 1 || K < 8 || K % 8) return TBS_EINVAL;
+    if (const char *v = getenv("TBS_GEMM_VARIANT")) g_tbs_gemm_variant = atoi(v);
+    long ldc = N;
+    if (getenv("TBS_GEMM_LDC0")) ldc = 0;   // tuning only: every row lands on row 0 (no store traffic)
     hipError_t e = launch_gemm_bf16((hipStream_t)stream, (const bf16_t *)A, (const bf16_t *)B, bias, C, M, N, K,
-                                    nullptr, N);
+                                    nullptr, ldc);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 
