@@ -153,11 +153,218 @@ k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *_
     }
 }
 
+// ------------------------------------------------------------------ register-resident variant
+// When the S' x V logits of one hypothesis fit in the registers of one workgroup
+// (V <= 1024 NV4 columns, S' <= SMAX), every logit is read from memory exactly
+// once and exponentiated exactly once: each thread keeps e = exp(l - m_loc) of
+// its own columns with its own row maximum m_loc, the (max, sum) pairs are
+// merged across the workgroup in one step, and the streaming sum of Eq. 4-6
+// becomes delta_nb[k] = sum_t (c_t exp(m_loc_t - m_t)) e[t][k].  The N best
+// are then taken per wave from registers and merged by the first wave.
+template <int NV4, int SMAX>
+__global__ void __launch_bounds__(EXP_THREADS)
+k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
+             float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
+             float *__restrict__ row_stats, float *__restrict__ delta_nb) {
+    constexpr int NC = NV4 * 4;  // columns per thread
+    __shared__ float s_pm[EXP_WAVES][SMAX], s_pz[EXP_WAVES][SMAX];
+    __shared__ float s_blank[SMAX];
+    __shared__ float s_cv[EXP_WAVES][TBS_MAX_BEAM];
+    __shared__ int s_ck[EXP_WAVES][TBS_MAX_BEAM];
+    const int pair = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int u = rv.pair_u[pair], h = rv.pair_h[pair];
+    const int row0 = rv.pair_row0[pair], sp = rv.pair_len[pair];
+    const int V = d.V, V4 = V >> 2;
+    const float4 *L4 = reinterpret_cast<const float4 *>(logits + (long)row0 * V);
+
+    // ---- one pass over memory: this thread's columns of every row
+    float e[SMAX][NC];
+    float mloc[SMAX], zloc[SMAX];
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) {
+        mloc[t] = -INFINITY;
+        zloc[t] = 0.f;
+        if (t < sp) {
+#pragma unroll
+            for (int q = 0; q < NV4; ++q) {
+                const int i4 = tid + EXP_THREADS * q;
+                float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                if (i4 < V4) x = L4[(long)t * V4 + i4];
+                e[t][4 * q + 0] = x.x; e[t][4 * q + 1] = x.y; e[t][4 * q + 2] = x.z; e[t][4 * q + 3] = x.w;
+                mloc[t] = fmaxf(mloc[t], fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w)));
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) e[t][c] = -INFINITY;
+        }
+    }
+    // the thread that owns the blank column publishes its raw logits
+    {
+        const int bq = (d.blank >> 2) / EXP_THREADS, bt = (d.blank >> 2) % EXP_THREADS, bc = d.blank & 3;
+        if (tid == bt) {
+#pragma unroll
+            for (int t = 0; t < SMAX; ++t)
+#pragma unroll
+                for (int q = 0; q < NV4; ++q)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (q == bq && c == bc) s_blank[t] = e[t][4 * q + c];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) {
+        const float mref = mloc[t] == -INFINITY ? 0.f : mloc[t];   // a thread (or row) with no columns
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            e[t][c] = __expf(e[t][c] - mref);
+            zloc[t] += e[t][c];
+        }
+    }
+    // ---- (max, sum) of every row across the workgroup
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) {
+        float m = mloc[t], z = zloc[t];
+        for (int off = 32; off > 0; off >>= 1) {
+            float m2 = __shfl_xor(m, off), z2 = __shfl_xor(z, off);
+            ms_combine(m, z, m2, z2);
+        }
+        if (lane == 0) { s_pm[wave][t] = m; s_pz[wave][t] = z; }
+    }
+    __syncthreads();
+    // ---- every thread: row statistics, forward variable (Eq. 3 as a scan), Eq. 7, its own coefficients
+    float cf[SMAX];
+    {
+        const float *dold = A.dhat + ((long)u * d.N + h) * d.S;
+        float alpha = 0.f, bprev = 0.f;
+#pragma unroll
+        for (int t = 0; t < SMAX; ++t) {
+            cf[t] = 0.f;
+            if (t < sp) {
+                float m = s_pm[0][t], z = s_pz[0][t];
+#pragma unroll
+                for (int w = 1; w < EXP_WAVES; ++w) ms_combine(m, z, s_pm[w][t], s_pz[w][t]);
+                const float b = __expf(s_blank[t] - m) / z;
+                alpha = (t == 0 ? 0.f : alpha * bprev) + dold[t];
+                bprev = b;
+                const float c = alpha / z;
+                cf[t] = mloc[t] == -INFINITY ? 0.f : c * __expf(mloc[t] - m);
+                if (tid == 0) {
+                    row_lc[row0 + t] = c > 0.f ? __logf(c) - m : -INFINITY;
+                    if (row_stats) {
+                        row_stats[(long)(row0 + t) * 3 + 0] = m;
+                        row_stats[(long)(row0 + t) * 3 + 1] = z;
+                        row_stats[(long)(row0 + t) * 3 + 2] = b;
+                    }
+                    if (t == sp - 1) dphi[pair] = alpha * b;
+                }
+            }
+        }
+    }
+    // ---- Eq. 4-6 from registers
+    float v[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < SMAX; ++t) acc += cf[t] * e[t][c];
+        v[c] = acc;
+    }
+    // blank is not a non-blank expansion; columns past V do not exist
+#pragma unroll
+    for (int q = 0; q < NV4; ++q)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int col = 4 * (tid + EXP_THREADS * q) + c;
+            if (col == d.blank || col >= V) v[4 * q + c] = 0.f;
+        }
+    if (delta_nb) {
+#pragma unroll
+        for (int q = 0; q < NV4; ++q) {
+            const int i4 = tid + EXP_THREADS * q;
+            if (i4 < V4)
+                reinterpret_cast<float4 *>(delta_nb + (long)pair * V)[i4] =
+                    make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+        }
+    }
+    // ---- N best of this wave's columns: N rounds of wave arg-max over registers
+    for (int n = 0; n < d.N; ++n) {
+        float bv = 0.f;      // only strictly positive scores are candidates
+        int bk = 0x7fffffff;
+#pragma unroll
+        for (int q = 0; q < NV4; ++q)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float x = v[4 * q + c];
+                if (x > bv) { bv = x; bk = 4 * (tid + EXP_THREADS * q) + c; }   // ascending columns: smallest wins ties
+            }
+        for (int off = 32; off > 0; off >>= 1) {
+            float ov = __shfl_xor(bv, off);
+            int ok = __shfl_xor(bk, off);
+            if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
+        }
+        if (lane == 0) { s_cv[wave][n] = bv; s_ck[wave][n] = bk; }
+#pragma unroll
+        for (int q = 0; q < NV4; ++q)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (4 * (tid + EXP_THREADS * q) + c == bk) v[4 * q + c] = -1.f;
+    }
+    __syncthreads();
+    // ---- merge the EXP_WAVES x N wave candidates (first wave)
+    if (wave == 0) {
+        const int nc = EXP_WAVES * d.N;   // at most 128: two per lane
+        float c0 = -1.f, c1 = -1.f;
+        int k0 = 0x7fffffff, k1 = 0x7fffffff;
+        if (lane < nc) { c0 = s_cv[lane / d.N][lane % d.N]; k0 = s_ck[lane / d.N][lane % d.N]; }
+        if (lane + 64 < nc) { c1 = s_cv[(lane + 64) / d.N][(lane + 64) % d.N]; k1 = s_ck[(lane + 64) / d.N][(lane + 64) % d.N]; }
+        for (int n = 0; n < d.N; ++n) {
+            float bv = c0;
+            int bk = k0;
+            if (c1 > bv || (c1 == bv && k1 < bk)) { bv = c1; bk = k1; }
+            for (int off = 32; off > 0; off >>= 1) {
+                float ov = __shfl_xor(bv, off);
+                int ok = __shfl_xor(bk, off);
+                if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
+            }
+            if (lane == 0) {
+                const bool ok = bv > 0.f && bk != 0x7fffffff;
+                cand_score[(long)pair * d.N + n] = ok ? __logf(bv) : -INFINITY;
+                cand_tok[(long)pair * d.N + n] = ok ? bk : -1;
+            }
+            if (k0 == bk) { c0 = -1.f; k0 = 0x7fffffff; }
+            if (k1 == bk) { c1 = -1.f; k1 = 0x7fffffff; }
+        }
+    }
+}
+
+template <int NV4, int SMAX>
+static void expand_reg_launch(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
+                              float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
+                              float *delta_nb) {
+    hipLaunchKernelGGL((k_expand_reg<NV4, SMAX>), dim3(pairs), dim3(EXP_THREADS), 0, st, d, logits, A, rv, row_lc, dphi,
+                       cand_score, cand_tok, row_stats, delta_nb);
+}
+
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
-                         float *delta_nb) {
+                         float *delta_nb, int force_generic) {
     if (pairs <= 0) return hipSuccess;
     size_t shm = (size_t)d.V * sizeof(float);
+    if (d.V % 4 == 0 && !force_generic) {
+#define TBS_EXPAND_REG(NV4, SMAX)                                                                              \
+    {                                                                                                          \
+        expand_reg_launch<NV4, SMAX>(st, d, pairs, logits, A, rv, row_lc, dphi, cand_score, cand_tok, row_stats, \
+                                     delta_nb);                                                                \
+        return hipGetLastError();                                                                              \
+    }
+        const int nv4 = (d.V / 4 + EXP_THREADS - 1) / EXP_THREADS;
+        if (nv4 <= 1 && d.S <= 4) TBS_EXPAND_REG(1, 4)
+        if (nv4 <= 1 && d.S <= 16) TBS_EXPAND_REG(1, 16)
+        if (nv4 <= 2 && d.S <= 8) TBS_EXPAND_REG(2, 8)
+        if (nv4 <= 4 && d.S <= 3) TBS_EXPAND_REG(4, 3)
+        if (nv4 <= 4 && d.S <= 5) TBS_EXPAND_REG(4, 5)
+#undef TBS_EXPAND_REG
+    }
     if (d.V % 4 == 0)
         hipLaunchKernelGGL(k_expand<true>, dim3(pairs), dim3(EXP_THREADS), shm, st, d, logits, A, rv, row_lc, dphi,
                            cand_score, cand_tok, row_stats, delta_nb);

@@ -272,7 +272,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->cand_tok, UN * d.N);
     c->row_stats = nullptr;
     c->delta_nb = nullptr;
-    if (cfg->debug) {
+    if (cfg->debug & 1) {
         rc |= dev_alloc(c, &c->row_stats, (size_t)M * 3);
         rc |= dev_alloc(c, &c->delta_nb, (size_t)UN * d.V);
     }
@@ -421,7 +421,7 @@ int tbs_expand(tbs_ctx *c) {
     {
         ProfScope ps(c, TBS_K_EXPAND, c->h_counts[TBS_CNT_ROWS]);
         HIPCHK(c, launch_expand(c->stream, c->cur, pairs, c->logits, c->A[c->a_cur], c->rv, c->row_lc, c->dphi,
-                                c->cand_score, c->cand_tok, c->row_stats, c->delta_nb));
+                                c->cand_score, c->cand_tok, c->row_stats, c->delta_nb, (c->cfg.debug & 2) != 0));
     }
     c->state = ST_EXPANDED;
     return TBS_OK;

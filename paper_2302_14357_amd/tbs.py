@@ -111,7 +111,7 @@ class Tbs:
 
     def __init__(self, model: dict, *, blank_id: int, beam_n: int, seg_s: int, max_utts: int,
                  max_frames_total: int, dtype: str = "bf16", act: str = "tanh", max_rounds_per_segment: int = 0,
-                 rounds_capacity: int = 0, max_nodes: int = 0, debug: bool = False, device: int = 0,
+                 rounds_capacity: int = 0, max_nodes: int = 0, debug: int = 0, device: int = 0,
                  stream=None):
         import torch
         self.torch = torch
@@ -148,7 +148,7 @@ class Tbs:
         self.stream = stream if stream is not None else torch.cuda.Stream(self.device)
         cfg = _Config(Dj, V, blank_id, beam_n, seg_s, max_utts, max_frames_total, L_, H, E,
                       {"tanh": 0, "relu": 1}[act], 1 if dtype == "bf16" else 0, max_rounds_per_segment,
-                      rounds_capacity, max_nodes, 1 if debug else 0, device, self.stream.cuda_stream)
+                      rounds_capacity, max_nodes, int(debug), device, self.stream.cuda_stream)
         torch.cuda.synchronize(self.device)
         self.ctx = C.c_void_p()
         _check(self.L.tbs_init(C.byref(cfg), C.byref(w), C.byref(self.ctx)))

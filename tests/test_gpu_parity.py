@@ -59,10 +59,10 @@ def _teacher_forced_state(rng, U, N, S, Dj):
     return counts, pred, dhat, logs
 
 
-def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3):
+def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, generic=False):
     model, offsets, enc = build_case(shape, n_utts=U)
     W = oracle_weights(shape, model)
-    tbs = make_tbs(shape, model, offsets, N, S, debug=True)
+    tbs = make_tbs(shape, model, offsets, N, S, debug=3 if generic else 1)
     enc_dev = tbs.upload_frames(enc)
     rng = np.random.default_rng(11)
     counts, pred, dhat, logs = _teacher_forced_state(rng, U, N, S, shape.d_joint)
@@ -125,10 +125,19 @@ def test_joiner_expand_tiny_fp32():
     _check_joiner_expand(SHAPES["tiny"], U=1, N=2, S=3, seg=16, tol=1e-4)  # ragged last segment (2 frames)
 
 
-@pytest.mark.parametrize("N,S", [(5, 3), (2, 1), (10, 5), (3, 50)])
-def test_joiner_expand_small_bf16(N, S):
+@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("N,S", [(5, 3), (2, 1), (10, 5), (3, 50), (4, 12), (32, 2)])
+def test_joiner_expand_small_bf16(N, S, generic):
+    """Both expansion kernels (register-resident and generic streaming) on every shape."""
     shape = small_bf16_shape(n_utts=5, vocab=200, d=128, hidden=64)
-    _check_joiner_expand(shape, U=5, N=N, S=S, seg=1 if S < 20 else 0)
+    _check_joiner_expand(shape, U=5, N=N, S=S, seg=1 if S < 20 else 0, generic=generic)
+
+
+@pytest.mark.parametrize("V,N,S", [(2048, 8, 7), (1028, 3, 2), (4096, 10, 5), (3000, 4, 3)])
+def test_joiner_expand_wide_vocab(V, N, S):
+    """Vocabulary widths that exercise every register-kernel instantiation and a ragged last column block."""
+    shape = small_bf16_shape(n_utts=4, vocab=V, d=64, hidden=64)
+    _check_joiner_expand(shape, U=4, N=N, S=S, seg=1, sample_pairs=6)
 
 
 def test_joiner_expand_odd_vocab():
@@ -145,6 +154,7 @@ def test_joiner_expand_librispeech_full_size_sampled():
 def test_joiner_expand_assistant_full_width_sampled():
     """Large-assistant widths (V=4096, Dj=1024, N=10, S=3) with a multi-tile row count."""
     _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=6)
+    _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=4, generic=True)
 
 
 # ------------------------------------------------------------------ whole decode
@@ -203,7 +213,7 @@ def test_decode_step_by_step_matches_oracle_trace():
         merges += before + len(r.a_tokens) - len(r.b_tokens)
         prev[r.seg] = len(r.b_tokens)
     assert merges > 0
-    tbs = make_tbs(shape, model, offsets, N, S, debug=True)
+    tbs = make_tbs(shape, model, offsets, N, S, debug=1)
     tbs.begin(tbs.upload_frames(enc), offsets)
     it = iter(ref.rounds)
     nseg = (T + S - 1) // S
