@@ -17,6 +17,7 @@
 
 #define EXP_THREADS 256
 #define EXP_WAVES (EXP_THREADS / 64)
+#define EXP_CAND_CAP 64   // candidates one wave may hand to the merge (>= TBS_MAX_BEAM)
 
 __device__ __forceinline__ void ms_combine(float &m, float &z, float m2, float z2) {
     float mn = fmaxf(m, m2);
@@ -169,8 +170,9 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
     constexpr int NC = NV4 * 4;  // columns per thread
     __shared__ float s_pm[EXP_WAVES][SMAX], s_pz[EXP_WAVES][SMAX];
     __shared__ float s_blank[SMAX];
-    __shared__ float s_cv[EXP_WAVES][TBS_MAX_BEAM];
-    __shared__ int s_ck[EXP_WAVES][TBS_MAX_BEAM];
+    __shared__ float s_cv[EXP_WAVES][EXP_CAND_CAP];
+    __shared__ int s_ck[EXP_WAVES][EXP_CAND_CAP];
+    __shared__ int s_cn[EXP_WAVES];
     const int pair = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int u = rv.pair_u[pair], h = rv.pair_h[pair];
     const int row0 = rv.pair_row0[pair], sp = rv.pair_len[pair];
@@ -214,9 +216,10 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) {
         const float mref = mloc[t] == -INFINITY ? 0.f : mloc[t];   // a thread (or row) with no columns
+        const float nm = -mref * 1.44269504088896341f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            e[t][c] = __expf(e[t][c] - mref);
+            e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));   // exp(l - m_loc)
             zloc[t] += e[t][c];
         }
     }
@@ -286,41 +289,98 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
                     make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
         }
     }
-    // ---- N best of this wave's columns: N rounds of wave arg-max over registers
-    for (int n = 0; n < d.N; ++n) {
-        float bv = 0.f;      // only strictly positive scores are candidates
-        int bk = 0x7fffffff;
+    // ---- candidates of this wave.  tau = the N-th largest of the 64 per-thread maxima is a lower
+    // bound of the wave's N-th largest score, so every score >= tau is a candidate (ties included)
+    // and usually only a few more than N qualify.  The maxima are ranked with a bitonic network.
+    float lmax = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) lmax = fmaxf(lmax, v[c]);
+    float sv = lmax;
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1)
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const float o = __shfl_xor(sv, j);
+            const bool desc = (lane & k) == 0, lower = (lane & j) == 0;
+            sv = (lower == desc) ? fmaxf(sv, o) : fminf(sv, o);
+        }
+    const float tau = __shfl(sv, d.N - 1);
+    int cnt = 0;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) cnt += (v[c] > 0.f && v[c] >= tau) ? 1 : 0;
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    const int total = __shfl(incl, 63);
+    if (total <= EXP_CAND_CAP) {
+        int pos = incl - cnt;
 #pragma unroll
         for (int q = 0; q < NV4; ++q)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const float x = v[4 * q + c];
-                if (x > bv) { bv = x; bk = 4 * (tid + EXP_THREADS * q) + c; }   // ascending columns: smallest wins ties
+                if (x > 0.f && x >= tau) {
+                    s_cv[wave][pos] = x;
+                    s_ck[wave][pos] = 4 * (tid + EXP_THREADS * q) + c;
+                    ++pos;
+                }
             }
-        for (int off = 32; off > 0; off >>= 1) {
-            float ov = __shfl_xor(bv, off);
-            int ok = __shfl_xor(bk, off);
-            if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
+        if (lane == 0) s_cn[wave] = total;
+    } else {
+        // many equal scores: take exactly the N best by N rounds of wave arg-max
+        for (int n = 0; n < d.N; ++n) {
+            float bv = 0.f;
+            int bk = 0x7fffffff;
+#pragma unroll
+            for (int q = 0; q < NV4; ++q)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float x = v[4 * q + c];
+                    if (x > bv) { bv = x; bk = 4 * (tid + EXP_THREADS * q) + c; }
+                }
+            for (int off = 32; off > 0; off >>= 1) {
+                float ov = __shfl_xor(bv, off);
+                int ok = __shfl_xor(bk, off);
+                if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
+            }
+            if (lane == 0) { s_cv[wave][n] = bv; s_ck[wave][n] = bk; }
+#pragma unroll
+            for (int q = 0; q < NV4; ++q)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (4 * (tid + EXP_THREADS * q) + c == bk) v[4 * q + c] = -1.f;
         }
-        if (lane == 0) { s_cv[wave][n] = bv; s_ck[wave][n] = bk; }
-#pragma unroll
-        for (int q = 0; q < NV4; ++q)
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (4 * (tid + EXP_THREADS * q) + c == bk) v[4 * q + c] = -1.f;
+        if (lane == 0) s_cn[wave] = d.N;
     }
     __syncthreads();
-    // ---- merge the EXP_WAVES x N wave candidates (first wave)
+    // ---- merge the waves' candidate lists (first wave): N rounds of arg-max, larger score first,
+    // smaller token on equal scores
     if (wave == 0) {
-        const int nc = EXP_WAVES * d.N;   // at most 128: two per lane
-        float c0 = -1.f, c1 = -1.f;
-        int k0 = 0x7fffffff, k1 = 0x7fffffff;
-        if (lane < nc) { c0 = s_cv[lane / d.N][lane % d.N]; k0 = s_ck[lane / d.N][lane % d.N]; }
-        if (lane + 64 < nc) { c1 = s_cv[(lane + 64) / d.N][(lane + 64) % d.N]; k1 = s_ck[(lane + 64) / d.N][(lane + 64) % d.N]; }
+        float cv[EXP_WAVES];
+        int ck[EXP_WAVES];
+        int base = 0;
+#pragma unroll
+        for (int i = 0; i < EXP_WAVES; ++i) { cv[i] = -1.f; ck[i] = 0x7fffffff; }
+#pragma unroll
+        for (int w = 0; w < EXP_WAVES; ++w) {
+            const int n_w = s_cn[w];
+            // entry e of list w has global index base+e; lane takes indices lane, lane+64, ...
+#pragma unroll
+            for (int i = 0; i < EXP_WAVES; ++i) {
+                const int e = lane + 64 * i - base;
+                if (e >= 0 && e < n_w) { cv[i] = s_cv[w][e]; ck[i] = s_ck[w][e]; }
+            }
+            base += n_w;
+        }
         for (int n = 0; n < d.N; ++n) {
-            float bv = c0;
-            int bk = k0;
-            if (c1 > bv || (c1 == bv && k1 < bk)) { bv = c1; bk = k1; }
+            float bv = -1.f;
+            int bk = 0x7fffffff;
+#pragma unroll
+            for (int i = 0; i < EXP_WAVES; ++i)
+                if (cv[i] > bv || (cv[i] == bv && ck[i] < bk)) { bv = cv[i]; bk = ck[i]; }
             for (int off = 32; off > 0; off >>= 1) {
                 float ov = __shfl_xor(bv, off);
                 int ok = __shfl_xor(bk, off);
@@ -331,8 +391,9 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
                 cand_score[(long)pair * d.N + n] = ok ? __logf(bv) : -INFINITY;
                 cand_tok[(long)pair * d.N + n] = ok ? bk : -1;
             }
-            if (k0 == bk) { c0 = -1.f; k0 = 0x7fffffff; }
-            if (k1 == bk) { c1 = -1.f; k1 = 0x7fffffff; }
+#pragma unroll
+            for (int i = 0; i < EXP_WAVES; ++i)
+                if (ck[i] == bk) { cv[i] = -1.f; ck[i] = 0x7fffffff; }
         }
     }
 }

@@ -59,8 +59,11 @@ def _teacher_forced_state(rng, U, N, S, Dj):
     return counts, pred, dhat, logs
 
 
-def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, generic=False):
+def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, generic=False, flat=False):
     model, offsets, enc = build_case(shape, n_utts=U)
+    if flat:   # every logit equal: every expansion ties, the smallest tokens must win
+        model["w_out"] = np.zeros_like(model["w_out"])
+        model["b_out"] = np.zeros_like(model["b_out"])
     W = oracle_weights(shape, model)
     tbs = make_tbs(shape, model, offsets, N, S, debug=3 if generic else 1)
     enc_dev = tbs.upload_frames(enc)
@@ -113,6 +116,8 @@ def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, gener
         margin = math.log(ref_nb[order[n_take - 1]]) - math.log(ref_nb[order[n_take]]) if n_take < shape.vocab - 1 else 1.0
         if margin > 2 * tol:
             assert set(ct[j][:n_take].tolist()) == set(order[:n_take].tolist())
+        if flat:
+            assert ct[j][:n_take].tolist() == list(range(1, n_take + 1))
         got_sorted = cs[j][:n_take]
         assert np.all(np.diff(got_sorted) <= 0)
         np.testing.assert_allclose(got_sorted, np.log(ref_nb[ct[j][:n_take]]), rtol=0, atol=tol)
@@ -138,6 +143,14 @@ def test_joiner_expand_wide_vocab(V, N, S):
     """Vocabulary widths that exercise every register-kernel instantiation and a ragged last column block."""
     shape = small_bf16_shape(n_utts=4, vocab=V, d=64, hidden=64)
     _check_joiner_expand(shape, U=4, N=N, S=S, seg=1, sample_pairs=6)
+
+
+@pytest.mark.parametrize("generic", [False, True])
+def test_expand_all_scores_equal(generic):
+    """Degenerate input: every expansion of a hypothesis has the same score (exercises the
+    tie order and the selection path taken when too many candidates reach the threshold)."""
+    shape = small_bf16_shape(n_utts=3, vocab=1024, d=64, hidden=64)
+    _check_joiner_expand(shape, U=3, N=6, S=3, seg=0, generic=generic, flat=True)
 
 
 def test_joiner_expand_odd_vocab():
