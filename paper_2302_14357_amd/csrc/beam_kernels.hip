@@ -33,6 +33,9 @@ __device__ bool same_sequence(const int2 *nodes, int a, int b) {
     return true;
 }
 
+__device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes, int *host_counts);
+__device__ bool last_workgroup(const RowView &rv, int n_groups);
+
 // ------------------------------------------------------------------ batch init
 __global__ void k_init_batch(Dims d, BView B, AView A0, AView A1, RowView rv, int2 *nodes, float *pool_p,
                              float *pool_h, float *pool_c, const float *pred_init, long pool_rows) {
@@ -60,6 +63,8 @@ __global__ void k_init_batch(Dims d, BView B, AView A0, AView A1, RowView rv, in
             rv.counts[TBS_CNT_ERR] = 0;
             rv.counts[TBS_CNT_UTTS] = 0;
             rv.counts[TBS_CNT_FRAMES] = 0;
+            rv.counts[TBS_CNT_TICKET] = 0;
+            rv.counts[TBS_CNT_NODE_BASE] = 1;
         }
     }
     for (int j = tid; j < d.Dj; j += blockDim.x) pool_p[(long)slot * d.Dj + j] = pred_init[j];
@@ -80,49 +85,50 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 
 // ------------------------------------------------------------------ segment head
 // A = ChooseNBest(B); B = []; d = (s, 0, ..., 0)   (Algorithm 1, head of the outer loop)
-__global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv) {
+__global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv,
+                                int *host_counts) {
     int u = blockIdx.x, lane = threadIdx.x;
     int left = utt_T[u] - seg * d.S;
     int sp = left < 0 ? 0 : (left > d.S ? d.S : left);
     if (lane == 0) rv.utt_sp[u] = sp;
     if (sp == 0) {  // finished (or empty) utterance: B keeps the final list
         if (lane == 0) A.count[u] = 0;
-        return;
-    }
-    int nB = B.count[u];
-    const double *bl = B.logs + (long)u * d.BCAP;
-    for (int i = lane; i < nB; i += WAVE) {
-        double si = bl[i];
-        int rank = 0;
-        for (int j = 0; j < nB; ++j) {
-            double sj = bl[j];
-            rank += (sj > si) || (sj == si && j < i);
+    } else {
+        int nB = B.count[u];
+        const double *bl = B.logs + (long)u * d.BCAP;
+        for (int i = lane; i < nB; i += WAVE) {
+            double si = bl[i];
+            int rank = 0;
+            for (int j = 0; j < nB; ++j) {
+                double sj = bl[j];
+                rank += (sj > si) || (sj == si && j < i);
+            }
+            if (rank < d.N) {
+                long a = (long)u * d.N + rank, b = (long)u * d.BCAP + i;
+                A.logs[a] = si;
+                A.node[a] = B.node[b];
+                A.hash[a] = B.hash[b];
+                A.len[a] = B.len[b];
+                A.pslot[a] = B.slot[b];
+                A.slot[a] = tbs_slot_id(u, parity, 0, rank, d.R, d.N);
+                A.pnode[a] = -1;
+                A.token[a] = -1;
+                float *dh = A.dhat + a * d.S;
+                dh[0] = 1.f;
+                for (int t = 1; t < d.S; ++t) dh[t] = 0.f;
+            }
         }
-        if (rank < d.N) {
-            long a = (long)u * d.N + rank, b = (long)u * d.BCAP + i;
-            A.logs[a] = si;
-            A.node[a] = B.node[b];
-            A.hash[a] = B.hash[b];
-            A.len[a] = B.len[b];
-            A.pslot[a] = B.slot[b];
-            A.slot[a] = tbs_slot_id(u, parity, 0, rank, d.R, d.N);
-            A.pnode[a] = -1;
-            A.token[a] = -1;
-            float *dh = A.dhat + a * d.S;
-            dh[0] = 1.f;
-            for (int t = 1; t < d.S; ++t) dh[t] = 0.f;
+        if (lane == 0) {
+            A.count[u] = nB < d.N ? nB : d.N;
+            B.count[u] = 0;
         }
     }
-    __syncthreads();
-    if (lane == 0) {
-        A.count[u] = nB < d.N ? nB : d.N;
-        B.count[u] = 0;
-    }
+    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, A, rv, 0, host_counts);
 }
 
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
-                                AView A, RowView rv) {
-    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(WAVE), 0, st, d, seg, parity, utt_T, B, A, rv);
+                                AView A, RowView rv, int *host_counts) {
+    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(WAVE), 0, st, d, seg, parity, utt_T, B, A, rv, host_counts);
     return hipGetLastError();
 }
 
@@ -149,263 +155,325 @@ hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv,
 }
 
 // ------------------------------------------------------------------ row list
-// Compacts the live (utterance, hypothesis) pairs and their (pair, frame) rows
-// for one joiner call, gives new hypotheses their trie nodes, and publishes the
-// counts to the host.  One workgroup; U is at most a few thousand.
-__global__ void k_rowlist(Dims d, int seg, const int *utt_T, const int *utt_off, AView A, RowView rv, int2 *nodes,
-                          int assign_nodes, int *host_counts) {
-    __shared__ int s_pairs[1024], s_rows[1024];
-    __shared__ int s_carry[4];
-    int tid = threadIdx.x;
-    if (tid == 0) { s_carry[0] = 0; s_carry[1] = 0; s_carry[2] = 0; s_carry[3] = 0; }
-    __syncthreads();
-    int node_base = rv.counts[TBS_CNT_NODES];
-    for (int base = 0; base < d.U; base += 1024) {
-        int u = base + tid;
-        int cnt = 0, sp = 0;
-        if (u < d.U) {
-            sp = rv.utt_sp[u];
-            cnt = sp > 0 ? A.count[u] : 0;
-        }
-        s_pairs[tid] = cnt;
-        s_rows[tid] = cnt * sp;
-        __syncthreads();
-        // inclusive Hillis-Steele scan over the chunk
-        for (int off = 1; off < 1024; off <<= 1) {
-            int vp = 0, vr = 0;
-            if (tid >= off) { vp = s_pairs[tid - off]; vr = s_rows[tid - off]; }
-            __syncthreads();
-            s_pairs[tid] += vp;
-            s_rows[tid] += vr;
-            __syncthreads();
-        }
-        int pair0 = s_carry[0] + s_pairs[tid] - cnt;
-        int row0 = s_carry[1] + s_rows[tid] - cnt * sp;
-        if (u < d.U) {
-            rv.utt_pair0[u] = pair0;
-            int t0 = seg * d.S;
-            for (int h = 0; h < cnt; ++h) {
-                int j = pair0 + h;
-                long a = (long)u * d.N + h;
-                rv.pair_u[j] = u;
-                rv.pair_h[j] = h;
-                rv.pair_row0[j] = row0 + h * sp;
-                rv.pair_len[j] = sp;
-                int slot = A.slot[a];
-                for (int t = 0; t < sp; ++t) {
-                    rv.row_enc[row0 + h * sp + t] = utt_off[u] + t0 + t;
-                    rv.row_slot[row0 + h * sp + t] = slot;
-                }
-                if (assign_nodes) {
-                    int node = node_base + j;
-                    if (node < d.max_nodes) {
-                        nodes[node] = make_int2(A.pnode[a], A.token[a]);
-                        A.node[a] = node;
-                    } else {
-                        A.node[a] = 0;
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        if (tid == 1023) {
-            s_carry[0] += s_pairs[1023];
-            s_carry[1] += s_rows[1023];
-        }
-        if (cnt > 0) { atomicAdd(&s_carry[2], 1); atomicAdd(&s_carry[3], sp); }
-        __syncthreads();
+// The joiner rows of a round are the (pair, frame) combinations of the live
+// (utterance, hypothesis) pairs, compacted.  The last workgroup to finish the
+// kernel that produced the new counts (segment head or select/merge) runs an
+// exclusive scan over the utterances with one wave and publishes the totals to
+// the host; a second, fully parallel kernel then fills the pair and row lists.
+__device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes,
+                                int *host_counts) {
+    const int lane = threadIdx.x & 63;
+    const int chunk = (d.U + 63) / 64;
+    const int u0 = lane * chunk, u1 = min(d.U, u0 + chunk);
+    // written by other workgroups of this launch: read past the L1
+    const volatile int *v_sp = rv.utt_sp, *v_cnt = A.count;
+    int pairs = 0, rows = 0, utts = 0, frames = 0;
+    for (int u = u0; u < u1; ++u) {
+        const int sp = v_sp[u];
+        const int cnt = sp > 0 ? v_cnt[u] : 0;
+        pairs += cnt;
+        rows += cnt * sp;
+        utts += cnt > 0;
+        frames += cnt > 0 ? sp : 0;
     }
-    if (tid == 0) {
-        int pairs = s_carry[0], rows = s_carry[1];
+    int ipairs = pairs, irows = rows;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int op = __shfl_up(ipairs, off), orr = __shfl_up(irows, off);
+        if (lane >= off) { ipairs += op; irows += orr; }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        utts += __shfl_xor(utts, off);
+        frames += __shfl_xor(frames, off);
+    }
+    int p = ipairs - pairs, r = irows - rows;
+    for (int u = u0; u < u1; ++u) {
+        const int sp = v_sp[u];
+        const int cnt = sp > 0 ? v_cnt[u] : 0;
+        rv.utt_pair0[u] = p;
+        rv.utt_row0[u] = r;
+        p += cnt;
+        r += cnt * sp;
+    }
+    const int tot_pairs = __shfl(ipairs, 63), tot_rows = __shfl(irows, 63);
+    if (lane == 0) {
         int err = rv.counts[TBS_CNT_ERR];
+        const int node_base = rv.counts[TBS_CNT_NODES];
         int nodes_used = node_base;
+        rv.counts[TBS_CNT_NODE_BASE] = node_base;
         if (assign_nodes) {
-            nodes_used = node_base + pairs;
+            nodes_used = node_base + tot_pairs;
             if (nodes_used > d.max_nodes) { err |= TBS_ERRF_NODES; nodes_used = d.max_nodes; }
         }
-        rv.counts[TBS_CNT_PAIRS] = pairs;
-        rv.counts[TBS_CNT_ROWS] = rows;
+        rv.counts[TBS_CNT_PAIRS] = tot_pairs;
+        rv.counts[TBS_CNT_ROWS] = tot_rows;
         rv.counts[TBS_CNT_NODES] = nodes_used;
         rv.counts[TBS_CNT_ERR] = err;
-        rv.counts[TBS_CNT_UTTS] = s_carry[2];
-        rv.counts[TBS_CNT_FRAMES] = s_carry[3];
+        rv.counts[TBS_CNT_UTTS] = utts;
+        rv.counts[TBS_CNT_FRAMES] = frames;
+        rv.counts[TBS_CNT_TICKET] = 0;
         if (host_counts) {  // pinned, device-mapped host memory: the host reads it after a stream sync
-            host_counts[TBS_CNT_PAIRS] = pairs;
-            host_counts[TBS_CNT_ROWS] = rows;
+            host_counts[TBS_CNT_PAIRS] = tot_pairs;
+            host_counts[TBS_CNT_ROWS] = tot_rows;
             host_counts[TBS_CNT_NODES] = nodes_used;
             host_counts[TBS_CNT_ERR] = err;
-            host_counts[TBS_CNT_UTTS] = s_carry[2];
-            host_counts[TBS_CNT_FRAMES] = s_carry[3];
+            host_counts[TBS_CNT_UTTS] = utts;
+            host_counts[TBS_CNT_FRAMES] = frames;
             __threadfence_system();
         }
     }
 }
 
-hipError_t launch_rowlist(hipStream_t st, const Dims &d, int seg, const int *utt_T, const int *utt_off, AView A,
-                          RowView rv, int2 *nodes, int assign_nodes, int *host_counts) {
-    hipLaunchKernelGGL(k_rowlist, dim3(1), dim3(1024), 0, st, d, seg, utt_T, utt_off, A, rv, nodes, assign_nodes,
-                       host_counts);
+// Called by every workgroup (one wave each) at its end; true in the last one to arrive.
+__device__ bool last_workgroup(const RowView &rv, int n_groups) {
+    __shared__ int s_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(&rv.counts[TBS_CNT_TICKET], 1) == n_groups - 1;
+    __syncthreads();
+    if (s_last) __threadfence();
+    return s_last != 0;
+}
+
+__global__ void k_rowscan(Dims d, AView A, RowView rv, int assign_nodes, int *host_counts) {
+    scan_utterances(d, A, rv, assign_nodes, host_counts);
+}
+
+hipError_t launch_rowscan(hipStream_t st, const Dims &d, AView A, RowView rv, int assign_nodes, int *host_counts) {
+    hipLaunchKernelGGL(k_rowscan, dim3(1), dim3(WAVE), 0, st, d, A, rv, assign_nodes, host_counts);
+    return hipGetLastError();
+}
+
+// One workgroup per utterance fills its pairs and rows, and gives new hypotheses their trie nodes.
+__global__ void k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes, int assign_nodes) {
+    const int u = blockIdx.x, lane = threadIdx.x;
+    const int sp = rv.utt_sp[u];
+    const int cnt = sp > 0 ? A.count[u] : 0;
+    if (cnt == 0) return;
+    const int pair0 = rv.utt_pair0[u], row0 = rv.utt_row0[u];
+    const int frame0 = utt_off[u] + seg * d.S;
+    const int node_base = rv.counts[TBS_CNT_NODE_BASE];
+    for (int idx = lane; idx < cnt * sp; idx += WAVE) {
+        const int h = idx / sp, t = idx - h * sp;
+        const long a = (long)u * d.N + h;
+        const int slot = A.slot[a];
+        rv.row_enc[row0 + idx] = frame0 + t;
+        rv.row_slot[row0 + idx] = slot;
+        if (t == 0) {
+            const int j = pair0 + h;
+            rv.pair_u[j] = u;
+            rv.pair_h[j] = h;
+            rv.pair_row0[j] = row0 + h * sp;
+            rv.pair_len[j] = sp;
+            rv.pair_slot[j] = slot;
+            if (assign_nodes) {
+                const int node = node_base + j;
+                if (node < d.max_nodes) {
+                    nodes[node] = make_int2(A.pnode[a], A.token[a]);
+                    A.node[a] = node;
+                } else {
+                    A.node[a] = 0;
+                }
+            }
+        }
+    }
+}
+
+hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
+                          int2 *nodes, int assign_nodes) {
+    hipLaunchKernelGGL(k_rowfill, dim3(d.U), dim3(WAVE), 0, st, d, seg, utt_off, A, rv, nodes, assign_nodes);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ select + merge
-// Second half of the inner loop of Algorithm 1 for one utterance per wave.
+// Second half of the inner loop of Algorithm 1, one utterance per wave.  The
+// utterance's B list, its A entries and its H*N candidates are staged in LDS
+// with one round of parallel loads, all list work happens there, and B and the
+// new A are written back once, so the kernel costs a handful of memory round
+// trips instead of one per list operation.
 #define CAND_MAX (TBS_MAX_BEAM * TBS_MAX_BEAM)
 
 __global__ void __launch_bounds__(WAVE)
 k_select_merge(Dims d, int parity, int round, int drop, const float *logits, const float *row_lc,
                const float *dphi, const float *cand_score, const int *cand_tok, AView A, AView An, BView B,
-               RowView rv, const int2 *nodes) {
+               RowView rv, const int2 *nodes, int *host_counts) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // B list of this utterance
+    double *s_blogs = reinterpret_cast<double *>(s_dyn);
+    u64 *s_bhash = reinterpret_cast<u64 *>(s_blogs + d.BCAP);
+    int *s_bnode = reinterpret_cast<int *>(s_bhash + d.BCAP);
+    int *s_blen = s_bnode + d.BCAP;
+    int *s_bslot = s_blen + d.BCAP;
     __shared__ double s_key[CAND_MAX];
+    __shared__ int s_ctok[CAND_MAX];
+    __shared__ double s_alogs[TBS_MAX_BEAM];
+    __shared__ u64 s_ahash[TBS_MAX_BEAM];
+    __shared__ int s_anode[TBS_MAX_BEAM], s_alen[TBS_MAX_BEAM], s_aslot[TBS_MAX_BEAM];
+    __shared__ double s_bkey[TBS_MAX_BEAM];
     __shared__ int s_sel[TBS_MAX_BEAM];      // candidate index by rank
     __shared__ int s_keep[TBS_MAX_BEAM];
-    __shared__ int s_found;
     __shared__ double s_thr;
     const int u = blockIdx.x, lane = threadIdx.x;
     const int N = d.N;
     const int H = rv.utt_sp[u] > 0 ? A.count[u] : 0;
     if (H == 0) {
         if (lane == 0) An.count[u] = 0;
-        return;
-    }
-    const int pair0 = rv.utt_pair0[u];
-    double *bl = B.logs + (long)u * d.BCAP;
-    int *bnode = B.node + (long)u * d.BCAP;
-    u64 *bhash = B.hash + (long)u * d.BCAP;
-    int *blen = B.len + (long)u * d.BCAP;
-    int *bslot = B.slot + (long)u * d.BCAP;
-    int nB = B.count[u];
-
-    // --- AddAndMerge of every blank expansion, in hypothesis order
-    for (int h = 0; h < H; ++h) {
-        long a = (long)u * N + h;
-        double key = A.logs[a] + log((double)dphi[pair0 + h]);
-        u64 hs = A.hash[a];
-        int ln = A.len[a], nd = A.node[a];
-        if (lane == 0) s_found = 0x7fffffff;
-        __syncthreads();
-        for (int base = 0; base < nB; base += WAVE) {
-            int i = base + lane;
-            bool hit = false;
-            if (i < nB && bhash[i] == hs && blen[i] == ln) hit = same_sequence(nodes, bnode[i], nd);
-            if (hit) atomicMin(&s_found, i);  // at most one entry can match; min keeps it deterministic
+    } else {
+        const int pair0 = rv.utt_pair0[u];
+        const long bbase = (long)u * d.BCAP;
+        const int nB0 = B.count[u];
+        int nB = nB0;
+        // --- stage B, A and the candidates
+        for (int i = lane; i < nB0; i += WAVE) {
+            s_blogs[i] = B.logs[bbase + i];
+            s_bhash[i] = B.hash[bbase + i];
+            s_bnode[i] = B.node[bbase + i];
+            s_blen[i] = B.len[bbase + i];
+            s_bslot[i] = B.slot[bbase + i];
         }
+        if (lane < H) {
+            const long a = (long)u * N + lane;
+            const double al = A.logs[a];
+            s_alogs[lane] = al;
+            s_ahash[lane] = A.hash[a];
+            s_anode[lane] = A.node[a];
+            s_alen[lane] = A.len[a];
+            s_aslot[lane] = A.slot[a];
+            s_bkey[lane] = al + log((double)dphi[pair0 + lane]);   // score of the blank expansion
+        }
+        if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
+        const int nc = H * N;
+        for (int c = lane; c < nc; c += WAVE) s_ctok[c] = cand_tok[(long)pair0 * N + c];
         __syncthreads();
-        int f = s_found == 0x7fffffff ? -1 : s_found;
-        if (lane == 0) {
-            if (f >= 0) {
-                bl[f] = log_add(bl[f], key);
+        for (int c = lane; c < nc; c += WAVE) {
+            const int tok = s_ctok[c];
+            s_key[c] = tok >= 0 ? s_alogs[c / N] + (double)cand_score[(long)pair0 * N + c] : nan("");
+        }
+
+        // --- AddAndMerge of every blank expansion, in hypothesis order
+        for (int h = 0; h < H; ++h) {
+            const u64 hs = s_ahash[h];
+            const int ln = s_alen[h], nd = s_anode[h];
+            int found = 0x7fffffff;
+            for (int base = 0; base < nB; base += WAVE) {
+                const int i = base + lane;
+                bool hit = false;
+                if (i < nB && s_bhash[i] == hs && s_blen[i] == ln) hit = same_sequence(nodes, s_bnode[i], nd);
+                const u64 m = __ballot(hit);
+                if (m) { found = base + __ffsll((long long)m) - 1; break; }   // at most one entry can match
+            }
+            if (found != 0x7fffffff) {
+                if (lane == 0) s_blogs[found] = log_add(s_blogs[found], s_bkey[h]);
             } else if (nB < d.BCAP) {
-                bl[nB] = key;
-                bnode[nB] = nd;
-                bhash[nB] = hs;
-                blen[nB] = ln;
-                bslot[nB] = A.slot[a];
-            } else {
+                if (lane == 0) {
+                    s_blogs[nB] = s_bkey[h];
+                    s_bhash[nB] = hs;
+                    s_bnode[nB] = nd;
+                    s_blen[nB] = ln;
+                    s_bslot[nB] = s_aslot[h];
+                }
+                ++nB;
+            } else if (lane == 0) {
                 atomicOr(&rv.counts[TBS_CNT_ERR], TBS_ERRF_BCAP);
             }
+            __syncthreads();
         }
-        if (f < 0 && nB < d.BCAP) ++nB;
-        __syncthreads();
-    }
-    if (lane == 0) B.count[u] = nB;
-
-    // --- threshold = ChooseNthScore(B, N), only defined when B holds N entries
-    const bool have_thr = nB >= N;
-    if (have_thr) {
+        // --- B back to memory: merged scores of old entries, and the new entries
         for (int i = lane; i < nB; i += WAVE) {
-            double si = bl[i];
-            int rank = 0;
-            for (int j = 0; j < nB; ++j) {
-                double sj = bl[j];
-                rank += (sj > si) || (sj == si && j < i);
+            B.logs[bbase + i] = s_blogs[i];
+            if (i >= nB0) {
+                B.hash[bbase + i] = s_bhash[i];
+                B.node[bbase + i] = s_bnode[i];
+                B.len[bbase + i] = s_blen[i];
+                B.slot[bbase + i] = s_bslot[i];
             }
-            if (rank == N - 1) s_thr = si;
         }
-    }
-    __syncthreads();
-    const double thr = have_thr ? s_thr : 0.0;
+        if (lane == 0) B.count[u] = nB;
 
-    // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates
-    const int nc = H * N;
-    for (int c = lane; c < nc; c += WAVE) {
-        int h = c / N;
-        int tok = cand_tok[(long)(pair0 + h) * N + (c % N)];
-        double key = -INFINITY;
-        if (tok >= 0) key = A.logs[(long)u * N + h] + (double)cand_score[(long)(pair0 + h) * N + (c % N)];
-        s_key[c] = tok >= 0 ? key : nan("");
-    }
-    if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
-    __syncthreads();
-    for (int c = lane; c < nc; c += WAVE) {
-        double kc = s_key[c];
-        if (kc != kc) continue;  // no candidate in this place
-        int hc = c / N, tc = cand_tok[(long)(pair0 + hc) * N + (c % N)];
-        int rank = 0;
-        for (int j = 0; j < nc; ++j) {
-            double kj = s_key[j];
-            if (kj != kj || j == c) continue;
-            int hj = j / N;
-            bool better = kj > kc;
-            if (kj == kc) {
-                int tj = cand_tok[(long)(pair0 + hj) * N + (j % N)];
-                better = (hj < hc) || (hj == hc && tj < tc);
+        // --- threshold = ChooseNthScore(B, N), only defined when B holds N entries
+        const bool have_thr = nB >= N;
+        if (have_thr) {
+            for (int i = lane; i < nB; i += WAVE) {
+                const double si = s_blogs[i];
+                int rank = 0;
+                for (int j = 0; j < nB; ++j) {
+                    const double sj = s_blogs[j];
+                    rank += (sj > si) || (sj == si && j < i);
+                }
+                if (rank == N - 1) s_thr = si;
             }
-            rank += better;
         }
-        if (rank < N) s_sel[rank] = c;
-    }
-    __syncthreads();
-    // --- threshold test, in rank order: keep iff |B| < N or score > threshold (strict)
-    if (lane < N) {
-        int c = s_sel[lane];
-        if (c >= 0) s_keep[lane] = (!have_thr) || (s_key[c] > thr);
-    }
-    __syncthreads();
-    if (drop) {
-        if (lane == 0) An.count[u] = 0;
-        return;
-    }
-    int pos = 0, total = 0;
-    for (int r = 0; r < N; ++r) {
-        int k = s_keep[r];
-        if (r < lane) pos += k;
-        total += k;
-    }
-    if (lane == 0) An.count[u] = total;
-    if (lane < N && s_keep[lane]) {
-        int c = s_sel[lane];
-        int h = c / N;
-        int tok = cand_tok[(long)(pair0 + h) * N + (c % N)];
-        long a = (long)u * N + h, an = (long)u * N + pos;
-        An.logs[an] = s_key[c];
-        An.pnode[an] = A.node[a];
-        An.node[an] = -1;
-        An.token[an] = tok;
-        An.hash[an] = hash_append(A.hash[a], tok);
-        An.len[an] = A.len[a] + 1;
-        An.pslot[an] = A.slot[a];
-        An.slot[an] = tbs_slot_id(u, parity, round, pos, d.R, N);
-        // d of the new hypothesis (Eq. 5 for the chosen token), normalised by its sum (Eq. 6)
-        int row0 = rv.pair_row0[pair0 + h], sp = rv.pair_len[pair0 + h];
-        float *dh = An.dhat + an * d.S;
-        float sum = 0.f;
-        for (int t = 0; t < sp; ++t) {
-            float x = __expf(logits[(long)(row0 + t) * d.V + tok] + row_lc[row0 + t]);
-            dh[t] = x;
-            sum += x;
+        // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates
+        for (int c = lane; c < nc; c += WAVE) {
+            const double kc = s_key[c];
+            if (kc != kc) continue;  // no candidate in this place
+            const int hc = c / N, tc = s_ctok[c];
+            int rank = 0;
+            for (int j = 0; j < nc; ++j) {
+                const double kj = s_key[j];
+                if (kj != kj || j == c) continue;
+                const int hj = j / N;
+                bool better = kj > kc;
+                if (kj == kc) better = (hj < hc) || (hj == hc && s_ctok[j] < tc);
+                rank += better;
+            }
+            if (rank < N) s_sel[rank] = c;
         }
-        float inv = 1.f / sum;
-        for (int t = 0; t < sp; ++t) dh[t] *= inv;
-        for (int t = sp; t < d.S; ++t) dh[t] = 0.f;
+        __syncthreads();
+        // --- threshold test, in rank order: keep iff |B| < N or score > threshold (strict)
+        const double thr = have_thr ? s_thr : 0.0;
+        if (lane < N) {
+            const int c = s_sel[lane];
+            if (c >= 0) s_keep[lane] = (!have_thr) || (s_key[c] > thr);
+        }
+        __syncthreads();
+        if (drop) {
+            if (lane == 0) An.count[u] = 0;
+        } else {
+            int pos = 0, total = 0;
+            for (int r = 0; r < N; ++r) {
+                const int k = s_keep[r];
+                if (r < lane) pos += k;
+                total += k;
+            }
+            if (lane == 0) An.count[u] = total;
+            if (lane < N && s_keep[lane]) {
+                const int c = s_sel[lane];
+                const int h = c / N;
+                const int tok = s_ctok[c];
+                const long an = (long)u * N + pos;
+                An.logs[an] = s_key[c];
+                An.pnode[an] = s_anode[h];
+                An.node[an] = -1;
+                An.token[an] = tok;
+                An.hash[an] = hash_append(s_ahash[h], tok);
+                An.len[an] = s_alen[h] + 1;
+                An.pslot[an] = s_aslot[h];
+                An.slot[an] = tbs_slot_id(u, parity, round, pos, d.R, N);
+                // d of the new hypothesis (Eq. 5 for the chosen token), normalised by its sum (Eq. 6)
+                const int sp = rv.utt_sp[u];
+                const int row0 = rv.utt_row0[u] + h * sp;
+                float *dh = An.dhat + an * d.S;
+                float sum = 0.f;
+                for (int t = 0; t < sp; ++t) {
+                    const float x = __expf(logits[(long)(row0 + t) * d.V + tok] + row_lc[row0 + t]);
+                    dh[t] = x;
+                    sum += x;
+                }
+                const float inv = 1.f / sum;
+                for (int t = 0; t < sp; ++t) dh[t] *= inv;
+                for (int t = sp; t < d.S; ++t) dh[t] = 0.f;
+            }
+        }
     }
+    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, An, rv, 1, host_counts);
 }
 
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
-                               const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes) {
-    hipLaunchKernelGGL(k_select_merge, dim3(d.U), dim3(WAVE), 0, st, d, parity, round, drop, logits, row_lc, dphi,
-                       cand_score, cand_tok, A, An, B, rv, nodes);
+                               const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes,
+                               int *host_counts) {
+    const size_t shm = (size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int));
+    hipLaunchKernelGGL(k_select_merge, dim3(d.U), dim3(WAVE), shm, st, d, parity, round, drop, logits, row_lc, dphi,
+                       cand_score, cand_tok, A, An, B, rv, nodes, host_counts);
     return hipGetLastError();
 }
 

@@ -92,18 +92,6 @@ hipError_t launch_lstm_pointwise(hipStream_t st, const Dims &d, int dtype, int p
     return hipGetLastError();
 }
 
-// out_row[j] = state slot of pair j (rows of the projection GEMM land there)
-__global__ void k_pair_slots(Dims d, int pairs, AView A, RowView rv, int *out_row) {
-    int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j < pairs) out_row[j] = A.slot[(long)rv.pair_u[j] * d.N + rv.pair_h[j]];
-}
-
-hipError_t launch_pair_slots(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, int *out_row) {
-    if (pairs <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_pair_slots, dim3((pairs + 255) / 256), dim3(256), 0, st, d, pairs, A, rv, out_row);
-    return hipGetLastError();
-}
-
 // wcat[r, :] = [ w_ih[r, 0:in] | w_hh[r, 0:hid] ], elements of 2 bytes
 __global__ void k_concat16(const uint16_t *w_ih, const uint16_t *w_hh, uint16_t *wcat, int rows, int in_dim,
                            int hid) {

@@ -58,7 +58,6 @@ struct tbs_ctx {
     void *xh[2];
     void *htop;
     float *gates;
-    int *out_row;
 
     // results
     int *res_count, *res_len, *res_tok, *res_ovf;
@@ -226,6 +225,10 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     d.R = cfg->rounds_capacity > 0 ? cfg->rounds_capacity : 32;
     if (cfg->max_rounds_per_segment > 0) d.R = cfg->max_rounds_per_segment;
     d.BCAP = d.N * d.R;
+    if (d.BCAP > 2048) {   // the merge kernel stages one utterance's B list in LDS
+        delete c;
+        return TBS_EINVAL;
+    }
     d.E = cfg->pred_embed;
     d.H = cfg->pred_hidden;
     d.L = cfg->pred_layers;
@@ -245,6 +248,8 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->B.len, U * d.BCAP);
     rc |= dev_alloc(c, &c->B.slot, U * d.BCAP);
     rc |= dev_alloc(c, &c->rv.utt_pair0, U);
+    rc |= dev_alloc(c, &c->rv.utt_row0, U);
+    rc |= dev_alloc(c, &c->rv.pair_slot, UN);
     rc |= dev_alloc(c, &c->rv.utt_sp, U);
     rc |= dev_alloc(c, &c->rv.pair_u, UN);
     rc |= dev_alloc(c, &c->rv.pair_h, UN);
@@ -288,7 +293,6 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         c->htop = p;
     }
     rc |= dev_alloc(c, &c->gates, (size_t)UN * 4 * d.H);
-    rc |= dev_alloc(c, &c->out_row, UN);
     for (int l = 0; l < d.L; ++l) {
         int in_dim = l == 0 ? d.E : d.H;
         char *p = nullptr;
@@ -381,10 +385,10 @@ int tbs_segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->round = 0;
     c->parity = seg_index & 1;
     AView &A = c->A[c->a_cur];
-    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv));
+    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv,
+                                   c->h_counts_dev));
     HIPCHK(c, launch_state_copy(c->stream, c->cur, A, c->rv, c->pool_p, c->pool_h, c->pool_c, c->pool_rows));
-    HIPCHK(c, launch_rowlist(c->stream, c->cur, c->seg, c->utt_T, c->utt_off, A, c->rv, c->nodes, 0,
-                             c->h_counts_dev));
+    HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, A, c->rv, c->nodes, 0));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
     c->state = ST_READY;
@@ -435,9 +439,8 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     {
         ProfScope ps(c, TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
         HIPCHK(c, launch_select_merge(c->stream, c->cur, c->parity, c->round, drop, c->logits, c->row_lc, c->dphi,
-                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes));
-        HIPCHK(c, launch_rowlist(c->stream, c->cur, c->seg, c->utt_T, c->utt_off, An, c->rv, c->nodes, 1,
-                                 c->h_counts_dev));
+                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes, c->h_counts_dev));
+        HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, An, c->rv, c->nodes, 1));
     }
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->a_cur ^= 1;
@@ -462,8 +465,7 @@ int tbs_predictor_step(tbs_ctx *c) {
             HIPCHK(c, launch_lstm_pointwise(c->stream, d, c->cfg.dtype, pairs, l, A, c->rv, c->gates, c->pool_h,
                                             c->pool_c, c->pool_rows, c->xh[(l + 1) & 1], c->htop));
         }
-        HIPCHK(c, launch_pair_slots(c->stream, d, pairs, A, c->rv, c->out_row));
-        HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, pairs, d.Dj, d.H, c->out_row, d.Dj));
+        HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, pairs, d.Dj, d.H, c->rv.pair_slot, d.Dj));
     }
     c->state = ST_READY;
     return TBS_OK;
@@ -621,8 +623,8 @@ int tbs_debug_rebuild(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->round = 0;
     c->parity = 0;
     HIPCHK(c, launch_set_sp(c->stream, c->cur, seg_index, c->utt_T, c->rv));
-    HIPCHK(c, launch_rowlist(c->stream, c->cur, c->seg, c->utt_T, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0,
-                             c->h_counts_dev));
+    HIPCHK(c, launch_rowscan(c->stream, c->cur, c->A[c->a_cur], c->rv, 0, c->h_counts_dev));
+    HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
     c->state = ST_READY;
