@@ -99,7 +99,9 @@ def main():
     roofline = None
     if not args.no_kernel_timing:
         H, E, Dj, V, L = shape.pred_hidden, shape.pred_embed, shape.d_joint, shape.vocab, shape.pred_layers
-        pred_flops_per_hyp = sum(2 * 4 * H * ((E if l == 0 else H) + H) for l in range(L)) + 2 * H * Dj
+        # bf16 models take the embedding half of layer 0 from a table made at init: no flops per round
+        in0 = 0 if shape.dtype == "bf16" else E
+        pred_flops_per_hyp = sum(2 * 4 * H * ((in0 if l == 0 else H) + H) for l in range(L)) + 2 * H * Dj
         for name, kid in (("joiner_gemm", KERNEL.JOINER), ("joiner_prep", KERNEL.PREP), ("expand", KERNEL.EXPAND),
                           ("select_merge", KERNEL.SELECT), ("predictor", KERNEL.PREDICTOR)):
             tbs.profile_select(kid)

@@ -160,44 +160,53 @@ hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv,
 // kernel that produced the new counts (segment head or select/merge) runs an
 // exclusive scan over the utterances with one wave and publishes the totals to
 // the host; a second, fully parallel kernel then fills the pair and row lists.
+__device__ __forceinline__ int load_fresh(const int *p) {
+    // value written by another workgroup of this launch: read it past this CU's L1
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes,
                                 int *host_counts) {
     const int lane = threadIdx.x & 63;
-    const int chunk = (d.U + 63) / 64;
-    const int u0 = lane * chunk, u1 = min(d.U, u0 + chunk);
-    // written by other workgroups of this launch: read past the L1
-    const volatile int *v_sp = rv.utt_sp, *v_cnt = A.count;
-    int pairs = 0, rows = 0, utts = 0, frames = 0;
-    for (int u = u0; u < u1; ++u) {
-        const int sp = v_sp[u];
-        const int cnt = sp > 0 ? v_cnt[u] : 0;
-        pairs += cnt;
-        rows += cnt * sp;
-        utts += cnt > 0;
-        frames += cnt > 0 ? sp : 0;
-    }
-    int ipairs = pairs, irows = rows;
-    for (int off = 1; off < 64; off <<= 1) {
-        const int op = __shfl_up(ipairs, off), orr = __shfl_up(irows, off);
-        if (lane >= off) { ipairs += op; irows += orr; }
+    int carry_p = 0, carry_r = 0, utts = 0, frames = 0;
+    constexpr int UNROLL = 4;   // independent loads in flight per step
+    for (int base = 0; base < d.U; base += 64 * UNROLL) {
+        int sp[UNROLL], cnt[UNROLL];
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const int u = base + 64 * k + lane;
+            sp[k] = u < d.U ? load_fresh(rv.utt_sp + u) : 0;
+            cnt[k] = u < d.U ? load_fresh(A.count + u) : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const int u = base + 64 * k + lane;
+            const int c = sp[k] > 0 ? cnt[k] : 0;
+            const int r = c * sp[k];
+            int ip = c, ir = r;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int op = __shfl_up(ip, off), orr = __shfl_up(ir, off);
+                if (lane >= off) { ip += op; ir += orr; }
+            }
+            if (u < d.U) {
+                rv.utt_pair0[u] = carry_p + ip - c;
+                rv.utt_row0[u] = carry_r + ir - r;
+            }
+            carry_p += __shfl(ip, 63);
+            carry_r += __shfl(ir, 63);
+            utts += c > 0;
+            frames += c > 0 ? sp[k] : 0;
+        }
     }
     for (int off = 32; off > 0; off >>= 1) {
         utts += __shfl_xor(utts, off);
         frames += __shfl_xor(frames, off);
     }
-    int p = ipairs - pairs, r = irows - rows;
-    for (int u = u0; u < u1; ++u) {
-        const int sp = v_sp[u];
-        const int cnt = sp > 0 ? v_cnt[u] : 0;
-        rv.utt_pair0[u] = p;
-        rv.utt_row0[u] = r;
-        p += cnt;
-        r += cnt * sp;
-    }
-    const int tot_pairs = __shfl(ipairs, 63), tot_rows = __shfl(irows, 63);
+    const int tot_pairs = carry_p, tot_rows = carry_r;
     if (lane == 0) {
-        int err = rv.counts[TBS_CNT_ERR];
-        const int node_base = rv.counts[TBS_CNT_NODES];
+        int err = load_fresh(rv.counts + TBS_CNT_ERR);
+        const int node_base = load_fresh(rv.counts + TBS_CNT_NODES);
         int nodes_used = node_base;
         rv.counts[TBS_CNT_NODE_BASE] = node_base;
         if (assign_nodes) {
@@ -265,6 +274,7 @@ __global__ void k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView 
             rv.pair_row0[j] = row0 + h * sp;
             rv.pair_len[j] = sp;
             rv.pair_slot[j] = slot;
+            rv.pair_tok[j] = A.token[a];
             if (assign_nodes) {
                 const int node = node_base + j;
                 if (node < d.max_nodes) {
@@ -341,12 +351,12 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
         }
         if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
         const int nc = H * N;
-        for (int c = lane; c < nc; c += WAVE) s_ctok[c] = cand_tok[(long)pair0 * N + c];
-        __syncthreads();
         for (int c = lane; c < nc; c += WAVE) {
-            const int tok = s_ctok[c];
-            s_key[c] = tok >= 0 ? s_alogs[c / N] + (double)cand_score[(long)pair0 * N + c] : nan("");
+            s_ctok[c] = cand_tok[(long)pair0 * N + c];
+            s_key[c] = (double)cand_score[(long)pair0 * N + c];
         }
+        __syncthreads();
+        for (int c = lane; c < nc; c += WAVE) s_key[c] = s_ctok[c] >= 0 ? s_alogs[c / N] + s_key[c] : nan("");
 
         // --- AddAndMerge of every blank expansion, in hypothesis order
         for (int h = 0; h < H; ++h) {

@@ -1,5 +1,6 @@
 // bf16 MFMA GEMM of the joiner (and of the predictor's dense layers):
-//   C[M,N] = A[M,K] * B[N,K]^T + bias[N],  bf16 inputs, fp32 accumulate, fp32 output.
+//   C[M,N] = A[M,K] * B[N,K]^T + bias[N],  bf16 inputs, fp32 accumulate, fp32 output
+// (optionally rows scattered through out_row, and a per-row bias gathered from a table).
 //
 // Workgroup = WM x WN waves; each wave owns TM x TN blocks of 32x32 computed
 // with v_mfma_f32_32x32x16_bf16, so a workgroup tile is (32 TM WM) x (32 TN WN).
@@ -17,9 +18,17 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
-#define GEMM_BK 64
 #define GEMM_XCDS 8
 #define GEMM_GROUP_M 4   // M tiles per XCD block
+
+// LDS rows hold BK bf16 = BK/8 chunks of 16 bytes; chunk c of row r sits at position c ^ swz(r).
+// A 16-byte-per-lane LDS read is served 16 lanes (256 bytes = all 64 banks) per cycle, so 16
+// consecutive rows reading the same chunk must land on 16 different (position, row parity)
+// places: 128-byte rows need 8 positions changing every second row, 256-byte rows 16 positions.
+template <int BK>
+__device__ __forceinline__ int gemm_swz(int row) {
+    return BK == 64 ? ((row >> 1) & 7) : (row & 15);
+}
 
 // Position idx of XCD xcd's tile sequence -> (tile_m, tile_n).  Tiles are ordered
 // in blocks of GEMM_GROUP_M rows of tiles (M fastest inside a block) and XCD x
@@ -45,16 +54,17 @@ __device__ __forceinline__ bool gemm_tile_of(int xcd, int idx, int tiles_m, int 
 // is prefetched during the last K tile of the current one and the epilogue's
 // stores are left in flight, so neither the load latency at the head of a tile
 // nor the store traffic at its tail stalls the matrix cores.
-template <int TM, int TN, int WM, int WN, bool KGUARD>
+template <int TM, int TN, int WM, int WN, int BK, bool KGUARD>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
             float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
-            int tiles_n) {
+            int tiles_n, const float *__restrict__ rowbias, const int *__restrict__ rowbias_idx) {
     constexpr int NT = 64 * WM * WN;
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
-    constexpr int A_CHUNKS = BM * 8 / NT, B_CHUNKS = BN * 8 / NT;  // 16-byte chunks per thread per K tile
-    constexpr int ROWS_PER_PASS = NT / 8;
-    constexpr int TILE_ELEMS = (BM + BN) * GEMM_BK;
+    constexpr int CH = BK / 8;                                       // 16-byte chunks per LDS row
+    constexpr int A_CHUNKS = BM * CH / NT, B_CHUNKS = BN * CH / NT;  // chunks per thread per K tile
+    constexpr int ROWS_PER_PASS = NT / CH;
+    constexpr int TILE_ELEMS = (BM + BN) * BK;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // 2 x [A tile | B tile]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -66,17 +76,17 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
     floatx16 acc[TM][TN];
 
     // chunk (row, kc) this thread moves per pass, and where it lands in an LDS buffer
-    const int kc = (tid & 7), crow = tid >> 3;
+    const int kc = tid % CH, crow = tid / CH;
     int la[A_CHUNKS], lb[B_CHUNKS];
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
         int row = crow + ROWS_PER_PASS * i;
-        la[i] = row * GEMM_BK + ((kc ^ ((row >> 1) & 7)) * 8);
+        la[i] = row * BK + ((kc ^ gemm_swz<BK>(row)) * 8);
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
         int row = crow + ROWS_PER_PASS * i;
-        lb[i] = BM * GEMM_BK + row * GEMM_BK + ((kc ^ ((row >> 1) & 7)) * 8);
+        lb[i] = BM * BK + row * BK + ((kc ^ gemm_swz<BK>(row)) * 8);
     }
     // global sources of the current tile (rows clamped, so reads stay in bounds)
     const bf16_t *ga[A_CHUNKS], *gb[B_CHUNKS];
@@ -91,12 +101,12 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
     const int frow = lane & 31, fsel = lane >> 5;
     int fa[TM], fb[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[i] = (wm * 32 * TM + i * 32 + frow) * GEMM_BK;
+    for (int i = 0; i < TM; ++i) fa[i] = (wm * 32 * TM + i * 32 + frow) * BK;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[j] = BM * GEMM_BK + (wn * 32 * TN + j * 32 + frow) * GEMM_BK;
-    const int fsw = (frow >> 1) & 7;
+    for (int j = 0; j < TN; ++j) fb[j] = BM * BK + (wn * 32 * TN + j * 32 + frow) * BK;
+    const int fsw = gemm_swz<BK>(frow);
 
-    const int ktiles = (K + GEMM_BK - 1) / GEMM_BK;
+    const int ktiles = (K + BK - 1) / BK;
     uint4 ra[A_CHUNKS], rb[B_CHUNKS];
     // prologue: K tile 0 of the first tile -> LDS buffer 0
     {
@@ -138,7 +148,7 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
             const bf16_t *cur = smem + buf * TILE_ELEMS;
             bf16_t *nxt = smem + (buf ^ 1) * TILE_ELEMS;
             const bool last = kt + 1 == ktiles;
-            const int kn = last ? 0 : (kt + 1) * GEMM_BK;
+            const int kn = last ? 0 : (kt + 1) * BK;
             const bool in = !KGUARD || (kn + kc * 8 < K);
 #pragma unroll
             for (int i = 0; i < A_CHUNKS; ++i) {
@@ -155,7 +165,7 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
+            for (int kk = 0; kk < BK / 16; ++kk) {
                 bf16x8 af[TM], bfr[TN];
                 const int cpos = ((kk * 2 + fsel) ^ fsw) * 8;
 #pragma unroll
@@ -179,7 +189,7 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
 
         // epilogue: lane holds column (lane & 31); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4
         const int m0 = tile_m * BM, n0 = tile_n * BN;
-        if (out_row == nullptr && m0 + BM <= M && n0 + BN <= N) {
+        if (out_row == nullptr && rowbias == nullptr && m0 + BM <= M && n0 + BN <= N) {
             // interior tile: address = uniform row base (scalar registers) + one per-lane offset
             // + a constant, so a store costs no vector address arithmetic
             const unsigned offl = (unsigned)(wm * 32 * TM + (lane >> 5) * 4) * (unsigned)ldc +
@@ -204,7 +214,9 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
                         int row = m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                         if (row < M && col < N) {
                             long orow = out_row ? out_row[row] : row;
-                            C[orow * ldc + col] = acc[i][j][r];
+                            float v = acc[i][j][r];
+                            if (rowbias) v += rowbias[(long)rowbias_idx[row] * N + col];   // per-row gathered bias
+                            C[orow * ldc + col] = v;
                         }
                     }
                 }
@@ -220,18 +232,19 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
     }
 }
 
-template <int TM, int TN, int WM, int WN, int OCC>
+template <int TM, int TN, int WM, int WN, int BK, int OCC>
 static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                              int N, int K, const int *out_row, long ldc) {
+                              int N, int K, const int *out_row, long ldc, const float *rowbias,
+                              const int *rowbias_idx) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const size_t shm = 2u * (BM + BN) * GEMM_BK * sizeof(bf16_t);
+    const size_t shm = 2u * (BM + BN) * BK * sizeof(bf16_t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<TM, TN, WM, WN, false>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<TM, TN, WM, WN, BK, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<TM, TN, WM, WN, true>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<TM, TN, WM, WN, BK, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -241,12 +254,12 @@ static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, 
     long g = ((total + GEMM_XCDS - 1) / GEMM_XCDS) * GEMM_XCDS;
     if (g > 256L * OCC) g = 256L * OCC;
     const dim3 grid((unsigned)g), block(64 * WM * WN);
-    if (K % GEMM_BK == 0)
-        hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, false>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
-                           ldc, tiles_m, tiles_n);
+    if (K % BK == 0)
+        hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, BK, false>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
+                           ldc, tiles_m, tiles_n, rowbias, rowbias_idx);
     else
-        hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, true>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
-                           ldc, tiles_m, tiles_n);
+        hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, BK, true>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
+                           ldc, tiles_m, tiles_n, rowbias, rowbias_idx);
     return hipGetLastError();
 }
 
@@ -254,7 +267,8 @@ static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, 
 int g_tbs_gemm_variant = 0;
 
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc) {
+                            int N, int K, const int *out_row, long ldc, const float *rowbias,
+                            const int *rowbias_idx) {
     if (M <= 0) return hipSuccess;
     int v = g_tbs_gemm_variant;
     if (v == 0) {
@@ -265,13 +279,15 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
         v = t256 >= 384 ? 5 : (t128 >= 256 ? 2 : 1);
     }
     switch (v) {
-        case 1: return gemm_launch<1, 1, 2, 2, 4>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 64x64, 4 waves
-        case 2: return gemm_launch<2, 2, 2, 2, 2>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 128x128, 4 waves
-        case 3: return gemm_launch<2, 2, 4, 2, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x128, 8 waves
-        case 4: return gemm_launch<4, 4, 2, 2, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 4 waves
-        case 5: return gemm_launch<2, 4, 4, 2, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 8 waves
-        case 6: return gemm_launch<4, 2, 2, 4, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 8 waves
-        case 7: return gemm_launch<2, 2, 2, 4, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 128x256, 8 waves
-        default: return gemm_launch<2, 2, 4, 4, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);  // 256x256, 16 waves
+        case 1: return gemm_launch<1, 1, 2, 2, 64, 4>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 64x64, 4 waves
+        case 2: return gemm_launch<2, 2, 2, 2, 64, 2>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 128x128, 4 waves
+        case 3: return gemm_launch<2, 2, 4, 2, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x128, 8 waves
+        case 4: return gemm_launch<4, 4, 2, 2, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 4 waves
+        case 5: return gemm_launch<2, 4, 4, 2, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 8 waves
+        case 6: return gemm_launch<4, 2, 2, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 8 waves
+        case 7: return gemm_launch<2, 2, 2, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 128x256, 8 waves
+        case 8: return gemm_launch<2, 2, 4, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 16 waves
+        case 9: return gemm_launch<1, 1, 2, 2, 128, 2>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);  // 64x64, K tile 128
+        default: return gemm_launch<1, 2, 2, 2, 128, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx); // 64x128, K tile 128
     }
 }

@@ -43,6 +43,23 @@ hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pair
     return hipGetLastError();
 }
 
+// bf16 models: the embedding half of the first layer's gates is a table made once
+// (embed * W_ih^T + b for every token), so the per-round input is only the parent's h.
+__global__ void k_pred_gather_h(Dims d, AView A, RowView rv, const float *pool_h, bf16_t *xh) {
+    int j = blockIdx.x;
+    long a = (long)rv.pair_u[j] * d.N + rv.pair_h[j];
+    long ps = A.pslot[a];
+    bf16_t *x = xh + (long)j * d.H;
+    for (int i = threadIdx.x; i < d.H; i += blockDim.x) x[i] = f2bf_p(pool_h[ps * d.H + i]);
+}
+
+hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, const float *pool_h,
+                                bf16_t *xh) {
+    if (pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_pred_gather_h, dim3(pairs), dim3(256), 0, st, d, A, rv, pool_h, xh);
+    return hipGetLastError();
+}
+
 // LSTM cell, gate order i, f, g, o; gates already hold W x + W h + b.
 __global__ void k_lstm_pointwise(Dims d, int dtype, int layer, AView A, RowView rv, const float *gates,
                                  float *pool_h, float *pool_c, long pool_rows, void *xh_next, void *htop) {

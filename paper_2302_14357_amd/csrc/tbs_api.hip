@@ -55,6 +55,7 @@ struct tbs_ctx {
     int *cand_tok;
 
     void *wcat[TBS_MAX_LAYERS];
+    float *emb_gates;   // bf16 models: [V, 4H] = embed * W_ih(layer 0)^T + b(layer 0)
     void *xh[2];
     void *htop;
     float *gates;
@@ -250,6 +251,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->rv.utt_pair0, U);
     rc |= dev_alloc(c, &c->rv.utt_row0, U);
     rc |= dev_alloc(c, &c->rv.pair_slot, UN);
+    rc |= dev_alloc(c, &c->rv.pair_tok, UN);
     rc |= dev_alloc(c, &c->rv.utt_sp, U);
     rc |= dev_alloc(c, &c->rv.pair_u, UN);
     rc |= dev_alloc(c, &c->rv.pair_h, UN);
@@ -299,6 +301,8 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         rc |= dev_alloc(c, &p, (size_t)4 * d.H * (in_dim + d.H) * elem_bytes(c));
         c->wcat[l] = p;
     }
+    c->emb_gates = nullptr;
+    if (cfg->dtype == 1) rc |= dev_alloc(c, &c->emb_gates, (size_t)d.V * 4 * d.H);
     rc |= dev_alloc(c, &c->res_count, U);
     rc |= dev_alloc(c, &c->res_len, UN);
     rc |= dev_alloc(c, &c->res_logs, UN);
@@ -324,6 +328,15 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         int in_dim = l == 0 ? d.E : d.H;
         e = launch_concat_weights(c->stream, elem_bytes(c), w->w_ih[l], w->w_hh[l], c->wcat[l], 4 * d.H, in_dim,
                                   d.H);
+        if (e != hipSuccess) {
+            c->last_hip = (int)e;
+            tbs_free(c);
+            return TBS_EHIP;
+        }
+    }
+    if (c->emb_gates) {
+        e = launch_gemm_bf16(c->stream, (const bf16_t *)w->embed, (const bf16_t *)w->w_ih[0], w->b_lstm[0],
+                             c->emb_gates, d.V, 4 * d.H, d.E, nullptr, 4L * d.H);
         if (e != hipSuccess) {
             c->last_hip = (int)e;
             tbs_free(c);
@@ -457,11 +470,20 @@ int tbs_predictor_step(tbs_ctx *c) {
     AView &A = c->A[c->a_cur];
     if (pairs > 0) {
         ProfScope ps(c, TBS_K_PREDICTOR, pairs);
-        HIPCHK(c, launch_pred_gather(c->stream, d, c->cfg.dtype, pairs, A, c->rv, c->w.embed, c->pool_h, c->xh[0]));
+        if (c->emb_gates)
+            HIPCHK(c, launch_pred_gather_h(c->stream, d, pairs, A, c->rv, c->pool_h, (bf16_t *)c->xh[0]));
+        else
+            HIPCHK(c, launch_pred_gather(c->stream, d, c->cfg.dtype, pairs, A, c->rv, c->w.embed, c->pool_h,
+                                         c->xh[0]));
         for (int l = 0; l < d.L; ++l) {
             int in_dim = l == 0 ? d.E : d.H;
-            HIPCHK(c, gemm(c, c->xh[l & 1], c->wcat[l], c->w.b_lstm[l], c->gates, pairs, 4 * d.H, in_dim + d.H,
-                           nullptr, 4L * d.H));
+            if (l == 0 && c->emb_gates)
+                HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->xh[0], (const bf16_t *)c->w.w_hh[0],
+                                           nullptr, c->gates, pairs, 4 * d.H, d.H, nullptr, 4L * d.H, c->emb_gates,
+                                           c->rv.pair_tok));
+            else
+                HIPCHK(c, gemm(c, c->xh[l & 1], c->wcat[l], c->w.b_lstm[l], c->gates, pairs, 4 * d.H,
+                               in_dim + d.H, nullptr, 4L * d.H));
             HIPCHK(c, launch_lstm_pointwise(c->stream, d, c->cfg.dtype, pairs, l, A, c->rv, c->gates, c->pool_h,
                                             c->pool_c, c->pool_rows, c->xh[(l + 1) & 1], c->htop));
         }

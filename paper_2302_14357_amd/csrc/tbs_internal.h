@@ -40,6 +40,7 @@ struct RowView {
     int *utt_sp;     // [U]  frames of each utterance in this segment (0 = finished)
     int *pair_u, *pair_h, *pair_row0, *pair_len;  // [pairs]
     int *pair_slot;  // [pairs] predictor-state slot of the pair's hypothesis
+    int *pair_tok;   // [pairs] last token of the pair's hypothesis (-1 if carried into the segment)
     int *row_enc;    // [rows] frame row in enc_proj
     int *row_slot;   // [rows] predictor-state slot
     int *counts;     // [8]: 0 pairs, 1 rows, 2 trie nodes used, 3 error flags, 4 live utterances,
@@ -79,7 +80,8 @@ hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act,
 hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
                            int K, const int *out_row, long ldc);
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc);
+                            int N, int K, const int *out_row, long ldc, const float *rowbias = nullptr,
+                            const int *rowbias_idx = nullptr);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
                          float *delta_nb, int force_generic);
@@ -89,6 +91,8 @@ hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int ro
                                int *host_counts);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
                               const void *embed, const float *pool_h, void *xh);
+hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, const float *pool_h,
+                                bf16_t *xh);
 hipError_t launch_lstm_pointwise(hipStream_t st, const Dims &d, int dtype, int pairs, int layer, AView A, RowView rv,
                                  const float *gates, float *pool_h, float *pool_c, long pool_rows, void *xh_next,
                                  void *htop);
