@@ -12,14 +12,23 @@
 
 #define WAVE 64
 
+// log(exp(a) + exp(b)); the correction term lies in [0, log 2] and is taken in fp32
+// (absolute error ~1e-7, far inside the score tolerance), the sum stays fp64
 __device__ __forceinline__ double log_add(double a, double b) {
     double mx = a > b ? a : b, mn = a > b ? b : a;
     if (isinf(mx)) return mx;
-    return mx + log1p(exp(mn - mx));
+    return mx + (double)log1pf(expf((float)(mn - mx)));
 }
 
 __device__ __forceinline__ u64 hash_append(u64 h, int token) {
     return (h ^ (u64)(unsigned)(token + 1)) * 0x100000001B3ull + 0x9E3779B97F4A7C15ull;
+}
+
+// value of lane `src` (uniform) of a double held one per lane, through scalar reads (no LDS round trip)
+__device__ __forceinline__ double lane_value(double v, int src) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+    return __hiloint2double(hi, lo);
 }
 
 __device__ bool same_sequence(const int2 *nodes, int a, int b) {
@@ -31,6 +40,16 @@ __device__ bool same_sequence(const int2 *nodes, int a, int b) {
         b = nb.x;
     }
     return true;
+}
+
+// Values handed from every workgroup of a launch to the one that runs the scan travel as
+// device-scope atomics (they bypass the per-CU L1 and the per-XCD L2), so publishing them needs
+// no cache write-back: the writer only waits for its own stores before taking a ticket.
+__device__ __forceinline__ int load_fresh(const int *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_fresh(int *p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes, int *host_counts);
@@ -90,9 +109,9 @@ __global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, B
     int u = blockIdx.x, lane = threadIdx.x;
     int left = utt_T[u] - seg * d.S;
     int sp = left < 0 ? 0 : (left > d.S ? d.S : left);
-    if (lane == 0) rv.utt_sp[u] = sp;
+    if (lane == 0) store_fresh(rv.utt_sp + u, sp);
     if (sp == 0) {  // finished (or empty) utterance: B keeps the final list
-        if (lane == 0) A.count[u] = 0;
+        if (lane == 0) store_fresh(A.count + u, 0);
     } else {
         int nB = B.count[u];
         const double *bl = B.logs + (long)u * d.BCAP;
@@ -119,7 +138,7 @@ __global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, B
             }
         }
         if (lane == 0) {
-            A.count[u] = nB < d.N ? nB : d.N;
+            store_fresh(A.count + u, nB < d.N ? nB : d.N);
             B.count[u] = 0;
         }
     }
@@ -160,11 +179,6 @@ hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv,
 // kernel that produced the new counts (segment head or select/merge) runs an
 // exclusive scan over the utterances with one wave and publishes the totals to
 // the host; a second, fully parallel kernel then fills the pair and row lists.
-__device__ __forceinline__ int load_fresh(const int *p) {
-    // value written by another workgroup of this launch: read it past this CU's L1
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 __device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes,
                                 int *host_counts) {
     const int lane = threadIdx.x & 63;
@@ -235,11 +249,12 @@ __device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv
 // Called by every workgroup (one wave each) at its end; true in the last one to arrive.
 __device__ bool last_workgroup(const RowView &rv, int n_groups) {
     __shared__ int s_last;
-    __threadfence();
+    __builtin_amdgcn_s_waitcnt(0);   // this wave's published stores have been acknowledged
     __syncthreads();
-    if (threadIdx.x == 0) s_last = atomicAdd(&rv.counts[TBS_CNT_TICKET], 1) == n_groups - 1;
+    if (threadIdx.x == 0)
+        s_last = __hip_atomic_fetch_add(&rv.counts[TBS_CNT_TICKET], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                 n_groups - 1;
     __syncthreads();
-    if (s_last) __threadfence();
     return s_last != 0;
 }
 
@@ -318,6 +333,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
     __shared__ u64 s_ahash[TBS_MAX_BEAM];
     __shared__ int s_anode[TBS_MAX_BEAM], s_alen[TBS_MAX_BEAM], s_aslot[TBS_MAX_BEAM];
     __shared__ double s_bkey[TBS_MAX_BEAM];
+    __shared__ int s_match[TBS_MAX_BEAM];
     __shared__ int s_sel[TBS_MAX_BEAM];      // candidate index by rank
     __shared__ int s_keep[TBS_MAX_BEAM];
     __shared__ double s_thr;
@@ -325,7 +341,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
     const int N = d.N;
     const int H = rv.utt_sp[u] > 0 ? A.count[u] : 0;
     if (H == 0) {
-        if (lane == 0) An.count[u] = 0;
+        if (lane == 0) store_fresh(An.count + u, 0);
     } else {
         const int pair0 = rv.utt_pair0[u];
         const long bbase = (long)u * d.BCAP;
@@ -347,7 +363,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
             s_anode[lane] = A.node[a];
             s_alen[lane] = A.len[a];
             s_aslot[lane] = A.slot[a];
-            s_bkey[lane] = al + log((double)dphi[pair0 + lane]);   // score of the blank expansion
+            s_bkey[lane] = al + (double)logf(dphi[pair0 + lane]);   // score of the blank expansion
         }
         if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
         const int nc = H * N;
@@ -358,34 +374,42 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
         __syncthreads();
         for (int c = lane; c < nc; c += WAVE) s_key[c] = s_ctok[c] >= 0 ? s_alogs[c / N] + s_key[c] : nan("");
 
-        // --- AddAndMerge of every blank expansion, in hypothesis order
-        for (int h = 0; h < H; ++h) {
-            const u64 hs = s_ahash[h];
-            const int ln = s_alen[h], nd = s_anode[h];
-            int found = 0x7fffffff;
-            for (int base = 0; base < nB; base += WAVE) {
-                const int i = base + lane;
-                bool hit = false;
-                if (i < nB && s_bhash[i] == hs && s_blen[i] == ln) hit = same_sequence(nodes, s_bnode[i], nd);
-                const u64 m = __ballot(hit);
-                if (m) { found = base + __ffsll((long long)m) - 1; break; }   // at most one entry can match
-            }
-            if (found != 0x7fffffff) {
-                if (lane == 0) s_blogs[found] = log_add(s_blogs[found], s_bkey[h]);
-            } else if (nB < d.BCAP) {
-                if (lane == 0) {
-                    s_blogs[nB] = s_bkey[h];
-                    s_bhash[nB] = hs;
-                    s_bnode[nB] = nd;
-                    s_blen[nB] = ln;
-                    s_bslot[nB] = s_aslot[h];
-                }
-                ++nB;
-            } else if (lane == 0) {
-                atomicOr(&rv.counts[TBS_CNT_ERR], TBS_ERRF_BCAP);
-            }
-            __syncthreads();
+        // --- AddAndMerge of every blank expansion.  The hypotheses of A are distinct sequences and so
+        // are the entries of B, so each hypothesis matches at most one old entry and no entry added in
+        // this round: all (hypothesis, entry) pairs are tested at once, matched scores are summed in
+        // place, and the unmatched hypotheses are appended in hypothesis order.
+        if (lane < H) s_match[lane] = -1;
+        __syncthreads();
+        for (int c = lane; c < H * nB0; c += WAVE) {
+            const int h = c / nB0, i = c - h * nB0;
+            if (s_bhash[i] == s_ahash[h] && s_blen[i] == s_alen[h] && same_sequence(nodes, s_bnode[i], s_anode[h]))
+                s_match[h] = i;
         }
+        __syncthreads();
+        {
+            const bool unmatched = lane < H && s_match[lane] < 0;
+            const u64 um = __ballot(unmatched);
+            const int n_new = __popcll(um);
+            if (lane < H) {
+                if (!unmatched) {
+                    const int f = s_match[lane];
+                    s_blogs[f] = log_add(s_blogs[f], s_bkey[lane]);
+                } else {
+                    const int pos = nB0 + __popcll(um & ((1ull << lane) - 1ull));
+                    if (pos < d.BCAP) {
+                        s_blogs[pos] = s_bkey[lane];
+                        s_bhash[pos] = s_ahash[lane];
+                        s_bnode[pos] = s_anode[lane];
+                        s_blen[pos] = s_alen[lane];
+                        s_bslot[pos] = s_aslot[lane];
+                    } else {
+                        atomicOr(&rv.counts[TBS_CNT_ERR], TBS_ERRF_BCAP);
+                    }
+                }
+            }
+            nB = min(nB0 + n_new, d.BCAP);
+        }
+        __syncthreads();
         // --- B back to memory: merged scores of old entries, and the new entries
         for (int i = lane; i < nB; i += WAVE) {
             B.logs[bbase + i] = s_blogs[i];
@@ -400,7 +424,18 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
 
         // --- threshold = ChooseNthScore(B, N), only defined when B holds N entries
         const bool have_thr = nB >= N;
-        if (have_thr) {
+        if (have_thr && nB <= 2 * WAVE) {
+            // rank of entry c = number of entries that beat it: the lanes hold the entries, one ballot per c
+            const double e0 = lane < nB ? s_blogs[lane] : nan(""), e1 = lane + WAVE < nB ? s_blogs[lane + WAVE] : nan("");
+#pragma unroll 4
+            for (int c = 0; c < nB; ++c) {
+                const double sc = c < WAVE ? lane_value(e0, c) : lane_value(e1, c - WAVE);
+                const bool b0 = e0 > sc || (e0 == sc && lane < c);
+                const bool b1 = e1 > sc || (e1 == sc && lane + WAVE < c);
+                const int rank = __popcll(__ballot(b0)) + __popcll(__ballot(b1));
+                if (rank == N - 1 && lane == 0) s_thr = sc;
+            }
+        } else if (have_thr) {
             for (int i = lane; i < nB; i += WAVE) {
                 const double si = s_blogs[i];
                 int rank = 0;
@@ -411,21 +446,40 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
                 if (rank == N - 1) s_thr = si;
             }
         }
-        // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates
-        for (int c = lane; c < nc; c += WAVE) {
-            const double kc = s_key[c];
-            if (kc != kc) continue;  // no candidate in this place
-            const int hc = c / N, tc = s_ctok[c];
-            int rank = 0;
-            for (int j = 0; j < nc; ++j) {
-                const double kj = s_key[j];
-                if (kj != kj || j == c) continue;
-                const int hj = j / N;
-                bool better = kj > kc;
-                if (kj == kc) better = (hj < hc) || (hj == hc && s_ctok[j] < tc);
-                rank += better;
+        // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates.  The rank of
+        // candidate c is the number of candidates that beat it; the lanes hold the candidates and one
+        // ballot per c counts them.
+        if (nc <= 2 * WAVE) {
+            const int j0 = lane, j1 = lane + WAVE;
+            const double k0 = j0 < nc ? s_key[j0] : nan(""), k1 = j1 < nc ? s_key[j1] : nan("");
+            const int t0 = j0 < nc ? s_ctok[j0] : 0, t1 = j1 < nc ? s_ctok[j1] : 0;
+            const int h0 = j0 / N, h1 = j1 / N;
+#pragma unroll 4
+            for (int c = 0; c < nc; ++c) {
+                const double kc = c < WAVE ? lane_value(k0, c) : lane_value(k1, c - WAVE);
+                const int tc = c < WAVE ? __builtin_amdgcn_readlane(t0, c) : __builtin_amdgcn_readlane(t1, c - WAVE);
+                const int hc = c / N;
+                const bool b0 = k0 > kc || (k0 == kc && (h0 < hc || (h0 == hc && t0 < tc)));
+                const bool b1 = k1 > kc || (k1 == kc && (h1 < hc || (h1 == hc && t1 < tc)));
+                const int rank = __popcll(__ballot(b0)) + __popcll(__ballot(b1));
+                if (kc == kc && rank < N && lane == 0) s_sel[rank] = c;   // kc != kc: no candidate in this place
             }
-            if (rank < N) s_sel[rank] = c;
+        } else {
+            for (int c = lane; c < nc; c += WAVE) {
+                const double kc = s_key[c];
+                if (kc != kc) continue;  // no candidate in this place
+                const int hc = c / N, tc = s_ctok[c];
+                int rank = 0;
+                for (int j = 0; j < nc; ++j) {
+                    const double kj = s_key[j];
+                    if (kj != kj || j == c) continue;
+                    const int hj = j / N;
+                    bool better = kj > kc;
+                    if (kj == kc) better = (hj < hc) || (hj == hc && s_ctok[j] < tc);
+                    rank += better;
+                }
+                if (rank < N) s_sel[rank] = c;
+            }
         }
         __syncthreads();
         // --- threshold test, in rank order: keep iff |B| < N or score > threshold (strict)
@@ -436,7 +490,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
         }
         __syncthreads();
         if (drop) {
-            if (lane == 0) An.count[u] = 0;
+            if (lane == 0) store_fresh(An.count + u, 0);
         } else {
             int pos = 0, total = 0;
             for (int r = 0; r < N; ++r) {
@@ -444,7 +498,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
                 if (r < lane) pos += k;
                 total += k;
             }
-            if (lane == 0) An.count[u] = total;
+            if (lane == 0) store_fresh(An.count + u, total);
             if (lane < N && s_keep[lane]) {
                 const int c = s_sel[lane];
                 const int h = c / N;

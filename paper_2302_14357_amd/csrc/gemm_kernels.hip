@@ -89,13 +89,19 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
         lb[i] = BM * BK + row * BK + ((kc ^ gemm_swz<BK>(row)) * 8);
     }
     // global sources of the current tile (rows clamped, so reads stay in bounds)
+    // Without a K guard the tiles go from global memory straight into LDS (no registers in
+    // between): lane l of a wave always fills LDS slot l of the wave's 1 KB destination, so it is
+    // the global chunk that is chosen per lane: slot position p of row r receives chunk p ^ swz(r).
+    constexpr bool DIRECT = !KGUARD;
+    const int kcg = DIRECT ? (kc ^ gemm_swz<BK>(crow)) : kc;   // ROWS_PER_PASS is a multiple of 16
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const bf16_t *ga[A_CHUNKS], *gb[B_CHUNKS];
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i)
-        ga[i] = A + (long)min(tile_m * BM + crow + ROWS_PER_PASS * i, M - 1) * K + kc * 8;
+        ga[i] = A + (long)min(tile_m * BM + crow + ROWS_PER_PASS * i, M - 1) * K + kcg * 8;
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i)
-        gb[i] = B + (long)min(tile_n * BN + crow + ROWS_PER_PASS * i, N - 1) * K + kc * 8;
+        gb[i] = B + (long)min(tile_n * BN + crow + ROWS_PER_PASS * i, N - 1) * K + kcg * 8;
 
     // fragment addresses: lane reads row (lane & 31) of a 32-row block, K chunk 2*kk + (lane >> 5)
     const int frow = lane & 31, fsel = lane >> 5;
@@ -109,8 +115,20 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
     const int ktiles = (K + BK - 1) / BK;
     uint4 ra[A_CHUNKS], rb[B_CHUNKS];
     // prologue: K tile 0 of the first tile -> LDS buffer 0
-    {
-        const bool in = !KGUARD || (kc * 8 < K);
+    if (DIRECT) {
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)ga[i],
+                                             (__attribute__((address_space(3))) void *)(smem + (i * NT + wave_u * 64) * 8),
+                                             16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gb[i],
+                                             (__attribute__((address_space(3))) void *)(smem + BM * BK + (i * NT + wave_u * 64) * 8),
+                                             16, 0, 0);
+        __builtin_amdgcn_s_waitcnt(0);
+    } else {
+        const bool in = kc * 8 < K;
 #pragma unroll
         for (int i = 0; i < A_CHUNKS; ++i) ra[i] = in ? *reinterpret_cast<const uint4 *>(ga[i]) : make_uint4(0, 0, 0, 0);
 #pragma unroll
@@ -139,26 +157,39 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
         const bf16_t *gan[A_CHUNKS], *gbn[B_CHUNKS];
 #pragma unroll
         for (int i = 0; i < A_CHUNKS; ++i)
-            gan[i] = have_next ? A + (long)min(next_m * BM + crow + ROWS_PER_PASS * i, M - 1) * K + kc * 8 : ga[i];
+            gan[i] = have_next ? A + (long)min(next_m * BM + crow + ROWS_PER_PASS * i, M - 1) * K + kcg * 8 : ga[i];
 #pragma unroll
         for (int i = 0; i < B_CHUNKS; ++i)
-            gbn[i] = have_next ? B + (long)min(next_n * BN + crow + ROWS_PER_PASS * i, N - 1) * K + kc * 8 : gb[i];
+            gbn[i] = have_next ? B + (long)min(next_n * BN + crow + ROWS_PER_PASS * i, N - 1) * K + kcg * 8 : gb[i];
 
         for (int kt = 0; kt < ktiles; ++kt) {
             const bf16_t *cur = smem + buf * TILE_ELEMS;
             bf16_t *nxt = smem + (buf ^ 1) * TILE_ELEMS;
             const bool last = kt + 1 == ktiles;
             const int kn = last ? 0 : (kt + 1) * BK;
-            const bool in = !KGUARD || (kn + kc * 8 < K);
+            if (DIRECT) {
 #pragma unroll
-            for (int i = 0; i < A_CHUNKS; ++i) {
-                const bf16_t *src = (last ? gan[i] : ga[i]) + kn;
-                ra[i] = in ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
-            }
+                for (int i = 0; i < A_CHUNKS; ++i)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)((last ? gan[i] : ga[i]) + kn),
+                        (__attribute__((address_space(3))) void *)(nxt + (i * NT + wave_u * 64) * 8), 16, 0, 0);
 #pragma unroll
-            for (int i = 0; i < B_CHUNKS; ++i) {
-                const bf16_t *src = (last ? gbn[i] : gb[i]) + kn;
-                rb[i] = in ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
+                for (int i = 0; i < B_CHUNKS; ++i)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)((last ? gbn[i] : gb[i]) + kn),
+                        (__attribute__((address_space(3))) void *)(nxt + BM * BK + (i * NT + wave_u * 64) * 8), 16, 0, 0);
+            } else {
+                const bool in = kn + kc * 8 < K;
+#pragma unroll
+                for (int i = 0; i < A_CHUNKS; ++i) {
+                    const bf16_t *src = (last ? gan[i] : ga[i]) + kn;
+                    ra[i] = in ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < B_CHUNKS; ++i) {
+                    const bf16_t *src = (last ? gbn[i] : gb[i]) + kn;
+                    rb[i] = in ? *reinterpret_cast<const uint4 *>(src) : make_uint4(0, 0, 0, 0);
+                }
             }
             // keep the prefetch ahead of the multiply: without this fence the compiler sinks the
             // loads down to their first use (the LDS stores below) and exposes their latency
@@ -179,10 +210,14 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
             }
             // the other buffer was last read one iteration ago, which every wave has left
+            if (DIRECT) {
+                __builtin_amdgcn_s_waitcnt(0);   // this wave's direct loads have landed in LDS
+            } else {
 #pragma unroll
-            for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<uint4 *>(nxt + la[i]) = ra[i];
+                for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<uint4 *>(nxt + la[i]) = ra[i];
 #pragma unroll
-            for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<uint4 *>(nxt + lb[i]) = rb[i];
+                for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<uint4 *>(nxt + lb[i]) = rb[i];
+            }
             __syncthreads();
             buf ^= 1;
         }

@@ -62,22 +62,27 @@ hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView 
 
 // LSTM cell, gate order i, f, g, o; gates already hold W x + W h + b.
 __global__ void k_lstm_pointwise(Dims d, int dtype, int layer, AView A, RowView rv, const float *gates,
-                                 float *pool_h, float *pool_c, long pool_rows, void *xh_next, void *htop) {
+                                 float *pool_h, float *pool_c, long pool_rows, void *xh_next, void *htop,
+                                 const float *emb_gates) {
     int j = blockIdx.x;
     int u = rv.pair_u[j], hh = rv.pair_h[j];
     long a = (long)u * d.N + hh;
     long ps = A.pslot[a], ns = A.slot[a];
     const float *g = gates + (long)j * 4 * d.H;
+    // first layer of bf16 models: the embedding half of the gates (and the bias) comes from the table
+    const float *eg = emb_gates ? emb_gates + (long)rv.pair_tok[j] * 4 * d.H : nullptr;
     const float *c_par = pool_c + ((long)layer * pool_rows + ps) * d.H;
     float *c_new = pool_c + ((long)layer * pool_rows + ns) * d.H;
     float *h_new = pool_h + ((long)layer * pool_rows + ns) * d.H;
     const bool last = layer + 1 == d.L;
     const float *h_par_next = last ? nullptr : pool_h + ((long)(layer + 1) * pool_rows + ps) * d.H;
     for (int i = threadIdx.x; i < d.H; i += blockDim.x) {
-        float ig = sigmoidf_(g[i]);
-        float fg = sigmoidf_(g[d.H + i]);
-        float gg = tanhf(g[2 * d.H + i]);
-        float og = sigmoidf_(g[3 * d.H + i]);
+        float gi = g[i], gf = g[d.H + i], gc = g[2 * d.H + i], go = g[3 * d.H + i];
+        if (eg) { gi += eg[i]; gf += eg[d.H + i]; gc += eg[2 * d.H + i]; go += eg[3 * d.H + i]; }
+        float ig = sigmoidf_(gi);
+        float fg = sigmoidf_(gf);
+        float gg = tanhf(gc);
+        float og = sigmoidf_(go);
         float c = fg * c_par[i] + ig * gg;
         float hv = og * tanhf(c);
         c_new[i] = c;
@@ -102,10 +107,10 @@ __global__ void k_lstm_pointwise(Dims d, int dtype, int layer, AView A, RowView 
 
 hipError_t launch_lstm_pointwise(hipStream_t st, const Dims &d, int dtype, int pairs, int layer, AView A, RowView rv,
                                  const float *gates, float *pool_h, float *pool_c, long pool_rows, void *xh_next,
-                                 void *htop) {
+                                 void *htop, const float *emb_gates) {
     if (pairs <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_lstm_pointwise, dim3(pairs), dim3(256), 0, st, d, dtype, layer, A, rv, gates, pool_h,
-                       pool_c, pool_rows, xh_next, htop);
+                       pool_c, pool_rows, xh_next, htop, emb_gates);
     return hipGetLastError();
 }
 

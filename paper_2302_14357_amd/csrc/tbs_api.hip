@@ -479,13 +479,13 @@ int tbs_predictor_step(tbs_ctx *c) {
             int in_dim = l == 0 ? d.E : d.H;
             if (l == 0 && c->emb_gates)
                 HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->xh[0], (const bf16_t *)c->w.w_hh[0],
-                                           nullptr, c->gates, pairs, 4 * d.H, d.H, nullptr, 4L * d.H, c->emb_gates,
-                                           c->rv.pair_tok));
+                                           nullptr, c->gates, pairs, 4 * d.H, d.H, nullptr, 4L * d.H));
             else
                 HIPCHK(c, gemm(c, c->xh[l & 1], c->wcat[l], c->w.b_lstm[l], c->gates, pairs, 4 * d.H,
                                in_dim + d.H, nullptr, 4L * d.H));
             HIPCHK(c, launch_lstm_pointwise(c->stream, d, c->cfg.dtype, pairs, l, A, c->rv, c->gates, c->pool_h,
-                                            c->pool_c, c->pool_rows, c->xh[(l + 1) & 1], c->htop));
+                                            c->pool_c, c->pool_rows, c->xh[(l + 1) & 1], c->htop,
+                                            l == 0 ? c->emb_gates : nullptr));
         }
         HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, pairs, d.Dj, d.H, c->rv.pair_slot, d.Dj));
     }

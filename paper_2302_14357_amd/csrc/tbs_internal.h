@@ -95,7 +95,7 @@ hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView 
                                 bf16_t *xh);
 hipError_t launch_lstm_pointwise(hipStream_t st, const Dims &d, int dtype, int pairs, int layer, AView A, RowView rv,
                                  const float *gates, float *pool_h, float *pool_c, long pool_rows, void *xh_next,
-                                 void *htop);
+                                 void *htop, const float *emb_gates);
 hipError_t launch_finalize(hipStream_t st, const Dims &d, BView B, const int2 *nodes, int *res_count, int *res_len,
                            double *res_logs, int *res_tok, int max_len, int *ovf);
 hipError_t launch_hyps_dump(hipStream_t st, const Dims &d, int group, AView A, BView B, const int2 *nodes, int cap,
