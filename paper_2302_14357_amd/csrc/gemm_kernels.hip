@@ -307,11 +307,12 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
     if (M <= 0) return hipSuccess;
     int v = g_tbs_gemm_variant;
     if (v == 0) {
-        // measured on MI355X: 256x256 tiles (8 waves) once they fill the chip 1.5 times over,
-        // 128x128 (two workgroups per CU) for mid sizes, 64x64 so that small problems still spread
+        // measured on MI355X: 256x256 tiles (8 waves, 64x128 per wave) once they fill the chip 1.5
+        // times over, 128x128 (two workgroups per CU) for mid sizes, 64x64 so that small problems
+        // still spread over the CUs
         long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
         long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-        v = t256 >= 384 ? 5 : (t128 >= 256 ? 2 : 1);
+        v = t256 >= 384 ? 6 : (t128 >= 256 ? 2 : 1);
     }
     switch (v) {
         case 1: return gemm_launch<1, 1, 2, 2, 64, 4>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 64x64, 4 waves
