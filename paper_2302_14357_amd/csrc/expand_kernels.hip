@@ -157,10 +157,10 @@ k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *_
 // ------------------------------------------------------------------ register-resident variant
 // When the S' x V logits of one hypothesis fit in the registers of one workgroup
 // (V <= 1024 NV4 columns, S' <= SMAX), every logit is read from memory exactly
-// once and exponentiated exactly once: each thread keeps e = exp(l - m_loc) of
-// its own columns with its own row maximum m_loc, the (max, sum) pairs are
-// merged across the workgroup in one step, and the streaming sum of Eq. 4-6
-// becomes delta_nb[k] = sum_t (c_t exp(m_loc_t - m_t)) e[t][k].  The N best
+// once and exponentiated exactly once: the row maxima m_t are reduced across the
+// workgroup first, each thread then keeps e = exp(l - m_t) of its own columns,
+// the row sums Z_t follow from one more reduction, and the streaming sum of
+// Eq. 4-6 becomes delta_nb[k] = sum_t c_t e[t][k] from registers.  The N best
 // are then taken per wave from registers and merged by the first wave.
 template <int NV4, int SMAX>
 __global__ void __launch_bounds__(EXP_THREADS)
@@ -181,11 +181,10 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
 
     // ---- one pass over memory: this thread's columns of every row
     float e[SMAX][NC];
-    float mloc[SMAX], zloc[SMAX];
+    float mrow[SMAX];
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) {
-        mloc[t] = -INFINITY;
-        zloc[t] = 0.f;
+        mrow[t] = -INFINITY;
         if (t < sp) {
 #pragma unroll
             for (int q = 0; q < NV4; ++q) {
@@ -193,48 +192,54 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
                 float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
                 if (i4 < V4) x = L4[(long)t * V4 + i4];
                 e[t][4 * q + 0] = x.x; e[t][4 * q + 1] = x.y; e[t][4 * q + 2] = x.z; e[t][4 * q + 3] = x.w;
-                mloc[t] = fmaxf(mloc[t], fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w)));
+                mrow[t] = fmaxf(mrow[t], fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w)));
             }
         } else {
 #pragma unroll
             for (int c = 0; c < NC; ++c) e[t][c] = -INFINITY;
         }
     }
-    // the thread that owns the blank column publishes its raw logits
+    // ---- row maxima across the workgroup (waves by shuffles, then through LDS)
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) {
+        float m = mrow[t];
+        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+        if (lane == 0) s_pm[wave][t] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) {
+        float m = s_pm[0][t];
+#pragma unroll
+        for (int w = 1; w < EXP_WAVES; ++w) m = fmaxf(m, s_pm[w][t]);
+        mrow[t] = t < sp ? m : 0.f;
+    }
+    // ---- e = exp(l - m_t), once per logit; row sums across the workgroup; the owner of the blank
+    // column publishes its exponentials
     {
         const int bq = (d.blank >> 2) / EXP_THREADS, bt = (d.blank >> 2) % EXP_THREADS, bc = d.blank & 3;
-        if (tid == bt) {
 #pragma unroll
-            for (int t = 0; t < SMAX; ++t)
+        for (int t = 0; t < SMAX; ++t) {
+            const float nm = -mrow[t] * 1.44269504088896341f;
+            float z = 0.f;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));
+                z += e[t][c];
+            }
+            for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off);
+            if (lane == 0) s_pz[wave][t] = z;
+            if (tid == bt) {
 #pragma unroll
                 for (int q = 0; q < NV4; ++q)
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
                         if (q == bq && c == bc) s_blank[t] = e[t][4 * q + c];
+            }
         }
-    }
-#pragma unroll
-    for (int t = 0; t < SMAX; ++t) {
-        const float mref = mloc[t] == -INFINITY ? 0.f : mloc[t];   // a thread (or row) with no columns
-        const float nm = -mref * 1.44269504088896341f;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));   // exp(l - m_loc)
-            zloc[t] += e[t][c];
-        }
-    }
-    // ---- (max, sum) of every row across the workgroup
-#pragma unroll
-    for (int t = 0; t < SMAX; ++t) {
-        float m = mloc[t], z = zloc[t];
-        for (int off = 32; off > 0; off >>= 1) {
-            float m2 = __shfl_xor(m, off), z2 = __shfl_xor(z, off);
-            ms_combine(m, z, m2, z2);
-        }
-        if (lane == 0) { s_pm[wave][t] = m; s_pz[wave][t] = z; }
     }
     __syncthreads();
-    // ---- every thread: row statistics, forward variable (Eq. 3 as a scan), Eq. 7, its own coefficients
+    // ---- every thread: row sums, forward variable (Eq. 3 as a scan), Eq. 7, the row coefficients
     float cf[SMAX];
     {
         const float *dold = A.dhat + ((long)u * d.N + h) * d.S;
@@ -243,18 +248,18 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
         for (int t = 0; t < SMAX; ++t) {
             cf[t] = 0.f;
             if (t < sp) {
-                float m = s_pm[0][t], z = s_pz[0][t];
+                float z = s_pz[0][t];
 #pragma unroll
-                for (int w = 1; w < EXP_WAVES; ++w) ms_combine(m, z, s_pm[w][t], s_pz[w][t]);
-                const float b = __expf(s_blank[t] - m) / z;
+                for (int w = 1; w < EXP_WAVES; ++w) z += s_pz[w][t];
+                const float b = s_blank[t] / z;
                 alpha = (t == 0 ? 0.f : alpha * bprev) + dold[t];
                 bprev = b;
                 const float c = alpha / z;
-                cf[t] = mloc[t] == -INFINITY ? 0.f : c * __expf(mloc[t] - m);
+                cf[t] = c;
                 if (tid == 0) {
-                    row_lc[row0 + t] = c > 0.f ? __logf(c) - m : -INFINITY;
+                    row_lc[row0 + t] = c > 0.f ? __logf(c) - mrow[t] : -INFINITY;
                     if (row_stats) {
-                        row_stats[(long)(row0 + t) * 3 + 0] = m;
+                        row_stats[(long)(row0 + t) * 3 + 0] = mrow[t];
                         row_stats[(long)(row0 + t) * 3 + 1] = z;
                         row_stats[(long)(row0 + t) * 3 + 2] = b;
                     }
