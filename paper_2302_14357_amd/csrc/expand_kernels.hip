@@ -28,6 +28,52 @@ __device__ __forceinline__ void ms_combine(float &m, float &z, float m2, float z
     z = a + b;
 }
 
+// ---- wave-wide reductions without LDS traffic: four DPP steps make every lane of a 16-lane row
+// hold the row's result, four scalar lane reads combine the rows.  The result is uniform.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+#define DPP_QUAD_SWAP1 0xB1   // quad_perm [1,0,3,2]
+#define DPP_QUAD_SWAP2 0x4E   // quad_perm [2,3,0,1]
+#define DPP_HALF_MIRROR 0x141
+#define DPP_MIRROR 0x140
+__device__ __forceinline__ float lane_f(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_f<DPP_QUAD_SWAP1>(v));
+    v = fmaxf(v, dpp_f<DPP_QUAD_SWAP2>(v));
+    v = fmaxf(v, dpp_f<DPP_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_f<DPP_MIRROR>(v));
+    return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp_f<DPP_QUAD_SWAP1>(v);
+    v += dpp_f<DPP_QUAD_SWAP2>(v);
+    v += dpp_f<DPP_HALF_MIRROR>(v);
+    v += dpp_f<DPP_MIRROR>(v);
+    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+}
+__device__ __forceinline__ int wave_min_int(int v) {
+    v = min(v, dpp_i<DPP_QUAD_SWAP1>(v));
+    v = min(v, dpp_i<DPP_QUAD_SWAP2>(v));
+    v = min(v, dpp_i<DPP_HALF_MIRROR>(v));
+    v = min(v, dpp_i<DPP_MIRROR>(v));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+// largest value of the wave and, among the lanes that hold it, the smallest key
+__device__ __forceinline__ void wave_argmax(float &bv, int &bk) {
+    const float wm = wave_max(bv);
+    bk = wave_min_int(bv == wm ? bk : 0x7fffffff);
+    bv = wm;
+}
+
 template <bool VEC4>
 __global__ void __launch_bounds__(EXP_THREADS)
 k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
@@ -202,8 +248,7 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
     // ---- row maxima across the workgroup (waves by shuffles, then through LDS)
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) {
-        float m = mrow[t];
-        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+        const float m = wave_max(mrow[t]);
         if (lane == 0) s_pm[wave][t] = m;
     }
     __syncthreads();
@@ -227,7 +272,7 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
                 e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));
                 z += e[t][c];
             }
-            for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off);
+            z = wave_sum(z);
             if (lane == 0) s_pz[wave][t] = z;
             if (tid == bt) {
 #pragma unroll
@@ -296,43 +341,39 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
     }
     // ---- candidates of this wave.  tau = the N-th largest of the 64 per-thread maxima is a lower
     // bound of the wave's N-th largest score, so every score >= tau is a candidate (ties included)
-    // and usually only a few more than N qualify.  The maxima are ranked with a bitonic network.
-    float lmax = 0.f;
+    // and usually only a few more than N qualify.  tau comes from N rounds of wave maximum over the
+    // thread maxima (one lane retires per round); candidates are compacted with ballots.
+    float tau = 0.f;
+    {
+        float lm = 0.f;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) lmax = fmaxf(lmax, v[c]);
-    float sv = lmax;
-#pragma unroll
-    for (int k = 2; k <= 64; k <<= 1)
-#pragma unroll
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            const float o = __shfl_xor(sv, j);
-            const bool desc = (lane & k) == 0, lower = (lane & j) == 0;
-            sv = (lower == desc) ? fmaxf(sv, o) : fminf(sv, o);
+        for (int c = 0; c < NC; ++c) lm = fmaxf(lm, v[c]);
+        for (int n = 0; n < d.N; ++n) {
+            tau = wave_max(lm);
+            if (!(tau > 0.f)) break;   // fewer than N positive maxima: every positive score qualifies
+            const u64 holders = __ballot(lm == tau);
+            if (lane == __ffsll((long long)holders) - 1) lm = -1.f;
         }
-    const float tau = __shfl(sv, d.N - 1);
-    int cnt = 0;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) cnt += (v[c] > 0.f && v[c] >= tau) ? 1 : 0;
-    int incl = cnt;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
     }
-    const int total = __shfl(incl, 63);
-    if (total <= EXP_CAND_CAP) {
-        int pos = incl - cnt;
+    int total = 0;
+    {
+        const u64 below = (1ull << lane) - 1ull;
 #pragma unroll
         for (int q = 0; q < NV4; ++q)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const float x = v[4 * q + c];
-                if (x > 0.f && x >= tau) {
+                const bool take = x > 0.f && x >= tau;
+                const u64 m = __ballot(take);
+                const int pos = total + __popcll(m & below);
+                if (take && pos < EXP_CAND_CAP) {
                     s_cv[wave][pos] = x;
                     s_ck[wave][pos] = 4 * (tid + EXP_THREADS * q) + c;
-                    ++pos;
                 }
+                total += __popcll(m);
             }
+    }
+    if (total <= EXP_CAND_CAP) {
         if (lane == 0) s_cn[wave] = total;
     } else {
         // many equal scores: take exactly the N best by N rounds of wave arg-max
@@ -344,13 +385,9 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const float x = v[4 * q + c];
-                    if (x > bv) { bv = x; bk = 4 * (tid + EXP_THREADS * q) + c; }
+                    if (x > bv) { bv = x; bk = 4 * (tid + EXP_THREADS * q) + c; }   // ascending columns
                 }
-            for (int off = 32; off > 0; off >>= 1) {
-                float ov = __shfl_xor(bv, off);
-                int ok = __shfl_xor(bk, off);
-                if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
-            }
+            wave_argmax(bv, bk);
             if (lane == 0) { s_cv[wave][n] = bv; s_ck[wave][n] = bk; }
 #pragma unroll
             for (int q = 0; q < NV4; ++q)
@@ -386,11 +423,7 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
 #pragma unroll
             for (int i = 0; i < EXP_WAVES; ++i)
                 if (cv[i] > bv || (cv[i] == bv && ck[i] < bk)) { bv = cv[i]; bk = ck[i]; }
-            for (int off = 32; off > 0; off >>= 1) {
-                float ov = __shfl_xor(bv, off);
-                int ok = __shfl_xor(bk, off);
-                if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
-            }
+            wave_argmax(bv, bk);
             if (lane == 0) {
                 const bool ok = bv > 0.f && bk != 0x7fffffff;
                 cand_score[(long)pair * d.N + n] = ok ? __logf(bv) : -INFINITY;
