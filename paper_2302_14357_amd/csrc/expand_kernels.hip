@@ -208,56 +208,123 @@ k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *_
 // the row sums Z_t follow from one more reduction, and the streaming sum of
 // Eq. 4-6 becomes delta_nb[k] = sum_t c_t e[t][k] from registers.  The N best
 // are then taken per wave from registers and merged by the first wave.
-template <int NV4, int SMAX>
-__global__ void __launch_bounds__(EXP_THREADS)
-k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
-             float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
-             float *__restrict__ row_stats, float *__restrict__ delta_nb) {
-    constexpr int NC = NV4 * 4;  // columns per thread
-    __shared__ float s_pm[EXP_WAVES][SMAX], s_pz[EXP_WAVES][SMAX];
-    __shared__ float s_blank[SMAX];
-    __shared__ float s_cv[EXP_WAVES][EXP_CAND_CAP];
-    __shared__ int s_ck[EXP_WAVES][EXP_CAND_CAP];
-    __shared__ int s_cn[EXP_WAVES];
-    const int pair = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int u = rv.pair_u[pair], h = rv.pair_h[pair];
-    const int row0 = rv.pair_row0[pair], sp = rv.pair_len[pair];
-    const int V = d.V, V4 = V >> 2;
-    const float4 *L4 = reinterpret_cast<const float4 *>(logits + (long)row0 * V);
+//
+// The arithmetic per logit is one exp, one multiply-add for the exponent and two
+// for the sums; everything else below is bookkeeping per wave, and at four waves
+// per hypothesis that bookkeeping costs as many issue cycles as the logits do.  It
+// is therefore written to be short: reductions in the integer domain or with the
+// DPP operand folded into the add, thresholds and ranks by counting against lane
+// values broadcast through scalar registers instead of rounds of arg-max.
+template <int SMAX>
+struct ExpandShared {
+    float pm[SMAX][EXP_WAVES], pz[SMAX][EXP_WAVES];   // per-wave row maxima and row sums
+    float blank[SMAX];
+    float cv[EXP_WAVES][EXP_CAND_CAP];   // candidates of each wave ...
+    int ck[EXP_WAVES][EXP_CAND_CAP];
+    float jv[EXP_WAVES * EXP_CAND_CAP];  // ... and all of them in one list, in any order
+    int jk[EXP_WAVES * EXP_CAND_CAP];
+    int jn;                              // entries of the joint list
+};
 
-    // ---- one pass over memory: this thread's columns of every row
-    float e[SMAX][NC];
+// What a workgroup needs to know of one (utterance, hypothesis) pair besides its logits.
+template <int SMAX>
+struct ExpandPair {
+    int pair, row0, sp;
+    float dold[SMAX];   // frame distribution of the hypothesis' last token (d_old of Eq. 3)
+};
+
+// Row lists and d_old are written by earlier kernels only: read through the constant address
+// space, so that a wave-uniform address becomes a scalar load into scalar registers.
+typedef const __attribute__((address_space(4))) int *cint_p;
+typedef const __attribute__((address_space(4))) float *cfloat_p;
+
+template <int SMAX>
+__device__ __forceinline__ void expand_pair_info(ExpandPair<SMAX> &pi, int pair, const Dims &d, const AView &A,
+                                                 const RowView &rv) {
+    pi.pair = pair;
+    pi.row0 = ((cint_p)rv.pair_row0)[pair];
+    pi.sp = ((cint_p)rv.pair_len)[pair];
+    const int u = ((cint_p)rv.pair_u)[pair], h = ((cint_p)rv.pair_h)[pair];
+    cfloat_p dold = (cfloat_p)A.dhat + ((long)u * d.N + h) * d.S;
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) pi.dold[t] = t < pi.sp ? dold[t] : 0.f;
+}
+
+// One pass over memory: this thread's columns of every row of the pair.  Every request is made
+// whatever S' and V are (rows past S' repeat the last row, columns past V the last column group;
+// expand_pair discards them), so that the loads are straight-line code with scalar row bases.
+template <int NV4, int SMAX>
+__device__ __forceinline__ void expand_load(float (&e)[SMAX][NV4 * 4], const float *__restrict__ logits, int row0,
+                                            int sp, int V) {
+    const int V4 = V >> 2, tid = threadIdx.x;
+    unsigned off[NV4];   // byte offsets within a row
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) off[q] = 16u * (unsigned)min(tid + EXP_THREADS * q, V4 - 1);
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) {
+        const char *row = reinterpret_cast<const char *>(logits + ((long)row0 + max(min(t, sp - 1), 0)) * V);
+#pragma unroll
+        for (int q = 0; q < NV4; ++q) {
+            const float4 x = *reinterpret_cast<const float4 *>(row + off[q]);
+            e[t][4 * q + 0] = x.x; e[t][4 * q + 1] = x.y; e[t][4 * q + 2] = x.z; e[t][4 * q + 3] = x.w;
+        }
+    }
+}
+
+// floats as integers of the same order (and back: the map is its own inverse)
+__device__ __forceinline__ int f2ord(float f) {
+    const int b = __float_as_int(f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float ord2f(int i) { return __int_as_float(i ^ ((i >> 31) & 0x7fffffff)); }
+
+// wave maximum through the integer order: the DPP operand folds into v_max_i32 and the four
+// row results combine on the scalar unit
+__device__ __forceinline__ float wave_max_ord(float f) {
+    int v = f2ord(f);
+    v = max(v, dpp_i<DPP_QUAD_SWAP1>(v));
+    v = max(v, dpp_i<DPP_QUAD_SWAP2>(v));
+    v = max(v, dpp_i<DPP_HALF_MIRROR>(v));
+    v = max(v, dpp_i<DPP_MIRROR>(v));
+    return ord2f(max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+                     max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48))));
+}
+
+// Everything after the load for one pair.
+template <int NV4, int SMAX>
+__device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const ExpandPair<SMAX> &pi,
+                                            ExpandShared<SMAX> &sm, const Dims &d, float *__restrict__ row_lc,
+                                            float *__restrict__ dphi, float *__restrict__ cand_score,
+                                            int *__restrict__ cand_tok, float *__restrict__ row_stats,
+                                            float *__restrict__ delta_nb) {
+    constexpr int NC = NV4 * 4;  // columns per thread
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int V = d.V, V4 = V >> 2;
+    // Rows past S' and columns past V hold copies of real logits (see expand_load): copies leave a
+    // row maximum unchanged, the row sums skip the copied columns, the copied rows get coefficient
+    // zero and the copied columns score zero below.
     float mrow[SMAX];
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) {
         mrow[t] = -INFINITY;
-        if (t < sp) {
 #pragma unroll
-            for (int q = 0; q < NV4; ++q) {
-                const int i4 = tid + EXP_THREADS * q;
-                float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-                if (i4 < V4) x = L4[(long)t * V4 + i4];
-                e[t][4 * q + 0] = x.x; e[t][4 * q + 1] = x.y; e[t][4 * q + 2] = x.z; e[t][4 * q + 3] = x.w;
-                mrow[t] = fmaxf(mrow[t], fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w)));
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < NC; ++c) e[t][c] = -INFINITY;
-        }
+        for (int c = 0; c < NC; ++c) mrow[t] = fmaxf(mrow[t], e[t][c]);
     }
-    // ---- row maxima across the workgroup (waves by shuffles, then through LDS)
+    // ---- row maxima across the workgroup (waves by DPP, then through LDS)
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) {
-        const float m = wave_max(mrow[t]);
-        if (lane == 0) s_pm[wave][t] = m;
+        const float m = wave_max_ord(mrow[t]);
+        if (lane == 0) sm.pm[t][wave] = m;
     }
+    if (tid == 0) sm.jn = 0;
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) {
-        float m = s_pm[0][t];
+        float m = sm.pm[t][0];
 #pragma unroll
-        for (int w = 1; w < EXP_WAVES; ++w) m = fmaxf(m, s_pm[w][t]);
-        mrow[t] = t < sp ? m : 0.f;
+        for (int w = 1; w < EXP_WAVES; ++w) m = fmaxf(m, sm.pm[t][w]);
+        __builtin_amdgcn_sched_barrier(0);   // one row at a time: the partial results of all rows at once cost registers
+        mrow[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(m)));   // uniform: a scalar register
     }
     // ---- e = exp(l - m_t), once per logit; row sums across the workgroup; the owner of the blank
     // column publishes its exponentials
@@ -268,18 +335,23 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
             const float nm = -mrow[t] * 1.44269504088896341f;
             float z = 0.f;
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));
-                z += e[t][c];
+            for (int q = 0; q < NV4; ++q) {
+                float zq = 0.f;
+#pragma unroll
+                for (int c = 4 * q; c < 4 * q + 4; ++c) {
+                    e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));
+                    zq += e[t][c];
+                }
+                z += (tid + EXP_THREADS * q < V4) ? zq : 0.f;
             }
             z = wave_sum(z);
-            if (lane == 0) s_pz[wave][t] = z;
+            if (lane == 0) sm.pz[t][wave] = z;
             if (tid == bt) {
 #pragma unroll
                 for (int q = 0; q < NV4; ++q)
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        if (q == bq && c == bc) s_blank[t] = e[t][4 * q + c];
+                        if (q == bq && c == bc) sm.blank[t] = e[t][4 * q + c];
             }
         }
     }
@@ -287,28 +359,28 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
     // ---- every thread: row sums, forward variable (Eq. 3 as a scan), Eq. 7, the row coefficients
     float cf[SMAX];
     {
-        const float *dold = A.dhat + ((long)u * d.N + h) * d.S;
         float alpha = 0.f, bprev = 0.f;
 #pragma unroll
         for (int t = 0; t < SMAX; ++t) {
             cf[t] = 0.f;
-            if (t < sp) {
-                float z = s_pz[0][t];
+            if (t < pi.sp) {
+                float z = sm.pz[t][0];
 #pragma unroll
-                for (int w = 1; w < EXP_WAVES; ++w) z += s_pz[w][t];
-                const float b = s_blank[t] / z;
-                alpha = (t == 0 ? 0.f : alpha * bprev) + dold[t];
+                for (int w = 1; w < EXP_WAVES; ++w) z += sm.pz[t][w];
+                __builtin_amdgcn_sched_barrier(0);
+                const float b = sm.blank[t] / z;
+                alpha = (t == 0 ? 0.f : alpha * bprev) + pi.dold[t];
                 bprev = b;
                 const float c = alpha / z;
-                cf[t] = c;
+                cf[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(c)));
                 if (tid == 0) {
-                    row_lc[row0 + t] = c > 0.f ? __logf(c) - mrow[t] : -INFINITY;
+                    row_lc[pi.row0 + t] = c > 0.f ? __logf(c) - mrow[t] : -INFINITY;
                     if (row_stats) {
-                        row_stats[(long)(row0 + t) * 3 + 0] = mrow[t];
-                        row_stats[(long)(row0 + t) * 3 + 1] = z;
-                        row_stats[(long)(row0 + t) * 3 + 2] = b;
+                        row_stats[(long)(pi.row0 + t) * 3 + 0] = mrow[t];
+                        row_stats[(long)(pi.row0 + t) * 3 + 1] = z;
+                        row_stats[(long)(pi.row0 + t) * 3 + 2] = b;
                     }
-                    if (t == sp - 1) dphi[pair] = alpha * b;
+                    if (t == pi.sp - 1) dphi[pi.pair] = alpha * b;
                 }
             }
         }
@@ -335,48 +407,69 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
         for (int q = 0; q < NV4; ++q) {
             const int i4 = tid + EXP_THREADS * q;
             if (i4 < V4)
-                reinterpret_cast<float4 *>(delta_nb + (long)pair * V)[i4] =
+                reinterpret_cast<float4 *>(delta_nb + (long)pi.pair * V)[i4] =
                     make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
         }
     }
-    // ---- candidates of this wave.  tau = the N-th largest of the 64 per-thread maxima is a lower
-    // bound of the wave's N-th largest score, so every score >= tau is a candidate (ties included)
-    // and usually only a few more than N qualify.  tau comes from N rounds of wave maximum over the
-    // thread maxima (one lane retires per round); candidates are compacted with ballots.
-    float tau = 0.f;
+    // ---- candidates of this wave: every score >= tau, where tau is a lower bound of the wave's
+    // N-th largest score (ties included, so usually only a few more than N qualify).  Scores are
+    // positive floats, ordered like their bit patterns.
+    float tau;
     {
         float lm = 0.f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) lm = fmaxf(lm, v[c]);
-        for (int n = 0; n < d.N; ++n) {
-            tau = wave_max(lm);
-            if (!(tau > 0.f)) break;   // fewer than N positive maxima: every positive score qualifies
-            const u64 holders = __ballot(lm == tau);
-            if (lane == __ffsll((long long)holders) - 1) lm = -1.f;
+        if (d.N <= 16) {
+            // N-th largest of the 16 quad maxima: each is a score of this wave, so the N-th largest
+            // of them cannot exceed the N-th largest of all.  The low four bits of a key give way to
+            // the quad's number, which makes the keys distinct; every lane counts the keys above its
+            // own, and the quad that counts N-1 holds the threshold (rounded down by those bits).
+            unsigned key = __float_as_uint(lm);
+            key = max(key, (unsigned)dpp_i<DPP_QUAD_SWAP1>((int)key));
+            key = max(key, (unsigned)dpp_i<DPP_QUAD_SWAP2>((int)key));
+            key = (key & ~15u) | (unsigned)(15 - (lane >> 2));
+            int above = 0;
+#pragma unroll
+            for (int g = 0; g < 16; ++g) above += (unsigned)__builtin_amdgcn_readlane((int)key, 4 * g) > key;
+            const u64 at = __ballot(above == d.N - 1);
+            const unsigned kth = (unsigned)__builtin_amdgcn_readlane((int)key, __ffsll((long long)at) - 1);
+            tau = __uint_as_float(kth & ~15u);
+        } else {
+            // N rounds of wave maximum over the thread maxima, one lane retiring per round
+            tau = 0.f;
+            for (int n = 0; n < d.N; ++n) {
+                tau = wave_max(lm);
+                if (!(tau > 0.f)) break;   // fewer than N positive maxima: every positive score qualifies
+                const u64 holders = __ballot(lm == tau);
+                if (lane == __ffsll((long long)holders) - 1) lm = -1.f;
+            }
         }
+        // the smallest normal float stands for "any positive score"
+        tau = fmaxf(tau, 1.17549435e-38f);
     }
     int total = 0;
     {
-        const u64 below = (1ull << lane) - 1ull;
 #pragma unroll
         for (int q = 0; q < NV4; ++q)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const float x = v[4 * q + c];
-                const bool take = x > 0.f && x >= tau;
+                const bool take = x >= tau;
                 const u64 m = __ballot(take);
-                const int pos = total + __popcll(m & below);
-                if (take && pos < EXP_CAND_CAP) {
-                    s_cv[wave][pos] = x;
-                    s_ck[wave][pos] = 4 * (tid + EXP_THREADS * q) + c;
+                if (m) {   // uniform
+                    const int pos = total + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                                                           __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                    if (take && pos < EXP_CAND_CAP) {
+                        sm.cv[wave][pos] = x;
+                        sm.ck[wave][pos] = 4 * (tid + EXP_THREADS * q) + c;
+                    }
+                    total += __popcll(m);
                 }
-                total += __popcll(m);
             }
     }
-    if (total <= EXP_CAND_CAP) {
-        if (lane == 0) s_cn[wave] = total;
-    } else {
+    if (total > EXP_CAND_CAP) {
         // many equal scores: take exactly the N best by N rounds of wave arg-max
+        total = 0;
         for (int n = 0; n < d.N; ++n) {
             float bv = 0.f;
             int bk = 0x7fffffff;
@@ -388,52 +481,88 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
                     if (x > bv) { bv = x; bk = 4 * (tid + EXP_THREADS * q) + c; }   // ascending columns
                 }
             wave_argmax(bv, bk);
-            if (lane == 0) { s_cv[wave][n] = bv; s_ck[wave][n] = bk; }
+            if (!(bv > 0.f)) break;
+            if (lane == 0) { sm.cv[wave][n] = bv; sm.ck[wave][n] = bk; }
+            total = n + 1;
 #pragma unroll
             for (int q = 0; q < NV4; ++q)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
                     if (4 * (tid + EXP_THREADS * q) + c == bk) v[4 * q + c] = -1.f;
         }
-        if (lane == 0) s_cn[wave] = d.N;
+    }
+    // append this wave's list to the joint list (the order of waves there does not matter: the
+    // merge below orders by score and token)
+    {
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&sm.jn, total);
+        base = __builtin_amdgcn_readfirstlane(base);
+        if (lane < total) {
+            sm.jv[base + lane] = sm.cv[wave][lane];
+            sm.jk[base + lane] = sm.ck[wave][lane];
+        }
     }
     __syncthreads();
-    // ---- merge the waves' candidate lists (first wave): N rounds of arg-max, larger score first,
-    // smaller token on equal scores
+    // ---- merge (first wave): larger score first, smaller token on equal scores
     if (wave == 0) {
-        float cv[EXP_WAVES];
-        int ck[EXP_WAVES];
-        int base = 0;
-#pragma unroll
-        for (int i = 0; i < EXP_WAVES; ++i) { cv[i] = -1.f; ck[i] = 0x7fffffff; }
-#pragma unroll
-        for (int w = 0; w < EXP_WAVES; ++w) {
-            const int n_w = s_cn[w];
-            // entry e of list w has global index base+e; lane takes indices lane, lane+64, ...
+        const int all = sm.jn;
+        float *cs = cand_score + (long)pi.pair * d.N;
+        int *ct = cand_tok + (long)pi.pair * d.N;
+        if (all <= 64) {
+            // one candidate per lane, as a 64-bit key (score bits, inverted token) that orders like
+            // the rule above; the rank of a candidate is the number of keys above its own
+            const bool have = lane < all;
+            const float x = have ? sm.jv[lane] : 0.f;
+            const int k = have ? sm.jk[lane] : 0x7fffffff;
+            const u64 key = ((u64)__float_as_uint(x) << 32) | (unsigned)(0x7fffffff - k);
+            int rank = 0;
+            for (int j = 0; j < all; ++j) {
+                const u64 kj = ((u64)(unsigned)__builtin_amdgcn_readlane((int)(key >> 32), j) << 32) |
+                               (unsigned)__builtin_amdgcn_readlane((int)key, j);
+                rank += kj > key;
+            }
+            if (have && rank < d.N) { cs[rank] = __logf(x); ct[rank] = k; }
+            if (lane >= all && lane < d.N) { cs[lane] = -INFINITY; ct[lane] = -1; }
+        } else {
+            float cv[EXP_WAVES];
+            int ck[EXP_WAVES];
 #pragma unroll
             for (int i = 0; i < EXP_WAVES; ++i) {
-                const int e = lane + 64 * i - base;
-                if (e >= 0 && e < n_w) { cv[i] = s_cv[w][e]; ck[i] = s_ck[w][e]; }
+                const bool have = lane + 64 * i < all;
+                cv[i] = have ? sm.jv[lane + 64 * i] : -1.f;
+                ck[i] = have ? sm.jk[lane + 64 * i] : 0x7fffffff;
             }
-            base += n_w;
-        }
-        for (int n = 0; n < d.N; ++n) {
-            float bv = -1.f;
-            int bk = 0x7fffffff;
+            for (int n = 0; n < d.N; ++n) {
+                float bv = -1.f;
+                int bk = 0x7fffffff;
 #pragma unroll
-            for (int i = 0; i < EXP_WAVES; ++i)
-                if (cv[i] > bv || (cv[i] == bv && ck[i] < bk)) { bv = cv[i]; bk = ck[i]; }
-            wave_argmax(bv, bk);
-            if (lane == 0) {
-                const bool ok = bv > 0.f && bk != 0x7fffffff;
-                cand_score[(long)pair * d.N + n] = ok ? __logf(bv) : -INFINITY;
-                cand_tok[(long)pair * d.N + n] = ok ? bk : -1;
+                for (int i = 0; i < EXP_WAVES; ++i)
+                    if (cv[i] > bv || (cv[i] == bv && ck[i] < bk)) { bv = cv[i]; bk = ck[i]; }
+                wave_argmax(bv, bk);
+                if (lane == 0) {
+                    const bool ok = bv > 0.f && bk != 0x7fffffff;
+                    cs[n] = ok ? __logf(bv) : -INFINITY;
+                    ct[n] = ok ? bk : -1;
+                }
+#pragma unroll
+                for (int i = 0; i < EXP_WAVES; ++i)
+                    if (ck[i] == bk) { cv[i] = -1.f; ck[i] = 0x7fffffff; }
             }
-#pragma unroll
-            for (int i = 0; i < EXP_WAVES; ++i)
-                if (ck[i] == bk) { cv[i] = -1.f; ck[i] = 0x7fffffff; }
         }
     }
+}
+
+template <int NV4, int SMAX>
+__global__ void __launch_bounds__(EXP_THREADS, (NV4 * SMAX == 20 ? 4 : 1))   // 80 logits per thread: four waves per SIMD still fit
+k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
+             float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
+             float *__restrict__ row_stats, float *__restrict__ delta_nb) {
+    __shared__ ExpandShared<SMAX> sm;
+    ExpandPair<SMAX> pi;
+    expand_pair_info(pi, blockIdx.x, d, A, rv);
+    float e[SMAX][NV4 * 4];
+    expand_load<NV4, SMAX>(e, logits, pi.row0, pi.sp, d.V);
+    expand_pair<NV4, SMAX>(e, pi, sm, d, row_lc, dphi, cand_score, cand_tok, row_stats, delta_nb);
 }
 
 template <int NV4, int SMAX>
@@ -457,7 +586,8 @@ hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *
         return hipGetLastError();                                                                              \
     }
         const int nv4 = (d.V / 4 + EXP_THREADS - 1) / EXP_THREADS;
-        if (nv4 <= 1 && d.S <= 4) TBS_EXPAND_REG(1, 4)
+        if (nv4 <= 1 && d.S <= 3) TBS_EXPAND_REG(1, 3)
+        if (nv4 <= 1 && d.S <= 5) TBS_EXPAND_REG(1, 5)
         if (nv4 <= 1 && d.S <= 16) TBS_EXPAND_REG(1, 16)
         if (nv4 <= 2 && d.S <= 8) TBS_EXPAND_REG(2, 8)
         if (nv4 <= 4 && d.S <= 3) TBS_EXPAND_REG(4, 3)

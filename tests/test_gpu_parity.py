@@ -59,13 +59,16 @@ def _teacher_forced_state(rng, U, N, S, Dj):
     return counts, pred, dhat, logs
 
 
-def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, generic=False, flat=False):
+_EXPAND_DEBUG = {"auto": 1, "generic": 3}   # tbs_config.debug: statistics kept + kernel choice
+
+
+def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, kernel="auto", flat=False):
     model, offsets, enc = build_case(shape, n_utts=U)
     if flat:   # every logit equal: every expansion ties, the smallest tokens must win
         model["w_out"] = np.zeros_like(model["w_out"])
         model["b_out"] = np.zeros_like(model["b_out"])
     W = oracle_weights(shape, model)
-    tbs = make_tbs(shape, model, offsets, N, S, debug=3 if generic else 1)
+    tbs = make_tbs(shape, model, offsets, N, S, debug=_EXPAND_DEBUG[kernel])
     enc_dev = tbs.upload_frames(enc)
     rng = np.random.default_rng(11)
     counts, pred, dhat, logs = _teacher_forced_state(rng, U, N, S, shape.d_joint)
@@ -130,27 +133,29 @@ def test_joiner_expand_tiny_fp32():
     _check_joiner_expand(SHAPES["tiny"], U=1, N=2, S=3, seg=16, tol=1e-4)  # ragged last segment (2 frames)
 
 
-@pytest.mark.parametrize("generic", [False, True])
+@pytest.mark.parametrize("kernel", ["auto", "generic"])
 @pytest.mark.parametrize("N,S", [(5, 3), (2, 1), (10, 5), (3, 50), (4, 12), (32, 2)])
-def test_joiner_expand_small_bf16(N, S, generic):
-    """Both expansion kernels (register-resident and generic streaming) on every shape."""
+def test_joiner_expand_small_bf16(N, S, kernel):
+    """Both expansion kernels (the one that holds a hypothesis' logits in registers, which gives
+    way to the other where S is beyond its range, and the two-pass kernel for any shape)."""
     shape = small_bf16_shape(n_utts=5, vocab=200, d=128, hidden=64)
-    _check_joiner_expand(shape, U=5, N=N, S=S, seg=1 if S < 20 else 0, generic=generic)
+    _check_joiner_expand(shape, U=5, N=N, S=S, seg=1 if S < 20 else 0, kernel=kernel)
 
 
-@pytest.mark.parametrize("V,N,S", [(2048, 8, 7), (1028, 3, 2), (4096, 10, 5), (3000, 4, 3)])
+@pytest.mark.parametrize("V,N,S", [(2048, 8, 7), (1028, 3, 2), (4096, 10, 5), (3000, 4, 3), (2000, 6, 5), (4096, 20, 3),
+                                   (1024, 16, 4), (4096, 32, 2)])
 def test_joiner_expand_wide_vocab(V, N, S):
     """Vocabulary widths that exercise every register-kernel instantiation and a ragged last column block."""
     shape = small_bf16_shape(n_utts=4, vocab=V, d=64, hidden=64)
     _check_joiner_expand(shape, U=4, N=N, S=S, seg=1, sample_pairs=6)
 
 
-@pytest.mark.parametrize("generic", [False, True])
-def test_expand_all_scores_equal(generic):
+@pytest.mark.parametrize("kernel", ["auto", "generic"])
+def test_expand_all_scores_equal(kernel):
     """Degenerate input: every expansion of a hypothesis has the same score (exercises the
     tie order and the selection path taken when too many candidates reach the threshold)."""
     shape = small_bf16_shape(n_utts=3, vocab=1024, d=64, hidden=64)
-    _check_joiner_expand(shape, U=3, N=6, S=3, seg=0, generic=generic, flat=True)
+    _check_joiner_expand(shape, U=3, N=6, S=3, seg=0, kernel=kernel, flat=True)
 
 
 def test_joiner_expand_odd_vocab():
@@ -167,7 +172,7 @@ def test_joiner_expand_librispeech_full_size_sampled():
 def test_joiner_expand_assistant_full_width_sampled():
     """Large-assistant widths (V=4096, Dj=1024, N=10, S=3) with a multi-tile row count."""
     _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=6)
-    _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=4, generic=True)
+    _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=4, kernel="generic")
 
 
 # ------------------------------------------------------------------ whole decode
