@@ -218,7 +218,6 @@ k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *_
 template <int SMAX>
 struct ExpandShared {
     float pm[SMAX][EXP_WAVES], pz[SMAX][EXP_WAVES];   // per-wave row maxima and row sums
-    float blank[SMAX];
     float cv[EXP_WAVES][EXP_CAND_CAP];   // candidates of each wave ...
     int ck[EXP_WAVES][EXP_CAND_CAP];
     float jv[EXP_WAVES * EXP_CAND_CAP];  // ... and all of them in one list, in any order
@@ -231,16 +230,18 @@ template <int SMAX>
 struct ExpandPair {
     int pair, row0, sp;
     float dold[SMAX];   // frame distribution of the hypothesis' last token (d_old of Eq. 3)
+    float lblank[SMAX]; // blank logit of each row
 };
 
-// Row lists and d_old are written by earlier kernels only: read through the constant address
-// space, so that a wave-uniform address becomes a scalar load into scalar registers.
+// Row lists, d_old and the logits are written by earlier kernels only: what every lane needs alike
+// is read through the constant address space, so that a wave-uniform address becomes a scalar
+// load into scalar registers.
 typedef const __attribute__((address_space(4))) int *cint_p;
 typedef const __attribute__((address_space(4))) float *cfloat_p;
 
 template <int SMAX>
 __device__ __forceinline__ void expand_pair_info(ExpandPair<SMAX> &pi, int pair, const Dims &d, const AView &A,
-                                                 const RowView &rv) {
+                                                 const RowView &rv, const float *logits) {
     pi.pair = pair;
     pi.row0 = ((cint_p)rv.pair_row0)[pair];
     pi.sp = ((cint_p)rv.pair_len)[pair];
@@ -248,6 +249,9 @@ __device__ __forceinline__ void expand_pair_info(ExpandPair<SMAX> &pi, int pair,
     cfloat_p dold = (cfloat_p)A.dhat + ((long)u * d.N + h) * d.S;
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) pi.dold[t] = t < pi.sp ? dold[t] : 0.f;
+    cfloat_p lb = (cfloat_p)logits + (long)pi.row0 * d.V + d.blank;
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) pi.lblank[t] = t < pi.sp ? lb[(long)t * d.V] : 0.f;
 }
 
 // One pass over memory: this thread's columns of every row of the pair.  Every request is made
@@ -326,34 +330,23 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
         __builtin_amdgcn_sched_barrier(0);   // one row at a time: the partial results of all rows at once cost registers
         mrow[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(m)));   // uniform: a scalar register
     }
-    // ---- e = exp(l - m_t), once per logit; row sums across the workgroup; the owner of the blank
-    // column publishes its exponentials
-    {
-        const int bq = (d.blank >> 2) / EXP_THREADS, bt = (d.blank >> 2) % EXP_THREADS, bc = d.blank & 3;
+    // ---- e = exp(l - m_t), once per logit; row sums across the workgroup
 #pragma unroll
-        for (int t = 0; t < SMAX; ++t) {
-            const float nm = -mrow[t] * 1.44269504088896341f;
-            float z = 0.f;
+    for (int t = 0; t < SMAX; ++t) {
+        const float nm = -mrow[t] * 1.44269504088896341f;
+        float z = 0.f;
 #pragma unroll
-            for (int q = 0; q < NV4; ++q) {
-                float zq = 0.f;
+        for (int q = 0; q < NV4; ++q) {
+            float zq = 0.f;
 #pragma unroll
-                for (int c = 4 * q; c < 4 * q + 4; ++c) {
-                    e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));
-                    zq += e[t][c];
-                }
-                z += (tid + EXP_THREADS * q < V4) ? zq : 0.f;
+            for (int c = 4 * q; c < 4 * q + 4; ++c) {
+                e[t][c] = __builtin_amdgcn_exp2f(fmaf(e[t][c], 1.44269504088896341f, nm));
+                zq += e[t][c];
             }
-            z = wave_sum(z);
-            if (lane == 0) sm.pz[t][wave] = z;
-            if (tid == bt) {
-#pragma unroll
-                for (int q = 0; q < NV4; ++q)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (q == bq && c == bc) sm.blank[t] = e[t][4 * q + c];
-            }
+            z += (tid + EXP_THREADS * q < V4) ? zq : 0.f;
         }
+        z = wave_sum(z);
+        if (lane == 0) sm.pz[t][wave] = z;
     }
     __syncthreads();
     // ---- every thread: row sums, forward variable (Eq. 3 as a scan), Eq. 7, the row coefficients
@@ -368,10 +361,11 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
 #pragma unroll
                 for (int w = 1; w < EXP_WAVES; ++w) z += sm.pz[t][w];
                 __builtin_amdgcn_sched_barrier(0);
-                const float b = sm.blank[t] / z;
+                const float rz = __builtin_amdgcn_rcpf(z);
+                const float b = __builtin_amdgcn_exp2f((pi.lblank[t] - mrow[t]) * 1.44269504088896341f) * rz;
                 alpha = (t == 0 ? 0.f : alpha * bprev) + pi.dold[t];
                 bprev = b;
-                const float c = alpha / z;
+                const float c = alpha * rz;
                 cf[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(c)));
                 if (tid == 0) {
                     row_lc[pi.row0 + t] = c > 0.f ? __logf(c) - mrow[t] : -INFINITY;
@@ -402,10 +396,12 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
             const int col = 4 * (tid + EXP_THREADS * q) + c;
             if (col == d.blank || col >= V) v[4 * q + c] = 0.f;
         }
-    if (delta_nb) {
+    if (delta_nb) {   // debug output: its indices are made afresh, not kept in registers from the loads
+        int t2 = threadIdx.x;
+        asm volatile("" : "+v"(t2));
 #pragma unroll
         for (int q = 0; q < NV4; ++q) {
-            const int i4 = tid + EXP_THREADS * q;
+            const int i4 = t2 + EXP_THREADS * q;
             if (i4 < V4)
                 reinterpret_cast<float4 *>(delta_nb + (long)pi.pair * V)[i4] =
                     make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
@@ -553,13 +549,13 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
 }
 
 template <int NV4, int SMAX>
-__global__ void __launch_bounds__(EXP_THREADS, (NV4 * SMAX == 20 ? 4 : 1))   // 80 logits per thread: four waves per SIMD still fit
+__global__ void __launch_bounds__(EXP_THREADS, (NV4 * SMAX == 20 ? 5 : 1))   // 80 logits per thread: five waves per SIMD still fit
 k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
              float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
              float *__restrict__ row_stats, float *__restrict__ delta_nb) {
     __shared__ ExpandShared<SMAX> sm;
     ExpandPair<SMAX> pi;
-    expand_pair_info(pi, blockIdx.x, d, A, rv);
+    expand_pair_info(pi, blockIdx.x, d, A, rv, logits);
     float e[SMAX][NV4 * 4];
     expand_load<NV4, SMAX>(e, logits, pi.row0, pi.sp, d.V);
     expand_pair<NV4, SMAX>(e, pi, sm, d, row_lc, dphi, cand_score, cand_tok, row_stats, delta_nb);
