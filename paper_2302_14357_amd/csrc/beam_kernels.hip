@@ -51,8 +51,12 @@ __device__ __forceinline__ int load_fresh(const int *p) {
 __device__ __forceinline__ void store_fresh(int *p, int v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void store_host(int *p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
-__device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes, int *host_counts);
+__device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes, int *host_counts,
+                                int seq);
 __device__ bool last_workgroup(const RowView &rv, int n_groups);
 
 // ------------------------------------------------------------------ batch init
@@ -105,7 +109,7 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 // ------------------------------------------------------------------ segment head
 // A = ChooseNBest(B); B = []; d = (s, 0, ..., 0)   (Algorithm 1, head of the outer loop)
 __global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv,
-                                int *host_counts) {
+                                int *host_counts, int seq) {
     int u = blockIdx.x, lane = threadIdx.x;
     int left = utt_T[u] - seg * d.S;
     int sp = left < 0 ? 0 : (left > d.S ? d.S : left);
@@ -142,12 +146,12 @@ __global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, B
             B.count[u] = 0;
         }
     }
-    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, A, rv, 0, host_counts);
+    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, A, rv, 0, host_counts, seq);
 }
 
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
-                                AView A, RowView rv, int *host_counts) {
-    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(WAVE), 0, st, d, seg, parity, utt_T, B, A, rv, host_counts);
+                                AView A, RowView rv, int *host_counts, int seq) {
+    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(WAVE), 0, st, d, seg, parity, utt_T, B, A, rv, host_counts, seq);
     return hipGetLastError();
 }
 
@@ -180,7 +184,7 @@ hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv,
 // exclusive scan over the utterances with one wave and publishes the totals to
 // the host; a second, fully parallel kernel then fills the pair and row lists.
 __device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes,
-                                int *host_counts) {
+                                int *host_counts, int seq) {
     const int lane = threadIdx.x & 63;
     int carry_p = 0, carry_r = 0, utts = 0, frames = 0;
     constexpr int UNROLL = 4;   // independent loads in flight per step
@@ -234,14 +238,18 @@ __device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv
         rv.counts[TBS_CNT_UTTS] = utts;
         rv.counts[TBS_CNT_FRAMES] = frames;
         rv.counts[TBS_CNT_TICKET] = 0;
-        if (host_counts) {  // pinned, device-mapped host memory: the host reads it after a stream sync
-            host_counts[TBS_CNT_PAIRS] = tot_pairs;
-            host_counts[TBS_CNT_ROWS] = tot_rows;
-            host_counts[TBS_CNT_NODES] = nodes_used;
-            host_counts[TBS_CNT_ERR] = err;
-            host_counts[TBS_CNT_UTTS] = utts;
-            host_counts[TBS_CNT_FRAMES] = frames;
-            __threadfence_system();
+        if (host_counts) {
+            // Pinned host memory, which the host polls while the stream runs on: the figures go out
+            // as uncached system-scope stores, and once they are acknowledged the sequence number
+            // of this scan follows in the slot the host mirror has no other use for.
+            store_host(host_counts + TBS_CNT_PAIRS, tot_pairs);
+            store_host(host_counts + TBS_CNT_ROWS, tot_rows);
+            store_host(host_counts + TBS_CNT_NODES, nodes_used);
+            store_host(host_counts + TBS_CNT_ERR, err);
+            store_host(host_counts + TBS_CNT_UTTS, utts);
+            store_host(host_counts + TBS_CNT_FRAMES, frames);
+            __builtin_amdgcn_s_waitcnt(0);
+            store_host(host_counts + TBS_CNT_TICKET, seq);
         }
     }
 }
@@ -258,12 +266,13 @@ __device__ bool last_workgroup(const RowView &rv, int n_groups) {
     return s_last != 0;
 }
 
-__global__ void k_rowscan(Dims d, AView A, RowView rv, int assign_nodes, int *host_counts) {
-    scan_utterances(d, A, rv, assign_nodes, host_counts);
+__global__ void k_rowscan(Dims d, AView A, RowView rv, int assign_nodes, int *host_counts, int seq) {
+    scan_utterances(d, A, rv, assign_nodes, host_counts, seq);
 }
 
-hipError_t launch_rowscan(hipStream_t st, const Dims &d, AView A, RowView rv, int assign_nodes, int *host_counts) {
-    hipLaunchKernelGGL(k_rowscan, dim3(1), dim3(WAVE), 0, st, d, A, rv, assign_nodes, host_counts);
+hipError_t launch_rowscan(hipStream_t st, const Dims &d, AView A, RowView rv, int assign_nodes, int *host_counts,
+                          int seq) {
+    hipLaunchKernelGGL(k_rowscan, dim3(1), dim3(WAVE), 0, st, d, A, rv, assign_nodes, host_counts, seq);
     return hipGetLastError();
 }
 
@@ -320,7 +329,7 @@ hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt
 __global__ void __launch_bounds__(WAVE)
 k_select_merge(Dims d, int parity, int round, int drop, const float *logits, const float *row_lc,
                const float *dphi, const float *cand_score, const int *cand_tok, AView A, AView An, BView B,
-               RowView rv, const int2 *nodes, int *host_counts) {
+               RowView rv, const int2 *nodes, int *host_counts, int seq) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // B list of this utterance
     double *s_blogs = reinterpret_cast<double *>(s_dyn);
     u64 *s_bhash = reinterpret_cast<u64 *>(s_blogs + d.BCAP);
@@ -528,16 +537,16 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
             }
         }
     }
-    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, An, rv, 1, host_counts);
+    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, An, rv, 1, host_counts, seq);
 }
 
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes,
-                               int *host_counts) {
+                               int *host_counts, int seq) {
     const size_t shm = (size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int));
     hipLaunchKernelGGL(k_select_merge, dim3(d.U), dim3(WAVE), shm, st, d, parity, round, drop, logits, row_lc, dphi,
-                       cand_score, cand_tok, A, An, B, rv, nodes, host_counts);
+                       cand_score, cand_tok, A, An, B, rv, nodes, host_counts, seq);
     return hipGetLastError();
 }
 

@@ -239,22 +239,33 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
                     for (int j = 0; j < TN; ++j) tr[offl + j * 32] = acc[i][j][r];
                 }
         } else {
+            // edge tiles and scattered rows.  The destination rows of a 32-row block are requested
+            // together and waited for once, outside any branch: a load behind a branch makes every
+            // later store wait for the store before it.
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i) {
+                long orow[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = min(m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), M - 1);
+                    orow[r] = out_row ? out_row[row] : row;
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(orow[r]));
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    int col = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+                    const int col = n0 + wn * 32 * TN + j * 32 + (lane & 31);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        int row = m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                        const int row = m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                         if (row < M && col < N) {
-                            long orow = out_row ? out_row[row] : row;
                             float v = acc[i][j][r];
                             if (rowbias) v += rowbias[(long)rowbias_idx[row] * N + col];   // per-row gathered bias
-                            C[orow * ldc + col] = v;
+                            C[orow[r] * ldc + col] = v;
                         }
                     }
                 }
+            }
         }
         if (!have_next) break;
         idx += jstride;
@@ -298,6 +309,133 @@ static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, 
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ small problems
+// When the whole product is one wave of 64x64 tiles or less, time is latency, not throughput: a
+// workgroup alone on its CU that fetches one K tile ahead waits a full memory round trip per K
+// tile.  This kernel asks for up to `ns` K tiles of 128 at once, straight into as many LDS
+// stages (32 KB each), and multiplies them as they land; a stage is refilled as soon as every
+// wave has read it.  One tile per workgroup, 4 waves of 32x32, bias folded into the accumulator.
+#define GS_BK 128
+#define GS_STAGE ((64 + 64) * GS_BK)   // bf16 elements of one stage: A tile, then B tile
+#define GS_LOADS 8                     // direct loads per wave and stage
+
+// s_waitcnt operand that waits for all but n vector-memory operations and for nothing else
+#define GS_VMCNT(n) (((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+
+// Workgroup barrier that orders LDS traffic only: vector-memory operations (the direct loads of
+// later stages) stay in flight across it, which __syncthreads would not allow.
+__device__ __forceinline__ void gs_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__global__ void __launch_bounds__(256)
+k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
+             float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
+             int ns) {
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // ns stages
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+    const int kt = K / GS_BK;
+
+    // Direct loads: one instruction fills 1 KB of LDS = 4 rows of 256 bytes, lane l the 16 bytes
+    // at row l/16, position l%16; the position holds global chunk (l%16) ^ (row & 15).
+    const int lrow = lane >> 4, lpos = lane & 15;
+    const bf16_t *ga[4], *gb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = i * 16 + wave * 4 + lrow;
+        const int ch = (lpos ^ (row & 15)) * 8;
+        ga[i] = A + (long)min(tile_m * 64 + row, M - 1) * K + ch;
+        gb[i] = B + (long)min(tile_n * 64 + row, N - 1) * K + ch;
+    }
+    auto fetch = [&](int chunk, int stage) {
+        bf16_t *dst = smem + stage * GS_STAGE + wave * 4 * GS_BK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ga[i] + chunk * GS_BK),
+                                             (__attribute__((address_space(3))) void *)(dst + i * 16 * GS_BK), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gb[i] + chunk * GS_BK),
+                                             (__attribute__((address_space(3))) void *)(dst + (64 + i * 16) * GS_BK), 16, 0, 0);
+    };
+    // the bias first: loads retire in order, so one requested behind the tiles would wait for them all
+    floatx16 acc;
+    {
+        const int col = tile_n * 64 + wn * 32 + (lane & 31);
+        float bv = (bias && col < N) ? bias[col] : 0.f;
+        asm volatile("" : "+v"(bv));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = bv;
+    }
+    const int first = min(ns, kt);
+    for (int c = 0; c < first; ++c) fetch(c, c);
+    const int frow = lane & 31, fsel = lane >> 5, fsw = frow & 15;
+    const int fa = (wm * 32 + frow) * GS_BK, fb = (64 + wn * 32 + frow) * GS_BK;
+    int stage = 0;
+    for (int c = 0; c < kt; ++c) {
+        // K tiles requested after this one and still allowed to be in flight
+        const int after = min(kt, c + ns) - 1 - c;
+        if (after >= 3) __builtin_amdgcn_s_waitcnt(GS_VMCNT(3 * GS_LOADS));
+        else if (after == 2) __builtin_amdgcn_s_waitcnt(GS_VMCNT(2 * GS_LOADS));
+        else if (after == 1) __builtin_amdgcn_s_waitcnt(GS_VMCNT(1 * GS_LOADS));
+        else __builtin_amdgcn_s_waitcnt(GS_VMCNT(0));
+        gs_barrier();      // every wave's share of this K tile is in LDS
+        const bf16_t *cur = smem + stage * GS_STAGE;
+        // all fragments of the K tile first, then the matrix instructions back to back
+        bf16x8 af[GS_BK / 16], bfr[GS_BK / 16];
+#pragma unroll
+        for (int kk = 0; kk < GS_BK / 16; ++kk) {
+            const int cpos = ((kk * 2 + fsel) ^ fsw) * 8;
+            af[kk] = *reinterpret_cast<const bf16x8 *>(cur + fa + cpos);
+            bfr[kk] = *reinterpret_cast<const bf16x8 *>(cur + fb + cpos);
+        }
+#pragma unroll
+        for (int kk = 0; kk < GS_BK / 16; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk], bfr[kk], acc, 0, 0, 0);
+        if (c + ns < kt) {
+            gs_barrier();      // every wave has read this stage
+            fetch(c + ns, stage);
+        }
+        stage = stage + 1 == ns ? 0 : stage + 1;
+    }
+    // epilogue: lane holds column (lane & 31); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4
+    const int col = tile_n * 64 + wn * 32 + (lane & 31);
+    // destination addresses first (all row indices requested at once, one wait), then stores that
+    // depend on no load: a store behind a branch would otherwise wait for the store before it
+    float *dst[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = min(tile_m * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), M - 1);
+        const long orow = out_row ? out_row[row] : row;
+        dst[r] = C + orow * ldc + col;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(dst[r]));   // the wait for the row indices happens here, once
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = tile_m * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (row < M && col < N) *dst[r] = acc[r];
+    }
+}
+
+// LDS stages k_gemm_small may use on the current device (0 = kernel not usable)
+static int gemm_small_stages() {
+    static int stages = -1;
+    if (stages < 0) {
+        stages = 0;
+        for (int ns = 5; ns >= 2; --ns)
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess) {
+                stages = ns;
+                break;
+            }
+        (void)hipGetLastError();
+    }
+    return stages;
+}
+
 // variant: 0 = choose by size; others force a tile shape (for tuning runs)
 int g_tbs_gemm_variant = 0;
 
@@ -306,6 +444,16 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
                             const int *rowbias_idx) {
     if (M <= 0) return hipSuccess;
     int v = g_tbs_gemm_variant;
+    if ((v == 0 || v == 11) && K % GS_BK == 0 && rowbias == nullptr) {
+        const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
+        const int ns_max = gemm_small_stages();
+        if (ns_max >= 2 && ((long)tiles_m * tiles_n <= 320 || v == 11)) {
+            const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
+            hipLaunchKernelGGL(k_gemm_small, dim3(tiles_m * tiles_n), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B,
+                               bias, C, M, N, K, out_row, ldc, tiles_m, ns);
+            return hipGetLastError();
+        }
+    }
     if (v == 0) {
         // measured on MI355X: 256x256 tiles (8 waves, 64x128 per wave) once they fill the chip 1.5
         // times over, 128x128 (two workgroups per CU) for mid sizes, 64x64 so that small problems

@@ -46,6 +46,7 @@ struct tbs_ctx {
     RowView rv;
     int *h_counts;      // pinned host mirror of rv.counts
     int *h_counts_dev;  // device view of the same memory
+    int seq;            // number of the last scan asked to publish its counts there
     int2 *nodes;
     long pool_rows;
     float *pool_p, *pool_h, *pool_c;
@@ -132,6 +133,23 @@ struct ProfScope {
         if (on) (void)hipEventRecord(c->events[idx].b, c->stream);
     }
 };
+
+// Wait for the counts of the scan numbered c->seq without draining the stream: the kernel that
+// runs the scan writes them into pinned host memory and its number last, so the host can size
+// and enqueue the next launches while the kernels behind that scan are still running.
+hipError_t wait_counts(tbs_ctx *c) {
+    const int want = c->seq;
+    for (unsigned spin = 1;; ++spin) {
+        if (__atomic_load_n(&c->h_counts[TBS_CNT_TICKET], __ATOMIC_ACQUIRE) == want) return hipSuccess;
+        if ((spin & 0x3FFF) == 0) {   // now and then: has the stream failed, or ended without the number?
+            const hipError_t e = hipStreamQuery(c->stream);
+            if (e == hipSuccess)
+                return __atomic_load_n(&c->h_counts[TBS_CNT_TICKET], __ATOMIC_ACQUIRE) == want ? hipSuccess
+                                                                                              : hipErrorUnknown;
+            if (e != hipErrorNotReady) return e;
+        }
+    }
+}
 
 int check_err_flags(tbs_ctx *c) {
     int err = c->h_counts[TBS_CNT_ERR];
@@ -384,6 +402,7 @@ int tbs_begin(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, in
     c->a_cur = 0;
     memset(c->h_counts, 0, TBS_CNT_SIZE * sizeof(int));
     c->h_counts[TBS_CNT_NODES] = 1;
+    c->seq = 0;
     c->n_calls = c->n_joined = c->n_launches = 0;
     c->n_frames = frame_offsets[U];
     c->state = ST_BEGUN;
@@ -399,10 +418,10 @@ int tbs_segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->parity = seg_index & 1;
     AView &A = c->A[c->a_cur];
     HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv,
-                                   c->h_counts_dev));
+                                   c->h_counts_dev, ++c->seq));
     HIPCHK(c, launch_state_copy(c->stream, c->cur, A, c->rv, c->pool_p, c->pool_h, c->pool_c, c->pool_rows));
     HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, A, c->rv, c->nodes, 0));
-    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, wait_counts(c));
     if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
     c->state = ST_READY;
     return TBS_OK;
@@ -452,10 +471,11 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     {
         ProfScope ps(c, TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
         HIPCHK(c, launch_select_merge(c->stream, c->cur, c->parity, c->round, drop, c->logits, c->row_lc, c->dphi,
-                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes, c->h_counts_dev));
+                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes, c->h_counts_dev,
+                                      ++c->seq));
         HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, An, c->rv, c->nodes, 1));
     }
-    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, wait_counts(c));
     c->a_cur ^= 1;
     if (live_host) *live_host = c->h_counts[TBS_CNT_PAIRS];
     c->state = ST_SELECTED;
@@ -645,7 +665,7 @@ int tbs_debug_rebuild(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->round = 0;
     c->parity = 0;
     HIPCHK(c, launch_set_sp(c->stream, c->cur, seg_index, c->utt_T, c->rv));
-    HIPCHK(c, launch_rowscan(c->stream, c->cur, c->A[c->a_cur], c->rv, 0, c->h_counts_dev));
+    HIPCHK(c, launch_rowscan(c->stream, c->cur, c->A[c->a_cur], c->rv, 0, c->h_counts_dev, ++c->seq));
     HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];

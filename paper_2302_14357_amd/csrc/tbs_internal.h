@@ -69,10 +69,11 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
                              float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
                              long pool_rows);
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
-                                AView A, RowView rv, int *host_counts);
+                                AView A, RowView rv, int *host_counts, int seq);
 hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv, float *pool_p, float *pool_h,
                              float *pool_c, long pool_rows);
-hipError_t launch_rowscan(hipStream_t st, const Dims &d, AView A, RowView rv, int assign_nodes, int *host_counts);
+hipError_t launch_rowscan(hipStream_t st, const Dims &d, AView A, RowView rv, int assign_nodes, int *host_counts,
+                          int seq);
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
                           int2 *nodes, int assign_nodes);
 hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
@@ -88,7 +89,7 @@ hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes,
-                               int *host_counts);
+                               int *host_counts, int seq);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
                               const void *embed, const float *pool_h, void *xh);
 hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, const float *pool_h,
