@@ -42,22 +42,11 @@ __device__ bool same_sequence(const int2 *nodes, int a, int b) {
     return true;
 }
 
-// Values handed from every workgroup of a launch to the one that runs the scan travel as
-// device-scope atomics (they bypass the per-CU L1 and the per-XCD L2), so publishing them needs
-// no cache write-back: the writer only waits for its own stores before taking a ticket.
-__device__ __forceinline__ int load_fresh(const int *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_fresh(int *p, int v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+// Figures for the host go out as uncached system-scope stores into pinned host memory, which the
+// host polls while the stream runs on.
 __device__ __forceinline__ void store_host(int *p, int v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
-
-__device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes, int *host_counts,
-                                int seq);
-__device__ bool last_workgroup(const RowView &rv, int n_groups);
 
 // ------------------------------------------------------------------ batch init
 __global__ void k_init_batch(Dims d, BView B, AView A0, AView A1, RowView rv, int2 *nodes, float *pool_p,
@@ -86,7 +75,7 @@ __global__ void k_init_batch(Dims d, BView B, AView A0, AView A1, RowView rv, in
             rv.counts[TBS_CNT_ERR] = 0;
             rv.counts[TBS_CNT_UTTS] = 0;
             rv.counts[TBS_CNT_FRAMES] = 0;
-            rv.counts[TBS_CNT_TICKET] = 0;
+            rv.counts[TBS_CNT_SEQ] = 0;
             rv.counts[TBS_CNT_NODE_BASE] = 1;
         }
     }
@@ -108,14 +97,13 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 
 // ------------------------------------------------------------------ segment head
 // A = ChooseNBest(B); B = []; d = (s, 0, ..., 0)   (Algorithm 1, head of the outer loop)
-__global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv,
-                                int *host_counts, int seq) {
+__global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv) {
     int u = blockIdx.x, lane = threadIdx.x;
     int left = utt_T[u] - seg * d.S;
     int sp = left < 0 ? 0 : (left > d.S ? d.S : left);
-    if (lane == 0) store_fresh(rv.utt_sp + u, sp);
+    if (lane == 0) rv.utt_sp[u] = sp;
     if (sp == 0) {  // finished (or empty) utterance: B keeps the final list
-        if (lane == 0) store_fresh(A.count + u, 0);
+        if (lane == 0) A.count[u] = 0;
     } else {
         int nB = B.count[u];
         const double *bl = B.logs + (long)u * d.BCAP;
@@ -142,16 +130,15 @@ __global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, B
             }
         }
         if (lane == 0) {
-            store_fresh(A.count + u, nB < d.N ? nB : d.N);
+            A.count[u] = nB < d.N ? nB : d.N;
             B.count[u] = 0;
         }
     }
-    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, A, rv, 0, host_counts, seq);
 }
 
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
-                                AView A, RowView rv, int *host_counts, int seq) {
-    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(WAVE), 0, st, d, seg, parity, utt_T, B, A, rv, host_counts, seq);
+                                AView A, RowView rv) {
+    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(WAVE), 0, st, d, seg, parity, utt_T, B, A, rv);
     return hipGetLastError();
 }
 
@@ -179,112 +166,78 @@ hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv,
 
 // ------------------------------------------------------------------ row list
 // The joiner rows of a round are the (pair, frame) combinations of the live
-// (utterance, hypothesis) pairs, compacted.  The last workgroup to finish the
-// kernel that produced the new counts (segment head or select/merge) runs an
-// exclusive scan over the utterances with one wave and publishes the totals to
-// the host; a second, fully parallel kernel then fills the pair and row lists.
-__device__ void scan_utterances(const Dims &d, const AView &A, const RowView &rv, int assign_nodes,
-                                int *host_counts, int seq) {
-    const int lane = threadIdx.x & 63;
-    int carry_p = 0, carry_r = 0, utts = 0, frames = 0;
-    constexpr int UNROLL = 4;   // independent loads in flight per step
-    for (int base = 0; base < d.U; base += 64 * UNROLL) {
-        int sp[UNROLL], cnt[UNROLL];
+// (utterance, hypothesis) pairs, compacted.  One workgroup (a wave) per
+// utterance: each reads the counts of ALL utterances, which the kernel before it
+// wrote, and sums those ahead of its own, so no workgroup waits for another and
+// nothing travels between them; it then fills its pairs and rows and gives new
+// hypotheses their trie nodes.  The first workgroup also owns the totals: it
+// publishes them to the host, with the number of this launch last, before it
+// fills anything.
+__device__ __forceinline__ int wave_sum_int(int v) {
 #pragma unroll
-        for (int k = 0; k < UNROLL; ++k) {
-            const int u = base + 64 * k + lane;
-            sp[k] = u < d.U ? load_fresh(rv.utt_sp + u) : 0;
-            cnt[k] = u < d.U ? load_fresh(A.count + u) : 0;
-        }
-#pragma unroll
-        for (int k = 0; k < UNROLL; ++k) {
-            const int u = base + 64 * k + lane;
-            const int c = sp[k] > 0 ? cnt[k] : 0;
-            const int r = c * sp[k];
-            int ip = c, ir = r;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int op = __shfl_up(ip, off), orr = __shfl_up(ir, off);
-                if (lane >= off) { ip += op; ir += orr; }
-            }
-            if (u < d.U) {
-                rv.utt_pair0[u] = carry_p + ip - c;
-                rv.utt_row0[u] = carry_r + ir - r;
-            }
-            carry_p += __shfl(ip, 63);
-            carry_r += __shfl(ir, 63);
-            utts += c > 0;
-            frames += c > 0 ? sp[k] : 0;
-        }
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        utts += __shfl_xor(utts, off);
-        frames += __shfl_xor(frames, off);
-    }
-    const int tot_pairs = carry_p, tot_rows = carry_r;
-    if (lane == 0) {
-        int err = load_fresh(rv.counts + TBS_CNT_ERR);
-        const int node_base = load_fresh(rv.counts + TBS_CNT_NODES);
-        int nodes_used = node_base;
-        rv.counts[TBS_CNT_NODE_BASE] = node_base;
-        if (assign_nodes) {
-            nodes_used = node_base + tot_pairs;
-            if (nodes_used > d.max_nodes) { err |= TBS_ERRF_NODES; nodes_used = d.max_nodes; }
-        }
-        rv.counts[TBS_CNT_PAIRS] = tot_pairs;
-        rv.counts[TBS_CNT_ROWS] = tot_rows;
-        rv.counts[TBS_CNT_NODES] = nodes_used;
-        rv.counts[TBS_CNT_ERR] = err;
-        rv.counts[TBS_CNT_UTTS] = utts;
-        rv.counts[TBS_CNT_FRAMES] = frames;
-        rv.counts[TBS_CNT_TICKET] = 0;
-        if (host_counts) {
-            // Pinned host memory, which the host polls while the stream runs on: the figures go out
-            // as uncached system-scope stores, and once they are acknowledged the sequence number
-            // of this scan follows in the slot the host mirror has no other use for.
-            store_host(host_counts + TBS_CNT_PAIRS, tot_pairs);
-            store_host(host_counts + TBS_CNT_ROWS, tot_rows);
-            store_host(host_counts + TBS_CNT_NODES, nodes_used);
-            store_host(host_counts + TBS_CNT_ERR, err);
-            store_host(host_counts + TBS_CNT_UTTS, utts);
-            store_host(host_counts + TBS_CNT_FRAMES, frames);
-            __builtin_amdgcn_s_waitcnt(0);
-            store_host(host_counts + TBS_CNT_TICKET, seq);
-        }
-    }
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
 }
 
-// Called by every workgroup (one wave each) at its end; true in the last one to arrive.
-__device__ bool last_workgroup(const RowView &rv, int n_groups) {
-    __shared__ int s_last;
-    __builtin_amdgcn_s_waitcnt(0);   // this wave's published stores have been acknowledged
-    __syncthreads();
-    if (threadIdx.x == 0)
-        s_last = __hip_atomic_fetch_add(&rv.counts[TBS_CNT_TICKET], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                 n_groups - 1;
-    __syncthreads();
-    return s_last != 0;
-}
-
-__global__ void k_rowscan(Dims d, AView A, RowView rv, int assign_nodes, int *host_counts, int seq) {
-    scan_utterances(d, A, rv, assign_nodes, host_counts, seq);
-}
-
-hipError_t launch_rowscan(hipStream_t st, const Dims &d, AView A, RowView rv, int assign_nodes, int *host_counts,
-                          int seq) {
-    hipLaunchKernelGGL(k_rowscan, dim3(1), dim3(WAVE), 0, st, d, A, rv, assign_nodes, host_counts, seq);
-    return hipGetLastError();
-}
-
-// One workgroup per utterance fills its pairs and rows, and gives new hypotheses their trie nodes.
-__global__ void k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes, int assign_nodes) {
+__global__ void __launch_bounds__(WAVE)
+k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes, int assign_nodes, int *host_counts,
+          int seq) {
     const int u = blockIdx.x, lane = threadIdx.x;
-    const int sp = rv.utt_sp[u];
-    const int cnt = sp > 0 ? A.count[u] : 0;
-    if (cnt == 0) return;
-    const int pair0 = rv.utt_pair0[u], row0 = rv.utt_row0[u];
+    // trie nodes handed out so far: launches alternate between two slots, so that the first
+    // workgroup can store the new figure while others still read the old one
+    const int slot_old = (seq & 1) ? TBS_CNT_NODE_BASE : TBS_CNT_NODES;
+    const int slot_new = (seq & 1) ? TBS_CNT_NODES : TBS_CNT_NODE_BASE;
+    const int node_base = rv.counts[slot_old];
     const int frame0 = utt_off[u] + seg * d.S;
-    const int node_base = rv.counts[TBS_CNT_NODE_BASE];
+    int before_p = 0, before_r = 0, tot_p = 0, tot_r = 0, utts = 0, frames = 0, my_sp = 0, my_cnt = 0;
+    for (int base = 0; base < d.U; base += WAVE) {
+        const int v = base + lane;
+        const int sp = v < d.U ? rv.utt_sp[v] : 0;
+        const int c = (v < d.U && sp > 0) ? A.count[v] : 0;
+        const int r = c * sp;
+        if (v < u) { before_p += c; before_r += r; }
+        if (v == u) { my_sp = sp; my_cnt = c; }
+        tot_p += c;
+        tot_r += r;
+        utts += c > 0;
+        frames += c > 0 ? sp : 0;
+    }
+    const int pair0 = wave_sum_int(before_p), row0 = wave_sum_int(before_r);
+    const int sp = wave_sum_int(my_sp), cnt = wave_sum_int(my_cnt);
+    if (u == 0) {
+        tot_p = wave_sum_int(tot_p);
+        tot_r = wave_sum_int(tot_r);
+        utts = wave_sum_int(utts);
+        frames = wave_sum_int(frames);
+        if (lane == 0) {
+            int err = rv.counts[TBS_CNT_ERR];
+            int nodes_used = node_base;
+            if (assign_nodes) {
+                nodes_used = node_base + tot_p;
+                if (nodes_used > d.max_nodes) { err |= TBS_ERRF_NODES; nodes_used = d.max_nodes; }
+            }
+            if (host_counts) {
+                store_host(host_counts + TBS_CNT_PAIRS, tot_p);
+                store_host(host_counts + TBS_CNT_ROWS, tot_r);
+                store_host(host_counts + TBS_CNT_NODES, nodes_used);
+                store_host(host_counts + TBS_CNT_ERR, err);
+                store_host(host_counts + TBS_CNT_UTTS, utts);
+                store_host(host_counts + TBS_CNT_FRAMES, frames);
+                __builtin_amdgcn_s_waitcnt(0);   // the figures are acknowledged before their number goes out
+                store_host(host_counts + TBS_CNT_SEQ, seq);
+            }
+            rv.counts[TBS_CNT_PAIRS] = tot_p;
+            rv.counts[TBS_CNT_ROWS] = tot_r;
+            rv.counts[slot_new] = nodes_used;
+            rv.counts[TBS_CNT_ERR] = err;
+            rv.counts[TBS_CNT_UTTS] = utts;
+            rv.counts[TBS_CNT_FRAMES] = frames;
+        }
+    }
+    if (lane == 0) {
+        rv.utt_pair0[u] = pair0;
+        rv.utt_row0[u] = row0;
+    }
     for (int idx = lane; idx < cnt * sp; idx += WAVE) {
         const int h = idx / sp, t = idx - h * sp;
         const long a = (long)u * d.N + h;
@@ -313,8 +266,9 @@ __global__ void k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView 
 }
 
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
-                          int2 *nodes, int assign_nodes) {
-    hipLaunchKernelGGL(k_rowfill, dim3(d.U), dim3(WAVE), 0, st, d, seg, utt_off, A, rv, nodes, assign_nodes);
+                          int2 *nodes, int assign_nodes, int *host_counts, int seq) {
+    hipLaunchKernelGGL(k_rowfill, dim3(d.U), dim3(WAVE), 0, st, d, seg, utt_off, A, rv, nodes, assign_nodes,
+                       host_counts, seq);
     return hipGetLastError();
 }
 
@@ -329,7 +283,7 @@ hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt
 __global__ void __launch_bounds__(WAVE)
 k_select_merge(Dims d, int parity, int round, int drop, const float *logits, const float *row_lc,
                const float *dphi, const float *cand_score, const int *cand_tok, AView A, AView An, BView B,
-               RowView rv, const int2 *nodes, int *host_counts, int seq) {
+               RowView rv, const int2 *nodes) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // B list of this utterance
     double *s_blogs = reinterpret_cast<double *>(s_dyn);
     u64 *s_bhash = reinterpret_cast<u64 *>(s_blogs + d.BCAP);
@@ -348,13 +302,14 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
     __shared__ double s_thr;
     const int u = blockIdx.x, lane = threadIdx.x;
     const int N = d.N;
-    const int H = rv.utt_sp[u] > 0 ? A.count[u] : 0;
+    // everything that describes the utterance in one round of loads
+    const int sp = rv.utt_sp[u], cntA = A.count[u], pair0 = rv.utt_pair0[u], urow0 = rv.utt_row0[u];
+    const int nB0 = B.count[u];
+    const int H = sp > 0 ? cntA : 0;
     if (H == 0) {
-        if (lane == 0) store_fresh(An.count + u, 0);
+        if (lane == 0) An.count[u] = 0;
     } else {
-        const int pair0 = rv.utt_pair0[u];
         const long bbase = (long)u * d.BCAP;
-        const int nB0 = B.count[u];
         int nB = nB0;
         // --- stage B, A and the candidates
         for (int i = lane; i < nB0; i += WAVE) {
@@ -499,7 +454,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
         }
         __syncthreads();
         if (drop) {
-            if (lane == 0) store_fresh(An.count + u, 0);
+            if (lane == 0) An.count[u] = 0;
         } else {
             int pos = 0, total = 0;
             for (int r = 0; r < N; ++r) {
@@ -507,7 +462,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
                 if (r < lane) pos += k;
                 total += k;
             }
-            if (lane == 0) store_fresh(An.count + u, total);
+            if (lane == 0) An.count[u] = total;
             if (lane < N && s_keep[lane]) {
                 const int c = s_sel[lane];
                 const int h = c / N;
@@ -522,8 +477,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
                 An.pslot[an] = s_aslot[h];
                 An.slot[an] = tbs_slot_id(u, parity, round, pos, d.R, N);
                 // d of the new hypothesis (Eq. 5 for the chosen token), normalised by its sum (Eq. 6)
-                const int sp = rv.utt_sp[u];
-                const int row0 = rv.utt_row0[u] + h * sp;
+                const int row0 = urow0 + h * sp;
                 float *dh = An.dhat + an * d.S;
                 float sum = 0.f;
                 for (int t = 0; t < sp; ++t) {
@@ -537,16 +491,14 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
             }
         }
     }
-    if (last_workgroup(rv, gridDim.x)) scan_utterances(d, An, rv, 1, host_counts, seq);
 }
 
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
-                               const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes,
-                               int *host_counts, int seq) {
+                               const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes) {
     const size_t shm = (size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int));
     hipLaunchKernelGGL(k_select_merge, dim3(d.U), dim3(WAVE), shm, st, d, parity, round, drop, logits, row_lc, dphi,
-                       cand_score, cand_tok, A, An, B, rv, nodes, host_counts, seq);
+                       cand_score, cand_tok, A, An, B, rv, nodes);
     return hipGetLastError();
 }
 

@@ -314,7 +314,7 @@ static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, 
 // workgroup alone on its CU that fetches one K tile ahead waits a full memory round trip per K
 // tile.  This kernel asks for up to `ns` K tiles of 128 at once, straight into as many LDS
 // stages (32 KB each), and multiplies them as they land; a stage is refilled as soon as every
-// wave has read it.  One tile per workgroup, 4 waves of 32x32, bias folded into the accumulator.
+// wave has read it.  One tile per workgroup, 4 waves of 32x32.
 #define GS_BK 128
 #define GS_STAGE ((64 + 64) * GS_BK)   // bf16 elements of one stage: A tile, then B tile
 #define GS_LOADS 8                     // direct loads per wave and stage
@@ -359,17 +359,11 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gb[i] + chunk * GS_BK),
                                              (__attribute__((address_space(3))) void *)(dst + (64 + i * 16) * GS_BK), 16, 0, 0);
     };
-    // the bias first: loads retire in order, so one requested behind the tiles would wait for them all
-    floatx16 acc;
-    {
-        const int col = tile_n * 64 + wn * 32 + (lane & 31);
-        float bv = (bias && col < N) ? bias[col] : 0.f;
-        asm volatile("" : "+v"(bv));
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = bv;
-    }
     const int first = min(ns, kt);
     for (int c = 0; c < first; ++c) fetch(c, c);
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const int frow = lane & 31, fsel = lane >> 5, fsw = frow & 15;
     const int fa = (wm * 32 + frow) * GS_BK, fb = (64 + wn * 32 + frow) * GS_BK;
     int stage = 0;
@@ -403,6 +397,9 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     const int col = tile_n * 64 + wn * 32 + (lane & 31);
     // destination addresses first (all row indices requested at once, one wait), then stores that
     // depend on no load: a store behind a branch would otherwise wait for the store before it
+    // (the bias is requested here, with the row indices: loads retire in order, so asked for at the
+    // top it would either wait for the tiles or hold them back)
+    const float bv = (bias && col < N) ? bias[col] : 0.f;
     float *dst[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -415,7 +412,7 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int row = tile_m * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (row < M && col < N) *dst[r] = acc[r];
+        if (row < M && col < N) *dst[r] = acc[r] + bv;
     }
 }
 

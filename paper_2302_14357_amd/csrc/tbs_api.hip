@@ -140,11 +140,11 @@ struct ProfScope {
 hipError_t wait_counts(tbs_ctx *c) {
     const int want = c->seq;
     for (unsigned spin = 1;; ++spin) {
-        if (__atomic_load_n(&c->h_counts[TBS_CNT_TICKET], __ATOMIC_ACQUIRE) == want) return hipSuccess;
+        if (__atomic_load_n(&c->h_counts[TBS_CNT_SEQ], __ATOMIC_ACQUIRE) == want) return hipSuccess;
         if ((spin & 0x3FFF) == 0) {   // now and then: has the stream failed, or ended without the number?
             const hipError_t e = hipStreamQuery(c->stream);
             if (e == hipSuccess)
-                return __atomic_load_n(&c->h_counts[TBS_CNT_TICKET], __ATOMIC_ACQUIRE) == want ? hipSuccess
+                return __atomic_load_n(&c->h_counts[TBS_CNT_SEQ], __ATOMIC_ACQUIRE) == want ? hipSuccess
                                                                                               : hipErrorUnknown;
             if (e != hipErrorNotReady) return e;
         }
@@ -417,10 +417,9 @@ int tbs_segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->round = 0;
     c->parity = seg_index & 1;
     AView &A = c->A[c->a_cur];
-    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv,
-                                   c->h_counts_dev, ++c->seq));
+    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv));
+    HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, A, c->rv, c->nodes, 0, c->h_counts_dev, ++c->seq));
     HIPCHK(c, launch_state_copy(c->stream, c->cur, A, c->rv, c->pool_p, c->pool_h, c->pool_c, c->pool_rows));
-    HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, A, c->rv, c->nodes, 0));
     HIPCHK(c, wait_counts(c));
     if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
     c->state = ST_READY;
@@ -471,9 +470,9 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     {
         ProfScope ps(c, TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
         HIPCHK(c, launch_select_merge(c->stream, c->cur, c->parity, c->round, drop, c->logits, c->row_lc, c->dphi,
-                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes, c->h_counts_dev,
-                                      ++c->seq));
-        HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, An, c->rv, c->nodes, 1));
+                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes));
+        HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, An, c->rv, c->nodes, 1, c->h_counts_dev,
+                                 ++c->seq));
     }
     HIPCHK(c, wait_counts(c));
     c->a_cur ^= 1;
@@ -665,8 +664,8 @@ int tbs_debug_rebuild(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->round = 0;
     c->parity = 0;
     HIPCHK(c, launch_set_sp(c->stream, c->cur, seg_index, c->utt_T, c->rv));
-    HIPCHK(c, launch_rowscan(c->stream, c->cur, c->A[c->a_cur], c->rv, 0, c->h_counts_dev, ++c->seq));
-    HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0));
+    HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0, c->h_counts_dev,
+                             ++c->seq));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
     c->state = ST_READY;

@@ -44,12 +44,12 @@ struct RowView {
     int *row_enc;    // [rows] frame row in enc_proj
     int *row_slot;   // [rows] predictor-state slot
     int *counts;     // [8]: 0 pairs, 1 rows, 2 trie nodes used, 3 error flags, 4 live utterances,
-                     //      5 frames joined (sum of S' over live utterances), 6 workgroup ticket,
-                     //      7 first trie node of the hypotheses made in this round
+                     //      5 frames joined (sum of S' over live utterances), 6 number of the launch that
+                     //      published the figures (host mirror), 7 the other slot of 2 (they alternate)
 };
 
 enum { TBS_CNT_PAIRS = 0, TBS_CNT_ROWS = 1, TBS_CNT_NODES = 2, TBS_CNT_ERR = 3, TBS_CNT_UTTS = 4, TBS_CNT_FRAMES = 5,
-       TBS_CNT_TICKET = 6, TBS_CNT_NODE_BASE = 7, TBS_CNT_SIZE = 8 };
+       TBS_CNT_SEQ = 6, TBS_CNT_NODE_BASE = 7, TBS_CNT_SIZE = 8 };
 enum { TBS_ERRF_BCAP = 1, TBS_ERRF_NODES = 2 };
 
 struct Dims {
@@ -69,13 +69,11 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
                              float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
                              long pool_rows);
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
-                                AView A, RowView rv, int *host_counts, int seq);
+                                AView A, RowView rv);
 hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv, float *pool_p, float *pool_h,
                              float *pool_c, long pool_rows);
-hipError_t launch_rowscan(hipStream_t st, const Dims &d, AView A, RowView rv, int assign_nodes, int *host_counts,
-                          int seq);
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
-                          int2 *nodes, int assign_nodes);
+                          int2 *nodes, int assign_nodes, int *host_counts, int seq);
 hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
                               const float *pool_p, RowView rv, void *amat);
 hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
@@ -88,8 +86,7 @@ hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *
                          float *delta_nb, int force_generic);
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
-                               const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes,
-                               int *host_counts, int seq);
+                               const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
                               const void *embed, const float *pool_h, void *xh);
 hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, const float *pool_h,
