@@ -36,6 +36,68 @@ WORKLOADS = {
 }
 
 
+def read_traffic(kernel, workload):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def measure_at_scale(iters=6):
+    """One joiner + expansion call on the shape of the largest configuration (1024 utterances,
+    N=10, S=5, Dj=1024, V=4096: 51200 joiner rows, a full beam everywhere), where the two kernels
+    are throughput-bound: the figures the roofline targets are stated for."""
+    import dataclasses
+    from tbs_inputs import SHAPES, make_model, make_utterances
+    from paper_2302_14357_amd import Tbs, BUF, KERNEL
+    U, N, S = 1024, 10, 5
+    shape = dataclasses.replace(SHAPES["throughput"], len_lo=S, len_hi=S)
+    model = make_model(shape)
+    offsets, enc = make_utterances(shape, model)
+    t = Tbs(model, blank_id=shape.blank_id, beam_n=N, seg_s=S, max_utts=U, max_frames_total=int(offsets[-1]),
+            dtype=shape.dtype, act=shape.act)
+    try:
+        enc_dev = t.upload_frames(enc)
+        rng = np.random.default_rng(0)
+        t.begin(enc_dev, offsets)
+        t.debug_write(BUF.A_COUNT, np.full(U, N, np.int32))
+        t.debug_write(BUF.A_LOGS, -rng.random((U, N)) * 10)
+        t.debug_write(BUF.A_PRED, (rng.standard_normal((U, N, shape.d_joint)) * 0.5).astype(np.float32))
+        dh = rng.random((U, N, S)).astype(np.float32)
+        t.debug_write(BUF.A_DHAT, dh / dh.sum(-1, keepdims=True))
+        out = {"workload": f"one joiner + expansion call, {U} utterances x {N} hypotheses x {S} frames, "
+                           f"Dj={shape.d_joint}, V={shape.vocab}"}
+        for name, kid in (("joiner_gemm", KERNEL.JOINER), ("expand", KERNEL.EXPAND)):
+            t.profile_select(kid)
+            rows = 0
+            for _ in range(iters):
+                rows = t.debug_rebuild(0)
+                t.joiner_segment()
+                t.expand()
+            r = t.profile_read()
+            us = r["total_ms"] / max(r["launches"], 1) * 1e3
+            if name == "joiner_gemm":
+                ach = 2.0 * rows * shape.d_joint * shape.vocab / (us * 1e-6) / 1e12
+                out[name] = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                             "frac": ach / PEAK_BF16_TFLOPS, "avg_us": us, "rows": rows,
+                             "traffic": read_traffic("gemm", "at_scale")}
+            else:
+                ach = rows * shape.vocab * 4.0 / (us * 1e-6) / 1e9
+                out[name] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": ach / PEAK_HBM_GBS, "avg_us": us, "rows": rows,
+                             "traffic": read_traffic("expand", "at_scale")}
+        t.profile_select(-1)
+        return out
+    finally:
+        t.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +109,10 @@ def main():
     ap.add_argument("--utts", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--at-scale-only", action="store_true",
+                    help="only the joiner + expansion call on the largest configuration's shape (for profiling)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one device copy of 256 MiB (the yardstick for the rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (each utterance is an independent search; "
@@ -56,6 +122,16 @@ def main():
     import torch
     from tbs_inputs import SHAPES, make_model, make_utterances
     from paper_2302_14357_amd import Tbs, KERNEL
+
+    if args.calibrate:   # reads 256 MiB and writes 256 MiB: torch's elementwise copy kernel
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.at_scale_only:
+        print(json.dumps({"roofline_at_scale": measure_at_scale()}))
+        return
 
     shape_name, N, S, U, cpu_utts = WORKLOADS[args.workload]
     N = args.beam or N
@@ -97,42 +173,43 @@ def main():
     # ---- per-kernel timing with HIP events on the library's stream (separate, untimed passes)
     kernels = {}
     roofline = None
+    at_scale = None
     if not args.no_kernel_timing:
         H, E, Dj, V, L = shape.pred_hidden, shape.pred_embed, shape.d_joint, shape.vocab, shape.pred_layers
-        # bf16 models take the embedding half of layer 0 from a table made at init: no flops per round
-        in0 = 0 if shape.dtype == "bf16" else E
-        pred_flops_per_hyp = sum(2 * 4 * H * ((in0 if l == 0 else H) + H) for l in range(L)) + 2 * H * Dj
-        for name, kid in (("joiner_gemm", KERNEL.JOINER), ("joiner_prep", KERNEL.PREP), ("expand", KERNEL.EXPAND),
-                          ("select_merge", KERNEL.SELECT), ("predictor", KERNEL.PREDICTOR)):
+        bf16 = shape.dtype == "bf16"
+        for name, kid in (("gemm", KERNEL.GEMM), ("joiner_gemm", KERNEL.JOINER), ("joiner_prep", KERNEL.PREP),
+                          ("expand", KERNEL.EXPAND), ("select_merge", KERNEL.SELECT), ("predictor", KERNEL.PREDICTOR)):
             tbs.profile_select(kid)
             step()
-            r = tbs.profile_read()
-            kernels[name] = r
+            kernels[name] = tbs.profile_read()
         tbs.profile_select(-1)
         for name, r in kernels.items():
             n, ms, units = max(r["launches"], 1), r["total_ms"], r["units"]
+            sec = ms * 1e-3
             r["avg_us"] = ms / n * 1e3
-            if name == "joiner_gemm":
-                r.update(bound="mfma", unit="TFLOP/s", peak=PEAK_BF16_TFLOPS,
-                         achieved=(2.0 * units * Dj * V) / (ms * 1e-3) / 1e12 if ms > 0 else 0.0)
-            elif name == "expand":
-                r.update(bound="hbm", unit="GB/s", peak=PEAK_HBM_GBS,
-                         achieved=(units * V * 4.0) / (ms * 1e-3) / 1e9 if ms > 0 else 0.0)
-            elif name == "joiner_prep":
-                per_row = Dj * (2 + 4 + 2) if shape.dtype == "bf16" else Dj * 12
-                r.update(bound="hbm", unit="GB/s", peak=PEAK_HBM_GBS,
-                         achieved=(units * per_row) / (ms * 1e-3) / 1e9 if ms > 0 else 0.0)
-            elif name == "predictor":
-                r.update(bound="mfma", unit="TFLOP/s", peak=PEAK_BF16_TFLOPS,
-                         achieved=(units * pred_flops_per_hyp) / (ms * 1e-3) / 1e12 if ms > 0 else 0.0)
-            else:
-                r.update(bound="hbm", unit="GB/s", peak=PEAK_HBM_GBS, achieved=0.0)
-            r["frac"] = r["achieved"] / r["peak"]
-        dom = max(("joiner_gemm", "expand", "predictor"), key=lambda k: kernels[k]["total_ms"])
+            if name == "gemm":            # every launch of the GEMM kernel (joiner and predictor); units = M*N*K
+                r.update(bound="mfma", unit="TFLOP/s", peak=PEAK_BF16_TFLOPS if bf16 else 157.3,
+                         achieved=2.0 * units / sec / 1e12 if ms > 0 else 0.0)
+            elif name == "joiner_gemm":   # units = joiner rows
+                r.update(bound="mfma", unit="TFLOP/s", peak=PEAK_BF16_TFLOPS if bf16 else 157.3,
+                         achieved=2.0 * units * Dj * V / sec / 1e12 if ms > 0 else 0.0)
+            elif name == "expand":        # algorithmic bytes: every logit read once
+                r.update(bound="hbm", unit="GB/s", peak=PEAK_HBM_GBS, achieved=units * V * 4.0 / sec / 1e9 if ms > 0 else 0.0)
+            elif name == "joiner_prep":   # one encoder row (2 B/elt) + one predictor row (4 B) in, one bf16 row out
+                per_row = Dj * (2 + 4 + 2) if bf16 else Dj * 12
+                r.update(bound="hbm", unit="GB/s", peak=PEAK_HBM_GBS, achieved=units * per_row / sec / 1e9 if ms > 0 else 0.0)
+            else:                         # kernel groups with no single roofline
+                r.update(bound=None, unit=None, peak=None, achieved=None)
+            r["frac"] = r["achieved"] / r["peak"] if r["peak"] else None
+        # the dominant single kernel of this workload: the GEMM kernel (three launches a round) or
+        # the expansion kernel, whichever took longer in total
+        dom = max(("gemm", "expand"), key=lambda k: kernels[k]["total_ms"])
         d = kernels[dom]
-        roofline = {"kernel": dom, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"],
-                    "unit": d["unit"], "frac": d["frac"], "traffic": None, "avg_us": d["avg_us"],
+        roofline = {"kernel": {"gemm": "k_gemm_small / k_gemm_bf16 (all launches)", "expand": "k_expand_reg"}[dom],
+                    "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
+                    "frac": d["frac"], "traffic": read_traffic(dom, args.workload), "avg_us": d["avg_us"],
                     "launches": d["launches"]}
+        at_scale = measure_at_scale()
 
     # ---- CPU oracle on a bounded sample of the same workload
     cpu = None
@@ -170,6 +247,7 @@ def main():
         "joins_per_frame": stats["joined_frames"] / max(frames, 1),
         "joiner_launches_per_step": stats["launches"],
         "roofline": roofline,
+        "roofline_at_scale": at_scale,
         "cpu_baseline": cpu,
         "kernels": kernels,
     }

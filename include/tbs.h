@@ -177,12 +177,13 @@ int tbs_debug_hyps(tbs_ctx *ctx, int32_t group, int32_t *tokens, int32_t *lens, 
 
 /* ---- timing of one kernel family, for the benchmark ---- */
 enum tbs_kernel_id { TBS_K_JOINER = 0, TBS_K_EXPAND = 1, TBS_K_SELECT = 2, TBS_K_PREDICTOR = 3,
-                     TBS_K_PREP = 4, TBS_K_COUNT = 5 };
+                     TBS_K_PREP = 4, TBS_K_GEMM = 5, TBS_K_COUNT = 6 };
 /* Bracket every launch of the chosen kernel family (-1: none) with HIP events
  * on the context's stream. */
 int tbs_profile_select(tbs_ctx *ctx, int32_t kernel_id);
 /* Resolve the events recorded so far: launches, their summed duration, and
- * the summed work units (joiner: rows; expand: rows; others: hypotheses). Resets. */
+ * the summed work units (joiner, expand, prep: rows; TBS_K_GEMM, every launch of the bf16/fp32
+ * GEMM kernel, joiner and predictor alike: multiply-adds M*N*K; others: hypotheses). Resets. */
 int tbs_profile_read(tbs_ctx *ctx, int64_t *launches, double *total_ms, int64_t *units);
 
 const char *tbs_strerror(int code);

@@ -161,6 +161,7 @@ int elem_bytes(const tbs_ctx *c) { return c->cfg.dtype == 1 ? 2 : 4; }
 
 hipError_t gemm(tbs_ctx *c, const void *A, const void *B, const float *bias, float *C, int M, int N, int K,
                 const int *out_row, long ldc) {
+    ProfScope ps(c, TBS_K_GEMM, (int64_t)M * N * K);
     if (c->cfg.dtype == 1)
         return launch_gemm_bf16(c->stream, (const bf16_t *)A, (const bf16_t *)B, bias, C, M, N, K, out_row, ldc);
     return launch_gemm_f32(c->stream, (const float *)A, (const float *)B, bias, C, M, N, K, out_row, ldc);
@@ -497,8 +498,7 @@ int tbs_predictor_step(tbs_ctx *c) {
         for (int l = 0; l < d.L; ++l) {
             int in_dim = l == 0 ? d.E : d.H;
             if (l == 0 && c->emb_gates)
-                HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->xh[0], (const bf16_t *)c->w.w_hh[0],
-                                           nullptr, c->gates, pairs, 4 * d.H, d.H, nullptr, 4L * d.H));
+                HIPCHK(c, gemm(c, c->xh[0], c->w.w_hh[0], nullptr, c->gates, pairs, 4 * d.H, d.H, nullptr, 4L * d.H));
             else
                 HIPCHK(c, gemm(c, c->xh[l & 1], c->wcat[l], c->w.b_lstm[l], c->gates, pairs, 4 * d.H,
                                in_dim + d.H, nullptr, 4L * d.H));

@@ -26,7 +26,7 @@ class BUF:
 
 
 class KERNEL:
-    JOINER, EXPAND, SELECT, PREDICTOR, PREP = range(5)
+    JOINER, EXPAND, SELECT, PREDICTOR, PREP, GEMM = range(6)
 
 
 class TbsError(RuntimeError):
