@@ -15,9 +15,12 @@ __device__ __forceinline__ bf16_t f2bf_p(float f) {
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + expf(-x)); }
 
 // xh[j, :] = [ embed[token_j, 0:E] | h_parent_j(layer 0)[0:H] ]
+// (Both gather kernels take the number of pairs from device memory and leave when launched
+// beyond it: the host enqueues them on the largest possible grid before it knows the count.)
 __global__ void k_pred_gather(Dims d, int dtype, AView A, RowView rv, const void *embed, const float *pool_h,
                               void *xh) {
     int j = blockIdx.x;
+    if (j >= rv.counts[TBS_CNT_PAIRS]) return;
     int u = rv.pair_u[j], h = rv.pair_h[j];
     long a = (long)u * d.N + h;
     int tok = A.token[a];
@@ -47,6 +50,7 @@ hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pair
 // (embed * W_ih^T + b for every token), so the per-round input is only the parent's h.
 __global__ void k_pred_gather_h(Dims d, AView A, RowView rv, const float *pool_h, bf16_t *xh) {
     int j = blockIdx.x;
+    if (j >= rv.counts[TBS_CNT_PAIRS]) return;
     long a = (long)rv.pair_u[j] * d.N + rv.pair_h[j];
     long ps = A.pslot[a];
     bf16_t *x = xh + (long)j * d.H;

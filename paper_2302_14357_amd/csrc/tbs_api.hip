@@ -13,6 +13,7 @@
 #include "tbs_internal.h"
 
 extern int g_tbs_gemm_variant;
+extern int g_tbs_gemm_group_m;
 
 namespace {
 
@@ -475,6 +476,18 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
         HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, An, c->rv, c->nodes, 1, c->h_counts_dev,
                                  ++c->seq));
     }
+    // The first kernel of the predictor step goes out before the counts are known, on the largest
+    // grid the round could need (it sizes itself from device memory): it runs while the host
+    // waits for the counts and enqueues the rest, which would otherwise leave the GPU idle.
+    {
+        ProfScope ps(c, TBS_K_PREDICTOR, 0);
+        if (c->emb_gates)
+            HIPCHK(c, launch_pred_gather_h(c->stream, c->cur, c->cur.U * c->cur.N, An, c->rv, c->pool_h,
+                                           (bf16_t *)c->xh[0]));
+        else
+            HIPCHK(c, launch_pred_gather(c->stream, c->cur, c->cfg.dtype, c->cur.U * c->cur.N, An, c->rv, c->w.embed,
+                                         c->pool_h, c->xh[0]));
+    }
     HIPCHK(c, wait_counts(c));
     c->a_cur ^= 1;
     if (live_host) *live_host = c->h_counts[TBS_CNT_PAIRS];
@@ -490,11 +503,7 @@ int tbs_predictor_step(tbs_ctx *c) {
     AView &A = c->A[c->a_cur];
     if (pairs > 0) {
         ProfScope ps(c, TBS_K_PREDICTOR, pairs);
-        if (c->emb_gates)
-            HIPCHK(c, launch_pred_gather_h(c->stream, d, pairs, A, c->rv, c->pool_h, (bf16_t *)c->xh[0]));
-        else
-            HIPCHK(c, launch_pred_gather(c->stream, d, c->cfg.dtype, pairs, A, c->rv, c->w.embed, c->pool_h,
-                                         c->xh[0]));
+        // (the input rows of the first layer were gathered behind select/merge)
         for (int l = 0; l < d.L; ++l) {
             int in_dim = l == 0 ? d.E : d.H;
             if (l == 0 && c->emb_gates)
@@ -742,6 +751,7 @@ int tbs_gemm_bf16(const void *A, const void *B, const float *bias, float *C, int
                   void *stream) {
     if (!A || !B || !C || M < 1 || N < 1 || K < 8 || K % 8) return TBS_EINVAL;
     if (const char *v = getenv("TBS_GEMM_VARIANT")) g_tbs_gemm_variant = atoi(v);
+    if (const char *v = getenv("TBS_GEMM_GROUP_M")) g_tbs_gemm_group_m = atoi(v) > 0 ? atoi(v) : 8;
     long ldc = N;
     if (getenv("TBS_GEMM_LDC0")) ldc = 0;   // tuning only: every row lands on row 0 (no store traffic)
     hipError_t e = launch_gemm_bf16((hipStream_t)stream, (const bf16_t *)A, (const bf16_t *)B, bias, C, M, N, K,
