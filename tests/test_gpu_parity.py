@@ -175,6 +175,16 @@ def test_joiner_expand_assistant_full_width_sampled():
     _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=4, kernel="generic")
 
 
+def test_joiner_expand_throughput_shape_sampled():
+    """The largest configuration's widths (Dj=1024, V=4096, N=10, S=5) with enough rows (320
+    utterances, ~8000 rows) that the joiner runs on the 256x256-tile persistent GEMM and the
+    expansion on the 80-logits-per-thread kernel: the two kernels the at-scale roofline figures
+    are measured on, sampled hypotheses against the oracle."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES["throughput"], n_utts=320, len_lo=25, len_hi=25)
+    _check_joiner_expand(shape, U=320, N=10, S=5, seg=3, sample_pairs=8)
+
+
 # ------------------------------------------------------------------ whole decode
 
 def _oracle_decode(shape, model, offsets, enc, N, S, threads=16, **kw):
@@ -299,6 +309,21 @@ def test_decode_librispeech_like_subset():
     same, amb, tot = compare_nbest(got, ref)
     print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
     assert same + amb == tot and same >= tot - 2
+
+
+@pytest.mark.parametrize("name,N,S", [("assistant", 10, 3), ("throughput", 10, 5)])
+def test_decode_large_shapes_short_utterances(name, N, S):
+    """Whole decodes at the widths of the two large configurations (V=4096, Dj=1024, LSTM 2x1024 /
+    1x1024) on a few short utterances, against the oracle."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES[name], n_utts=4)
+    lengths = np.array([7, 16, 23, 30])
+    model, offsets, enc = build_case(shape, n_utts=4, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, N, S)
+    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    same, amb, tot = compare_nbest(got, ref)
+    print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
+    assert same + amb == tot and same >= tot - 1
 
 
 def test_decode_full_batch_contains_the_subset():
