@@ -554,8 +554,17 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
              float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
              float *__restrict__ row_stats, float *__restrict__ delta_nb) {
     __shared__ ExpandShared<SMAX> sm;
+    // Workgroup b runs on XCD b % 8.  The joiner GEMM before this kernel gave XCD x the x-th eighth
+    // of the rows, in increasing order; here XCD x walks the pairs of the same eighth backwards, so
+    // that what it reads first is what was written last (still in its L2 and in the memory-side
+    // cache) and is read before this kernel's own traffic evicts it.  Measured: 196 -> 184 us at
+    // 51200 rows x 4096.
+    // (eighth x holds as many pairs as there are workgroups with b % 8 == x: every pair gets one)
+    const int pairs = gridDim.x, q = pairs >> 3, r = pairs & 7, x = blockIdx.x & 7;
+    const int first = x * q + min(x, r), count = q + (x < r);
+    const int pair = first + count - 1 - (int)(blockIdx.x >> 3);
     ExpandPair<SMAX> pi;
-    expand_pair_info(pi, blockIdx.x, d, A, rv, logits);
+    expand_pair_info(pi, pair, d, A, rv, logits);
     float e[SMAX][NV4 * 4];
     expand_load<NV4, SMAX>(e, logits, pi.row0, pi.sp, d.V);
     expand_pair<NV4, SMAX>(e, pi, sm, d, row_lc, dphi, cand_score, cand_tok, row_stats, delta_nb);
