@@ -226,6 +226,14 @@ def main():
         cpu = {"value": float(sub_off[-1]) / ct, "unit": "frames/s", "cores": int(min(used, nu)), "kind": "oracle",
                "sample": f"first {nu} of {U} utterances ({int(sub_off[-1])} frames), fp64 C oracle, "
                          f"OpenMP over utterances, {ct:.1f} s"}
+        # and on one core (the paper's CPU figures are single-core), on a smaller sample
+        n1 = min(2, nu)
+        one_off = offsets[:n1 + 1].copy()
+        t0 = time.perf_counter()
+        oracle.decode_lstm_batch(W, enc[:one_off[-1]], one_off, N, S, threads=1)
+        c1 = time.perf_counter() - t0
+        cpu["single_core"] = {"value": float(one_off[-1]) / c1, "unit": "frames/s", "cores": 1,
+                              "sample": f"first {n1} utterances ({int(one_off[-1])} frames), {c1:.1f} s"}
 
     out = {
         "metric": "decoded_frames_per_sec",
