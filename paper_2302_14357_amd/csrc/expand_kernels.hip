@@ -505,17 +505,17 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
         float *cs = cand_score + (long)pi.pair * d.N;
         int *ct = cand_tok + (long)pi.pair * d.N;
         if (all <= 64) {
-            // one candidate per lane; its rank is the number of candidates that beat it, counted
-            // against the joint list read from LDS at one address for all lanes
+            // one candidate per lane, as a 64-bit key (score bits, inverted token) that orders like
+            // the rule above; the rank of a candidate is the number of keys above its own
             const bool have = lane < all;
             const float x = have ? sm.jv[lane] : 0.f;
             const int k = have ? sm.jk[lane] : 0x7fffffff;
+            const u64 key = ((u64)__float_as_uint(x) << 32) | (unsigned)(0x7fffffff - k);
             int rank = 0;
-#pragma unroll 4
             for (int j = 0; j < all; ++j) {
-                const float xj = sm.jv[j];
-                const int kj = sm.jk[j];
-                rank += xj > x || (xj == x && kj < k);
+                const u64 kj = ((u64)(unsigned)__builtin_amdgcn_readlane((int)(key >> 32), j) << 32) |
+                               (unsigned)__builtin_amdgcn_readlane((int)key, j);
+                rank += kj > key;
             }
             if (have && rank < d.N) { cs[rank] = __logf(x); ct[rank] = k; }
             if (lane >= all && lane < d.N) { cs[lane] = -INFINITY; ct[lane] = -1; }
