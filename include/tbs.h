@@ -69,7 +69,9 @@ typedef struct tbs_config {
     int32_t max_nodes;        /* capacity of the token trie; 0 = 4*N*(max_frames_total+max_utts*S) */
     int32_t debug;            /* bit 0: also keep per-row softmax statistics and the full non-blank
                                  expansion scores for tbs_debug_read; bit 1: always use the
-                                 generic two-pass expansion kernel (tests cover both) */
+                                 generic two-pass expansion kernel; bit 3: keep the LSTM cell update a
+                                 kernel of its own also where it would run inside the gate GEMM
+                                 (tests cover both) */
     int32_t device_id;
     void *stream;             /* hipStream_t to enqueue on (0 = the null stream) */
 } tbs_config;

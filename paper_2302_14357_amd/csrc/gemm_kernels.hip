@@ -328,10 +328,20 @@ static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, 
 // later stages) stay in flight across it, which __syncthreads would not allow.
 __device__ __forceinline__ void gs_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+__device__ __forceinline__ float gs_sigmoid(float x) { return 1.f / (1.f + expf(-x)); }
+__device__ __forceinline__ bf16_t gs_bf16(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// LSTM = true: the product is the gate pre-activations of an LSTM layer (N = 4H, gate-interleaved
+// columns) and the epilogue is the cell update; C, out_row and ldc are not used.
+template <bool LSTM>
 __global__ void __launch_bounds__(256)
 k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
              float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
-             int tiles_n, int ns) {
+             int tiles_n, int ns, LstmEp ep) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // ns stages
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -371,10 +381,18 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     const int col = tile_n * 64 + wn * 32 + (lane & 31);
     const float bv = (bias && col < N) ? bias[col] : 0.f;
     int orow[16];
+    int e_ps = 0, e_ns = 0, e_tok = 0;   // LSTM: the row this lane updates in the epilogue
+    if (LSTM) {
+        const int erow = min(tile_m * 64 + wm * 32 + (lane >> 1), M - 1);
+        e_ps = ep.pslot[erow];
+        e_ns = ep.slot[erow];
+        e_tok = ep.emb_gates ? ep.tok[erow] : 0;
+    } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = min(tile_m * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), M - 1);
-        orow[r] = out_row ? out_row[row] : row;
+        for (int r = 0; r < 16; ++r) {
+            const int row = min(tile_m * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), M - 1);
+            orow[r] = out_row ? out_row[row] : row;
+        }
     }
     asm volatile("" ::: "memory");
     const int first = min(ns, kt);
@@ -411,6 +429,56 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         }
         stage = stage + 1 == ns ? 0 : stage + 1;
     }
+    if (LSTM) {
+        // The wave's 32 x 32 block of gates goes through LDS (the stages are free once every wave is
+        // past the last K tile) and comes back as 32 rows x 8 hidden units x 4 gates: lane l takes
+        // row l/2 and units 4(l%2)..4(l%2)+3, i.e. 16 consecutive floats of the row.
+        gs_barrier();
+        float *sacc = reinterpret_cast<float *>(smem) + wave * (32 * 36);   // rows padded to 36 floats
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            sacc[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * 36 + (lane & 31)] = acc[r] + bv;
+        const int rowb = lane >> 1, half = lane & 1;
+        const int row = tile_m * 64 + wm * 32 + rowb;
+        const int j0 = tile_n * 16 + wn * 8 + half * 4;   // first hidden unit of this lane
+        float4 g4[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) g4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
+        if (row < M && j0 < ep.H) {
+            const int H = ep.H;
+            if (ep.emb_gates) {
+                const float4 *eg = reinterpret_cast<const float4 *>(ep.emb_gates + (long)e_tok * 4 * H + 4 * j0);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 e4 = eg[q];
+                    g4[q].x += e4.x; g4[q].y += e4.y; g4[q].z += e4.z; g4[q].w += e4.w;
+                }
+            }
+            const float4 cp4 = *reinterpret_cast<const float4 *>(ep.c_par + (long)e_ps * H + j0);
+            const float cp[4] = {cp4.x, cp4.y, cp4.z, cp4.w};
+            float cn[4], hn[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float ig = gs_sigmoid(g4[q].x), fg = gs_sigmoid(g4[q].y), gg = tanhf(g4[q].z), og = gs_sigmoid(g4[q].w);
+                cn[q] = fg * cp[q] + ig * gg;
+                hn[q] = og * tanhf(cn[q]);
+            }
+            *reinterpret_cast<float4 *>(ep.c_new + (long)e_ns * H + j0) = make_float4(cn[0], cn[1], cn[2], cn[3]);
+            *reinterpret_cast<float4 *>(ep.h_new + (long)e_ns * H + j0) = make_float4(hn[0], hn[1], hn[2], hn[3]);
+            const uint2 hb = make_uint2((unsigned)gs_bf16(hn[0]) | ((unsigned)gs_bf16(hn[1]) << 16),
+                                        (unsigned)gs_bf16(hn[2]) | ((unsigned)gs_bf16(hn[3]) << 16));
+            if (ep.h_par_next == nullptr) {
+                *reinterpret_cast<uint2 *>(ep.out16 + (long)row * H + j0) = hb;
+            } else {
+                const float4 hp = *reinterpret_cast<const float4 *>(ep.h_par_next + (long)e_ps * H + j0);
+                *reinterpret_cast<uint2 *>(ep.out16 + (long)row * 2 * H + j0) = hb;
+                *reinterpret_cast<uint2 *>(ep.out16 + (long)row * 2 * H + H + j0) =
+                    make_uint2((unsigned)gs_bf16(hp.x) | ((unsigned)gs_bf16(hp.y) << 16),
+                               (unsigned)gs_bf16(hp.z) | ((unsigned)gs_bf16(hp.w) << 16));
+            }
+        }
+        return;
+    }
     // epilogue: lane holds column (lane & 31); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4.
     // Every address is made before the first store, outside any branch: a wait behind a branch
     // would make each store wait for the store before it.
@@ -432,7 +500,10 @@ static int gemm_small_stages() {
     if (stages < 0) {
         stages = 0;
         for (int ns = 5; ns >= 2; --ns)
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess &&
+                hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess) {
                 stages = ns;
@@ -441,6 +512,24 @@ static int gemm_small_stages() {
         (void)hipGetLastError();
     }
     return stages;
+}
+
+bool gemm_lstm_fits(int M, int H, int K) {
+    const int ns_max = gemm_small_stages();
+    const long tiles = (long)((M + 63) / 64) * ((4 * H + 63) / 64);
+    return ns_max >= 2 && H % 4 == 0 && K % GS_BK == 0 && K / GS_BK <= ns_max && tiles <= 320;
+}
+
+hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
+                            const LstmEp &ep) {
+    if (M <= 0) return hipSuccess;
+    if (!gemm_lstm_fits(M, ep.H, K)) return hipErrorInvalidValue;
+    const int N = 4 * ep.H, tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
+    const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
+    const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
+    hipLaunchKernelGGL(k_gemm_small<true>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, Wp, biasp,
+                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep);
+    return hipGetLastError();
 }
 
 // variant: 0 = choose by size; others force a tile shape (for tuning runs)
@@ -457,8 +546,8 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
         if (ns_max >= 2 && ((long)tiles_m * tiles_n <= 320 || v == 11)) {
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
             const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
-            hipLaunchKernelGGL(k_gemm_small, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C, M,
-                               N, K, out_row, ldc, tiles_m, tiles_n, ns);
+            hipLaunchKernelGGL(k_gemm_small<false>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
+                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{});
             return hipGetLastError();
         }
     }

@@ -51,8 +51,7 @@ hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pair
 __global__ void k_pred_gather_h(Dims d, AView A, RowView rv, const float *pool_h, bf16_t *xh) {
     int j = blockIdx.x;
     if (j >= rv.counts[TBS_CNT_PAIRS]) return;
-    long a = (long)rv.pair_u[j] * d.N + rv.pair_h[j];
-    long ps = A.pslot[a];
+    long ps = rv.pair_pslot[j];
     bf16_t *x = xh + (long)j * d.H;
     for (int i = threadIdx.x; i < d.H; i += blockDim.x) x[i] = f2bf_p(pool_h[ps * d.H + i]);
 }
@@ -69,9 +68,7 @@ __global__ void k_lstm_pointwise(Dims d, int dtype, int layer, AView A, RowView 
                                  float *pool_h, float *pool_c, long pool_rows, void *xh_next, void *htop,
                                  const float *emb_gates) {
     int j = blockIdx.x;
-    int u = rv.pair_u[j], hh = rv.pair_h[j];
-    long a = (long)u * d.N + hh;
-    long ps = A.pslot[a], ns = A.slot[a];
+    long ps = rv.pair_pslot[j], ns = rv.pair_slot[j];   // parent's and own state slot
     const float *g = gates + (long)j * 4 * d.H;
     // first layer of bf16 models: the embedding half of the gates (and the bias) comes from the table
     const float *eg = emb_gates ? emb_gates + (long)rv.pair_tok[j] * 4 * d.H : nullptr;
@@ -146,5 +143,22 @@ hipError_t launch_concat_weights(hipStream_t st, int elem_bytes, const void *w_i
     else
         hipLaunchKernelGGL(k_concat32, dim3(blocks), dim3(256), 0, st, (const uint32_t *)w_ih, (const uint32_t *)w_hh,
                            (uint32_t *)wcat, rows, in_dim, hid);
+    return hipGetLastError();
+}
+
+// dst row 4j+g = src row g*H+j (rows of row_bytes bytes, a multiple of 4): the gate-interleaved
+// order the fused gate GEMM wants
+__global__ void k_permute_gate_rows(const uint32_t *src, uint32_t *dst, int H, long row_words) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= 4L * H * row_words) return;
+    const long r = idx / row_words, w = idx % row_words;
+    const long j = r >> 2, g = r & 3;
+    dst[idx] = src[(g * H + j) * row_words + w];
+}
+
+hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes) {
+    const long words = row_bytes / 4, n = 4L * H * words;
+    hipLaunchKernelGGL(k_permute_gate_rows, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const uint32_t *)src,
+                       (uint32_t *)dst, H, words);
     return hipGetLastError();
 }

@@ -58,6 +58,11 @@ struct tbs_ctx {
 
     void *wcat[TBS_MAX_LAYERS];
     float *emb_gates;   // bf16 models: [V, 4H] = embed * W_ih(layer 0)^T + b(layer 0)
+    // gate-interleaved copies (row 4j+g = gate g of unit j) for the GEMM that updates the cell in its
+    // epilogue: layer 0 [4H, H] (recurrent half), layers >= 1 [4H, 2H]; biases of layers >= 1; the table
+    void *wperm[TBS_MAX_LAYERS];
+    float *bperm[TBS_MAX_LAYERS];
+    float *emb_gates_perm;
     void *xh[2];
     void *htop;
     float *gates;
@@ -271,6 +276,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->rv.utt_pair0, U);
     rc |= dev_alloc(c, &c->rv.utt_row0, U);
     rc |= dev_alloc(c, &c->rv.pair_slot, UN);
+    rc |= dev_alloc(c, &c->rv.pair_pslot, UN);
     rc |= dev_alloc(c, &c->rv.pair_tok, UN);
     rc |= dev_alloc(c, &c->rv.utt_sp, U);
     rc |= dev_alloc(c, &c->rv.pair_u, UN);
@@ -322,7 +328,22 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         c->wcat[l] = p;
     }
     c->emb_gates = nullptr;
-    if (cfg->dtype == 1) rc |= dev_alloc(c, &c->emb_gates, (size_t)d.V * 4 * d.H);
+    c->emb_gates_perm = nullptr;
+    char *wih0p = nullptr;      // scratch of the table's construction
+    float *b0p = nullptr;
+    if (cfg->dtype == 1) {
+        rc |= dev_alloc(c, &c->emb_gates, (size_t)d.V * 4 * d.H);
+        rc |= dev_alloc(c, &c->emb_gates_perm, (size_t)d.V * 4 * d.H);
+        rc |= dev_alloc(c, &wih0p, (size_t)4 * d.H * d.E * 2);
+        rc |= dev_alloc(c, &b0p, (size_t)4 * d.H);
+        for (int l = 0; l < d.L; ++l) {
+            char *p = nullptr;
+            rc |= dev_alloc(c, &p, (size_t)4 * d.H * (l == 0 ? d.H : 2 * d.H) * 2);
+            c->wperm[l] = p;
+            c->bperm[l] = nullptr;
+            if (l > 0) rc |= dev_alloc(c, &c->bperm[l], (size_t)4 * d.H);
+        }
+    }
     rc |= dev_alloc(c, &c->res_count, U);
     rc |= dev_alloc(c, &c->res_len, UN);
     rc |= dev_alloc(c, &c->res_logs, UN);
@@ -355,7 +376,23 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         }
     }
     if (c->emb_gates) {
-        e = launch_gemm_bf16(c->stream, (const bf16_t *)w->embed, (const bf16_t *)w->w_ih[0], w->b_lstm[0],
+        // gate-interleaved copies: the table through the permuted input weights and bias of layer 0,
+        // the recurrent (layers >= 1: concatenated) weights and biases directly
+        e = launch_permute_gate_rows(c->stream, w->w_ih[0], wih0p, d.H, (long)d.E * 2);
+        if (e == hipSuccess) e = launch_permute_gate_rows(c->stream, w->b_lstm[0], b0p, d.H, 4);
+        if (e == hipSuccess)
+            e = launch_gemm_bf16(c->stream, (const bf16_t *)w->embed, (const bf16_t *)wih0p, b0p, c->emb_gates_perm, d.V,
+                                 4 * d.H, d.E, nullptr, 4L * d.H);
+        for (int l = 0; l < d.L && e == hipSuccess; ++l) {
+            if (l == 0) {
+                e = launch_permute_gate_rows(c->stream, w->w_hh[0], c->wperm[0], d.H, (long)d.H * 2);
+            } else {
+                e = launch_permute_gate_rows(c->stream, c->wcat[l], c->wperm[l], d.H, (long)2 * d.H * 2);
+                if (e == hipSuccess) e = launch_permute_gate_rows(c->stream, w->b_lstm[l], c->bperm[l], d.H, 4);
+            }
+        }
+        if (e == hipSuccess)
+            e = launch_gemm_bf16(c->stream, (const bf16_t *)w->embed, (const bf16_t *)w->w_ih[0], w->b_lstm[0],
                              c->emb_gates, d.V, 4 * d.H, d.E, nullptr, 4L * d.H);
         if (e != hipSuccess) {
             c->last_hip = (int)e;
@@ -506,6 +543,26 @@ int tbs_predictor_step(tbs_ctx *c) {
         // (the input rows of the first layer were gathered behind select/merge)
         for (int l = 0; l < d.L; ++l) {
             int in_dim = l == 0 ? d.E : d.H;
+            const int K = (l == 0 && c->emb_gates) ? d.H : in_dim + d.H;
+            if (c->emb_gates && !(c->cfg.debug & 8) && gemm_lstm_fits(pairs, d.H, K)) {
+                // small problem: the cell update runs in the epilogue of the gate GEMM
+                const bool last = l + 1 == d.L;
+                LstmEp ep;
+                ep.pslot = c->rv.pair_pslot;
+                ep.slot = c->rv.pair_slot;
+                ep.tok = c->rv.pair_tok;
+                ep.emb_gates = l == 0 ? c->emb_gates_perm : nullptr;
+                ep.c_par = c->pool_c + (size_t)l * c->pool_rows * d.H;
+                ep.c_new = c->pool_c + (size_t)l * c->pool_rows * d.H;
+                ep.h_new = c->pool_h + (size_t)l * c->pool_rows * d.H;
+                ep.h_par_next = last ? nullptr : c->pool_h + (size_t)(l + 1) * c->pool_rows * d.H;
+                ep.out16 = (bf16_t *)(last ? c->htop : c->xh[(l + 1) & 1]);
+                ep.H = d.H;
+                ProfScope pg(c, TBS_K_GEMM, (int64_t)pairs * 4 * d.H * K);
+                HIPCHK(c, launch_gemm_lstm(c->stream, (const bf16_t *)c->xh[l & 1], (const bf16_t *)c->wperm[l], c->bperm[l],
+                                           pairs, K, ep));
+                continue;
+            }
             if (l == 0 && c->emb_gates)
                 HIPCHK(c, gemm(c, c->xh[0], c->w.w_hh[0], nullptr, c->gates, pairs, 4 * d.H, d.H, nullptr, 4L * d.H));
             else

@@ -40,6 +40,7 @@ struct RowView {
     int *utt_sp;     // [U]  frames of each utterance in this segment (0 = finished)
     int *pair_u, *pair_h, *pair_row0, *pair_len;  // [pairs]
     int *pair_slot;  // [pairs] predictor-state slot of the pair's hypothesis
+    int *pair_pslot; // [pairs] slot of the hypothesis it was made from (source of the recurrent state)
     int *pair_tok;   // [pairs] last token of the pair's hypothesis (-1 if carried into the segment)
     int *row_enc;    // [rows] frame row in enc_proj
     int *row_slot;   // [rows] predictor-state slot
@@ -64,6 +65,19 @@ __host__ __device__ inline int tbs_slot_id(int u, int parity, int r, int i, int 
     return ((u * 2 + parity) * (R + 1) + r) * N + i;
 }
 
+// LSTM cell update done in the epilogue of the gate GEMM (small problems): the weight rows are
+// stored gate-interleaved (row 4j+g = gate g of hidden unit j, gate order i, f, g, o), so a 64-wide
+// output tile holds all four gates of 16 units.
+struct LstmEp {
+    const int *pslot, *slot, *tok;   // per row: parent's state slot, own state slot, last token
+    const float *emb_gates;          // [V, 4H] gate-interleaved input half of the gates (+ bias), or null
+    const float *c_par;              // cell states of this layer, indexed by slot
+    float *c_new, *h_new;            // the same pools, written at the row's own slot
+    const float *h_par_next;         // hidden states of the next layer (null for the last layer)
+    bf16_t *out16;                   // last layer: [rows, H] top hidden state; else [rows, 2H] next layer's input
+    int H;
+};
+
 // ---- launchers (each enqueues on `st` and returns the HIP status) ----
 hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, AView A1, RowView rv, int2 *nodes,
                              float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
@@ -81,6 +95,11 @@ hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
                             int N, int K, const int *out_row, long ldc, const float *rowbias = nullptr,
                             const int *rowbias_idx = nullptr);
+// true if launch_gemm_lstm can run this problem (small, K a multiple of 128 that fits the LDS stages)
+bool gemm_lstm_fits(int M, int H, int K);
+hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
+                            const LstmEp &ep);
+hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
                          float *delta_nb, int force_generic);

@@ -227,6 +227,19 @@ def test_decode_small_bf16_and_edges(N, S):
     assert st["joiner_calls"] == sum(r.joiner_calls for r in ref) or amb > 0
 
 
+@pytest.mark.parametrize("debug", [0, 8])
+def test_decode_cell_update_inside_and_outside_the_gate_gemm(debug):
+    """Two LSTM layers of 128 units: both layers fit the gate GEMM whose epilogue updates the cell
+    (debug=0); debug=8 keeps the cell update a kernel of its own.  Both against the oracle."""
+    shape = small_bf16_shape(n_utts=5, vocab=96, d=128, hidden=128, layers=2)
+    lengths = np.array([4, 9, 15, 22, 31])
+    model, offsets, enc = build_case(shape, n_utts=5, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, 4, 3)
+    got, st = _gpu_decode(shape, model, offsets, enc, 4, 3, debug=debug)
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot and same >= tot - 1
+
+
 def test_decode_step_by_step_matches_oracle_trace():
     """Drive the step entry points and compare A and B with the oracle after every round."""
     shape = small_bf16_shape(n_utts=1, vocab=48, d=64, hidden=64)
