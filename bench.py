@@ -101,8 +101,8 @@ def measure_at_scale(iters=6):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="librispeech", choices=sorted(WORKLOADS))
     ap.add_argument("--beam", type=int, default=0)
     ap.add_argument("--seg", type=int, default=0)
