@@ -191,11 +191,15 @@ int tbs_profile_read(tbs_ctx *ctx, int64_t *launches, double *total_ms, int64_t 
 const char *tbs_strerror(int code);
 int tbs_last_hip_error(const tbs_ctx *ctx);
 
-/* Plain bf16 GEMM of the joiner's own kernel, C[M,N] = A[M,K] * B[N,K]^T +
+/* Plain bf16 GEMM of the joiner's own kernels, C[M,N] = A[M,K] * B[N,K]^T +
  * bias[N] with float32 accumulation and output, exported so that the MFMA
- * tiling can be checked and timed on its own.  All pointers DEVICE. */
+ * tilings can be checked and timed on their own.  All pointers DEVICE, row-major,
+ * K a multiple of 8.  kernel: 0 = the choice the decode makes for this size;
+ * 1, 2, 3 = 64x64, 128x128, 256x256 workgroup tiles of the persistent kernel;
+ * 4 = the multi-stage kernel for small problems (K a multiple of 128, else
+ * TBS_EINVAL).  Asynchronous on `stream`. */
 int tbs_gemm_bf16(const void *A, const void *B, const float *bias, float *C, int32_t M, int32_t N,
-                  int32_t K, void *stream);
+                  int32_t K, int32_t kernel, void *stream);
 
 #ifdef __cplusplus
 }

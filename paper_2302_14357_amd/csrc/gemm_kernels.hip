@@ -58,7 +58,7 @@ template <int TM, int TN, int WM, int WN, int BK, bool KGUARD>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
             float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
-            int tiles_n, const float *__restrict__ rowbias, const int *__restrict__ rowbias_idx, int group_m) {
+            int tiles_n, int group_m) {
     constexpr int NT = 64 * WM * WN;
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr int CH = BK / 8;                                       // 16-byte chunks per LDS row
@@ -224,7 +224,7 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
 
         // epilogue: lane holds column (lane & 31); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4
         const int m0 = tile_m * BM, n0 = tile_n * BN;
-        if (out_row == nullptr && rowbias == nullptr && m0 + BM <= M && n0 + BN <= N) {
+        if (out_row == nullptr && m0 + BM <= M && n0 + BN <= N) {
             // interior tile: address = uniform row base (scalar registers) + one per-lane offset
             // + a constant, so a store costs no vector address arithmetic
             const unsigned offl = (unsigned)(wm * 32 * TM + (lane >> 5) * 4) * (unsigned)ldc +
@@ -259,9 +259,7 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
                     for (int r = 0; r < 16; ++r) {
                         const int row = m0 + wm * 32 * TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                         if (row < M && col < N) {
-                            float v = acc[i][j][r];
-                            if (rowbias) v += rowbias[(long)rowbias_idx[row] * N + col];   // per-row gathered bias
-                            C[orow[r] * ldc + col] = v;
+                            C[orow[r] * ldc + col] = acc[i][j][r];
                         }
                     }
                 }
@@ -278,12 +276,9 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
     }
 }
 
-int g_tbs_gemm_group_m = GEMM_GROUP_M;   // row tiles per XCD block (tuning runs may change it)
-
 template <int TM, int TN, int WM, int WN, int BK, int OCC>
 static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                              int N, int K, const int *out_row, long ldc, const float *rowbias,
-                              const int *rowbias_idx) {
+                              int N, int K, const int *out_row, long ldc) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const size_t shm = 2u * (BM + BN) * BK * sizeof(bf16_t);
@@ -304,10 +299,10 @@ static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, 
     const dim3 grid((unsigned)g), block(64 * WM * WN);
     if (K % BK == 0)
         hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, BK, false>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
-                           ldc, tiles_m, tiles_n, rowbias, rowbias_idx, g_tbs_gemm_group_m);
+                           ldc, tiles_m, tiles_n, GEMM_GROUP_M);
     else
         hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, BK, true>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
-                           ldc, tiles_m, tiles_n, rowbias, rowbias_idx, g_tbs_gemm_group_m);
+                           ldc, tiles_m, tiles_n, GEMM_GROUP_M);
     return hipGetLastError();
 }
 
@@ -532,18 +527,15 @@ hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, c
     return hipGetLastError();
 }
 
-// variant: 0 = choose by size; others force a tile shape (for tuning runs)
-int g_tbs_gemm_variant = 0;
-
+// kernel: 0 = by size (what the decode uses); 1..4 force one (tests run every kernel on every shape):
+// 1 = 64x64 tiles, 2 = 128x128, 3 = 256x256 (all k_gemm_bf16), 4 = k_gemm_small
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, const float *rowbias,
-                            const int *rowbias_idx) {
+                            int N, int K, const int *out_row, long ldc, int kernel) {
     if (M <= 0) return hipSuccess;
-    int v = g_tbs_gemm_variant;
-    if ((v == 0 || v == 11) && K % GS_BK == 0 && rowbias == nullptr) {
+    if ((kernel == 0 || kernel == 4) && K % GS_BK == 0) {
         const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
         const int ns_max = gemm_small_stages();
-        if (ns_max >= 2 && ((long)tiles_m * tiles_n <= 320 || v == 11)) {
+        if (ns_max >= 2 && ((long)tiles_m * tiles_n <= 320 || kernel == 4)) {
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
             const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
             hipLaunchKernelGGL(k_gemm_small<false>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
@@ -551,24 +543,19 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
             return hipGetLastError();
         }
     }
-    if (v == 0) {
-        // measured on MI355X: 256x256 tiles (8 waves, 64x128 per wave) once they fill the chip 1.5
+    if (kernel == 4) return hipErrorInvalidValue;   // k_gemm_small needs K in multiples of 128
+    if (kernel == 0) {
+        // measured on MI355X: 256x256 tiles (8 waves, 128x64 per wave) once they fill the chip 1.5
         // times over, 128x128 (two workgroups per CU) for mid sizes, 64x64 so that small problems
         // still spread over the CUs
         long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
         long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-        v = t256 >= 384 ? 6 : (t128 >= 256 ? 2 : 1);
+        kernel = t256 >= 384 ? 3 : (t128 >= 256 ? 2 : 1);
     }
-    switch (v) {
-        case 1: return gemm_launch<1, 1, 2, 2, 64, 4>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 64x64, 4 waves
-        case 2: return gemm_launch<2, 2, 2, 2, 64, 2>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 128x128, 4 waves
-        case 3: return gemm_launch<2, 2, 4, 2, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x128, 8 waves
-        case 4: return gemm_launch<4, 4, 2, 2, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 4 waves
-        case 5: return gemm_launch<2, 4, 4, 2, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 8 waves
-        case 6: return gemm_launch<4, 2, 2, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 8 waves
-        case 7: return gemm_launch<2, 2, 2, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 128x256, 8 waves
-        case 8: return gemm_launch<2, 2, 4, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);   // 256x256, 16 waves
-        case 9: return gemm_launch<1, 1, 2, 2, 128, 2>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx);  // 64x64, K tile 128
-        default: return gemm_launch<1, 2, 2, 2, 128, 1>(st, A, B, bias, C, M, N, K, out_row, ldc, rowbias, rowbias_idx); // 64x128, K tile 128
+    switch (kernel) {
+        case 1: return gemm_launch<1, 1, 2, 2, 64, 4>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 64x64, 4 waves
+        case 2: return gemm_launch<2, 2, 2, 2, 64, 2>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 128x128, 4 waves
+        case 3: return gemm_launch<4, 2, 2, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 8 waves
+        default: return hipErrorInvalidValue;
     }
 }

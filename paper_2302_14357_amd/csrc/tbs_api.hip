@@ -12,8 +12,6 @@
 
 #include "tbs_internal.h"
 
-extern int g_tbs_gemm_variant;
-extern int g_tbs_gemm_group_m;
 
 namespace {
 
@@ -805,14 +803,11 @@ int tbs_profile_read(tbs_ctx *c, int64_t *launches, double *total_ms, int64_t *u
 }
 
 int tbs_gemm_bf16(const void *A, const void *B, const float *bias, float *C, int32_t M, int32_t N, int32_t K,
-                  void *stream) {
-    if (!A || !B || !C || M < 1 || N < 1 || K < 8 || K % 8) return TBS_EINVAL;
-    if (const char *v = getenv("TBS_GEMM_VARIANT")) g_tbs_gemm_variant = atoi(v);
-    if (const char *v = getenv("TBS_GEMM_GROUP_M")) g_tbs_gemm_group_m = atoi(v) > 0 ? atoi(v) : 8;
-    long ldc = N;
-    if (getenv("TBS_GEMM_LDC0")) ldc = 0;   // tuning only: every row lands on row 0 (no store traffic)
+                  int32_t kernel, void *stream) {
+    if (!A || !B || !C || M < 1 || N < 1 || K < 8 || K % 8 || kernel < 0 || kernel > 4) return TBS_EINVAL;
+    if (kernel == 4 && K % 128) return TBS_EINVAL;
     hipError_t e = launch_gemm_bf16((hipStream_t)stream, (const bf16_t *)A, (const bf16_t *)B, bias, C, M, N, K,
-                                    nullptr, ldc);
+                                    nullptr, N, kernel);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 

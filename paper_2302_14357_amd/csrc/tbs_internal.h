@@ -93,8 +93,7 @@ hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act,
 hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
                            int K, const int *out_row, long ldc);
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, const float *rowbias = nullptr,
-                            const int *rowbias_idx = nullptr);
+                            int N, int K, const int *out_row, long ldc, int kernel = 0);
 // true if launch_gemm_lstm can run this problem (small, K a multiple of 128 that fits the LDS stages)
 bool gemm_lstm_fits(int M, int H, int K);
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,

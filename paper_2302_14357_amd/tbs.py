@@ -88,7 +88,7 @@ def load_library():
     L.tbs_strerror.argtypes = [C.c_int]
     L.tbs_strerror.restype = C.c_char_p
     L.tbs_last_hip_error.argtypes = [vp]
-    L.tbs_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    L.tbs_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
     _lib = L
     return L
 
@@ -298,7 +298,7 @@ class Tbs:
         return {"launches": n.value, "total_ms": ms.value, "units": units.value}
 
 
-def gemm_bf16(a, b, bias=None):
+def gemm_bf16(a, b, bias=None, kernel=0):
     """C = a @ b.T (+ bias) through the library's MFMA GEMM; a [M,K], b [N,K] bf16 torch tensors."""
     import torch
     L = load_library()
@@ -307,5 +307,5 @@ def gemm_bf16(a, b, bias=None):
     out = torch.empty((M, N), dtype=torch.float32, device=a.device)
     st = torch.cuda.current_stream(a.device).cuda_stream
     _check(L.tbs_gemm_bf16(a.data_ptr(), b.data_ptr(), bias.data_ptr() if bias is not None else None,
-                           out.data_ptr(), M, N, K, st))
+                           out.data_ptr(), M, N, K, kernel, st))
     return out

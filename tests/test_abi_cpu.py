@@ -48,7 +48,7 @@ def test_strerror_and_invalid_configs():
     # null context on every entry point
     assert L.tbs_joiner_segment(None) == -1 and L.tbs_expand(None) == -1
     assert L.tbs_select_merge(None, None) == -1 and L.tbs_predictor_step(None) == -1
-    assert L.tbs_gemm_bf16(None, None, None, None, 1, 1, 8, None) == -1
+    assert L.tbs_gemm_bf16(None, None, None, None, 1, 1, 8, 0, None) == -1
     L.tbs_free(None)
 
 

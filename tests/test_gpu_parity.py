@@ -31,15 +31,20 @@ def _bf16_values(rng, shape, scale=1.0):
 
 # ------------------------------------------------------------------ the MFMA GEMM on its own
 
-@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (200, 192, 128), (37, 100, 72), (1000, 1024, 512),
-                                   (4100, 4096, 1024)])
-def test_gemm_bf16_tiles(M, N, K):
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (200, 192, 128), (37, 100, 72), (1000, 1024, 512), (300, 2560, 640),
+                                   (4100, 4096, 1024), (513, 257, 256)])
+def test_gemm_bf16_tiles(M, N, K, kernel):
+    """Every GEMM kernel (0 = the one the decode would pick; 64x64, 128x128, 256x256 tiles of the
+    persistent kernel; the multi-stage kernel for small problems) on shapes with ragged edges."""
     import torch
     from paper_2302_14357_amd import gemm_bf16
+    if kernel == 4 and K % 128:
+        pytest.skip("the multi-stage kernel takes K in multiples of 128")
     rng = np.random.default_rng(M + N + K)
     a, b = _bf16_values(rng, (M, K)), _bf16_values(rng, (N, K), 0.1)
     bias = torch.from_numpy(rng.standard_normal(N).astype(np.float32))
-    got = gemm_bf16(a.cuda(), b.cuda(), bias.cuda()).cpu().numpy()
+    got = gemm_bf16(a.cuda(), b.cuda(), bias.cuda(), kernel=kernel).cpu().numpy()
     want = a.to(torch.float64).numpy() @ b.to(torch.float64).numpy().T + bias.numpy().astype(np.float64)
     np.testing.assert_allclose(got, want, rtol=1e-4, atol=1e-4 * math.sqrt(K))
 
