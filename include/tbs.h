@@ -153,7 +153,8 @@ enum tbs_buffer {
     TBS_BUF_A_PRED = 3,    /* float  [U,N,Dj]   projected predictor outputs of A */
     TBS_BUF_LOGITS = 4,    /* float  [rows,V]   joiner logits of the current round */
     TBS_BUF_ROW_STATS = 5, /* float  [rows,3]   row max, sum of exp(l-max), blank probability (debug=1) */
-    TBS_BUF_DELTA_BLANK = 6, /* float [pairs]   blank expansion score relative to the hypothesis score */
+    TBS_BUF_DELTA_BLANK = 6, /* float [pairs]   natural logarithm of the blank expansion score (Eq. 7) relative to
+                                                the hypothesis score */
     TBS_BUF_DELTA_NB = 7,  /* float  [pairs,V]  non-blank expansion scores, relative (debug=1) */
     TBS_BUF_CAND_SCORE = 8, /* float [pairs,N]  log of the N best relative scores per hypothesis */
     TBS_BUF_CAND_TOKEN = 9, /* int32 [pairs,N]  their tokens (-1 = none) */

@@ -118,8 +118,8 @@ __global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, B
                 A.pnode[a] = -1;
                 A.token[a] = -1;
                 float *dh = A.dhat + a * d.S;
-                dh[0] = 1.f;
-                for (int t = 1; t < d.S; ++t) dh[t] = 0.f;
+                dh[0] = 0.f;   // d = (s, 0, ..., 0), normalised and as logarithms
+                for (int t = 1; t < d.S; ++t) dh[t] = -INFINITY;
             }
         }
         if (lane == 0) {
@@ -321,7 +321,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
             s_anode[lane] = A.node[a];
             s_alen[lane] = A.len[a];
             s_aslot[lane] = A.slot[a];
-            s_bkey[lane] = al + (double)logf(dphi[pair0 + lane]);   // score of the blank expansion
+            s_bkey[lane] = al + (double)dphi[pair0 + lane];   // score of the blank expansion (dphi holds log delta_blank)
         }
         if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
         const int nc = H * N;
@@ -447,16 +447,20 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
                 An.slot[an] = tbs_slot_id(u, parity, round, pos, d.R, N);
                 // d of the new hypothesis (Eq. 5 for the chosen token), normalised by its sum (Eq. 6)
                 const int row0 = urow0 + h * sp;
+                // (kept as logarithms: over a long segment d spans more than the range of float, and
+                // the small entries matter to the next blank expansion)
                 float *dh = An.dhat + an * d.S;
-                float sum = 0.f;
+                float mx = -INFINITY;
                 for (int t = 0; t < sp; ++t) {
-                    const float x = __expf(logits[(long)(row0 + t) * d.V + tok] + row_lc[row0 + t]);
+                    const float x = logits[(long)(row0 + t) * d.V + tok] + row_lc[row0 + t];
                     dh[t] = x;
-                    sum += x;
+                    mx = fmaxf(mx, x);
                 }
-                const float inv = 1.f / sum;
-                for (int t = 0; t < sp; ++t) dh[t] *= inv;
-                for (int t = sp; t < d.S; ++t) dh[t] = 0.f;
+                float sum = 0.f;
+                for (int t = 0; t < sp; ++t) sum += __expf(dh[t] - mx);
+                const float lz = mx + __logf(sum);
+                for (int t = 0; t < sp; ++t) dh[t] -= lz;
+                for (int t = sp; t < d.S; ++t) dh[t] = -INFINITY;
             }
         }
     }

@@ -7,7 +7,7 @@
 // the blank products of Eq. 3 collapse into a forward variable
 //     alpha_1 = d_old[1],  alpha_t = alpha_{t-1} b_{t-1} + d_old[t]
 // (alpha_t = sum_{t1<=t} d_old[t1] Bl(t1,t)), so that
-//     delta_blank   = alpha_S' b_S'                                  (Eq. 7)
+//     delta_blank   = alpha_S' b_S'                                  (Eq. 7; handed on as its logarithm)
 //     d[k][t]       = alpha_t exp(l[t,k]-m_t) / Z_t                   (Eq. 4-5)
 //     delta_nb[k]   = sum_t d[k][t] = sum_t exp(l[t,k] + lc_t)        (Eq. 6)
 // with lc_t = log(alpha_t / Z_t) - m_t.  The [S+1,S+1] table, the [V,S] tensor
@@ -27,6 +27,51 @@ __device__ __forceinline__ void ms_combine(float &m, float &z, float m2, float z
     m = mn;
     z = a + b;
 }
+
+
+// Forward variable of Eq. 3 with extended range.  With blank probabilities of a few percent the
+// products of Eq. 3 leave the range of float after ~25 frames, while the blank expansion they end
+// in (Eq. 7) is still compared with the threshold and kept in B.  alpha is therefore carried as
+// m * 2^e, m renormalised to [0.5, 1) at every frame:
+//     alpha_t = alpha_{t-1} b_{t-1} + d_old[t]
+// For the same reason d_old itself arrives as logarithms: d_old[t] of a token emitted late in a
+// long segment is tiny, but it is multiplied by correspondingly few blanks, so every frame
+// contributes alike to the blank expansion.
+struct ScanAlpha {
+    float m;
+    int e;
+    __device__ __forceinline__ void start() { m = 0.f; e = 0; }
+    // logd = log d_old[t] (-inf: no mass at this frame)
+    __device__ __forceinline__ void step(float bprev, float logd) {
+        m *= bprev;
+        if (logd > -INFINITY) {
+            // d_old[t] = md * 2^kd with md in [0.5, 1)
+            const float l2 = logd * 1.44269504088896341f;
+            const float fl = floorf(l2);
+            const int kd = (int)fl + 1;
+            const float md = __builtin_amdgcn_exp2f(l2 - fl - 1.f);
+            if (m == 0.f || e < kd - 40) {   // what came before is below 2^-40 of d_old: beyond float
+                m = md;
+                e = kd;
+            } else {
+                m += ldexpf(md, kd - e);     // kd - e <= 40; far below, d_old[t] vanishes instead
+            }
+        }
+        int k;
+        m = frexpf(m, &k);
+        e += k;
+    }
+    // log(alpha): natural logarithm, -inf for zero
+    __device__ __forceinline__ float log_value() const {
+        return m > 0.f ? __logf(m) + (float)e * 0.69314718055994531f : -INFINITY;
+    }
+    __device__ __forceinline__ float value() const { return ldexpf(m, e); }   // may underflow to 0
+    // log(alpha * b): natural logarithm of Eq. 7
+    __device__ __forceinline__ float log_times(float b) const {
+        const float x = m * b;
+        return x > 0.f ? __logf(x) + (float)e * 0.69314718055994531f : -INFINITY;
+    }
+};
 
 // ---- wave-wide reductions without LDS traffic: four DPP steps make every lane of a 16-lane row
 // hold the row's result, four scalar lane reads combine the rows.  The result is uniform.
@@ -125,11 +170,11 @@ k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *_
     // ---- forward variable over the segment (Eq. 3 folded into a scan) and Eq. 7
     if (tid == 0) {
         const float *dold = A.dhat + ((long)u * d.N + h) * d.S;
-        float alpha = 0.f;
+        ScanAlpha al;
+        al.start();
         for (int t = 0; t < sp; ++t) {
-            alpha = (t == 0 ? 0.f : alpha * s_b[t - 1]) + dold[t];
-            float c = alpha / s_z[t];
-            float lc = c > 0.f ? __logf(c) - s_m[t] : -INFINITY;
+            al.step(t == 0 ? 0.f : s_b[t - 1], dold[t]);
+            float lc = al.log_value() - __logf(s_z[t]) - s_m[t];   // log(alpha_t / Z_t) - m_t, no underflow
             s_lc[t] = lc;
             row_lc[row0 + t] = lc;
             if (row_stats) {
@@ -138,7 +183,7 @@ k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *_
                 row_stats[(long)(row0 + t) * 3 + 2] = s_b[t];
             }
         }
-        dphi[pair] = alpha * s_b[sp - 1];
+        dphi[pair] = al.log_times(s_b[sp - 1]);
     }
     __syncthreads();
 
@@ -229,7 +274,7 @@ struct ExpandShared {
 template <int SMAX>
 struct ExpandPair {
     int pair, row0, sp;
-    float dold[SMAX];   // frame distribution of the hypothesis' last token (d_old of Eq. 3)
+    float dold[SMAX];   // frame distribution of the hypothesis' last token (d_old of Eq. 3), as logarithms
     float lblank[SMAX]; // blank logit of each row
 };
 
@@ -248,7 +293,7 @@ __device__ __forceinline__ void expand_pair_info(ExpandPair<SMAX> &pi, int pair,
     const int u = ((cint_p)rv.pair_u)[pair], h = ((cint_p)rv.pair_h)[pair];
     cfloat_p dold = (cfloat_p)A.dhat + ((long)u * d.N + h) * d.S;
 #pragma unroll
-    for (int t = 0; t < SMAX; ++t) pi.dold[t] = t < pi.sp ? dold[t] : 0.f;
+    for (int t = 0; t < SMAX; ++t) pi.dold[t] = t < pi.sp ? dold[t] : -INFINITY;
     cfloat_p lb = (cfloat_p)logits + (long)pi.row0 * d.V + d.blank;
 #pragma unroll
     for (int t = 0; t < SMAX; ++t) pi.lblank[t] = t < pi.sp ? lb[(long)t * d.V] : 0.f;
@@ -352,7 +397,9 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
     // ---- every thread: row sums, forward variable (Eq. 3 as a scan), Eq. 7, the row coefficients
     float cf[SMAX];
     {
-        float alpha = 0.f, bprev = 0.f;
+        ScanAlpha al;
+        al.start();
+        float bprev = 0.f;
 #pragma unroll
         for (int t = 0; t < SMAX; ++t) {
             cf[t] = 0.f;
@@ -363,18 +410,18 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
                 __builtin_amdgcn_sched_barrier(0);
                 const float rz = __builtin_amdgcn_rcpf(z);
                 const float b = __builtin_amdgcn_exp2f((pi.lblank[t] - mrow[t]) * 1.44269504088896341f) * rz;
-                alpha = (t == 0 ? 0.f : alpha * bprev) + pi.dold[t];
+                al.step(bprev, pi.dold[t]);
                 bprev = b;
-                const float c = alpha * rz;
+                const float c = al.value() * rz;
                 cf[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(c)));
                 if (tid == 0) {
-                    row_lc[pi.row0 + t] = c > 0.f ? __logf(c) - mrow[t] : -INFINITY;
+                    row_lc[pi.row0 + t] = al.log_value() - __logf(z) - mrow[t];   // log(alpha_t / Z_t) - m_t, no underflow
                     if (row_stats) {
                         row_stats[(long)(pi.row0 + t) * 3 + 0] = mrow[t];
                         row_stats[(long)(pi.row0 + t) * 3 + 1] = z;
                         row_stats[(long)(pi.row0 + t) * 3 + 2] = b;
                     }
-                    if (t == pi.sp - 1) dphi[pi.pair] = alpha * b;
+                    if (t == pi.sp - 1) dphi[pi.pair] = al.log_times(b);
                 }
             }
         }

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "tbs_internal.h"
+#include <math.h>
 
 
 namespace {
@@ -681,6 +682,10 @@ int tbs_debug_read(tbs_ctx *c, int32_t which, void *dst, size_t bytes) {
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (tmp) (void)hipFree(tmp);
     HIPCHK(c, e);
+    if (which == TBS_BUF_A_DHAT) {   // kept as logarithms, handed out as plain values
+        float *v = (float *)dst;
+        for (size_t i = 0; i < n / sizeof(float); ++i) v[i] = expf(v[i]);
+    }
     return TBS_OK;
 }
 
@@ -700,10 +705,14 @@ int tbs_debug_write(tbs_ctx *c, int32_t which, const void *src, size_t bytes) {
             if (bytes != sizeof(double) * UN) return TBS_EINVAL;
             HIPCHK(c, hipMemcpyAsync(A.logs, src, bytes, hipMemcpyHostToDevice, c->stream));
             break;
-        case TBS_BUF_A_DHAT:
+        case TBS_BUF_A_DHAT: {   // the library keeps logarithms; the caller gives and gets plain values
             if (bytes != sizeof(float) * UN * d.S) return TBS_EINVAL;
-            HIPCHK(c, hipMemcpyAsync(A.dhat, src, bytes, hipMemcpyHostToDevice, c->stream));
+            std::vector<float> lg((size_t)UN * d.S);
+            const float *v = (const float *)src;
+            for (size_t i = 0; i < lg.size(); ++i) lg[i] = v[i] > 0.f ? logf(v[i]) : -INFINITY;
+            HIPCHK(c, hipMemcpy(A.dhat, lg.data(), bytes, hipMemcpyHostToDevice));
             break;
+        }
         case TBS_BUF_A_PRED: {
             if (bytes != sizeof(float) * UN * d.Dj) return TBS_EINVAL;
             float *tmp = nullptr;

@@ -20,7 +20,7 @@ struct AView {
     int *pslot;     // slot of the hypothesis it was made from (source of the recurrent state)
     int *pnode;     // trie node of the hypothesis it was made from
     int *token;     // last token (-1 for hypotheses carried into the segment)
-    float *dhat;    // [U, N, S] frame distribution of the last token, normalised
+    float *dhat;    // [U, N, S] frame distribution of the last token, normalised, as natural logarithms
 };
 
 // Group B (hypotheses that took their blank for this segment), [U, BCAP].

@@ -1,7 +1,7 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element
 by element, on the same seeded inputs.
 
-Tolerances.  Expansion scores (spec bar): relative 1e-3 on scores
+Tolerances.  Expansion scores: relative 1e-3 on scores
 relative to the hypothesis score, i.e. |log gpu - log oracle| <= 1e-3, for
 entries above 1e-30.  For bf16 models the oracle rounds act(e+p) and the
 recurrent inputs to bf16 at the same points as the kernels; what remains is
@@ -111,7 +111,7 @@ def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, kerne
         d_old = dhat[u, h, :L].astype(np.float64)
         J, Bl, d, ref_nb, ref_phi = oracle.expansion_scores(ref_logits[None], d_old[None], shape.blank_id)
         np.testing.assert_allclose(stats[r0:r0 + L, 2], J[0, :, shape.blank_id], rtol=tol)
-        assert abs(math.log(dphi[j]) - math.log(ref_phi[0])) <= tol
+        assert abs(dphi[j] - math.log(ref_phi[0])) <= tol   # the kernel hands on log delta_blank
         ref_nb = ref_nb[0]
         big = ref_nb > 1e-30
         err = np.abs(np.log(dnb[j][big]) - np.log(ref_nb[big]))
@@ -341,6 +341,39 @@ def test_decode_large_shapes_short_utterances(name, N, S):
     got, st = _gpu_decode(shape, model, offsets, enc, N, S)
     same, amb, tot = compare_nbest(got, ref)
     print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
+    assert same + amb == tot and same >= tot - 1
+
+
+@pytest.mark.parametrize("N,S", [(2, 1), (2, 5), (10, 1), (10, 2), (10, 5), (5, 2), (5, 5)])
+def test_decode_librispeech_like_beam_and_segment_sweep(N, S):
+    """The Librispeech-like configuration's sweep of beam and segment sizes, at its widths, on three
+    utterances of 30-60 frames, whole decode against the oracle."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES["librispeech"], n_utts=3)
+    lengths = np.array([31, 44, 60])
+    model, offsets, enc = build_case(shape, n_utts=3, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, N, S)
+    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot and same >= tot - 1
+    assert st["joiner_calls"] == sum(r.joiner_calls for r in ref) or amb > 0
+
+
+@pytest.mark.parametrize("S", [10, 20, 50])
+def test_decode_long_segments(S):
+    """The long-segment configuration (Librispeech-like widths, N=5, S in {10, 20, 50}): the scan of
+    Eq. 3 over long segments and the expansion kernels for S beyond the register-resident range."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES["librispeech"], n_utts=2)
+    lengths = np.array([75, 128])
+    model, offsets, enc = build_case(shape, n_utts=2, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, 5, S)
+    # a segment of S frames can take more rounds than the default workspace is sized for
+    got, st = _gpu_decode(shape, model, offsets, enc, 5, S, rounds_capacity=4 * S)
+    same, amb, tot = compare_nbest(got, ref)
+    print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
+    # (with blank probabilities of a few percent the blank products over such segments span ~1e-85:
+    # this is the case that needs the forward variable and d carried with extended range)
     assert same + amb == tot and same >= tot - 1
 
 
