@@ -148,7 +148,7 @@ def test_joiner_expand_small_bf16(N, S, kernel):
 
 
 @pytest.mark.parametrize("V,N,S", [(2048, 8, 7), (1028, 3, 2), (4096, 10, 5), (3000, 4, 3), (2000, 6, 5), (4096, 20, 3),
-                                   (1024, 16, 4), (4096, 32, 2)])
+                                   (1024, 16, 4), (4096, 32, 2), (16000, 3, 2), (5001, 4, 3)])
 def test_joiner_expand_wide_vocab(V, N, S):
     """Vocabulary widths that exercise every register-kernel instantiation and a ragged last column block."""
     shape = small_bf16_shape(n_utts=4, vocab=V, d=64, hidden=64)
@@ -374,6 +374,38 @@ def test_decode_long_segments(S):
     print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
     # (with blank probabilities of a few percent the blank products over such segments span ~1e-85:
     # this is the case that needs the forward variable and d carried with extended range)
+    assert same + amb == tot and same >= tot - 1
+
+
+@pytest.mark.parametrize("name,N,S,U", [("assistant", 10, 3, 300), ("throughput", 10, 5, 200)])
+def test_decode_large_batch_contains_the_small_one(name, N, S, U):
+    """The large configurations' widths with enough utterances that every round runs on the kernels
+    chosen at scale (256x256-tile joiner GEMM, 80- or 48-logit-per-thread expansion, LSTM cell
+    update as its own kernel behind a large gate GEMM): the first four utterances must decode
+    exactly as in the four-utterance batch, which is checked against the oracle above."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES[name], n_utts=U)
+    lengths = np.concatenate([np.array([7, 16, 23, 30]), np.full(U - 4, 12)])
+    model, offsets, enc = build_case(shape, n_utts=U, lengths=lengths)
+    full, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    off4 = offsets[:5].copy()
+    part, _ = _gpu_decode(shape, model, off4, enc[:off4[-1]], N, S)
+    for u in range(4):
+        assert [y for y, _ in part[u]] == [y for y, _ in full[u]]
+        np.testing.assert_allclose([s for _, s in part[u]], [s for _, s in full[u]], atol=2e-3)
+    assert st["frames"] == int(offsets[-1])
+
+
+@pytest.mark.parametrize("N,S", [(32, 2), (17, 3)])
+def test_decode_wide_beams(N, S):
+    """Beams up to the library's maximum: the list kernels' general paths (more than 64 candidates
+    per utterance, B lists of hundreds of entries)."""
+    shape = small_bf16_shape(n_utts=3, vocab=96, d=64, hidden=64)
+    lengths = np.array([5, 11, 18])
+    model, offsets, enc = build_case(shape, n_utts=3, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, N, S)
+    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    same, amb, tot = compare_nbest(got, ref)
     assert same + amb == tot and same >= tot - 1
 
 
