@@ -90,15 +90,29 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 
 // ------------------------------------------------------------------ segment head
 // A = ChooseNBest(B); B = []; d = (s, 0, ..., 0)   (Algorithm 1, head of the outer loop)
-__global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv) {
-    int u = blockIdx.x, lane = threadIdx.x;
+// The first wave ranks B and writes A; then the whole workgroup moves the survivors' predictor
+// state into this segment's arena (slot r=0): the arena of the segment before last is reused,
+// and a survivor may have been carried, untouched, from there.
+#define SEG_THREADS 256
+__global__ void __launch_bounds__(SEG_THREADS)
+k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv, float *pool_p,
+                float *pool_h, float *pool_c, long pool_rows) {
+    __shared__ int s_src[TBS_MAX_BEAM], s_dst[TBS_MAX_BEAM];
+    __shared__ int s_n;
+    const int u = blockIdx.x, tid = threadIdx.x;
     int left = utt_T[u] - seg * d.S;
     int sp = left < 0 ? 0 : (left > d.S ? d.S : left);
-    if (lane == 0) rv.utt_sp[u] = sp;
+    if (tid == 0) {
+        rv.utt_sp[u] = sp;
+        s_n = 0;
+    }
     if (sp == 0) {  // finished (or empty) utterance: B keeps the final list
-        if (lane == 0) A.count[u] = 0;
-    } else {
-        int nB = B.count[u];
+        if (tid == 0) A.count[u] = 0;
+        return;
+    }
+    const int nB = B.count[u];
+    if (tid < WAVE) {
+        const int lane = tid;
         const double *bl = B.logs + (long)u * d.BCAP;
         for (int i = lane; i < nB; i += WAVE) {
             double si = bl[i];
@@ -109,51 +123,45 @@ __global__ void k_segment_begin(Dims d, int seg, int parity, const int *utt_T, B
             }
             if (rank < d.N) {
                 long a = (long)u * d.N + rank, b = (long)u * d.BCAP + i;
+                const int src = B.slot[b], dst = tbs_slot_id(u, parity, 0, rank, d.R, d.N);
                 A.logs[a] = si;
                 A.node[a] = B.node[b];
                 A.hash[a] = B.hash[b];
                 A.len[a] = B.len[b];
-                A.pslot[a] = B.slot[b];
-                A.slot[a] = tbs_slot_id(u, parity, 0, rank, d.R, d.N);
+                A.pslot[a] = src;
+                A.slot[a] = dst;
                 A.pnode[a] = -1;
                 A.token[a] = -1;
                 float *dh = A.dhat + a * d.S;
                 dh[0] = 0.f;   // d = (s, 0, ..., 0), normalised and as logarithms
                 for (int t = 1; t < d.S; ++t) dh[t] = -INFINITY;
+                s_src[rank] = src;
+                s_dst[rank] = dst;
             }
         }
         if (lane == 0) {
             A.count[u] = nB < d.N ? nB : d.N;
             B.count[u] = 0;
+            s_n = nB < d.N ? nB : d.N;
         }
+    }
+    __syncthreads();
+    const int n = s_n;
+    for (int i = 0; i < n; ++i) {
+        const long src = s_src[i], dst = s_dst[i];
+        for (int j = tid; j < d.Dj; j += SEG_THREADS) pool_p[dst * d.Dj + j] = pool_p[src * d.Dj + j];
+        for (int l = 0; l < d.L; ++l)
+            for (int j = tid; j < d.H; j += SEG_THREADS) {
+                pool_h[((long)l * pool_rows + dst) * d.H + j] = pool_h[((long)l * pool_rows + src) * d.H + j];
+                pool_c[((long)l * pool_rows + dst) * d.H + j] = pool_c[((long)l * pool_rows + src) * d.H + j];
+            }
     }
 }
 
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
-                                AView A, RowView rv) {
-    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(WAVE), 0, st, d, seg, parity, utt_T, B, A, rv);
-    return hipGetLastError();
-}
-
-// Survivors move their predictor state into this segment's arena (slot r=0).
-__global__ void k_state_copy(Dims d, AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c,
-                             long pool_rows) {
-    int u = blockIdx.x / d.N, i = blockIdx.x % d.N;
-    if (rv.utt_sp[u] == 0 || i >= A.count[u]) return;
-    long a = (long)u * d.N + i;
-    long src = A.pslot[a], dst = A.slot[a];
-    for (int j = threadIdx.x; j < d.Dj; j += blockDim.x) pool_p[dst * d.Dj + j] = pool_p[src * d.Dj + j];
-    for (int l = 0; l < d.L; ++l)
-        for (int j = threadIdx.x; j < d.H; j += blockDim.x) {
-            pool_h[((long)l * pool_rows + dst) * d.H + j] = pool_h[((long)l * pool_rows + src) * d.H + j];
-            pool_c[((long)l * pool_rows + dst) * d.H + j] = pool_c[((long)l * pool_rows + src) * d.H + j];
-        }
-}
-
-hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv, float *pool_p, float *pool_h,
-                             float *pool_c, long pool_rows) {
-    hipLaunchKernelGGL(k_state_copy, dim3(d.U * d.N), dim3(256), 0, st, d, A, rv, pool_p, pool_h, pool_c,
-                       pool_rows);
+                                AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows) {
+    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(SEG_THREADS), 0, st, d, seg, parity, utt_T, B, A, rv, pool_p,
+                       pool_h, pool_c, pool_rows);
     return hipGetLastError();
 }
 

@@ -23,9 +23,13 @@ __device__ __forceinline__ float joiner_act(float x, int act) { return act == 0 
 
 // ------------------------------------------------------------------ activation rows
 // a[r, :] = act(e[row_enc[r], :] + p[row_slot[r], :]), 8 elements per thread.
+// (rows_dev: when not null the row count is read from device memory and `rows` only sized the
+// grid: the host enqueues the kernel before it knows the count)
 __global__ void k_joiner_prep_bf16(int rows, int Dj, int act, const bf16_t *__restrict__ enc,
                                    const float *__restrict__ pool_p, const int *__restrict__ row_enc,
-                                   const int *__restrict__ row_slot, bf16_t *__restrict__ amat) {
+                                   const int *__restrict__ row_slot, bf16_t *__restrict__ amat,
+                                   const int *__restrict__ rows_dev) {
+    if (rows_dev) rows = *rows_dev;
     int chunks = Dj / 8;
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long)rows * chunks) return;
@@ -50,7 +54,9 @@ __global__ void k_joiner_prep_bf16(int rows, int Dj, int act, const bf16_t *__re
 
 __global__ void k_joiner_prep_f32(int rows, int Dj, int act, const float *__restrict__ enc,
                                   const float *__restrict__ pool_p, const int *__restrict__ row_enc,
-                                  const int *__restrict__ row_slot, float *__restrict__ amat) {
+                                  const int *__restrict__ row_slot, float *__restrict__ amat,
+                                  const int *__restrict__ rows_dev) {
+    if (rows_dev) rows = *rows_dev;
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long)rows * Dj) return;
     int r = (int)(idx / Dj), j = (int)(idx % Dj);
@@ -58,16 +64,16 @@ __global__ void k_joiner_prep_f32(int rows, int Dj, int act, const float *__rest
 }
 
 hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
-                              const float *pool_p, RowView rv, void *amat) {
+                              const float *pool_p, RowView rv, void *amat, const int *rows_dev) {
     if (rows <= 0) return hipSuccess;
     if (dtype == 1) {
         long n = (long)rows * (d.Dj / 8);
         hipLaunchKernelGGL(k_joiner_prep_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rows, d.Dj, act,
-                           (const bf16_t *)enc, pool_p, rv.row_enc, rv.row_slot, (bf16_t *)amat);
+                           (const bf16_t *)enc, pool_p, rv.row_enc, rv.row_slot, (bf16_t *)amat, rows_dev);
     } else {
         long n = (long)rows * d.Dj;
         hipLaunchKernelGGL(k_joiner_prep_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rows, d.Dj, act,
-                           (const float *)enc, pool_p, rv.row_enc, rv.row_slot, (float *)amat);
+                           (const float *)enc, pool_p, rv.row_enc, rv.row_slot, (float *)amat, rows_dev);
     }
     return hipGetLastError();
 }

@@ -47,6 +47,7 @@ struct tbs_ctx {
     int *h_counts;      // pinned host mirror of rv.counts
     int *h_counts_dev;  // device view of the same memory
     int seq;            // number of the last scan asked to publish its counts there
+    bool prep_ahead;    // the joiner input rows of the coming call are already being made (see tbs_segment_begin)
     int2 *nodes;
     long pool_rows;
     float *pool_p, *pool_h, *pool_c;
@@ -441,6 +442,7 @@ int tbs_begin(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, in
     memset(c->h_counts, 0, TBS_CNT_SIZE * sizeof(int));
     c->h_counts[TBS_CNT_NODES] = 1;
     c->seq = 0;
+    c->prep_ahead = false;
     c->n_calls = c->n_joined = c->n_launches = 0;
     c->n_frames = frame_offsets[U];
     c->state = ST_BEGUN;
@@ -455,9 +457,19 @@ int tbs_segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->round = 0;
     c->parity = seg_index & 1;
     AView &A = c->A[c->a_cur];
-    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv));
+    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h,
+                                   c->pool_c, c->pool_rows));
     HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, A, c->rv, c->nodes, 0, c->h_counts_dev, ++c->seq));
-    HIPCHK(c, launch_state_copy(c->stream, c->cur, A, c->rv, c->pool_p, c->pool_h, c->pool_c, c->pool_rows));
+    // The joiner input rows of the first round go out before the counts are known, on the largest
+    // grid a round can need (the kernel takes the row count from device memory): it runs while the
+    // host waits for the counts and enqueues the GEMM.
+    {
+        const Dims &d = c->cur;
+        ProfScope ps(c, TBS_K_PREP, 0);
+        HIPCHK(c, launch_joiner_prep(c->stream, d, c->cfg.dtype, c->cfg.act, d.U * d.N * d.S, c->enc, c->pool_p, c->rv,
+                                     c->amat, c->rv.counts + TBS_CNT_ROWS));
+        c->prep_ahead = true;
+    }
     HIPCHK(c, wait_counts(c));
     if (rows_host) *rows_host = c->h_counts[TBS_CNT_ROWS];
     c->state = ST_READY;
@@ -470,11 +482,12 @@ int tbs_joiner_segment(tbs_ctx *c) {
     const int rows = c->h_counts[TBS_CNT_ROWS];
     if (c->round + 1 > c->cur.R) return TBS_EOVERFLOW;
     c->round += 1;
-    {
+    if (!c->prep_ahead) {
         ProfScope ps(c, TBS_K_PREP, rows);
         HIPCHK(c, launch_joiner_prep(c->stream, c->cur, c->cfg.dtype, c->cfg.act, rows, c->enc, c->pool_p, c->rv,
                                      c->amat));
     }
+    c->prep_ahead = false;
     {
         ProfScope ps(c, TBS_K_JOINER, rows);
         HIPCHK(c, gemm(c, c->amat, c->w.w_out, c->w.b_out, c->logits, rows, c->cur.V, c->cur.Dj, nullptr,
@@ -690,6 +703,7 @@ int tbs_debug_read(tbs_ctx *c, int32_t which, void *dst, size_t bytes) {
 }
 
 int tbs_debug_write(tbs_ctx *c, int32_t which, const void *src, size_t bytes) {
+    if (c) c->prep_ahead = false;   // the state the rows were made from is being replaced
     if (!c || !src) return TBS_EINVAL;
     if (c->state == ST_INIT) return TBS_ESTATE;
     const Dims &d = c->cur;
@@ -736,6 +750,7 @@ int tbs_debug_rebuild(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->seg = seg_index;
     c->round = 0;
     c->parity = 0;
+    c->prep_ahead = false;
     HIPCHK(c, launch_set_sp(c->stream, c->cur, seg_index, c->utt_T, c->rv));
     HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0, c->h_counts_dev,
                              ++c->seq));

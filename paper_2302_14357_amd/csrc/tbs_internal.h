@@ -83,13 +83,11 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
                              float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
                              long pool_rows);
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
-                                AView A, RowView rv);
-hipError_t launch_state_copy(hipStream_t st, const Dims &d, AView A, RowView rv, float *pool_p, float *pool_h,
-                             float *pool_c, long pool_rows);
+                                AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows);
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
                           int2 *nodes, int assign_nodes, int *host_counts, int seq);
 hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
-                              const float *pool_p, RowView rv, void *amat);
+                              const float *pool_p, RowView rv, void *amat, const int *rows_dev = nullptr);
 hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
                            int K, const int *out_row, long ldc);
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
