@@ -70,8 +70,10 @@ typedef struct tbs_config {
     int32_t debug;            /* bit 0: also keep per-row softmax statistics and the full non-blank
                                  expansion scores for tbs_debug_read; bit 1: always use the
                                  generic two-pass expansion kernel; bit 3: keep the LSTM cell update a
-                                 kernel of its own also where it would run inside the gate GEMM
-                                 (tests cover both) */
+                                 kernel of its own also where it would run inside the gate GEMM;
+                                 bit 4: always form the joiner input rows in a kernel of their own,
+                                 also where the predictor projection's epilogue would (tests cover
+                                 each pair of variants) */
     int32_t device_id;
     void *stream;             /* hipStream_t to enqueue on (0 = the null stream) */
 } tbs_config;

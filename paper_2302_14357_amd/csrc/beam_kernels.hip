@@ -253,6 +253,7 @@ k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes,
             rv.pair_len[j] = sp;
             rv.pair_slot[j] = slot;
             rv.pair_pslot[j] = A.pslot[a];
+            rv.pair_frame0[j] = frame0;
             rv.pair_tok[j] = A.token[a];
             if (assign_nodes) {
                 const int node = node_base + j;

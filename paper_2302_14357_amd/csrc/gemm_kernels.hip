@@ -330,13 +330,18 @@ __device__ __forceinline__ bf16_t gs_bf16(float f) {
     return (bf16_t)(u >> 16);
 }
 
-// LSTM = true: the product is the gate pre-activations of an LSTM layer (N = 4H, gate-interleaved
+// MODE 0: C[out_row[r], :] = A[r, :] B^T + bias.
+// MODE 1: the product is the gate pre-activations of an LSTM layer (N = 4H, gate-interleaved
 // columns) and the epilogue is the cell update; C, out_row and ldc are not used.
-template <bool LSTM>
+// MODE 2: the product is the predictor projection p of new hypotheses (row r = pair r, stored at
+// C[out_row[r], :]); the epilogue also forms the joiner input rows act(e[frame] + p) of the pair's
+// frames (Section 3.1), so that the next joiner call needs no kernel of its own for them.
+template <int MODE>
 __global__ void __launch_bounds__(256)
 k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
              float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
-             int tiles_n, int ns, LstmEp ep) {
+             int tiles_n, int ns, LstmEp ep, JoinEp jp) {
+    constexpr bool LSTM = MODE == 1;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // ns stages
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -377,11 +382,18 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     const float bv = (bias && col < N) ? bias[col] : 0.f;
     int orow[16];
     int e_ps = 0, e_ns = 0, e_tok = 0;   // LSTM: the row this lane updates in the epilogue
+    int e_f0 = 0;                        // (MODE 2: destination slot, first joiner row, frames, first frame)
     if (LSTM) {
         const int erow = min(tile_m * 64 + wm * 32 + (lane >> 1), M - 1);
         e_ps = ep.pslot[erow];
         e_ns = ep.slot[erow];
         e_tok = ep.emb_gates ? ep.tok[erow] : 0;
+    } else if (MODE == 2) {
+        const int erow = min(tile_m * 64 + wm * 32 + (lane >> 1), M - 1);
+        e_ns = out_row[erow];
+        e_ps = jp.pair_row0[erow];
+        e_tok = jp.pair_len[erow];
+        e_f0 = jp.pair_frame0[erow];
     } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -474,6 +486,57 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         }
         return;
     }
+    if (MODE == 2) {
+        // Same passage through LDS: lane l takes row l/2 and 16 consecutive columns, stores them
+        // as the projection and, for each frame of the pair, adds the encoder row and activates.
+        gs_barrier();
+        float *sacc = reinterpret_cast<float *>(smem) + wave * (32 * 36);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            sacc[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * 36 + (lane & 31)] = acc[r] + bv;
+        const int rowb = lane >> 1, half = lane & 1;
+        const int row = tile_m * 64 + wm * 32 + rowb;
+        const int c0 = tile_n * 64 + wn * 32 + half * 16;
+        float4 p4[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) p4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
+        if (row < M && c0 < N) {
+            float4 *crow = reinterpret_cast<float4 *>(C + (long)e_ns * ldc + c0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) crow[q] = p4[q];
+            const float p[16] = {p4[0].x, p4[0].y, p4[0].z, p4[0].w, p4[1].x, p4[1].y, p4[1].z, p4[1].w,
+                                 p4[2].x, p4[2].y, p4[2].z, p4[2].w, p4[3].x, p4[3].y, p4[3].z, p4[3].w};
+            const int len = e_tok;
+            for (int t0 = 0; t0 < len; t0 += 4) {
+                uint4 ev[4][2];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint4 *src =
+                        reinterpret_cast<const uint4 *>(jp.enc + (long)(e_f0 + min(t0 + q, len - 1)) * N + c0);
+                    ev[q][0] = src[0];
+                    ev[q][1] = src[1];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (t0 + q < len) {
+                        const unsigned w[8] = {ev[q][0].x, ev[q][0].y, ev[q][0].z, ev[q][0].w,
+                                               ev[q][1].x, ev[q][1].y, ev[q][1].z, ev[q][1].w};
+                        unsigned o[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const float lo = tbs_joiner_act(__uint_as_float(w[i] << 16) + p[2 * i], jp.act);
+                            const float hi = tbs_joiner_act(__uint_as_float(w[i] & 0xFFFF0000u) + p[2 * i + 1], jp.act);
+                            o[i] = (unsigned)gs_bf16(lo) | ((unsigned)gs_bf16(hi) << 16);
+                        }
+                        uint4 *dstp = reinterpret_cast<uint4 *>(jp.amat + (long)(e_ps + t0 + q) * N + c0);
+                        dstp[0] = make_uint4(o[0], o[1], o[2], o[3]);
+                        dstp[1] = make_uint4(o[4], o[5], o[6], o[7]);
+                    }
+                }
+            }
+        }
+        return;
+    }
     // epilogue: lane holds column (lane & 31); accumulator r is row 8*(r/4) + 4*(lane/32) + r%4.
     // Every address is made before the first store, outside any branch: a wait behind a branch
     // would make each store wait for the store before it.
@@ -495,10 +558,13 @@ static int gemm_small_stages() {
     if (stages < 0) {
         stages = 0;
         for (int ns = 5; ns >= 2; --ns)
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<false>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<0>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess &&
-                hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<true>),
+                hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess &&
+                hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess) {
                 stages = ns;
@@ -522,8 +588,26 @@ hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, c
     const int N = 4 * ep.H, tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
-    hipLaunchKernelGGL(k_gemm_small<true>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, Wp, biasp,
-                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep);
+    hipLaunchKernelGGL(k_gemm_small<1>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, Wp, biasp,
+                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep, JoinEp{});
+    return hipGetLastError();
+}
+
+bool gemm_join_fits(int M, int N, int K) {
+    const int ns_max = gemm_small_stages();
+    const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
+    return ns_max >= 2 && N % 16 == 0 && K % GS_BK == 0 && K / GS_BK <= ns_max && tiles <= 320;
+}
+
+hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
+                            int N, int K, const int *out_row, long ldc, const JoinEp &jp) {
+    if (M <= 0) return hipSuccess;
+    if (!gemm_join_fits(M, N, K) || !out_row) return hipErrorInvalidValue;
+    const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
+    const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
+    const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
+    hipLaunchKernelGGL(k_gemm_small<2>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C, M,
+                       N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp);
     return hipGetLastError();
 }
 
@@ -538,8 +622,8 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
         if (ns_max >= 2 && ((long)tiles_m * tiles_n <= 320 || kernel == 4)) {
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
             const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
-            hipLaunchKernelGGL(k_gemm_small<false>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
-                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{});
+            hipLaunchKernelGGL(k_gemm_small<0>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
+                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{});
             return hipGetLastError();
         }
     }

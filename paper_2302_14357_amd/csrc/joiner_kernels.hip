@@ -45,8 +45,8 @@ __global__ void k_joiner_prep_bf16(int rows, int Dj, int act, const bf16_t *__re
     unsigned o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        unsigned lo = f2bf(joiner_act(e[2 * i] + p[2 * i], act));
-        unsigned hi = f2bf(joiner_act(e[2 * i + 1] + p[2 * i + 1], act));
+        unsigned lo = f2bf(tbs_joiner_act(e[2 * i] + p[2 * i], act));
+        unsigned hi = f2bf(tbs_joiner_act(e[2 * i + 1] + p[2 * i + 1], act));
         o[i] = lo | (hi << 16);
     }
     *reinterpret_cast<uint4 *>(amat + (long)r * Dj + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);

@@ -277,6 +277,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->rv.utt_row0, U);
     rc |= dev_alloc(c, &c->rv.pair_slot, UN);
     rc |= dev_alloc(c, &c->rv.pair_pslot, UN);
+    rc |= dev_alloc(c, &c->rv.pair_frame0, UN);
     rc |= dev_alloc(c, &c->rv.pair_tok, UN);
     rc |= dev_alloc(c, &c->rv.utt_sp, U);
     rc |= dev_alloc(c, &c->rv.pair_u, UN);
@@ -584,7 +585,23 @@ int tbs_predictor_step(tbs_ctx *c) {
                                             c->pool_c, c->pool_rows, c->xh[(l + 1) & 1], c->htop,
                                             l == 0 ? c->emb_gates : nullptr));
         }
-        HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, pairs, d.Dj, d.H, c->rv.pair_slot, d.Dj));
+        if (c->cfg.dtype == 1 && !(c->cfg.debug & 16) && gemm_join_fits(pairs, d.Dj, d.H)) {
+            // small problem: the projection's epilogue also makes the joiner input rows of the coming
+            // round (every row of that round belongs to one of these pairs)
+            JoinEp jp;
+            jp.pair_row0 = c->rv.pair_row0;
+            jp.pair_len = c->rv.pair_len;
+            jp.pair_frame0 = c->rv.pair_frame0;
+            jp.enc = (const bf16_t *)c->enc;
+            jp.amat = (bf16_t *)c->amat;
+            jp.act = c->cfg.act;
+            ProfScope pg(c, TBS_K_GEMM, (int64_t)pairs * d.Dj * d.H);
+            HIPCHK(c, launch_gemm_join(c->stream, (const bf16_t *)c->htop, (const bf16_t *)c->w.w_proj, c->w.b_proj,
+                                       c->pool_p, pairs, d.Dj, d.H, c->rv.pair_slot, d.Dj, jp));
+            c->prep_ahead = true;
+        } else {
+            HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, pairs, d.Dj, d.H, c->rv.pair_slot, d.Dj));
+        }
     }
     c->state = ST_READY;
     return TBS_OK;

@@ -41,6 +41,7 @@ struct RowView {
     int *pair_u, *pair_h, *pair_row0, *pair_len;  // [pairs]
     int *pair_slot;  // [pairs] predictor-state slot of the pair's hypothesis
     int *pair_pslot; // [pairs] slot of the hypothesis it was made from (source of the recurrent state)
+    int *pair_frame0; // [pairs] row in enc_proj of the pair's first frame of the segment
     int *pair_tok;   // [pairs] last token of the pair's hypothesis (-1 if carried into the segment)
     int *row_enc;    // [rows] frame row in enc_proj
     int *row_slot;   // [rows] predictor-state slot
@@ -65,6 +66,15 @@ __host__ __device__ inline int tbs_slot_id(int u, int parity, int r, int i, int 
     return ((u * 2 + parity) * (R + 1) + r) * N + i;
 }
 
+// Joiner activation of the bf16 path.  tanh x = 1 - 2 / (exp(2x) + 1) with the hardware exponential
+// and reciprocal: the absolute error is a few fp32 units of 1, far below the bf16 rounding the
+// result goes through; both kernels that form joiner input rows use it, so they agree bit for bit.
+__device__ __forceinline__ float tbs_joiner_act(float x, int act) {
+    if (act != 0) return fmaxf(x, 0.f);
+    const float t = __expf(2.f * x);
+    return 1.f - 2.f * __builtin_amdgcn_rcpf(t + 1.f);
+}
+
 // LSTM cell update done in the epilogue of the gate GEMM (small problems): the weight rows are
 // stored gate-interleaved (row 4j+g = gate g of hidden unit j, gate order i, f, g, o), so a 64-wide
 // output tile holds all four gates of 16 units.
@@ -76,6 +86,16 @@ struct LstmEp {
     const float *h_par_next;         // hidden states of the next layer (null for the last layer)
     bf16_t *out16;                   // last layer: [rows, H] top hidden state; else [rows, 2H] next layer's input
     int H;
+};
+
+// Joiner input rows made in the epilogue of the predictor projection (small problems): row r of
+// the product is the projection of pair r, whose frames pair_frame0[r] .. + pair_len[r] - 1 give
+// the joiner rows pair_row0[r] ..: amat[row, :] = act(enc[frame, :] + projection).
+struct JoinEp {
+    const int *pair_row0, *pair_len, *pair_frame0;
+    const bf16_t *enc;   // [frames, Dj]
+    bf16_t *amat;        // [rows, Dj]
+    int act;             // 0 tanh, 1 relu
 };
 
 // ---- launchers (each enqueues on `st` and returns the HIP status) ----
@@ -96,6 +116,10 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
 bool gemm_lstm_fits(int M, int H, int K);
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
                             const LstmEp &ep);
+// the same for the projection GEMM that also makes the next joiner call's input rows (bf16 models)
+bool gemm_join_fits(int M, int N, int K);
+hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
+                            int N, int K, const int *out_row, long ldc, const JoinEp &jp);
 hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,

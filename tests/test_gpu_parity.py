@@ -245,6 +245,27 @@ def test_decode_cell_update_inside_and_outside_the_gate_gemm(debug):
     assert same + amb == tot and same >= tot - 1
 
 
+@pytest.mark.parametrize("d,hidden,N,S", [(128, 128, 4, 3), (144, 128, 5, 7), (80, 256, 8, 2)])
+def test_decode_joiner_rows_from_the_projection_epilogue(d, hidden, N, S):
+    """Where the predictor projection is a small GEMM its epilogue also forms the joiner input rows
+    of the coming round; debug=16 keeps them a kernel of their own.  Widths that leave a ragged
+    column tile, segments longer than the epilogue's chunk of four frames, more pairs than one
+    row tile.  The two variants do the same arithmetic: identical results, and both against the
+    oracle."""
+    shape = small_bf16_shape(n_utts=14, vocab=96, d=d, hidden=hidden, layers=1)
+    lengths = np.array([0, 1, 3, 5, 8, 9, 11, 14, 15, 17, 20, 23, 26, 29])
+    model, offsets, enc = build_case(shape, n_utts=14, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, N, S)
+    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    own, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=16)
+    for a, b in zip(got, own):
+        assert [h[0] for h in a] == [h[0] for h in b]
+        np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-6, atol=1e-6)
+    assert st["joiner_calls"] == st2["joiner_calls"]
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot and same >= tot - 2
+
+
 def test_decode_step_by_step_matches_oracle_trace():
     """Drive the step entry points and compare A and B with the oracle after every round."""
     shape = small_bf16_shape(n_utts=1, vocab=48, d=64, hidden=64)
