@@ -74,6 +74,9 @@ typedef struct tbs_config {
                                  bit 4: always form the joiner input rows in a kernel of their own,
                                  also where the predictor projection's epilogue would (tests cover
                                  each pair of variants) */
+    int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
+                                 collects encoder frames in; 0 = no streaming.  At least seg_s; one
+                                 push may bring an utterance up to this many minus seg_s - 1 frames */
     int32_t device_id;
     void *stream;             /* hipStream_t to enqueue on (0 = the null stream) */
 } tbs_config;
@@ -135,6 +138,22 @@ int tbs_predictor_step(tbs_ctx *ctx);
 int tbs_decode(tbs_ctx *ctx, const void *enc_proj, const int32_t *frame_offsets, int32_t U,
                int32_t *tokens, int32_t *lens, double *logscores, int32_t *nbest_count,
                int32_t max_len);
+
+/* Streaming (Section 3.2, the remarks after Algorithm 1: the encoder output may arrive segment by
+ * segment, and the segment size of the encoder need not be that of the decoder).
+ * tbs_stream_begin binds U utterances with no frames yet (B as after tbs_begin).
+ * tbs_push_segment appends the frames enc_proj DEVICE [sum n_u, Dj], ragged by frame_offsets
+ * HOST [U+1] (n_u >= 0 new frames of utterance u), to the utterances' buffers and runs Algorithm
+ * 1's outer loop for every whole segment of S buffered frames of every utterance, utterances
+ * advancing independently; flush != 0 also decodes each utterance's remaining frames as one
+ * shorter segment (the end of the utterance; later frames start a new segment).  B is the state
+ * kept between calls: tbs_result after any push returns ChooseNBest(B) for the frames decoded so
+ * far.  Pushing all frames of a batch in any pieces and flushing at the end gives what tbs_decode
+ * gives.  On return the frames have been copied: the caller may reuse enc_proj.
+ * TBS_EINVAL (nothing changed) if a buffer would overflow or the frames pushed since
+ * tbs_stream_begin would exceed max_frames_total. */
+int tbs_stream_begin(tbs_ctx *ctx, int32_t U);
+int tbs_push_segment(tbs_ctx *ctx, const void *enc_proj, const int32_t *frame_offsets, int32_t flush);
 
 /* ChooseNBest(B) of every utterance, as tbs_decode returns it (for callers
  * that drive the step functions themselves). */

@@ -60,6 +60,7 @@ __global__ void k_init_batch(Dims d, BView B, AView A0, AView A1, RowView rv, in
         A1.count[u] = 0;
         rv.utt_sp[u] = 0;
         rv.utt_pair0[u] = 0;
+        rv.utt_par[u] = 1;
         if (u == 0) {
             nodes[0] = make_int2(-1, -1);
             rv.counts[TBS_CNT_PAIRS] = 0;
@@ -95,7 +96,7 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 // and a survivor may have been carried, untouched, from there.
 #define SEG_THREADS 256
 __global__ void __launch_bounds__(SEG_THREADS)
-k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A, RowView rv, float *pool_p,
+k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv, float *pool_p,
                 float *pool_h, float *pool_c, long pool_rows) {
     __shared__ int s_src[TBS_MAX_BEAM], s_dst[TBS_MAX_BEAM];
     __shared__ int s_n;
@@ -111,6 +112,7 @@ k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A,
         return;
     }
     const int nB = B.count[u];
+    const int parity = rv.utt_par[u] ^ 1;   // the arena the survivors are not in
     if (tid < WAVE) {
         const int lane = tid;
         const double *bl = B.logs + (long)u * d.BCAP;
@@ -146,6 +148,7 @@ k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A,
         }
     }
     __syncthreads();
+    if (tid == 0) rv.utt_par[u] = parity;   // (every thread has read the old value)
     const int n = s_n;
     for (int i = 0; i < n; ++i) {
         const long src = s_src[i], dst = s_dst[i];
@@ -158,9 +161,9 @@ k_segment_begin(Dims d, int seg, int parity, const int *utt_T, BView B, AView A,
     }
 }
 
-hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
+hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const int *utt_T, BView B,
                                 AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows) {
-    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(SEG_THREADS), 0, st, d, seg, parity, utt_T, B, A, rv, pool_p,
+    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(SEG_THREADS), 0, st, d, seg, utt_T, B, A, rv, pool_p,
                        pool_h, pool_c, pool_rows);
     return hipGetLastError();
 }
@@ -284,7 +287,7 @@ hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt
 #define CAND_MAX (TBS_MAX_BEAM * TBS_MAX_BEAM)
 
 __global__ void __launch_bounds__(WAVE)
-k_select_merge(Dims d, int parity, int round, int drop, const float *logits, const float *row_lc,
+k_select_merge(Dims d, int round, int drop, const float *logits, const float *row_lc,
                const float *dphi, const float *cand_score, const int *cand_tok, AView A, AView An, BView B,
                RowView rv, const int2 *nodes) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // B list of this utterance
@@ -307,7 +310,7 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
     const int N = d.N;
     // everything that describes the utterance in one round of loads
     const int sp = rv.utt_sp[u], cntA = A.count[u], pair0 = rv.utt_pair0[u], urow0 = rv.utt_row0[u];
-    const int nB0 = B.count[u];
+    const int nB0 = B.count[u], parity = rv.utt_par[u];
     const int H = sp > 0 ? cntA : 0;
     if (H == 0) {
         if (lane == 0) An.count[u] = 0;
@@ -475,11 +478,11 @@ k_select_merge(Dims d, int parity, int round, int drop, const float *logits, con
     }
 }
 
-hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
+hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes) {
     const size_t shm = (size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int));
-    hipLaunchKernelGGL(k_select_merge, dim3(d.U), dim3(WAVE), shm, st, d, parity, round, drop, logits, row_lc, dphi,
+    hipLaunchKernelGGL(k_select_merge, dim3(d.U), dim3(WAVE), shm, st, d, round, drop, logits, row_lc, dphi,
                        cand_score, cand_tok, A, An, B, rv, nodes);
     return hipGetLastError();
 }
@@ -593,6 +596,7 @@ __global__ void k_set_sp(Dims d, int seg, const int *utt_T, RowView rv) {
     if (u >= d.U) return;
     int left = utt_T[u] - seg * d.S;
     rv.utt_sp[u] = left < 0 ? 0 : (left > d.S ? d.S : left);
+    rv.utt_par[u] = 0;   // the arena k_debug_fill_a puts the hypotheses' states in
 }
 
 hipError_t launch_debug_fill_a(hipStream_t st, const Dims &d, AView A) {

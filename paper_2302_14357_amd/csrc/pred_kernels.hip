@@ -162,3 +162,30 @@ hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, 
                        (uint32_t *)dst, H, words);
     return hipGetLastError();
 }
+
+// ------------------------------------------------------------------ streaming: frame buffer
+// Copies whole frames (rows) between the caller's array, the per-utterance frame buffers and
+// the spare area used to move leftovers to the front.  UNIT = 16 or 4 bytes.
+template <typename UNIT>
+__global__ void k_stream_copy(int U, const UNIT *__restrict__ src, UNIT *__restrict__ dst, const int *__restrict__ desc,
+                              long row_units) {
+    const int u = blockIdx.x;
+    const long s0 = (long)desc[u] * row_units, d0 = (long)desc[U + u] * row_units;
+    const long total = (long)desc[2 * U + u] * row_units;
+    for (long i = (long)blockIdx.y * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.y * blockDim.x)
+        dst[d0 + i] = src[s0 + i];
+}
+
+hipError_t launch_stream_copy(hipStream_t st, int U, const void *src, void *dst, const int *desc, long row_bytes) {
+    if (U <= 0) return hipSuccess;
+    const bool wide = row_bytes % 16 == 0 && (reinterpret_cast<uintptr_t>(src) & 15) == 0 &&
+                      (reinterpret_cast<uintptr_t>(dst) & 15) == 0;
+    const dim3 grid(U, 4), block(256);
+    if (wide)
+        hipLaunchKernelGGL(k_stream_copy<uint4>, grid, block, 0, st, U, (const uint4 *)src, (uint4 *)dst, desc,
+                           row_bytes / 16);
+    else
+        hipLaunchKernelGGL(k_stream_copy<unsigned>, grid, block, 0, st, U, (const unsigned *)src, (unsigned *)dst, desc,
+                           row_bytes / 4);
+    return hipGetLastError();
+}

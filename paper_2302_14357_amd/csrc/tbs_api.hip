@@ -39,11 +39,19 @@ struct tbs_ctx {
     int *utt_T, *utt_off;
     std::vector<int> h_T;
     int max_T;
-    int seg, round, parity, a_cur;
+    int seg, round, a_cur;
 
     AView A[2];
     BView B;
     RowView rv;
+    // streaming: per-utterance frame buffers [U, stream_cap, Dj], a spare area [U, S, Dj] for moving
+    // leftovers to the front, and what the host knows of them
+    void *stream_enc, *stream_tmp;
+    int stream_cap;
+    bool streaming;
+    std::vector<int> s_fill;   // frames buffered per utterance (they start at the front of its buffer)
+    int *h_desc;               // pinned: descriptors of the frame copies and of a decode step
+    int *d_desc;
     int *h_counts;      // pinned host mirror of rv.counts
     int *h_counts_dev;  // device view of the same memory
     int seq;            // number of the last scan asked to publish its counts there
@@ -197,6 +205,7 @@ void tbs_free(tbs_ctx *c) {
     (void)hipStreamSynchronize(c->stream);
     for (void *p : c->allocs) (void)hipFree(p);
     if (c->h_counts) (void)hipHostFree(c->h_counts);
+    if (c->h_desc) (void)hipHostFree(c->h_desc);
     for (auto &e : c->events) {
         (void)hipEventDestroy(e.a);
         (void)hipEventDestroy(e.b);
@@ -215,6 +224,8 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         return TBS_EINVAL;
     if (cfg->act < 0 || cfg->act > 1 || cfg->dtype < 0 || cfg->dtype > 1) return TBS_EINVAL;
     if (cfg->max_rounds_per_segment < 0 || cfg->rounds_capacity < 0 || cfg->max_nodes < 0) return TBS_EINVAL;
+    if (cfg->stream_buffer_frames < 0 || (cfg->stream_buffer_frames != 0 && cfg->stream_buffer_frames < cfg->seg_s))
+        return TBS_EINVAL;
     if (cfg->vocab > 16000) return TBS_EINVAL;  // the expansion kernel keeps one row of scores in LDS
     if (cfg->dtype == 1 && (cfg->d_joint % 8 || cfg->pred_hidden % 8 || cfg->pred_embed % 8)) return TBS_EINVAL;
     if (!w->w_out || !w->b_out || !w->embed || !w->w_proj || !w->b_proj || !w->pred_init) return TBS_EINVAL;
@@ -229,6 +240,11 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     c->state = ST_INIT;
     c->last_hip = 0;
     c->h_counts = nullptr;
+    c->h_desc = nullptr;
+    c->d_desc = nullptr;
+    c->stream_enc = c->stream_tmp = nullptr;
+    c->stream_cap = 0;
+    c->streaming = false;
     c->res_tok = nullptr;
     c->res_max_len = 0;
     c->prof_kernel = -1;
@@ -280,6 +296,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->rv.pair_frame0, UN);
     rc |= dev_alloc(c, &c->rv.pair_tok, UN);
     rc |= dev_alloc(c, &c->rv.utt_sp, U);
+    rc |= dev_alloc(c, &c->rv.utt_par, U);
     rc |= dev_alloc(c, &c->rv.pair_u, UN);
     rc |= dev_alloc(c, &c->rv.pair_h, UN);
     rc |= dev_alloc(c, &c->rv.pair_row0, UN);
@@ -353,6 +370,20 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         tbs_free(c);
         return TBS_ENOMEM;
     }
+    if (cfg->stream_buffer_frames > 0) {
+        c->stream_cap = cfg->stream_buffer_frames;
+        char *p = nullptr, *q = nullptr;
+        rc = dev_alloc(c, &p, (size_t)U * c->stream_cap * d.Dj * elem_bytes(c));
+        rc |= dev_alloc(c, &q, (size_t)U * d.S * d.Dj * elem_bytes(c));
+        rc |= dev_alloc(c, &c->d_desc, 3 * U);
+        c->stream_enc = p;
+        c->stream_tmp = q;
+        if (rc == 0 && hipHostMalloc((void **)&c->h_desc, 3 * U * sizeof(int), hipHostMallocDefault) != hipSuccess) rc = 1;
+        if (rc) {
+            tbs_free(c);
+            return TBS_ENOMEM;
+        }
+    }
     e = hipHostMalloc((void **)&c->h_counts, TBS_CNT_SIZE * sizeof(int), hipHostMallocMapped);
     if (e != hipSuccess) {
         c->last_hip = (int)e;
@@ -412,6 +443,32 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     return TBS_OK;
 }
 
+// B = [([], 1, InitPredictor(), Null)] for U utterances whose lengths and first frames are h_T / offsets
+static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int32_t U, int max_T, long frames) {
+    HIPCHK(c, hipSetDevice(c->cfg.device_id));
+    c->cur = c->d;
+    c->cur.U = U;
+    c->enc = enc;
+    c->max_T = max_T;
+    HIPCHK(c, hipMemcpyAsync(c->utt_T, c->h_T.data(), sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->utt_off, offsets, sizeof(int) * (U + 1), hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, launch_init_batch(c->stream, c->cur, c->B, c->A[0], c->A[1], c->rv, c->nodes, c->pool_p, c->pool_h,
+                                c->pool_c, c->w.pred_init, c->pool_rows));
+    // the two host arrays above are read by the copies: finish them before returning
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->seg = -1;
+    c->round = 0;
+    c->a_cur = 0;
+    memset(c->h_counts, 0, TBS_CNT_SIZE * sizeof(int));
+    c->h_counts[TBS_CNT_NODES] = 1;
+    c->seq = 0;
+    c->prep_ahead = false;
+    c->n_calls = c->n_joined = c->n_launches = 0;
+    c->n_frames = frames;
+    c->state = ST_BEGUN;
+    return TBS_OK;
+}
+
 int tbs_begin(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, int32_t U) {
     if (!c || !frame_offsets || U < 1 || U > c->d.U) return TBS_EINVAL;
     if (frame_offsets[0] != 0) return TBS_EINVAL;
@@ -425,40 +482,35 @@ int tbs_begin(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, in
     }
     if (frame_offsets[U] > c->cfg.max_frames_total) return TBS_EINVAL;
     if (frame_offsets[U] > 0 && !enc_proj) return TBS_EINVAL;
-    HIPCHK(c, hipSetDevice(c->cfg.device_id));
-    c->cur = c->d;
-    c->cur.U = U;
-    c->enc = enc_proj;
-    c->max_T = max_T;
-    HIPCHK(c, hipMemcpyAsync(c->utt_T, c->h_T.data(), sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
-    HIPCHK(c, hipMemcpyAsync(c->utt_off, frame_offsets, sizeof(int) * (U + 1), hipMemcpyHostToDevice, c->stream));
-    HIPCHK(c, launch_init_batch(c->stream, c->cur, c->B, c->A[0], c->A[1], c->rv, c->nodes, c->pool_p, c->pool_h,
-                                c->pool_c, c->w.pred_init, c->pool_rows));
-    // the two host arrays above are read by the copies: finish them before returning
-    HIPCHK(c, hipStreamSynchronize(c->stream));
-    c->seg = -1;
-    c->round = 0;
-    c->parity = 1;
-    c->a_cur = 0;
-    memset(c->h_counts, 0, TBS_CNT_SIZE * sizeof(int));
-    c->h_counts[TBS_CNT_NODES] = 1;
-    c->seq = 0;
-    c->prep_ahead = false;
-    c->n_calls = c->n_joined = c->n_launches = 0;
-    c->n_frames = frame_offsets[U];
-    c->state = ST_BEGUN;
-    return TBS_OK;
+    c->streaming = false;
+    return begin_batch(c, enc_proj, frame_offsets, U, max_T, frame_offsets[U]);
 }
+
+int tbs_stream_begin(tbs_ctx *c, int32_t U) {
+    if (!c || U < 1 || U > c->d.U) return TBS_EINVAL;
+    if (c->stream_cap == 0) return TBS_EINVAL;   // no stream_buffer_frames in the configuration
+    c->h_T.assign(U, 0);
+    std::vector<int32_t> off(U + 1, 0);
+    c->s_fill.assign(U, 0);
+    c->streaming = true;
+    return begin_batch(c, c->stream_enc, off.data(), U, 0, 0);
+}
+
+static int segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host);
 
 int tbs_segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     if (!c || seg_index < 0) return TBS_EINVAL;
+    if (c->streaming) return TBS_ESTATE;   // a stream's segments are started by tbs_push_segment
+    return segment_begin(c, seg_index, rows_host);
+}
+
+static int segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     if (c->state != ST_BEGUN && c->state != ST_READY && c->state != ST_SELECTED) return TBS_ESTATE;
     if (c->state != ST_BEGUN && c->h_counts[TBS_CNT_PAIRS] != 0) return TBS_ESTATE;  // A not empty yet
     c->seg = seg_index;
     c->round = 0;
-    c->parity = seg_index & 1;
     AView &A = c->A[c->a_cur];
-    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->parity, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h,
+    HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h,
                                    c->pool_c, c->pool_rows));
     HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, A, c->rv, c->nodes, 0, c->h_counts_dev, ++c->seq));
     // The joiner input rows of the first round go out before the counts are known, on the largest
@@ -521,7 +573,7 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
     {
         ProfScope ps(c, TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
-        HIPCHK(c, launch_select_merge(c->stream, c->cur, c->parity, c->round, drop, c->logits, c->row_lc, c->dphi,
+        HIPCHK(c, launch_select_merge(c->stream, c->cur, c->round, drop, c->logits, c->row_lc, c->dphi,
                                       c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes));
         HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, An, c->rv, c->nodes, 1, c->h_counts_dev,
                                  ++c->seq));
@@ -635,6 +687,96 @@ int tbs_result(tbs_ctx *c, int32_t *tokens, int32_t *lens, double *logscores, in
     return ovf ? TBS_EOVERFLOW : TBS_OK;
 }
 
+// the inner loop of Algorithm 1 (while Length(A) > 0) for the segment just started
+static int run_rounds(tbs_ctx *c, int rows) {
+    int rc;
+    while (rows > 0) {
+        int live = 0;
+        if ((rc = tbs_joiner_segment(c))) return rc;
+        if ((rc = tbs_expand(c))) return rc;
+        if ((rc = tbs_select_merge(c, &live))) return rc;
+        if ((rc = tbs_predictor_step(c))) return rc;
+        rows = c->h_counts[TBS_CNT_ROWS];
+    }
+    return TBS_OK;
+}
+
+int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, int32_t flush) {
+    if (!c || !frame_offsets) return TBS_EINVAL;
+    if (!c->streaming || c->state == ST_INIT) return TBS_ESTATE;
+    if (c->state != ST_BEGUN && c->h_counts[TBS_CNT_PAIRS] != 0) return TBS_ESTATE;   // a segment is under way
+    const Dims &d = c->cur;
+    const int U = d.U, S = d.S, cap = c->stream_cap;
+    if (frame_offsets[0] != 0) return TBS_EINVAL;
+    for (int u = 0; u < U; ++u) {
+        const int n = frame_offsets[u + 1] - frame_offsets[u];
+        if (n < 0 || c->s_fill[u] + n > cap) return TBS_EINVAL;
+    }
+    if (c->n_frames + frame_offsets[U] > c->cfg.max_frames_total) return TBS_EINVAL;
+    if (frame_offsets[U] > 0 && !enc_proj) return TBS_EINVAL;
+    HIPCHK(c, hipSetDevice(c->cfg.device_id));
+    const long row_bytes = (long)d.Dj * elem_bytes(c);
+    int *src = c->h_desc, *dst = c->h_desc + U, *cnt = c->h_desc + 2 * U;
+    // the descriptors and the caller's frames are read by the stream: every use below ends with
+    // the stream drained before the host touches them again
+    if (frame_offsets[U] > 0) {
+        for (int u = 0; u < U; ++u) {
+            src[u] = frame_offsets[u];
+            dst[u] = u * cap + c->s_fill[u];
+            cnt[u] = frame_offsets[u + 1] - frame_offsets[u];
+            c->s_fill[u] += cnt[u];
+        }
+        HIPCHK(c, hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, launch_stream_copy(c->stream, U, enc_proj, c->stream_enc, c->d_desc, row_bytes));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        c->n_frames += frame_offsets[U];
+    }
+    // decode: every utterance with a whole segment buffered (or, at a flush, with anything
+    // buffered) takes one step; utterances advance independently of each other
+    std::vector<int> pos(U, 0);
+    int *take = src, *first = dst;   // reuse of the pinned area: [U] frames of this step, [U + 1] first frame rows
+    for (;;) {
+        bool any = false;
+        for (int u = 0; u < U; ++u) {
+            const int avail = c->s_fill[u] - pos[u];
+            take[u] = avail >= S ? S : (flush ? avail : 0);
+            first[u] = u * cap + pos[u];
+            any = any || take[u] > 0;
+        }
+        if (!any) break;
+        HIPCHK(c, hipMemcpyAsync(c->utt_T, take, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, hipMemcpyAsync(c->utt_off, first, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
+        int rows = 0;
+        int rc = segment_begin(c, 0, &rows);   // waits for the counts: the two copies above are done
+        if (rc) return rc;
+        if ((rc = run_rounds(c, rows))) return rc;
+        for (int u = 0; u < U; ++u) pos[u] += take[u];
+    }
+    // what is left (less than a segment) moves to the front of its buffer, through the spare area
+    bool left = false;
+    for (int u = 0; u < U; ++u) {
+        const int n = c->s_fill[u] - pos[u];
+        src[u] = u * cap + pos[u];
+        dst[u] = u * S;
+        cnt[u] = pos[u] > 0 ? n : 0;
+        left = left || cnt[u] > 0;
+        c->s_fill[u] = n;
+    }
+    if (left) {
+        HIPCHK(c, hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, launch_stream_copy(c->stream, U, c->stream_enc, c->stream_tmp, c->d_desc, row_bytes));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        for (int u = 0; u < U; ++u) {
+            src[u] = u * S;
+            dst[u] = u * cap;
+        }
+        HIPCHK(c, hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, launch_stream_copy(c->stream, U, c->stream_tmp, c->stream_enc, c->d_desc, row_bytes));
+    }
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return check_err_flags(c);
+}
+
 int tbs_decode(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, int32_t U, int32_t *tokens,
                int32_t *lens, double *logscores, int32_t *nbest_count, int32_t max_len) {
     int rc = tbs_begin(c, enc_proj, frame_offsets, U);
@@ -645,14 +787,7 @@ int tbs_decode(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, i
         int rows = 0;
         rc = tbs_segment_begin(c, seg, &rows);
         if (rc) return rc;
-        while (rows > 0) {                           // while Length(A) > 0
-            int live = 0;
-            if ((rc = tbs_joiner_segment(c))) return rc;
-            if ((rc = tbs_expand(c))) return rc;
-            if ((rc = tbs_select_merge(c, &live))) return rc;
-            if ((rc = tbs_predictor_step(c))) return rc;
-            rows = c->h_counts[TBS_CNT_ROWS];
-        }
+        if ((rc = run_rounds(c, rows))) return rc;   // while Length(A) > 0
     }
     return tbs_result(c, tokens, lens, logscores, nbest_count, max_len);
 }
@@ -766,7 +901,6 @@ int tbs_debug_rebuild(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     if (c->state == ST_INIT) return TBS_ESTATE;
     c->seg = seg_index;
     c->round = 0;
-    c->parity = 0;
     c->prep_ahead = false;
     HIPCHK(c, launch_set_sp(c->stream, c->cur, seg_index, c->utt_T, c->rv));
     HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, c->A[c->a_cur], c->rv, c->nodes, 0, c->h_counts_dev,

@@ -38,6 +38,8 @@ struct RowView {
     int *utt_pair0;  // [U]  first pair of each utterance
     int *utt_row0;   // [U]  first joiner row of each utterance
     int *utt_sp;     // [U]  frames of each utterance in this segment (0 = finished)
+    int *utt_par;    // [U]  which of the two state arenas the utterance's current segment writes to; flips each
+                     //      time the utterance starts a segment (survivors sit in the other one)
     int *pair_u, *pair_h, *pair_row0, *pair_len;  // [pairs]
     int *pair_slot;  // [pairs] predictor-state slot of the pair's hypothesis
     int *pair_pslot; // [pairs] slot of the hypothesis it was made from (source of the recurrent state)
@@ -102,7 +104,7 @@ struct JoinEp {
 hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, AView A1, RowView rv, int2 *nodes,
                              float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
                              long pool_rows);
-hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, int parity, const int *utt_T, BView B,
+hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const int *utt_T, BView B,
                                 AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows);
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
                           int2 *nodes, int assign_nodes, int *host_counts, int seq);
@@ -124,7 +126,7 @@ hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, 
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
                          float *delta_nb, int force_generic);
-hipError_t launch_select_merge(hipStream_t st, const Dims &d, int parity, int round, int drop, const float *logits,
+hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
@@ -142,4 +144,7 @@ hipError_t launch_gather_pred(hipStream_t st, const Dims &d, AView A, const floa
 hipError_t launch_concat_weights(hipStream_t st, int elem_bytes, const void *w_ih, const void *w_hh, void *wcat,
                                  int rows, int in_dim, int hid);
 hipError_t launch_debug_fill_a(hipStream_t st, const Dims &d, AView A);
+// rows of row_bytes bytes: for every utterance u, n[u] rows from src row src_row[u] on to dst row
+// dst_row[u] on (desc = [src_row | dst_row | n], each [U]); the ranges of src and dst must not overlap
+hipError_t launch_stream_copy(hipStream_t st, int U, const void *src, void *dst, const int *desc, long row_bytes);
 hipError_t launch_set_sp(hipStream_t st, const Dims &d, int seg, const int *utt_T, RowView rv);

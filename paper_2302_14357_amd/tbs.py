@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "tbs_init", "tbs_free", "tbs_begin", "tbs_segment_begin", "tbs_joiner_segment", "tbs_expand",
     "tbs_select_merge", "tbs_predictor_step", "tbs_decode", "tbs_result", "tbs_stats", "tbs_debug_read",
     "tbs_debug_write", "tbs_debug_rebuild", "tbs_debug_hyps", "tbs_profile_select", "tbs_profile_read",
-    "tbs_strerror", "tbs_last_hip_error", "tbs_gemm_bf16",
+    "tbs_strerror", "tbs_last_hip_error", "tbs_gemm_bf16", "tbs_stream_begin", "tbs_push_segment",
 ]
 
 TBS_MAX_LAYERS = 4
@@ -39,7 +39,7 @@ class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "d_joint", "vocab", "blank_id", "beam_n", "seg_s", "max_utts", "max_frames_total", "pred_layers",
         "pred_hidden", "pred_embed", "act", "dtype", "max_rounds_per_segment", "rounds_capacity", "max_nodes",
-        "debug", "device_id")] + [("stream", C.c_void_p)]
+        "debug", "stream_buffer_frames", "device_id")] + [("stream", C.c_void_p)]
 
 
 class _Weights(C.Structure):
@@ -78,6 +78,8 @@ def load_library():
     L.tbs_predictor_step.argtypes = [vp]
     L.tbs_decode.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, i32]
     L.tbs_result.argtypes = [vp, vp, vp, vp, vp, i32]
+    L.tbs_stream_begin.argtypes = [vp, i32]
+    L.tbs_push_segment.argtypes = [vp, vp, vp, i32]
     L.tbs_stats.argtypes = [vp, i64p, i64p, i64p, i64p]
     L.tbs_debug_read.argtypes = [vp, i32, vp, C.c_size_t]
     L.tbs_debug_write.argtypes = [vp, i32, vp, C.c_size_t]
@@ -111,8 +113,8 @@ class Tbs:
 
     def __init__(self, model: dict, *, blank_id: int, beam_n: int, seg_s: int, max_utts: int,
                  max_frames_total: int, dtype: str = "bf16", act: str = "tanh", max_rounds_per_segment: int = 0,
-                 rounds_capacity: int = 0, max_nodes: int = 0, debug: int = 0, device: int = 0,
-                 stream=None):
+                 rounds_capacity: int = 0, max_nodes: int = 0, debug: int = 0, stream_buffer_frames: int = 0,
+                 device: int = 0, stream=None):
         import torch
         self.torch = torch
         self.L = load_library()
@@ -148,7 +150,8 @@ class Tbs:
         self.stream = stream if stream is not None else torch.cuda.Stream(self.device)
         cfg = _Config(Dj, V, blank_id, beam_n, seg_s, max_utts, max_frames_total, L_, H, E,
                       {"tanh": 0, "relu": 1}[act], 1 if dtype == "bf16" else 0, max_rounds_per_segment,
-                      rounds_capacity, max_nodes, int(debug), device, self.stream.cuda_stream)
+                      rounds_capacity, max_nodes, int(debug), int(stream_buffer_frames), device,
+                      self.stream.cuda_stream)
         torch.cuda.synchronize(self.device)
         self.ctx = C.c_void_p()
         _check(self.L.tbs_init(C.byref(cfg), C.byref(w), C.byref(self.ctx)))
@@ -230,6 +233,17 @@ class Tbs:
         """tbs_decode into caller-provided host arrays (no Python work in the timed region)."""
         return self.L.tbs_decode(self.ctx, enc_dev.data_ptr(), _hp(offsets), len(offsets) - 1, _hp(tok), _hp(lens),
                                  _hp(logs), _hp(cnt), max_len)
+
+    def stream_begin(self, n_utts: int):
+        self.U = int(n_utts)
+        _check(self.L.tbs_stream_begin(self.ctx, self.U), self.ctx)
+
+    def push_segment(self, enc_dev, offsets, flush: bool = False):
+        """Append offsets[u+1]-offsets[u] new frames to every utterance u and decode what is ready."""
+        offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+        assert enc_dev is None or (enc_dev.dtype == self.mat_dtype and enc_dev.is_contiguous())
+        ptr = enc_dev.data_ptr() if enc_dev is not None and enc_dev.numel() > 0 else None
+        _check(self.L.tbs_push_segment(self.ctx, ptr, _hp(offsets), 1 if flush else 0), self.ctx)
 
     def result(self, max_len: int = 256):
         tok, lens, logs, cnt = self._result_arrays(max_len)

@@ -38,7 +38,8 @@ def test_strerror_and_invalid_configs():
     good = dict(d_joint=64, vocab=32, blank_id=0, beam_n=2, seg_s=3, max_utts=1, max_frames_total=50,
                 pred_layers=1, pred_hidden=64, pred_embed=64, act=0, dtype=0)
     for bad in (dict(beam_n=0), dict(beam_n=33), dict(seg_s=0), dict(vocab=1), dict(blank_id=32),
-                dict(pred_layers=5), dict(dtype=2), dict(act=3), dict(max_utts=0), dict(dtype=1, d_joint=60)):
+                dict(pred_layers=5), dict(dtype=2), dict(act=3), dict(max_utts=0), dict(dtype=1, d_joint=60),
+                dict(stream_buffer_frames=2), dict(stream_buffer_frames=-1)):
         c = tbs._Config(**{**good, **bad})
         assert L.tbs_init(C.byref(c), C.byref(w), C.byref(ctx)) == -1, bad
         assert not ctx.value
@@ -49,6 +50,7 @@ def test_strerror_and_invalid_configs():
     assert L.tbs_joiner_segment(None) == -1 and L.tbs_expand(None) == -1
     assert L.tbs_select_merge(None, None) == -1 and L.tbs_predictor_step(None) == -1
     assert L.tbs_gemm_bf16(None, None, None, None, 1, 1, 8, 0, None) == -1
+    assert L.tbs_stream_begin(None, 1) == -1 and L.tbs_push_segment(None, None, None, 0) == -1
     L.tbs_free(None)
 
 

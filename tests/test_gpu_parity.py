@@ -266,6 +266,109 @@ def test_decode_joiner_rows_from_the_projection_epilogue(d, hidden, N, S):
     assert same + amb == tot and same >= tot - 2
 
 
+@pytest.mark.parametrize("base,N,S", [("tiny", 2, 3), ("small64", 4, 3), ("small128", 5, 4)])
+def test_decode_relu_joiner(base, N, S):
+    """The joiner with a ReLU in place of tanh (the activation of the paper's Librispeech model,
+    Section 4): fp32 model, bf16 model with the input rows from their own kernel (width 64) and
+    from the projection's epilogue (width 128)."""
+    import dataclasses
+    if base == "tiny":
+        shape, kw = dataclasses.replace(SHAPES["tiny"], act="relu"), {}
+    else:
+        w = int(base[5:])
+        shape = dataclasses.replace(small_bf16_shape(n_utts=6, vocab=80, d=w, hidden=w), act="relu")
+        kw = dict(n_utts=6, lengths=np.array([2, 5, 9, 14, 20, 27]))
+    model, offsets, enc = build_case(shape, **kw)
+    ref = _oracle_decode(shape, model, offsets, enc, N, S)
+    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    same, amb, tot = compare_nbest(got, ref, score_tol=1e-3)
+    assert same + amb == tot and same >= tot - 1
+
+
+# ------------------------------------------------------------------ streaming
+
+def _push_in_pieces(tbs, shape, offsets, enc, piece_of, flush_last=True):
+    """Feed every utterance its frames in pieces of piece_of(u, call) frames until all are in."""
+    U = len(offsets) - 1
+    T = np.diff(offsets)
+    sent = np.zeros(U, dtype=np.int64)
+    tbs.stream_begin(U)
+    call = 0
+    while (sent < T).any():
+        n = np.array([min(int(piece_of(u, call)), int(T[u] - sent[u])) for u in range(U)])
+        off = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+        rows = np.concatenate([enc[offsets[u] + sent[u]: offsets[u] + sent[u] + n[u]] for u in range(U)]) \
+            if n.sum() else np.zeros((0, enc.shape[1]), np.float32)
+        sent += n
+        last = not (sent < T).any()
+        tbs.push_segment(tbs.upload_frames(rows), off, flush=(last and flush_last))
+        call += 1
+    if T.sum() == 0:
+        tbs.push_segment(None, np.zeros(U + 1, np.int32), flush=True)
+
+
+@pytest.mark.parametrize("N,S,pieces", [(4, 3, "random"), (3, 4, "one"), (5, 3, "segment"), (2, 5, "uneven")])
+def test_streaming_in_pieces_equals_decode(N, S, pieces):
+    """Encoder frames arriving in pieces (frame by frame, in decoder-sized segments, in random
+    sizes different per utterance, or some utterances much faster than others) and a flush at
+    the end give what tbs_decode gives on the whole utterances (Section 3.2: the encoder's
+    segment size need not be the decoder's), and that agrees with the oracle."""
+    shape = small_bf16_shape(n_utts=7, vocab=64, d=128, hidden=128, layers=1)
+    lengths = np.array([0, 1, 4, 9, 13, 22, 30])
+    model, offsets, enc = build_case(shape, n_utts=7, lengths=lengths)
+    rng = np.random.default_rng(5)
+    draws = rng.integers(0, 2 * S + 2, size=(7, 200))
+    piece_of = {"random": lambda u, c: draws[u, c], "one": lambda u, c: 1, "segment": lambda u, c: S,
+                "uneven": lambda u, c: (u % 3) * 3 + 1}[pieces]
+    whole, st0 = _gpu_decode(shape, model, offsets, enc, N, S)
+    tbs = make_tbs(shape, model, offsets, N, S, stream_buffer_frames=3 * S + 2)
+    _push_in_pieces(tbs, shape, offsets, enc, piece_of)
+    got = tbs.result()
+    st = tbs.stats()
+    tbs.close()
+    for a, b in zip(got, whole):
+        assert [h[0] for h in a] == [h[0] for h in b]
+        np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-5, atol=1e-5)
+    assert st["frames"] == int(lengths.sum()) and st["joined_frames"] == st0["joined_frames"]
+    ref = _oracle_decode(shape, model, offsets, enc, N, S)
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot and same >= tot - 1
+
+
+def test_streaming_partial_results_and_limits():
+    """Between pushes B holds the result for the frames decoded so far: with no flush, that is the
+    oracle's decode of each utterance's whole segments.  A push beyond the buffer is refused and
+    changes nothing; step calls and pushes do not mix."""
+    from paper_2302_14357_amd.tbs import TbsError
+    shape = small_bf16_shape(n_utts=3, vocab=48, d=64, hidden=64)
+    N, S = 3, 4
+    lengths = np.array([10, 17, 6])
+    model, offsets, enc = build_case(shape, n_utts=3, lengths=lengths)
+    tbs = make_tbs(shape, model, offsets, N, S, stream_buffer_frames=12)
+    with pytest.raises(TbsError):
+        tbs.push_segment(None, np.zeros(4, np.int32))          # no stream begun
+    _push_in_pieces(tbs, shape, offsets, enc, lambda u, c: 5, flush_last=False)
+    got = tbs.result()
+    done = (lengths // S) * S
+    off2 = np.concatenate([[0], np.cumsum(done)]).astype(np.int32)
+    enc2 = np.concatenate([enc[offsets[u]: offsets[u] + done[u]] for u in range(3)])
+    ref = _oracle_decode(shape, model, off2, enc2, N, S)
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot and same >= tot - 1
+    # 2, 1, 2 frames are still buffered; 11 more do not fit into 12
+    with pytest.raises(TbsError):
+        tbs.push_segment(tbs.upload_frames(np.zeros((11, 64), np.float32)), np.array([0, 11, 11, 11], np.int32))
+    with pytest.raises(TbsError):
+        tbs.segment_begin(0)
+    assert tbs.result() == got
+    # the rest of the stream still decodes: flush the leftovers
+    tbs.push_segment(None, np.zeros(4, np.int32), flush=True)
+    full = _oracle_decode(shape, model, offsets, enc, N, S)
+    same, amb, tot = compare_nbest(tbs.result(), full)
+    assert same + amb == tot and same >= tot - 1
+    tbs.close()
+
+
 def test_decode_step_by_step_matches_oracle_trace():
     """Drive the step entry points and compare A and B with the oracle after every round."""
     shape = small_bf16_shape(n_utts=1, vocab=48, d=64, hidden=64)
