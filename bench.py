@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--beam", type=int, default=0)
     ap.add_argument("--seg", type=int, default=0)
     ap.add_argument("--utts", type=int, default=0)
+    ap.add_argument("--stream-piece", type=int, default=0,
+                    help="decode through tbs_push_segment, every utterance receiving this many frames per "
+                         "push (0 = tbs_decode on whole utterances, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--at-scale-only", action="store_true",
@@ -144,8 +147,9 @@ def main():
     U = len(offsets) - 1
     frames = int(offsets[-1])
 
+    piece = args.stream_piece
     tbs = Tbs(model, blank_id=shape.blank_id, beam_n=N, seg_s=S, max_utts=U, max_frames_total=frames,
-              dtype=shape.dtype, act=shape.act)
+              dtype=shape.dtype, act=shape.act, stream_buffer_frames=(piece + S) if piece else 0)
     enc_dev = tbs.upload_frames(enc)           # inputs resident in HBM before the timed region
     max_len = 256
     tok = np.full((U, N, max_len), -1, np.int32)
@@ -153,10 +157,27 @@ def main():
     logs = np.zeros((U, N), np.float64)
     cnt = np.zeros(U, np.int32)
 
+    pushes = []
+    if piece:   # the pieces of every push, resident in HBM like the whole utterances of the headline
+        T = np.diff(offsets)
+        for start in range(0, int(T.max()), piece):
+            n = np.clip(T - start, 0, piece)
+            idx = np.concatenate([np.arange(offsets[u] + start, offsets[u] + start + n[u]) for u in range(U)])
+            pushes.append((enc_dev[torch.from_numpy(idx).to(enc_dev.device)].contiguous(),
+                           np.concatenate([[0], np.cumsum(n)]).astype(np.int32)))
+        torch.cuda.synchronize()
+        args.no_kernel_timing = args.no_cpu_baseline = True
+
     def step():
-        rc = tbs.decode_raw(enc_dev, offsets, tok, lens, logs, cnt, max_len)
+        if piece:
+            tbs.stream_begin(U)
+            for i, (e, off) in enumerate(pushes):
+                tbs.push_segment(e, off, flush=(i + 1 == len(pushes)))
+            rc = tbs.L.tbs_result(tbs.ctx, tok.ctypes.data, lens.ctypes.data, logs.ctypes.data, cnt.ctypes.data, max_len)
+        else:
+            rc = tbs.decode_raw(enc_dev, offsets, tok, lens, logs, cnt, max_len)
         if rc != 0:
-            raise RuntimeError(f"tbs_decode failed with {rc}")
+            raise RuntimeError(f"decode failed with {rc}")
 
     for _ in range(args.warmup):
         step()
@@ -250,7 +271,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{shape.name}-like: {U} utterances, {frames} frames, Dj={shape.d_joint}, "
                                f"V={shape.vocab}, LSTM {shape.pred_layers}x{shape.pred_hidden}, N={N}, S={S}",
-                   "beam_n": N, "seg_s": S, "utterances": U, "frames": frames},
+                   "beam_n": N, "seg_s": S, "utterances": U, "frames": frames,
+                   "entry": f"tbs_push_segment, {piece} frames per utterance and push" if piece else "tbs_decode"},
         "calls_per_frame": stats["joiner_calls"] / max(frames, 1),
         "joins_per_frame": stats["joined_frames"] / max(frames, 1),
         "joiner_launches_per_step": stats["launches"],

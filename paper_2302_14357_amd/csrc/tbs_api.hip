@@ -378,7 +378,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         rc |= dev_alloc(c, &c->d_desc, 3 * U);
         c->stream_enc = p;
         c->stream_tmp = q;
-        if (rc == 0 && hipHostMalloc((void **)&c->h_desc, 3 * U * sizeof(int), hipHostMallocDefault) != hipSuccess) rc = 1;
+        if (rc == 0 && hipHostMalloc((void **)&c->h_desc, 11 * U * sizeof(int), hipHostMallocDefault) != hipSuccess) rc = 1;
         if (rc) {
             tbs_free(c);
             return TBS_ENOMEM;
@@ -716,9 +716,13 @@ int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offs
     if (frame_offsets[U] > 0 && !enc_proj) return TBS_EINVAL;
     HIPCHK(c, hipSetDevice(c->cfg.device_id));
     const long row_bytes = (long)d.Dj * elem_bytes(c);
-    int *src = c->h_desc, *dst = c->h_desc + U, *cnt = c->h_desc + 2 * U;
-    // the descriptors and the caller's frames are read by the stream: every use below ends with
-    // the stream drained before the host touches them again
+    // Pinned descriptor areas, one per use within a call (the stream reads them later than the host
+    // writes them); the call ends with the stream drained, so the next call may write them again.
+    const int Um = c->d.U;
+    int *src = c->h_desc, *dst = src + U, *cnt = src + 2 * U;           // appending the new frames
+    int *take = c->h_desc + 3 * Um, *first = take + Um;                  // a decode step
+    int *src1 = c->h_desc + 5 * Um, *dst1 = src1 + U, *cnt1 = src1 + 2 * U;   // leftovers to the spare area
+    int *src2 = c->h_desc + 8 * Um, *dst2 = src2 + U, *cnt2 = src2 + 2 * U;   // and back to the front
     if (frame_offsets[U] > 0) {
         for (int u = 0; u < U; ++u) {
             src[u] = frame_offsets[u];
@@ -726,15 +730,13 @@ int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offs
             cnt[u] = frame_offsets[u + 1] - frame_offsets[u];
             c->s_fill[u] += cnt[u];
         }
-        HIPCHK(c, hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, hipMemcpyAsync(c->d_desc, src, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, launch_stream_copy(c->stream, U, enc_proj, c->stream_enc, c->d_desc, row_bytes));
-        HIPCHK(c, hipStreamSynchronize(c->stream));
         c->n_frames += frame_offsets[U];
     }
     // decode: every utterance with a whole segment buffered (or, at a flush, with anything
     // buffered) takes one step; utterances advance independently of each other
     std::vector<int> pos(U, 0);
-    int *take = src, *first = dst;   // reuse of the pinned area: [U] frames of this step, [U + 1] first frame rows
     for (;;) {
         bool any = false;
         for (int u = 0; u < U; ++u) {
@@ -756,21 +758,17 @@ int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offs
     bool left = false;
     for (int u = 0; u < U; ++u) {
         const int n = c->s_fill[u] - pos[u];
-        src[u] = u * cap + pos[u];
-        dst[u] = u * S;
-        cnt[u] = pos[u] > 0 ? n : 0;
-        left = left || cnt[u] > 0;
+        src1[u] = u * cap + pos[u];
+        dst1[u] = src2[u] = u * S;
+        dst2[u] = u * cap;
+        cnt1[u] = cnt2[u] = pos[u] > 0 ? n : 0;
+        left = left || cnt1[u] > 0;
         c->s_fill[u] = n;
     }
     if (left) {
-        HIPCHK(c, hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, hipMemcpyAsync(c->d_desc, src1, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, launch_stream_copy(c->stream, U, c->stream_enc, c->stream_tmp, c->d_desc, row_bytes));
-        HIPCHK(c, hipStreamSynchronize(c->stream));
-        for (int u = 0; u < U; ++u) {
-            src[u] = u * S;
-            dst[u] = u * cap;
-        }
-        HIPCHK(c, hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, hipMemcpyAsync(c->d_desc, src2, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, launch_stream_copy(c->stream, U, c->stream_tmp, c->stream_enc, c->d_desc, row_bytes));
     }
     HIPCHK(c, hipStreamSynchronize(c->stream));
