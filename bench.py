@@ -204,6 +204,7 @@ def main():
             step()
             kernels[name] = tbs.profile_read()
         tbs.profile_select(-1)
+        event_cost = tbs.profile_overhead(200)
         for name, r in kernels.items():
             n, ms, units = max(r["launches"], 1), r["total_ms"], r["units"]
             sec = ms * 1e-3
@@ -229,7 +230,10 @@ def main():
         roofline = {"kernel": {"gemm": "k_gemm_small / k_gemm_bf16 (all launches)", "expand": "k_expand_reg"}[dom],
                     "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
                     "frac": d["frac"], "traffic": read_traffic(dom, args.workload), "avg_us": d["avg_us"],
-                    "launches": d["launches"]}
+                    "launches": d["launches"],
+                    # the same event pair around a kernel that does nothing: what events add to every
+                    # launch of a microsecond-scale kernel (a kernel trace shows that kernel's own time)
+                    "event_pair_around_empty_kernel_us": event_cost}
         at_scale = measure_at_scale()
 
     # ---- CPU oracle on a bounded sample of the same workload

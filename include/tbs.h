@@ -209,6 +209,10 @@ int tbs_profile_select(tbs_ctx *ctx, int32_t kernel_id);
  * the summed work units (joiner, expand, prep: rows; TBS_K_GEMM, every launch of the bf16/fp32
  * GEMM kernel, joiner and predictor alike: multiply-adds M*N*K; others: hypotheses). Resets. */
 int tbs_profile_read(tbs_ctx *ctx, int64_t *launches, double *total_ms, int64_t *units);
+/* What the event pair itself adds: the same bracket around n launches of a kernel that does
+ * nothing (k_empty, one wave), average in microseconds (HOST).  A kernel trace of the same run
+ * shows k_empty's own duration; the difference is the cost events add to every bracket. */
+int tbs_profile_overhead(tbs_ctx *ctx, int32_t n, double *avg_us);
 
 const char *tbs_strerror(int code);
 int tbs_last_hip_error(const tbs_ctx *ctx);

@@ -95,13 +95,25 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 // state into this segment's arena (slot r=0): the arena of the segment before last is reused,
 // and a survivor may have been carried, untouched, from there.
 #define SEG_THREADS 256
+#define SEG_BATCH 10   // values a thread has in flight in the state copy
 __global__ void __launch_bounds__(SEG_THREADS)
 k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv, float *pool_p,
                 float *pool_h, float *pool_c, long pool_rows) {
     __shared__ int s_src[TBS_MAX_BEAM], s_dst[TBS_MAX_BEAM];
     __shared__ int s_n;
     const int u = blockIdx.x, tid = threadIdx.x;
-    int left = utt_T[u] - seg * d.S;
+    // Everything the head of the kernel needs is requested at once, before anything is known:
+    // the utterance's figures and, per thread, one entry of B (the first SEG_THREADS entries
+    // cover every list but the very longest), so that the ranking below starts after one memory
+    // round trip instead of four.
+    __shared__ double s_bl[2048];           // BCAP is at most 2048
+    const long bb = (long)u * d.BCAP;
+    const int e0 = min(tid, d.BCAP - 1);
+    const int T_u = utt_T[u], nB = B.count[u], par_old = rv.utt_par[u];
+    const double my_logs = B.logs[bb + e0];
+    const int my_slot = B.slot[bb + e0], my_node = B.node[bb + e0], my_len = B.len[bb + e0];
+    const u64 my_hash = B.hash[bb + e0];
+    int left = T_u - seg * d.S;
     int sp = left < 0 ? 0 : (left > d.S ? d.S : left);
     if (tid == 0) {
         rv.utt_sp[u] = sp;
@@ -111,54 +123,83 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
         if (tid == 0) A.count[u] = 0;
         return;
     }
-    const int nB = B.count[u];
-    const int parity = rv.utt_par[u] ^ 1;   // the arena the survivors are not in
-    if (tid < WAVE) {
-        const int lane = tid;
-        const double *bl = B.logs + (long)u * d.BCAP;
-        for (int i = lane; i < nB; i += WAVE) {
-            double si = bl[i];
-            int rank = 0;
-            for (int j = 0; j < nB; ++j) {
-                double sj = bl[j];
-                rank += (sj > si) || (sj == si && j < i);
-            }
-            if (rank < d.N) {
-                long a = (long)u * d.N + rank, b = (long)u * d.BCAP + i;
-                const int src = B.slot[b], dst = tbs_slot_id(u, parity, 0, rank, d.R, d.N);
-                A.logs[a] = si;
-                A.node[a] = B.node[b];
-                A.hash[a] = B.hash[b];
-                A.len[a] = B.len[b];
-                A.pslot[a] = src;
-                A.slot[a] = dst;
-                A.pnode[a] = -1;
-                A.token[a] = -1;
-                float *dh = A.dhat + a * d.S;
-                dh[0] = 0.f;   // d = (s, 0, ..., 0), normalised and as logarithms
-                for (int t = 1; t < d.S; ++t) dh[t] = -INFINITY;
-                s_src[rank] = src;
-                s_dst[rank] = dst;
-            }
+    const int parity = par_old ^ 1;   // the arena the survivors are not in
+    // the scores go through LDS: ranking by counting reads every score once per entry
+    if (tid < nB) s_bl[tid] = my_logs;
+    for (int i = tid + SEG_THREADS; i < nB; i += SEG_THREADS) s_bl[i] = B.logs[bb + i];
+    __syncthreads();
+    for (int i = tid; i < nB; i += SEG_THREADS) {
+        const double si = s_bl[i];
+        int rank = 0;
+        for (int j = 0; j < nB; ++j) {
+            const double sj = s_bl[j];
+            rank += (sj > si) || (sj == si && j < i);
         }
-        if (lane == 0) {
-            A.count[u] = nB < d.N ? nB : d.N;
-            B.count[u] = 0;
-            s_n = nB < d.N ? nB : d.N;
+        if (rank < d.N) {
+            const long a = (long)u * d.N + rank, b = bb + i;
+            const bool mine = i == tid;
+            const int src = mine ? my_slot : B.slot[b], dst = tbs_slot_id(u, parity, 0, rank, d.R, d.N);
+            A.logs[a] = si;
+            A.node[a] = mine ? my_node : B.node[b];
+            A.hash[a] = mine ? my_hash : B.hash[b];
+            A.len[a] = mine ? my_len : B.len[b];
+            A.pslot[a] = src;
+            A.slot[a] = dst;
+            A.pnode[a] = -1;
+            A.token[a] = -1;
+            float *dh = A.dhat + a * d.S;
+            dh[0] = 0.f;   // d = (s, 0, ..., 0), normalised and as logarithms
+            for (int t = 1; t < d.S; ++t) dh[t] = -INFINITY;
+            s_src[rank] = src;
+            s_dst[rank] = dst;
         }
+    }
+    if (tid == 0) {
+        A.count[u] = nB < d.N ? nB : d.N;
+        s_n = nB < d.N ? nB : d.N;
     }
     __syncthreads();
-    if (tid == 0) rv.utt_par[u] = parity;   // (every thread has read the old value)
-    const int n = s_n;
-    for (int i = 0; i < n; ++i) {
-        const long src = s_src[i], dst = s_dst[i];
-        for (int j = tid; j < d.Dj; j += SEG_THREADS) pool_p[dst * d.Dj + j] = pool_p[src * d.Dj + j];
-        for (int l = 0; l < d.L; ++l)
-            for (int j = tid; j < d.H; j += SEG_THREADS) {
-                pool_h[((long)l * pool_rows + dst) * d.H + j] = pool_h[((long)l * pool_rows + src) * d.H + j];
-                pool_c[((long)l * pool_rows + dst) * d.H + j] = pool_c[((long)l * pool_rows + src) * d.H + j];
-            }
+    if (tid == 0) {   // (every thread has read the old values by now)
+        rv.utt_par[u] = parity;
+        B.count[u] = 0;
     }
+    // The survivors' predictor outputs and LSTM states move to their new slots.  The copy is one
+    // flat list of n x (Dj + 2 L H) values; a thread requests SEG_BATCH of them before it stores the
+    // first, so the whole copy costs a few memory round trips instead of one per value.
+    const int n = s_n;
+    auto copy_all = [&](auto unit_tag, int w) {   // w = floats per unit
+        using UNIT = decltype(unit_tag);
+        const int up = d.Dj / w, uh = d.H / w, per = up + 2 * d.L * uh, total = n * per;
+        for (int base = tid; base < total; base += SEG_THREADS * SEG_BATCH) {
+            UNIT v[SEG_BATCH];
+            UNIT *to[SEG_BATCH];
+#pragma unroll
+            for (int k = 0; k < SEG_BATCH; ++k) {
+                const int idx = min(base + k * SEG_THREADS, total - 1);
+                const int i = idx / per;
+                int r = idx - i * per;
+                const long src = s_src[i], dst = s_dst[i];
+                const UNIT *from;
+                if (r < up) {
+                    from = reinterpret_cast<const UNIT *>(pool_p + src * d.Dj) + r;
+                    to[k] = reinterpret_cast<UNIT *>(pool_p + dst * d.Dj) + r;
+                } else {
+                    r -= up;
+                    const int l = r / (2 * uh), q = r - l * 2 * uh;
+                    float *pool = q < uh ? pool_h : pool_c;
+                    const int j = q < uh ? q : q - uh;
+                    from = reinterpret_cast<const UNIT *>(pool + ((long)l * pool_rows + src) * d.H) + j;
+                    to[k] = reinterpret_cast<UNIT *>(pool + ((long)l * pool_rows + dst) * d.H) + j;
+                }
+                v[k] = *from;
+            }
+#pragma unroll
+            for (int k = 0; k < SEG_BATCH; ++k)
+                if (base + k * SEG_THREADS < total) *to[k] = v[k];
+        }
+    };
+    if (((d.Dj | d.H) & 3) == 0) copy_all(float4{}, 4);
+    else copy_all(float{}, 1);
 }
 
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const int *utt_T, BView B,

@@ -189,3 +189,10 @@ hipError_t launch_stream_copy(hipStream_t st, int U, const void *src, void *dst,
                            row_bytes / 4);
     return hipGetLastError();
 }
+
+// ------------------------------------------------------------------ timing yardstick
+__global__ void k_empty() {}
+hipError_t launch_empty(hipStream_t st) {
+    hipLaunchKernelGGL(k_empty, dim3(1), dim3(64), 0, st);
+    return hipGetLastError();
+}

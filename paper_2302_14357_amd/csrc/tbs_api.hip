@@ -975,6 +975,31 @@ int tbs_profile_read(tbs_ctx *c, int64_t *launches, double *total_ms, int64_t *u
     return TBS_OK;
 }
 
+int tbs_profile_overhead(tbs_ctx *c, int32_t n, double *avg_us) {
+    if (!c || n < 1 || !avg_us) return TBS_EINVAL;
+    if (c->events.empty()) return TBS_ESTATE;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    double tot = 0.0;
+    int done = 0;
+    while (done < n) {
+        const int batch = std::min<int>(n - done, (int)c->events.size());
+        for (int i = 0; i < batch; ++i) {
+            HIPCHK(c, hipEventRecord(c->events[i].a, c->stream));
+            HIPCHK(c, launch_empty(c->stream));
+            HIPCHK(c, hipEventRecord(c->events[i].b, c->stream));
+        }
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        for (int i = 0; i < batch; ++i) {
+            float ms = 0.f;
+            HIPCHK(c, hipEventElapsedTime(&ms, c->events[i].a, c->events[i].b));
+            tot += ms;
+        }
+        done += batch;
+    }
+    *avg_us = tot * 1e3 / n;
+    return TBS_OK;
+}
+
 int tbs_gemm_bf16(const void *A, const void *B, const float *bias, float *C, int32_t M, int32_t N, int32_t K,
                   int32_t kernel, void *stream) {
     if (!A || !B || !C || M < 1 || N < 1 || K < 8 || K % 8 || kernel < 0 || kernel > 4) return TBS_EINVAL;

@@ -147,4 +147,5 @@ hipError_t launch_debug_fill_a(hipStream_t st, const Dims &d, AView A);
 // rows of row_bytes bytes: for every utterance u, n[u] rows from src row src_row[u] on to dst row
 // dst_row[u] on (desc = [src_row | dst_row | n], each [U]); the ranges of src and dst must not overlap
 hipError_t launch_stream_copy(hipStream_t st, int U, const void *src, void *dst, const int *desc, long row_bytes);
+hipError_t launch_empty(hipStream_t st);   // a kernel that does nothing (timing yardstick)
 hipError_t launch_set_sp(hipStream_t st, const Dims &d, int seg, const int *utt_T, RowView rv);

@@ -15,6 +15,7 @@ EXPORTED_SYMBOLS = [
     "tbs_select_merge", "tbs_predictor_step", "tbs_decode", "tbs_result", "tbs_stats", "tbs_debug_read",
     "tbs_debug_write", "tbs_debug_rebuild", "tbs_debug_hyps", "tbs_profile_select", "tbs_profile_read",
     "tbs_strerror", "tbs_last_hip_error", "tbs_gemm_bf16", "tbs_stream_begin", "tbs_push_segment",
+    "tbs_profile_overhead",
 ]
 
 TBS_MAX_LAYERS = 4
@@ -87,6 +88,7 @@ def load_library():
     L.tbs_debug_hyps.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32]
     L.tbs_profile_select.argtypes = [vp, i32]
     L.tbs_profile_read.argtypes = [vp, i64p, C.POINTER(C.c_double), i64p]
+    L.tbs_profile_overhead.argtypes = [vp, i32, C.POINTER(C.c_double)]
     L.tbs_strerror.argtypes = [C.c_int]
     L.tbs_strerror.restype = C.c_char_p
     L.tbs_last_hip_error.argtypes = [vp]
@@ -305,6 +307,12 @@ class Tbs:
     # ---- timing
     def profile_select(self, kernel_id: int):
         _check(self.L.tbs_profile_select(self.ctx, kernel_id), self.ctx)
+
+    def profile_overhead(self, n: int = 200) -> float:
+        """Microseconds an event pair reads around a kernel that does nothing."""
+        us = C.c_double(0.0)
+        _check(self.L.tbs_profile_overhead(self.ctx, n, C.byref(us)), self.ctx)
+        return us.value
 
     def profile_read(self):
         n, ms, units = C.c_int64(), C.c_double(), C.c_int64()
