@@ -234,6 +234,10 @@ k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes,
     const int slot_new = (seq & 1) ? TBS_CNT_NODES : TBS_CNT_NODE_BASE;
     const int node_base = rv.counts[slot_old];
     const int frame0 = utt_off[u] + seg * d.S;
+    // what the fill below needs of this utterance's hypotheses, lane h holding hypothesis h:
+    // requested together with the counts, so the kernel costs one memory round trip, not two
+    const long ah = (long)u * d.N + min(lane, d.N - 1);
+    const int h_slot = A.slot[ah], h_pslot = A.pslot[ah], h_tok = A.token[ah], h_pnode = A.pnode[ah];
     int before_p = 0, before_r = 0, tot_p = 0, tot_r = 0, utts = 0, frames = 0, my_sp = 0, my_cnt = 0;
     for (int base = 0; base < d.U; base += WAVE) {
         const int v = base + lane;
@@ -283,10 +287,15 @@ k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes,
         rv.utt_pair0[u] = pair0;
         rv.utt_row0[u] = row0;
     }
-    for (int idx = lane; idx < cnt * sp; idx += WAVE) {
-        const int h = idx / sp, t = idx - h * sp;
+    for (int base = 0; base < cnt * sp; base += WAVE) {   // (cnt and sp are the same in every lane)
+        const int idx = base + lane;
+        const bool valid = idx < cnt * sp;
+        const int h = valid ? idx / sp : 0, t = idx - h * sp;
+        // every lane takes part in the exchanges, whatever it does with the result
+        const int slot = __shfl(h_slot, h), pslot = __shfl(h_pslot, h), tok = __shfl(h_tok, h),
+                  pnode = __shfl(h_pnode, h);
+        if (!valid) continue;
         const long a = (long)u * d.N + h;
-        const int slot = A.slot[a];
         rv.row_enc[row0 + idx] = frame0 + t;
         rv.row_slot[row0 + idx] = slot;
         if (t == 0) {
@@ -296,13 +305,13 @@ k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes,
             rv.pair_row0[j] = row0 + h * sp;
             rv.pair_len[j] = sp;
             rv.pair_slot[j] = slot;
-            rv.pair_pslot[j] = A.pslot[a];
+            rv.pair_pslot[j] = pslot;
             rv.pair_frame0[j] = frame0;
-            rv.pair_tok[j] = A.token[a];
+            rv.pair_tok[j] = tok;
             if (assign_nodes) {
                 const int node = node_base + j;
                 if (node < d.max_nodes) {
-                    nodes[node] = make_int2(A.pnode[a], A.token[a]);
+                    nodes[node] = make_int2(pnode, tok);
                     A.node[a] = node;
                 } else {
                     A.node[a] = 0;
