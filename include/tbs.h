@@ -72,8 +72,10 @@ typedef struct tbs_config {
                                  generic two-pass expansion kernel; bit 3: keep the LSTM cell update a
                                  kernel of its own also where it would run inside the gate GEMM;
                                  bit 4: always form the joiner input rows in a kernel of their own,
-                                 also where the predictor projection's epilogue would (tests cover
-                                 each pair of variants) */
+                                 also where the predictor projection's epilogue would; bit 5: always
+                                 gather the first LSTM layer's input rows in a kernel of their own,
+                                 also where the row list kernel would (tests cover each pair of
+                                 variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

@@ -224,10 +224,9 @@ __device__ __forceinline__ int wave_sum_int(int v) {
     return v;
 }
 
-__global__ void __launch_bounds__(WAVE)
-k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes, int assign_nodes, int *host_counts,
-          int seq) {
-    const int u = blockIdx.x, lane = threadIdx.x;
+__device__ __forceinline__ void rowfill_lists(const Dims &d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes,
+                                              int assign_nodes, int *host_counts, int seq, int u, int lane, bool share,
+                                              int *s_pslot, int *s_pair0, int *s_cnt) {
     // trie nodes handed out so far: launches alternate between two slots, so that the first
     // workgroup can store the new figure while others still read the old one
     const int slot_old = (seq & 1) ? TBS_CNT_NODE_BASE : TBS_CNT_NODES;
@@ -319,12 +318,61 @@ k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes,
             }
         }
     }
+    if (share) {   // for the other waves of the workgroup
+        if (lane < d.N) s_pslot[lane] = h_pslot;
+        if (lane == 0) {
+            *s_pair0 = pair0;
+            *s_cnt = cnt;
+        }
+    }
+}
+
+// With gather_h not null the workgroup has four waves: the first does all of the above, then all
+// four write the first LSTM layer's input rows of this utterance's new hypotheses,
+// gather_xh[pair, :] = bf16(h of the parent), which would otherwise take a kernel of its own between
+// this one and the gate GEMM.
+__device__ __forceinline__ unsigned rowfill_bf16(float f) {
+    unsigned v = __float_as_uint(f);
+    v += 0x7FFFu + ((v >> 16) & 1u);   // round to nearest, ties to even
+    return v >> 16;
+}
+
+__global__ void __launch_bounds__(256)
+k_rowfill(Dims d, int seg, const int *utt_off, AView A, RowView rv, int2 *nodes, int assign_nodes, int *host_counts,
+          int seq, const float *gather_h, bf16_t *gather_xh) {
+    __shared__ int s_pslot[TBS_MAX_BEAM];
+    __shared__ int s_pair0, s_cnt;
+    const int u = blockIdx.x;
+    if (threadIdx.x < WAVE) rowfill_lists(d, seg, utt_off, A, rv, nodes, assign_nodes, host_counts, seq, u, threadIdx.x,
+                                          gather_h != nullptr, s_pslot, &s_pair0, &s_cnt);
+    if (gather_h == nullptr) return;   // (one wave launched)
+    __syncthreads();
+    const int cnt = s_cnt, pair0 = s_pair0, H4 = d.H >> 2, total = cnt * H4;
+    for (int base = threadIdx.x; base < total; base += 256 * 4) {
+        float4 v[4];
+        int at[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int idx = min(base + k * 256, total - 1);
+            const int h = idx / H4, i = idx - h * H4;
+            v[k] = reinterpret_cast<const float4 *>(gather_h + (long)s_pslot[h] * d.H)[i];
+            at[k] = (pair0 + h) * H4 + i;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (base + k * 256 < total)
+                reinterpret_cast<uint2 *>(gather_xh)[at[k]] =
+                    make_uint2(rowfill_bf16(v[k].x) | (rowfill_bf16(v[k].y) << 16),
+                               rowfill_bf16(v[k].z) | (rowfill_bf16(v[k].w) << 16));
+    }
 }
 
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
-                          int2 *nodes, int assign_nodes, int *host_counts, int seq) {
-    hipLaunchKernelGGL(k_rowfill, dim3(d.U), dim3(WAVE), 0, st, d, seg, utt_off, A, rv, nodes, assign_nodes,
-                       host_counts, seq);
+                          int2 *nodes, int assign_nodes, int *host_counts, int seq, const float *gather_h,
+                          bf16_t *gather_xh) {
+    if (gather_h && (d.H & 3)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_rowfill, dim3(d.U), dim3(gather_h ? 256 : WAVE), 0, st, d, seg, utt_off, A, rv, nodes,
+                       assign_nodes, host_counts, seq, gather_h, gather_xh);
     return hipGetLastError();
 }
 

@@ -571,17 +571,23 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     if (c->state != ST_EXPANDED) return TBS_ESTATE;
     AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];
     const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
+    bool gathered = false;
     {
         ProfScope ps(c, TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
         HIPCHK(c, launch_select_merge(c->stream, c->cur, c->round, drop, c->logits, c->row_lc, c->dphi,
                                       c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes));
+        // small batches: the row list kernel also writes the first LSTM layer's input rows
+        const bool fused_gather = c->emb_gates && !(c->cfg.debug & 32) && (c->cur.H & 3) == 0 &&
+                                  (long)c->cur.U * c->cur.N <= 1024;
         HIPCHK(c, launch_rowfill(c->stream, c->cur, c->seg, c->utt_off, An, c->rv, c->nodes, 1, c->h_counts_dev,
-                                 ++c->seq));
+                                 ++c->seq, fused_gather ? c->pool_h : nullptr,
+                                 fused_gather ? (bf16_t *)c->xh[0] : nullptr));
+        gathered = fused_gather;
     }
-    // The first kernel of the predictor step goes out before the counts are known, on the largest
-    // grid the round could need (it sizes itself from device memory): it runs while the host
+    // Otherwise the first kernel of the predictor step goes out before the counts are known, on the
+    // largest grid the round could need (it sizes itself from device memory): it runs while the host
     // waits for the counts and enqueues the rest, which would otherwise leave the GPU idle.
-    {
+    if (!gathered) {
         ProfScope ps(c, TBS_K_PREDICTOR, 0);
         if (c->emb_gates)
             HIPCHK(c, launch_pred_gather_h(c->stream, c->cur, c->cur.U * c->cur.N, An, c->rv, c->pool_h,

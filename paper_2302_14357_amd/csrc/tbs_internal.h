@@ -106,8 +106,10 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
                              long pool_rows);
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const int *utt_T, BView B,
                                 AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows);
+// gather_h / gather_xh not null: also writes gather_xh[pair, :] = bf16(gather_h[parent slot, :]) (H wide)
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
-                          int2 *nodes, int assign_nodes, int *host_counts, int seq);
+                          int2 *nodes, int assign_nodes, int *host_counts, int seq, const float *gather_h = nullptr,
+                          bf16_t *gather_xh = nullptr);
 hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
                               const float *pool_p, RowView rv, void *amat, const int *rows_dev = nullptr);
 hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
