@@ -503,6 +503,26 @@ def test_decode_long_segments(S):
     assert same + amb == tot and same >= tot - 1
 
 
+def test_decode_largest_segment_and_smallest_vocabulary():
+    """The limits of the configuration: S = 128 (the largest segment the library takes; one full
+    segment and a ragged one) with a small model, and V = 2 (blank and one token: every hypothesis
+    has one expansion, top-N and threshold degenerate) at several beam widths."""
+    shape = small_bf16_shape(n_utts=2, vocab=24, d=64, hidden=64)
+    lengths = np.array([140, 131])
+    model, offsets, enc = build_case(shape, n_utts=2, lengths=lengths)
+    ref = _oracle_decode(shape, model, offsets, enc, 3, 128)
+    got, st = _gpu_decode(shape, model, offsets, enc, 3, 128, rounds_capacity=512)
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot and same >= tot - 1
+    shape2 = small_bf16_shape(n_utts=3, vocab=2, d=64, hidden=64)
+    model2, off2, enc2 = build_case(shape2, n_utts=3, lengths=np.array([5, 11, 2]))
+    for N, S in ((1, 1), (3, 2), (4, 5)):
+        ref2 = _oracle_decode(shape2, model2, off2, enc2, N, S)
+        got2, _ = _gpu_decode(shape2, model2, off2, enc2, N, S)
+        same, amb, tot = compare_nbest(got2, ref2)
+        assert same + amb == tot and same >= tot - 1, (N, S)
+
+
 @pytest.mark.parametrize("name,N,S,U", [("assistant", 10, 3, 300), ("throughput", 10, 5, 200)])
 def test_decode_large_batch_contains_the_small_one(name, N, S, U):
     """The large configurations' widths with enough utterances that every round runs on the kernels
