@@ -95,7 +95,7 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 // state into this segment's arena (slot r=0): the arena of the segment before last is reused,
 // and a survivor may have been carried, untouched, from there.
 #define SEG_THREADS 256
-#define SEG_BATCH 10   // values a thread has in flight in the state copy
+#define SEG_BATCH 5    // survivors whose rows a thread has in flight together in the state copy
 __global__ void __launch_bounds__(SEG_THREADS)
 k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv, float *pool_p,
                 float *pool_h, float *pool_c, long pool_rows) {
@@ -163,39 +163,42 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
         rv.utt_par[u] = parity;
         B.count[u] = 0;
     }
-    // The survivors' predictor outputs and LSTM states move to their new slots.  The copy is one
-    // flat list of n x (Dj + 2 L H) values; a thread requests SEG_BATCH of them before it stores the
-    // first, so the whole copy costs a few memory round trips instead of one per value.
+    // The survivors' predictor outputs and LSTM states move to their new slots.  Thread j moves
+    // element j (16 bytes where the widths allow) of every survivor's output row and of its h and c
+    // rows of one layer: up to 3 x SEG_BATCH values requested before the first is stored, so the
+    // copy costs a memory round trip per layer, not one per value.
     const int n = s_n;
     auto copy_all = [&](auto unit_tag, int w) {   // w = floats per unit
         using UNIT = decltype(unit_tag);
-        const int up = d.Dj / w, uh = d.H / w, per = up + 2 * d.L * uh, total = n * per;
-        for (int base = tid; base < total; base += SEG_THREADS * SEG_BATCH) {
-            UNIT v[SEG_BATCH];
-            UNIT *to[SEG_BATCH];
+        const int up = d.Dj / w, uh = d.H / w, widest = max(up, uh);
+        for (int j = tid; j < widest; j += SEG_THREADS) {
+            const int jp = min(j, up - 1), jh = min(j, uh - 1);
+            for (int i0 = 0; i0 < n; i0 += SEG_BATCH)
+                for (int l = 0; l < d.L; ++l) {
+                    UNIT vp[SEG_BATCH], vh[SEG_BATCH], vc[SEG_BATCH];
+                    long src[SEG_BATCH], dst[SEG_BATCH];
 #pragma unroll
-            for (int k = 0; k < SEG_BATCH; ++k) {
-                const int idx = min(base + k * SEG_THREADS, total - 1);
-                const int i = idx / per;
-                int r = idx - i * per;
-                const long src = s_src[i], dst = s_dst[i];
-                const UNIT *from;
-                if (r < up) {
-                    from = reinterpret_cast<const UNIT *>(pool_p + src * d.Dj) + r;
-                    to[k] = reinterpret_cast<UNIT *>(pool_p + dst * d.Dj) + r;
-                } else {
-                    r -= up;
-                    const int l = r / (2 * uh), q = r - l * 2 * uh;
-                    float *pool = q < uh ? pool_h : pool_c;
-                    const int j = q < uh ? q : q - uh;
-                    from = reinterpret_cast<const UNIT *>(pool + ((long)l * pool_rows + src) * d.H) + j;
-                    to[k] = reinterpret_cast<UNIT *>(pool + ((long)l * pool_rows + dst) * d.H) + j;
+                    for (int k = 0; k < SEG_BATCH; ++k) {
+                        const int i = min(i0 + k, n - 1);
+                        src[k] = __builtin_amdgcn_readfirstlane(s_src[i]);   // the same in every lane: scalar
+                        dst[k] = __builtin_amdgcn_readfirstlane(s_dst[i]);   // address arithmetic below
+                    }
+#pragma unroll
+                    for (int k = 0; k < SEG_BATCH; ++k) {
+                        if (l == 0) vp[k] = reinterpret_cast<const UNIT *>(pool_p + src[k] * d.Dj)[jp];
+                        vh[k] = reinterpret_cast<const UNIT *>(pool_h + ((long)l * pool_rows + src[k]) * d.H)[jh];
+                        vc[k] = reinterpret_cast<const UNIT *>(pool_c + ((long)l * pool_rows + src[k]) * d.H)[jh];
+                    }
+#pragma unroll
+                    for (int k = 0; k < SEG_BATCH; ++k) {
+                        if (i0 + k >= n) continue;
+                        if (l == 0 && j < up) reinterpret_cast<UNIT *>(pool_p + dst[k] * d.Dj)[j] = vp[k];
+                        if (j < uh) {
+                            reinterpret_cast<UNIT *>(pool_h + ((long)l * pool_rows + dst[k]) * d.H)[j] = vh[k];
+                            reinterpret_cast<UNIT *>(pool_c + ((long)l * pool_rows + dst[k]) * d.H)[j] = vc[k];
+                        }
+                    }
                 }
-                v[k] = *from;
-            }
-#pragma unroll
-            for (int k = 0; k < SEG_BATCH; ++k)
-                if (base + k * SEG_THREADS < total) *to[k] = v[k];
         }
     };
     if (((d.Dj | d.H) & 3) == 0) copy_all(float4{}, 4);
