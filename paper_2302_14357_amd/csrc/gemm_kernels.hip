@@ -387,7 +387,7 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         const int erow = min(tile_m * 64 + wm * 32 + (lane >> 1), M - 1);
         e_ps = ep.pslot[erow];
         e_ns = ep.slot[erow];
-        e_tok = ep.emb_gates ? ep.tok[erow] : 0;
+        e_tok = ep.tok[erow];   // (unconditionally: a load behind a condition would be waited for at once)
     } else if (MODE == 2) {
         const int erow = min(tile_m * 64 + wm * 32 + (lane >> 1), M - 1);
         e_ns = out_row[erow];
@@ -453,15 +453,23 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         for (int q = 0; q < 4; ++q) g4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
         if (row < M && j0 < ep.H) {
             const int H = ep.H;
+            // everything the update reads from memory is requested before any of it is used: the
+            // parent's cell state, the parent's h of the next layer, the input half of the gates
+            // (the latter two from addresses that are valid whether they are needed or not)
+            const float4 cp4 = *reinterpret_cast<const float4 *>(ep.c_par + (long)e_ps * H + j0);
+            const float4 hp = *reinterpret_cast<const float4 *>((ep.h_par_next ? ep.h_par_next : ep.c_par) + (long)e_ps * H + j0);
+            const float4 *eg = ep.emb_gates ? reinterpret_cast<const float4 *>(ep.emb_gates + (long)e_tok * 4 * H + 4 * j0)
+                                            : reinterpret_cast<const float4 *>(ep.c_par + (long)e_ps * H + j0);
+            const int estep = ep.emb_gates ? 1 : 0;
+            float4 e4[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) e4[q] = eg[q * estep];
             if (ep.emb_gates) {
-                const float4 *eg = reinterpret_cast<const float4 *>(ep.emb_gates + (long)e_tok * 4 * H + 4 * j0);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const float4 e4 = eg[q];
-                    g4[q].x += e4.x; g4[q].y += e4.y; g4[q].z += e4.z; g4[q].w += e4.w;
+                    g4[q].x += e4[q].x; g4[q].y += e4[q].y; g4[q].z += e4[q].z; g4[q].w += e4[q].w;
                 }
             }
-            const float4 cp4 = *reinterpret_cast<const float4 *>(ep.c_par + (long)e_ps * H + j0);
             const float cp[4] = {cp4.x, cp4.y, cp4.z, cp4.w};
             float cn[4], hn[4];
 #pragma unroll
@@ -477,7 +485,6 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
             if (ep.h_par_next == nullptr) {
                 *reinterpret_cast<uint2 *>(ep.out16 + (long)row * H + j0) = hb;
             } else {
-                const float4 hp = *reinterpret_cast<const float4 *>(ep.h_par_next + (long)e_ps * H + j0);
                 *reinterpret_cast<uint2 *>(ep.out16 + (long)row * 2 * H + j0) = hb;
                 *reinterpret_cast<uint2 *>(ep.out16 + (long)row * 2 * H + H + j0) =
                     make_uint2((unsigned)gs_bf16(hp.x) | ((unsigned)gs_bf16(hp.y) << 16),
