@@ -496,32 +496,48 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     if (MODE == 2) {
         // Same passage through LDS: lane l takes row l/2 and 16 consecutive columns, stores them
         // as the projection and, for each frame of the pair, adds the encoder row and activates.
+        // The first four encoder frames are requested before the passage (clamped addresses, valid
+        // in every lane) and nothing is stored before they are used, so their round trip runs
+        // beside the barrier and the LDS traffic.
+        const int rowb = lane >> 1, half = lane & 1;
+        const int row = tile_m * 64 + wm * 32 + rowb;
+        const int c0 = tile_n * 64 + wn * 32 + half * 16;
+        const int len = e_tok;
+        uint4 ev0[4][2];
+        {
+            const int c0c = min(c0, N - 16);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint4 *src =
+                    reinterpret_cast<const uint4 *>(jp.enc + (long)(e_f0 + max(min(q, len - 1), 0)) * N + c0c);
+                ev0[q][0] = src[0];
+                ev0[q][1] = src[1];
+            }
+        }
         gs_barrier();
         float *sacc = reinterpret_cast<float *>(smem) + wave * (32 * 36);
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             sacc[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * 36 + (lane & 31)] = acc[r] + bv;
-        const int rowb = lane >> 1, half = lane & 1;
-        const int row = tile_m * 64 + wm * 32 + rowb;
-        const int c0 = tile_n * 64 + wn * 32 + half * 16;
         float4 p4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) p4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
         if (row < M && c0 < N) {
-            float4 *crow = reinterpret_cast<float4 *>(C + (long)e_ns * ldc + c0);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) crow[q] = p4[q];
             const float p[16] = {p4[0].x, p4[0].y, p4[0].z, p4[0].w, p4[1].x, p4[1].y, p4[1].z, p4[1].w,
                                  p4[2].x, p4[2].y, p4[2].z, p4[2].w, p4[3].x, p4[3].y, p4[3].z, p4[3].w};
-            const int len = e_tok;
             for (int t0 = 0; t0 < len; t0 += 4) {
                 uint4 ev[4][2];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const uint4 *src =
-                        reinterpret_cast<const uint4 *>(jp.enc + (long)(e_f0 + min(t0 + q, len - 1)) * N + c0);
-                    ev[q][0] = src[0];
-                    ev[q][1] = src[1];
+                    if (t0 == 0) {
+                        ev[q][0] = ev0[q][0];
+                        ev[q][1] = ev0[q][1];
+                    } else {
+                        const uint4 *src =
+                            reinterpret_cast<const uint4 *>(jp.enc + (long)(e_f0 + min(t0 + q, len - 1)) * N + c0);
+                        ev[q][0] = src[0];
+                        ev[q][1] = src[1];
+                    }
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -541,6 +557,9 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
                     }
                 }
             }
+            float4 *crow = reinterpret_cast<float4 *>(C + (long)e_ns * ldc + c0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) crow[q] = p4[q];
         }
         return;
     }
