@@ -74,8 +74,10 @@ typedef struct tbs_config {
                                  bit 4: always form the joiner input rows in a kernel of their own,
                                  also where the predictor projection's epilogue would; bit 5: always
                                  gather the first LSTM layer's input rows in a kernel of their own,
-                                 also where the row list kernel would (tests cover each pair of
-                                 variants) */
+                                 also where the row list kernel would; bit 6: enqueue the predictor
+                                 step only once the host knows how many hypotheses the round
+                                 created, also where it could go out ahead of that (tests cover
+                                 each pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

@@ -336,11 +336,15 @@ __device__ __forceinline__ bf16_t gs_bf16(float f) {
 // MODE 2: the product is the predictor projection p of new hypotheses (row r = pair r, stored at
 // C[out_row[r], :]); the epilogue also forms the joiner input rows act(e[frame] + p) of the pair's
 // frames (Section 3.1), so that the next joiner call needs no kernel of its own for them.
+// m_dev not null: the kernel was enqueued before the host knew the number of rows.  M is then only
+// an upper bound (it sizes the grid and keeps every address inside the buffers); the rows that
+// exist are the first *m_dev, read from device memory: workgroups beyond them leave once their K
+// tiles have landed, and the epilogue stores nothing for the others' surplus rows.
 template <int MODE>
 __global__ void __launch_bounds__(256)
 k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
              float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
-             int tiles_n, int ns, LstmEp ep, JoinEp jp) {
+             int tiles_n, int ns, LstmEp ep, JoinEp jp, const int *__restrict__ m_dev) {
     constexpr bool LSTM = MODE == 1;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // ns stages
     const int tid = threadIdx.x, lane = tid & 63;
@@ -404,6 +408,11 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     asm volatile("" ::: "memory");
     const int first = min(ns, kt);
     for (int c = 0; c < first; ++c) fetch(c, c);
+    const int m_live = m_dev ? min(*m_dev, M) : M;   // (the same in every lane: a scalar load)
+    if (tile_m * 64 >= m_live) {   // no row of this tile exists: leave, once nothing is on its way into LDS
+        __builtin_amdgcn_s_waitcnt(GS_VMCNT(0));
+        return;
+    }
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -451,7 +460,7 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         float4 g4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) g4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
-        if (row < M && j0 < ep.H) {
+        if (row < m_live && j0 < ep.H) {
             const int H = ep.H;
             // everything the update reads from memory is requested before any of it is used: the
             // parent's cell state, the parent's h of the next layer, the input half of the gates
@@ -508,8 +517,9 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
             const int c0c = min(c0, N - 16);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint4 *src =
-                    reinterpret_cast<const uint4 *>(jp.enc + (long)(e_f0 + max(min(q, len - 1), 0)) * N + c0c);
+                // (a row that does not exist has no descriptor: frame 0 keeps the address valid)
+                const long fr = row < m_live ? (long)e_f0 + max(min(q, len - 1), 0) : 0;
+                const uint4 *src = reinterpret_cast<const uint4 *>(jp.enc + fr * N + c0c);
                 ev0[q][0] = src[0];
                 ev0[q][1] = src[1];
             }
@@ -522,7 +532,7 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         float4 p4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) p4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
-        if (row < M && c0 < N) {
+        if (row < m_live && c0 < N) {
             const float p[16] = {p4[0].x, p4[0].y, p4[0].z, p4[0].w, p4[1].x, p4[1].y, p4[1].z, p4[1].w,
                                  p4[2].x, p4[2].y, p4[2].z, p4[2].w, p4[3].x, p4[3].y, p4[3].z, p4[3].w};
             for (int t0 = 0; t0 < len; t0 += 4) {
@@ -574,7 +584,7 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int row = tile_m * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (row < M && col < N) *dst[r] = acc[r] + bv;
+        if (row < m_live && col < N) *dst[r] = acc[r] + bv;
     }
 }
 
@@ -601,6 +611,11 @@ static int gemm_small_stages() {
     return stages;
 }
 
+bool gemm_small_fits(int M, int N, int K) {   // what launch_gemm_bf16 sends to k_gemm_small by itself
+    const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
+    return K % GS_BK == 0 && gemm_small_stages() >= 2 && tiles <= 320;
+}
+
 bool gemm_lstm_fits(int M, int H, int K) {
     const int ns_max = gemm_small_stages();
     const long tiles = (long)((M + 63) / 64) * ((4 * H + 63) / 64);
@@ -608,14 +623,14 @@ bool gemm_lstm_fits(int M, int H, int K) {
 }
 
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
-                            const LstmEp &ep) {
+                            const LstmEp &ep, const int *m_dev) {
     if (M <= 0) return hipSuccess;
     if (!gemm_lstm_fits(M, ep.H, K)) return hipErrorInvalidValue;
     const int N = 4 * ep.H, tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
     hipLaunchKernelGGL(k_gemm_small<1>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, Wp, biasp,
-                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep, JoinEp{});
+                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep, JoinEp{}, m_dev);
     return hipGetLastError();
 }
 
@@ -626,22 +641,23 @@ bool gemm_join_fits(int M, int N, int K) {
 }
 
 hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, const JoinEp &jp) {
+                            int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev) {
     if (M <= 0) return hipSuccess;
     if (!gemm_join_fits(M, N, K) || !out_row) return hipErrorInvalidValue;
     const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
     hipLaunchKernelGGL(k_gemm_small<2>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C, M,
-                       N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp);
+                       N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp, m_dev);
     return hipGetLastError();
 }
 
 // kernel: 0 = by size (what the decode uses); 1..4 force one (tests run every kernel on every shape):
 // 1 = 64x64 tiles, 2 = 128x128, 3 = 256x256 (all k_gemm_bf16), 4 = k_gemm_small
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, int kernel) {
+                            int N, int K, const int *out_row, long ldc, int kernel, const int *m_dev) {
     if (M <= 0) return hipSuccess;
+    if (m_dev && !gemm_small_fits(M, N, K)) return hipErrorInvalidValue;   // only k_gemm_small reads its row count
     if ((kernel == 0 || kernel == 4) && K % GS_BK == 0) {
         const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
         const int ns_max = gemm_small_stages();
@@ -649,7 +665,7 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
             const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
             hipLaunchKernelGGL(k_gemm_small<0>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
-                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{});
+                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, m_dev);
             return hipGetLastError();
         }
     }

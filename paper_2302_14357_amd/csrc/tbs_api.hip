@@ -56,6 +56,7 @@ struct tbs_ctx {
     int *h_counts_dev;  // device view of the same memory
     int seq;            // number of the last scan asked to publish its counts there
     bool prep_ahead;    // the joiner input rows of the coming call are already being made (see tbs_segment_begin)
+    bool pred_ahead;    // the predictor kernels of this round are already enqueued (see tbs_select_merge)
     int2 *nodes;
     long pool_rows;
     float *pool_p, *pool_h, *pool_c;
@@ -463,6 +464,7 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     c->h_counts[TBS_CNT_NODES] = 1;
     c->seq = 0;
     c->prep_ahead = false;
+    c->pred_ahead = false;
     c->n_calls = c->n_joined = c->n_launches = 0;
     c->n_frames = frames;
     c->state = ST_BEGUN;
@@ -509,6 +511,7 @@ static int segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     if (c->state != ST_BEGUN && c->h_counts[TBS_CNT_PAIRS] != 0) return TBS_ESTATE;  // A not empty yet
     c->seg = seg_index;
     c->round = 0;
+    c->pred_ahead = false;
     AView &A = c->A[c->a_cur];
     HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h,
                                    c->pool_c, c->pool_rows));
@@ -566,6 +569,9 @@ int tbs_expand(tbs_ctx *c) {
     return TBS_OK;
 }
 
+static bool predictor_all_fused(const tbs_ctx *c, int M);
+static int predictor_launch(tbs_ctx *c, int M, const int *m_dev);
+
 int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     if (!c) return TBS_EINVAL;
     if (c->state != ST_EXPANDED) return TBS_ESTATE;
@@ -596,70 +602,118 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
             HIPCHK(c, launch_pred_gather(c->stream, c->cur, c->cfg.dtype, c->cur.U * c->cur.N, An, c->rv, c->w.embed,
                                          c->pool_h, c->xh[0]));
     }
+    // Small batches: the predictor step itself goes out now, sized for every hypothesis the round
+    // could have created and reading the number it did create from device memory.  The host's
+    // round trip (counts into pinned memory, the host seeing them, a launch reaching the GPU: 7-8 us
+    // during which the GPU had nothing to run) then lies beside these kernels instead of in front
+    // of them.  A round that created nothing (the last of every segment) pays two launches that
+    // leave at once.
+    c->pred_ahead = false;
+    c->a_cur ^= 1;   // (the new hypotheses are the current group from here on)
+    if (!(c->cfg.debug & 64) && predictor_all_fused(c, c->cur.U * c->cur.N)) {
+        ProfScope ps(c, TBS_K_PREDICTOR, 0);
+        const int rc = predictor_launch(c, c->cur.U * c->cur.N, c->rv.counts + TBS_CNT_PAIRS);
+        if (rc) return rc;
+        c->prep_ahead = false;   // (known only with the counts: see tbs_predictor_step)
+        c->pred_ahead = true;
+    }
     HIPCHK(c, wait_counts(c));
-    c->a_cur ^= 1;
     if (live_host) *live_host = c->h_counts[TBS_CNT_PAIRS];
     c->state = ST_SELECTED;
     return check_err_flags(c);
+}
+
+// UpdatePredictorOutput for the first M pairs (or, with m_dev, for as many as *m_dev says once the
+// kernels run: then M is the upper bound the launches are sized for, and only the forms that can
+// read their row count from device memory may be used: see predictor_all_fused).
+static bool predictor_all_fused(const tbs_ctx *c, int M) {
+    const Dims &d = c->cur;
+    if (c->cfg.dtype != 1 || !c->emb_gates || (c->cfg.debug & (8 | 16))) return false;
+    for (int l = 0; l < d.L; ++l)
+        if (!gemm_lstm_fits(M, d.H, l == 0 ? d.H : 2 * d.H)) return false;
+    return gemm_join_fits(M, d.Dj, d.H);
+}
+
+static int64_t predictor_madds(const tbs_ctx *c, int64_t pairs) {   // multiply-adds of its GEMMs
+    const Dims &d = c->cur;
+    int64_t n = pairs * d.Dj * d.H;
+    for (int l = 0; l < d.L; ++l) {
+        const int in_dim = l == 0 ? d.E : d.H;
+        n += pairs * 4 * d.H * ((l == 0 && c->emb_gates) ? d.H : in_dim + d.H);
+    }
+    return n;
+}
+
+static int predictor_launch(tbs_ctx *c, int M, const int *m_dev) {
+    const Dims &d = c->cur;
+    AView &A = c->A[c->a_cur];
+    // (the input rows of the first layer were gathered behind select/merge)
+    for (int l = 0; l < d.L; ++l) {
+        int in_dim = l == 0 ? d.E : d.H;
+        const int K = (l == 0 && c->emb_gates) ? d.H : in_dim + d.H;
+        if (c->emb_gates && !(c->cfg.debug & 8) && gemm_lstm_fits(M, d.H, K)) {
+            // small problem: the cell update runs in the epilogue of the gate GEMM
+            const bool last = l + 1 == d.L;
+            LstmEp ep;
+            ep.pslot = c->rv.pair_pslot;
+            ep.slot = c->rv.pair_slot;
+            ep.tok = c->rv.pair_tok;
+            ep.emb_gates = l == 0 ? c->emb_gates_perm : nullptr;
+            ep.c_par = c->pool_c + (size_t)l * c->pool_rows * d.H;
+            ep.c_new = c->pool_c + (size_t)l * c->pool_rows * d.H;
+            ep.h_new = c->pool_h + (size_t)l * c->pool_rows * d.H;
+            ep.h_par_next = last ? nullptr : c->pool_h + (size_t)(l + 1) * c->pool_rows * d.H;
+            ep.out16 = (bf16_t *)(last ? c->htop : c->xh[(l + 1) & 1]);
+            ep.H = d.H;
+            ProfScope pg(c, TBS_K_GEMM, m_dev ? 0 : (int64_t)M * 4 * d.H * K);
+            HIPCHK(c, launch_gemm_lstm(c->stream, (const bf16_t *)c->xh[l & 1], (const bf16_t *)c->wperm[l], c->bperm[l],
+                                       M, K, ep, m_dev));
+            continue;
+        }
+        if (m_dev) return TBS_ESTATE;   // (predictor_all_fused was not asked)
+        if (l == 0 && c->emb_gates)
+            HIPCHK(c, gemm(c, c->xh[0], c->w.w_hh[0], nullptr, c->gates, M, 4 * d.H, d.H, nullptr, 4L * d.H));
+        else
+            HIPCHK(c, gemm(c, c->xh[l & 1], c->wcat[l], c->w.b_lstm[l], c->gates, M, 4 * d.H, in_dim + d.H, nullptr,
+                           4L * d.H));
+        HIPCHK(c, launch_lstm_pointwise(c->stream, d, c->cfg.dtype, M, l, A, c->rv, c->gates, c->pool_h, c->pool_c,
+                                        c->pool_rows, c->xh[(l + 1) & 1], c->htop, l == 0 ? c->emb_gates : nullptr));
+    }
+    if (c->cfg.dtype == 1 && !(c->cfg.debug & 16) && gemm_join_fits(M, d.Dj, d.H)) {
+        // small problem: the projection's epilogue also makes the joiner input rows of the coming
+        // round (every row of that round belongs to one of these pairs)
+        JoinEp jp;
+        jp.pair_row0 = c->rv.pair_row0;
+        jp.pair_len = c->rv.pair_len;
+        jp.pair_frame0 = c->rv.pair_frame0;
+        jp.enc = (const bf16_t *)c->enc;
+        jp.amat = (bf16_t *)c->amat;
+        jp.act = c->cfg.act;
+        ProfScope pg(c, TBS_K_GEMM, m_dev ? 0 : (int64_t)M * d.Dj * d.H);
+        HIPCHK(c, launch_gemm_join(c->stream, (const bf16_t *)c->htop, (const bf16_t *)c->w.w_proj, c->w.b_proj,
+                                   c->pool_p, M, d.Dj, d.H, c->rv.pair_slot, d.Dj, jp, m_dev));
+        c->prep_ahead = true;
+    } else {
+        if (m_dev) return TBS_ESTATE;
+        HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, M, d.Dj, d.H, c->rv.pair_slot, d.Dj));
+    }
+    return TBS_OK;
 }
 
 int tbs_predictor_step(tbs_ctx *c) {
     if (!c) return TBS_EINVAL;
     if (c->state != ST_SELECTED) return TBS_ESTATE;
     const int pairs = c->h_counts[TBS_CNT_PAIRS];
-    const Dims &d = c->cur;
-    AView &A = c->A[c->a_cur];
-    if (pairs > 0) {
+    if (c->pred_ahead) {
+        // the kernels went out behind select/merge, before the counts were known; now they are
+        c->pred_ahead = false;
+        c->prep_ahead = pairs > 0;   // (with no pairs the projection made no joiner input rows)
+        if (c->prof_kernel == TBS_K_GEMM) c->prof_units += predictor_madds(c, pairs);
+        if (c->prof_kernel == TBS_K_PREDICTOR) c->prof_units += pairs;
+    } else if (pairs > 0) {
         ProfScope ps(c, TBS_K_PREDICTOR, pairs);
-        // (the input rows of the first layer were gathered behind select/merge)
-        for (int l = 0; l < d.L; ++l) {
-            int in_dim = l == 0 ? d.E : d.H;
-            const int K = (l == 0 && c->emb_gates) ? d.H : in_dim + d.H;
-            if (c->emb_gates && !(c->cfg.debug & 8) && gemm_lstm_fits(pairs, d.H, K)) {
-                // small problem: the cell update runs in the epilogue of the gate GEMM
-                const bool last = l + 1 == d.L;
-                LstmEp ep;
-                ep.pslot = c->rv.pair_pslot;
-                ep.slot = c->rv.pair_slot;
-                ep.tok = c->rv.pair_tok;
-                ep.emb_gates = l == 0 ? c->emb_gates_perm : nullptr;
-                ep.c_par = c->pool_c + (size_t)l * c->pool_rows * d.H;
-                ep.c_new = c->pool_c + (size_t)l * c->pool_rows * d.H;
-                ep.h_new = c->pool_h + (size_t)l * c->pool_rows * d.H;
-                ep.h_par_next = last ? nullptr : c->pool_h + (size_t)(l + 1) * c->pool_rows * d.H;
-                ep.out16 = (bf16_t *)(last ? c->htop : c->xh[(l + 1) & 1]);
-                ep.H = d.H;
-                ProfScope pg(c, TBS_K_GEMM, (int64_t)pairs * 4 * d.H * K);
-                HIPCHK(c, launch_gemm_lstm(c->stream, (const bf16_t *)c->xh[l & 1], (const bf16_t *)c->wperm[l], c->bperm[l],
-                                           pairs, K, ep));
-                continue;
-            }
-            if (l == 0 && c->emb_gates)
-                HIPCHK(c, gemm(c, c->xh[0], c->w.w_hh[0], nullptr, c->gates, pairs, 4 * d.H, d.H, nullptr, 4L * d.H));
-            else
-                HIPCHK(c, gemm(c, c->xh[l & 1], c->wcat[l], c->w.b_lstm[l], c->gates, pairs, 4 * d.H,
-                               in_dim + d.H, nullptr, 4L * d.H));
-            HIPCHK(c, launch_lstm_pointwise(c->stream, d, c->cfg.dtype, pairs, l, A, c->rv, c->gates, c->pool_h,
-                                            c->pool_c, c->pool_rows, c->xh[(l + 1) & 1], c->htop,
-                                            l == 0 ? c->emb_gates : nullptr));
-        }
-        if (c->cfg.dtype == 1 && !(c->cfg.debug & 16) && gemm_join_fits(pairs, d.Dj, d.H)) {
-            // small problem: the projection's epilogue also makes the joiner input rows of the coming
-            // round (every row of that round belongs to one of these pairs)
-            JoinEp jp;
-            jp.pair_row0 = c->rv.pair_row0;
-            jp.pair_len = c->rv.pair_len;
-            jp.pair_frame0 = c->rv.pair_frame0;
-            jp.enc = (const bf16_t *)c->enc;
-            jp.amat = (bf16_t *)c->amat;
-            jp.act = c->cfg.act;
-            ProfScope pg(c, TBS_K_GEMM, (int64_t)pairs * d.Dj * d.H);
-            HIPCHK(c, launch_gemm_join(c->stream, (const bf16_t *)c->htop, (const bf16_t *)c->w.w_proj, c->w.b_proj,
-                                       c->pool_p, pairs, d.Dj, d.H, c->rv.pair_slot, d.Dj, jp));
-            c->prep_ahead = true;
-        } else {
-            HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, pairs, d.Dj, d.H, c->rv.pair_slot, d.Dj));
-        }
+        const int rc = predictor_launch(c, pairs, nullptr);
+        if (rc) return rc;
     }
     c->state = ST_READY;
     return TBS_OK;

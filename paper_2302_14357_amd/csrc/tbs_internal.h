@@ -114,16 +114,19 @@ hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act,
                               const float *pool_p, RowView rv, void *amat, const int *rows_dev = nullptr);
 hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
                            int K, const int *out_row, long ldc);
+// m_dev (launch_gemm_bf16 only where gemm_small_fits; the fused forms always): the launch is enqueued
+// before the host knows the row count; M is an upper bound and the count is read from *m_dev
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, int kernel = 0);
+                            int N, int K, const int *out_row, long ldc, int kernel = 0, const int *m_dev = nullptr);
+bool gemm_small_fits(int M, int N, int K);
 // true if launch_gemm_lstm can run this problem (small, K a multiple of 128 that fits the LDS stages)
 bool gemm_lstm_fits(int M, int H, int K);
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
-                            const LstmEp &ep);
+                            const LstmEp &ep, const int *m_dev = nullptr);
 // the same for the projection GEMM that also makes the next joiner call's input rows (bf16 models)
 bool gemm_join_fits(int M, int N, int K);
 hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, const JoinEp &jp);
+                            int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev = nullptr);
 hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,

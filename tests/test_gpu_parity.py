@@ -232,11 +232,12 @@ def test_decode_small_bf16_and_edges(N, S):
     assert st["joiner_calls"] == sum(r.joiner_calls for r in ref) or amb > 0
 
 
-@pytest.mark.parametrize("debug", [0, 8, 32, 8 + 16 + 32])
+@pytest.mark.parametrize("debug", [0, 8, 32, 64, 8 + 16 + 32])
 def test_decode_cell_update_inside_and_outside_the_gate_gemm(debug):
     """Two LSTM layers of 128 units: both layers fit the gate GEMM whose epilogue updates the cell
     (debug=0); debug=8 keeps the cell update a kernel of its own, 32 the gather of the first layer's
-    input rows (otherwise part of the row list kernel), 56 every step that has a fused form.  All
+    input rows (otherwise part of the row list kernel), 64 the predictor step behind the host's wait
+    for the counts (otherwise enqueued ahead of it), 56 every step that has a fused form.  All
     against the oracle."""
     shape = small_bf16_shape(n_utts=5, vocab=96, d=128, hidden=128, layers=2)
     lengths = np.array([4, 9, 15, 22, 31])
