@@ -71,6 +71,8 @@ __global__ void k_init_batch(Dims d, BView B, AView A0, AView A1, RowView rv, in
             rv.counts[TBS_CNT_FRAMES] = 0;
             rv.counts[TBS_CNT_SEQ] = 0;
             rv.counts[TBS_CNT_NODE_BASE] = 1;
+            rv.counts[TBS_CNT_ACC_CALLS] = 0;
+            rv.counts[TBS_CNT_ACC_JOINED] = 0;
         }
     }
     for (int j = tid; j < d.Dj; j += blockDim.x) pool_p[(long)slot * d.Dj + j] = pred_init[j];
@@ -267,7 +269,15 @@ __device__ __forceinline__ void rowfill_lists(const Dims &d, int seg, const int 
                 nodes_used = node_base + tot_p;
                 if (nodes_used > d.max_nodes) { err |= TBS_ERRF_NODES; nodes_used = d.max_nodes; }
             }
+            // every row list is followed by one joiner call over its rows: the counters of Section
+            // 4.2 (invocations, frames joined; per utterance summed) are kept here, so that the host
+            // need not see every row list
+            const int acc_calls = rv.counts[TBS_CNT_ACC_CALLS] + utts, acc_joined = rv.counts[TBS_CNT_ACC_JOINED] + frames;
+            rv.counts[TBS_CNT_ACC_CALLS] = acc_calls;
+            rv.counts[TBS_CNT_ACC_JOINED] = acc_joined;
             if (host_counts) {
+                store_host(host_counts + TBS_CNT_ACC_CALLS, acc_calls);
+                store_host(host_counts + TBS_CNT_ACC_JOINED, acc_joined);
                 store_host(host_counts + TBS_CNT_PAIRS, tot_p);
                 store_host(host_counts + TBS_CNT_ROWS, tot_r);
                 store_host(host_counts + TBS_CNT_NODES, nodes_used);

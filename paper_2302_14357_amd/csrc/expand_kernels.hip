@@ -123,12 +123,13 @@ template <bool VEC4>
 __global__ void __launch_bounds__(EXP_THREADS)
 k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
          float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
-         float *__restrict__ row_stats, float *__restrict__ delta_nb) {
+         float *__restrict__ row_stats, float *__restrict__ delta_nb, const int *__restrict__ pairs_dev) {
     extern __shared__ float s_dnb[];  // [V]
     __shared__ float s_m[TBS_MAX_SEG], s_z[TBS_MAX_SEG], s_b[TBS_MAX_SEG], s_lc[TBS_MAX_SEG];
     __shared__ float s_rv[EXP_WAVES];
     __shared__ int s_rk[EXP_WAVES];
     const int pair = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (pairs_dev && pair >= *pairs_dev) return;   // (enqueued on an upper-bound grid, see k_expand_reg)
     const int u = rv.pair_u[pair], h = rv.pair_h[pair];
     const int row0 = rv.pair_row0[pair], sp = rv.pair_len[pair];
     const int V = d.V;
@@ -599,7 +600,7 @@ template <int NV4, int SMAX>
 __global__ void __launch_bounds__(EXP_THREADS, (NV4 * SMAX == 20 ? 5 : 1))   // 80 logits per thread: five waves per SIMD still fit
 k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
              float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
-             float *__restrict__ row_stats, float *__restrict__ delta_nb) {
+             float *__restrict__ row_stats, float *__restrict__ delta_nb, const int *__restrict__ pairs_dev) {
     __shared__ ExpandShared<SMAX> sm;
     // Workgroup b runs on XCD b % 8.  The joiner GEMM before this kernel gave XCD x the x-th eighth
     // of the rows, in increasing order; here XCD x walks the pairs of the same eighth backwards, so
@@ -607,9 +608,16 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
     // cache) and is read before this kernel's own traffic evicts it.  Measured: 196 -> 184 us at
     // 51200 rows x 4096.
     // (eighth x holds as many pairs as there are workgroups with b % 8 == x: every pair gets one)
-    const int pairs = gridDim.x, q = pairs >> 3, r = pairs & 7, x = blockIdx.x & 7;
-    const int first = x * q + min(x, r), count = q + (x < r);
-    const int pair = first + count - 1 - (int)(blockIdx.x >> 3);
+    // (pairs_dev not null: the launch went out before the host knew the number of pairs; the grid is
+    // an upper bound and the workgroups beyond the count in device memory leave)
+    int pair = blockIdx.x;
+    if (pairs_dev) {
+        if (pair >= *pairs_dev) return;
+    } else {
+        const int pairs = gridDim.x, q = pairs >> 3, r = pairs & 7, x = blockIdx.x & 7;
+        const int first = x * q + min(x, r), count = q + (x < r);
+        pair = first + count - 1 - (int)(blockIdx.x >> 3);
+    }
     ExpandPair<SMAX> pi;
     expand_pair_info(pi, pair, d, A, rv, logits);
     float e[SMAX][NV4 * 4];
@@ -620,21 +628,21 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
 template <int NV4, int SMAX>
 static void expand_reg_launch(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                               float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
-                              float *delta_nb) {
+                              float *delta_nb, const int *pairs_dev) {
     hipLaunchKernelGGL((k_expand_reg<NV4, SMAX>), dim3(pairs), dim3(EXP_THREADS), 0, st, d, logits, A, rv, row_lc, dphi,
-                       cand_score, cand_tok, row_stats, delta_nb);
+                       cand_score, cand_tok, row_stats, delta_nb, pairs_dev);
 }
 
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
-                         float *delta_nb, int force_generic) {
+                         float *delta_nb, int force_generic, const int *pairs_dev) {
     if (pairs <= 0) return hipSuccess;
     size_t shm = (size_t)d.V * sizeof(float);
     if (d.V % 4 == 0 && !force_generic) {
 #define TBS_EXPAND_REG(NV4, SMAX)                                                                              \
     {                                                                                                          \
         expand_reg_launch<NV4, SMAX>(st, d, pairs, logits, A, rv, row_lc, dphi, cand_score, cand_tok, row_stats, \
-                                     delta_nb);                                                                \
+                                     delta_nb, pairs_dev);                                                     \
         return hipGetLastError();                                                                              \
     }
         const int nv4 = (d.V / 4 + EXP_THREADS - 1) / EXP_THREADS;
@@ -648,9 +656,9 @@ hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *
     }
     if (d.V % 4 == 0)
         hipLaunchKernelGGL(k_expand<true>, dim3(pairs), dim3(EXP_THREADS), shm, st, d, logits, A, rv, row_lc, dphi,
-                           cand_score, cand_tok, row_stats, delta_nb);
+                           cand_score, cand_tok, row_stats, delta_nb, pairs_dev);
     else
         hipLaunchKernelGGL(k_expand<false>, dim3(pairs), dim3(EXP_THREADS), shm, st, d, logits, A, rv, row_lc, dphi,
-                           cand_score, cand_tok, row_stats, delta_nb);
+                           cand_score, cand_tok, row_stats, delta_nb, pairs_dev);
     return hipGetLastError();
 }

@@ -82,7 +82,7 @@ struct tbs_ctx {
     int res_max_len;
 
     // counters
-    int64_t n_calls, n_joined, n_frames, n_launches;
+    int64_t n_frames, n_launches;   // (joiner invocations and frames joined are counted on the device)
 
     // profiling
     int prof_kernel;
@@ -439,7 +439,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         tbs_free(c);
         return TBS_EHIP;
     }
-    c->n_calls = c->n_joined = c->n_frames = c->n_launches = 0;
+    c->n_frames = c->n_launches = 0;
     *out = c;
     return TBS_OK;
 }
@@ -465,7 +465,7 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     c->seq = 0;
     c->prep_ahead = false;
     c->pred_ahead = false;
-    c->n_calls = c->n_joined = c->n_launches = 0;
+    c->n_launches = 0;
     c->n_frames = frames;
     c->state = ST_BEGUN;
     return TBS_OK;
@@ -550,8 +550,6 @@ int tbs_joiner_segment(tbs_ctx *c) {
                        c->cur.V));
     }
     c->n_launches += 1;
-    c->n_calls += c->h_counts[TBS_CNT_UTTS];
-    c->n_joined += c->h_counts[TBS_CNT_FRAMES];
     c->state = ST_JOINED;
     return TBS_OK;
 }
@@ -747,18 +745,75 @@ int tbs_result(tbs_ctx *c, int32_t *tokens, int32_t *lens, double *logscores, in
     return ovf ? TBS_EOVERFLOW : TBS_OK;
 }
 
-// the inner loop of Algorithm 1 (while Length(A) > 0) for the segment just started
-static int run_rounds(tbs_ctx *c, int rows) {
-    int rc;
-    while (rows > 0) {
-        int live = 0;
+// Small batches: the head of a segment and its whole first round enqueued in one go, with one
+// wait at the end.  Every kernel that needs a count (rows for the joiner GEMM and its input rows,
+// pairs for the expansion and the predictor step) reads it from device memory and is sized for
+// the most the batch can have; the host's round trip after the first row list (7-8 us with
+// nothing for the GPU to run) disappears.  Not while a kernel family is being timed (the brackets
+// want the counts at launch).
+static bool segment_ahead_ok(const tbs_ctx *c) {
+    const Dims &d = c->cur;
+    return !(c->cfg.debug & 64) && c->prof_kernel < 0 && c->cfg.dtype == 1 && d.R >= 1 &&
+           gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj) && predictor_all_fused(c, d.U * d.N);
+}
+
+static int segment_begin_ahead(tbs_ctx *c, int32_t seg_index) {
+    if (c->state != ST_BEGUN && c->state != ST_READY && c->state != ST_SELECTED) return TBS_ESTATE;
+    if (c->state != ST_BEGUN && c->h_counts[TBS_CNT_PAIRS] != 0) return TBS_ESTATE;  // A not empty yet
+    const Dims &d = c->cur;
+    c->seg = seg_index;
+    c->round = 1;
+    AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];
+    const int *rows_dev = c->rv.counts + TBS_CNT_ROWS, *pairs_dev = c->rv.counts + TBS_CNT_PAIRS;
+    // A = ChooseNBest(B), B = [], the row list, the joiner input rows
+    HIPCHK(c, launch_segment_begin(c->stream, d, c->seg, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h, c->pool_c,
+                                   c->pool_rows));
+    HIPCHK(c, launch_rowfill(c->stream, d, c->seg, c->utt_off, A, c->rv, c->nodes, 0, c->h_counts_dev, ++c->seq));
+    HIPCHK(c, launch_joiner_prep(c->stream, d, c->cfg.dtype, c->cfg.act, d.U * d.N * d.S, c->enc, c->pool_p, c->rv,
+                                 c->amat, rows_dev));
+    // first round: joiner, expansion, select/merge, row list, predictor step
+    HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, c->logits,
+                               d.U * d.N * d.S, d.V, d.Dj, nullptr, d.V, 0, rows_dev));
+    c->n_launches += 1;
+    HIPCHK(c, launch_expand(c->stream, d, d.U * d.N, c->logits, A, c->rv, c->row_lc, c->dphi, c->cand_score,
+                            c->cand_tok, c->row_stats, c->delta_nb, (c->cfg.debug & 2) != 0, pairs_dev));
+    const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
+    HIPCHK(c, launch_select_merge(c->stream, d, c->round, drop, c->logits, c->row_lc, c->dphi, c->cand_score,
+                                  c->cand_tok, A, An, c->B, c->rv, c->nodes));
+    const bool fused_gather = !(c->cfg.debug & 32) && (d.H & 3) == 0 && (long)d.U * d.N <= 1024;
+    HIPCHK(c, launch_rowfill(c->stream, d, c->seg, c->utt_off, An, c->rv, c->nodes, 1, c->h_counts_dev, ++c->seq,
+                             fused_gather ? c->pool_h : nullptr, fused_gather ? (bf16_t *)c->xh[0] : nullptr));
+    if (!fused_gather)
+        HIPCHK(c, launch_pred_gather_h(c->stream, d, d.U * d.N, An, c->rv, c->pool_h, (bf16_t *)c->xh[0]));
+    c->a_cur ^= 1;
+    const int rc = predictor_launch(c, d.U * d.N, pairs_dev);
+    if (rc) return rc;
+    c->prep_ahead = false;
+    c->pred_ahead = true;
+    HIPCHK(c, wait_counts(c));
+    c->state = ST_SELECTED;
+    return check_err_flags(c);
+}
+
+// one segment: the head of the outer loop of Algorithm 1 and its inner loop (while Length(A) > 0)
+static int run_segment(tbs_ctx *c, int32_t seg_index) {
+    int rc, rows = 0, live = 0;
+    if (segment_ahead_ok(c)) {
+        if ((rc = segment_begin_ahead(c, seg_index))) return rc;
+    } else {
+        if ((rc = segment_begin(c, seg_index, &rows))) return rc;
+        if (rows == 0) return TBS_OK;
         if ((rc = tbs_joiner_segment(c))) return rc;
         if ((rc = tbs_expand(c))) return rc;
         if ((rc = tbs_select_merge(c, &live))) return rc;
-        if ((rc = tbs_predictor_step(c))) return rc;
-        rows = c->h_counts[TBS_CNT_ROWS];
     }
-    return TBS_OK;
+    for (;;) {
+        if ((rc = tbs_predictor_step(c))) return rc;
+        if (c->h_counts[TBS_CNT_ROWS] == 0) return TBS_OK;
+        if ((rc = tbs_joiner_segment(c))) return rc;
+        if ((rc = tbs_expand(c))) return rc;
+        if ((rc = tbs_select_merge(c, &live))) return rc;
+    }
 }
 
 int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, int32_t flush) {
@@ -808,10 +863,8 @@ int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offs
         if (!any) break;
         HIPCHK(c, hipMemcpyAsync(c->utt_T, take, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, hipMemcpyAsync(c->utt_off, first, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
-        int rows = 0;
-        int rc = segment_begin(c, 0, &rows);   // waits for the counts: the two copies above are done
+        const int rc = run_segment(c, 0);   // (waits for counts: the two copies above are done by then)
         if (rc) return rc;
-        if ((rc = run_rounds(c, rows))) return rc;
         for (int u = 0; u < U; ++u) pos[u] += take[u];
     }
     // what is left (less than a segment) moves to the front of its buffer, through the spare area
@@ -842,18 +895,16 @@ int tbs_decode(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, i
     const int S = c->cur.S;
     const int nseg = (c->max_T + S - 1) / S;
     for (int seg = 0; seg < nseg; ++seg) {          // while t <= Length(enc)
-        int rows = 0;
-        rc = tbs_segment_begin(c, seg, &rows);
-        if (rc) return rc;
-        if ((rc = run_rounds(c, rows))) return rc;   // while Length(A) > 0
+        if ((rc = run_segment(c, seg))) return rc;
     }
     return tbs_result(c, tokens, lens, logscores, nbest_count, max_len);
 }
 
 int tbs_stats(const tbs_ctx *c, int64_t *joiner_calls, int64_t *joined_frames, int64_t *frames, int64_t *launches) {
     if (!c) return TBS_EINVAL;
-    if (joiner_calls) *joiner_calls = c->n_calls;
-    if (joined_frames) *joined_frames = c->n_joined;
+    // (running sums kept by the row list kernel, as of the last counts the host waited for)
+    if (joiner_calls) *joiner_calls = c->h_counts[TBS_CNT_ACC_CALLS];
+    if (joined_frames) *joined_frames = c->h_counts[TBS_CNT_ACC_JOINED];
     if (frames) *frames = c->n_frames;
     if (launches) *launches = c->n_launches;
     return TBS_OK;

@@ -49,11 +49,13 @@ struct RowView {
     int *row_slot;   // [rows] predictor-state slot
     int *counts;     // [8]: 0 pairs, 1 rows, 2 trie nodes used, 3 error flags, 4 live utterances,
                      //      5 frames joined (sum of S' over live utterances), 6 number of the launch that
-                     //      published the figures (host mirror), 7 the other slot of 2 (they alternate)
+                     //      published the figures (host mirror), 7 the other slot of 2 (they alternate),
+                     //      8 and 9 running sums of 4 and 5 over the row lists made since the batch began
+                     //      (joiner invocations and frames joined, per utterance summed)
 };
 
 enum { TBS_CNT_PAIRS = 0, TBS_CNT_ROWS = 1, TBS_CNT_NODES = 2, TBS_CNT_ERR = 3, TBS_CNT_UTTS = 4, TBS_CNT_FRAMES = 5,
-       TBS_CNT_SEQ = 6, TBS_CNT_NODE_BASE = 7, TBS_CNT_SIZE = 8 };
+       TBS_CNT_SEQ = 6, TBS_CNT_NODE_BASE = 7, TBS_CNT_ACC_CALLS = 8, TBS_CNT_ACC_JOINED = 9, TBS_CNT_SIZE = 10 };
 enum { TBS_ERRF_BCAP = 1, TBS_ERRF_NODES = 2 };
 
 struct Dims {
@@ -130,7 +132,7 @@ hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, co
 hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
-                         float *delta_nb, int force_generic);
+                         float *delta_nb, int force_generic, const int *pairs_dev = nullptr);
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes);
