@@ -57,6 +57,7 @@ struct tbs_ctx {
     int seq;            // number of the last scan asked to publish its counts there
     bool prep_ahead;    // the joiner input rows of the coming call are already being made (see tbs_segment_begin)
     bool pred_ahead;    // the predictor kernels of this round are already enqueued (see tbs_select_merge)
+    bool join_ahead;    // and so is the joiner GEMM of the next round
     int2 *nodes;
     long pool_rows;
     float *pool_p, *pool_h, *pool_c;
@@ -465,6 +466,7 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     c->seq = 0;
     c->prep_ahead = false;
     c->pred_ahead = false;
+    c->join_ahead = false;
     c->n_launches = 0;
     c->n_frames = frames;
     c->state = ST_BEGUN;
@@ -512,6 +514,7 @@ static int segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     c->seg = seg_index;
     c->round = 0;
     c->pred_ahead = false;
+    c->join_ahead = false;
     AView &A = c->A[c->a_cur];
     HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h,
                                    c->pool_c, c->pool_rows));
@@ -538,6 +541,15 @@ int tbs_joiner_segment(tbs_ctx *c) {
     const int rows = c->h_counts[TBS_CNT_ROWS];
     if (c->round + 1 > c->cur.R) return TBS_EOVERFLOW;
     c->round += 1;
+    if (c->join_ahead) {   // enqueued behind the predictor step, before the counts were known
+        c->join_ahead = false;
+        c->prep_ahead = false;
+        if (c->prof_kernel == TBS_K_JOINER) c->prof_units += rows;
+        if (c->prof_kernel == TBS_K_GEMM) c->prof_units += (int64_t)rows * c->cur.V * c->cur.Dj;
+        c->n_launches += 1;
+        c->state = ST_JOINED;
+        return TBS_OK;
+    }
     if (!c->prep_ahead) {
         ProfScope ps(c, TBS_K_PREP, rows);
         HIPCHK(c, launch_joiner_prep(c->stream, c->cur, c->cfg.dtype, c->cfg.act, rows, c->enc, c->pool_p, c->rv,
@@ -607,6 +619,7 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     // of them.  A round that created nothing (the last of every segment) pays two launches that
     // leave at once.
     c->pred_ahead = false;
+    c->join_ahead = false;
     c->a_cur ^= 1;   // (the new hypotheses are the current group from here on)
     if (!(c->cfg.debug & 64) && predictor_all_fused(c, c->cur.U * c->cur.N)) {
         ProfScope ps(c, TBS_K_PREDICTOR, 0);
@@ -614,6 +627,17 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
         if (rc) return rc;
         c->prep_ahead = false;   // (known only with the counts: see tbs_predictor_step)
         c->pred_ahead = true;
+        // and the joiner GEMM of the next round behind them (its input rows come from the
+        // projection's epilogue), reading the number of rows from device memory
+        const Dims &d = c->cur;
+        if (c->round + 1 <= d.R && gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj)) {
+            ProfScope pj(c, TBS_K_JOINER, 0);
+            ProfScope pg(c, TBS_K_GEMM, 0);
+            HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out,
+                                       c->logits, d.U * d.N * d.S, d.V, d.Dj, nullptr, d.V, 0,
+                                       c->rv.counts + TBS_CNT_ROWS));
+            c->join_ahead = true;
+        }
     }
     HIPCHK(c, wait_counts(c));
     if (live_host) *live_host = c->h_counts[TBS_CNT_PAIRS];
@@ -790,6 +814,12 @@ static int segment_begin_ahead(tbs_ctx *c, int32_t seg_index) {
     if (rc) return rc;
     c->prep_ahead = false;
     c->pred_ahead = true;
+    c->join_ahead = false;
+    if (c->round + 1 <= d.R) {   // and the joiner GEMM of the second round
+        HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, c->logits,
+                                   d.U * d.N * d.S, d.V, d.Dj, nullptr, d.V, 0, rows_dev));
+        c->join_ahead = true;
+    }
     HIPCHK(c, wait_counts(c));
     c->state = ST_SELECTED;
     return check_err_flags(c);
