@@ -338,8 +338,8 @@ __device__ __forceinline__ bf16_t gs_bf16(float f) {
 // frames (Section 3.1), so that the next joiner call needs no kernel of its own for them.
 // m_dev not null: the kernel was enqueued before the host knew the number of rows.  M is then only
 // an upper bound (it sizes the grid and keeps every address inside the buffers); the rows that
-// exist are the first *m_dev, read from device memory: workgroups beyond them leave once their K
-// tiles have landed, and the epilogue stores nothing for the others' surplus rows.
+// exist are the first *m_dev, read from device memory: workgroups beyond them leave at once, and the
+// epilogue stores nothing for the others' surplus rows.
 template <int MODE>
 __global__ void __launch_bounds__(256)
 k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
@@ -406,13 +406,10 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         }
     }
     asm volatile("" ::: "memory");
+    const int m_live = m_dev ? min(*m_dev, M) : M;   // (the same in every lane: a scalar load)
+    if (tile_m * 64 >= m_live) return;   // no row of this tile exists (before anything is on its way into LDS)
     const int first = min(ns, kt);
     for (int c = 0; c < first; ++c) fetch(c, c);
-    const int m_live = m_dev ? min(*m_dev, M) : M;   // (the same in every lane: a scalar load)
-    if (tile_m * 64 >= m_live) {   // no row of this tile exists: leave, once nothing is on its way into LDS
-        __builtin_amdgcn_s_waitcnt(GS_VMCNT(0));
-        return;
-    }
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
