@@ -157,7 +157,8 @@ hipError_t wait_counts(tbs_ctx *c) {
     const int want = c->seq;
     for (unsigned spin = 1;; ++spin) {
         if (__atomic_load_n(&c->h_counts[TBS_CNT_SEQ], __ATOMIC_ACQUIRE) == want) return hipSuccess;
-        if ((spin & 0x3FFF) == 0) {   // now and then: has the stream failed, or ended without the number?
+        if ((spin & 0x3FFFFF) == 0) {   // every few milliseconds (a query costs microseconds, during which the
+                                        // number would go unnoticed): has the stream failed, or ended without it?
             const hipError_t e = hipStreamQuery(c->stream);
             if (e == hipSuccess)
                 return __atomic_load_n(&c->h_counts[TBS_CNT_SEQ], __ATOMIC_ACQUIRE) == want ? hipSuccess
