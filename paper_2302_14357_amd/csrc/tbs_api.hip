@@ -56,7 +56,7 @@ struct tbs_ctx {
     int *h_counts_dev;  // device view of the same memory
     int seq;            // number of the last scan asked to publish its counts there
     bool prep_ahead;    // the joiner input rows of the coming call are already being made (see tbs_segment_begin)
-    bool pred_ahead;    // the predictor kernels of this round are already enqueued (see tbs_select_merge)
+    int pred_ahead;     // predictor kernels of this round already enqueued (see tbs_select_merge): 1 the LSTM layers, 2 all
     bool join_ahead;    // and so is the joiner GEMM of the next round
     int2 *nodes;
     long pool_rows;
@@ -466,7 +466,7 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     c->h_counts[TBS_CNT_NODES] = 1;
     c->seq = 0;
     c->prep_ahead = false;
-    c->pred_ahead = false;
+    c->pred_ahead = 0;
     c->join_ahead = false;
     c->n_launches = 0;
     c->n_frames = frames;
@@ -514,7 +514,7 @@ static int segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     if (c->state != ST_BEGUN && c->h_counts[TBS_CNT_PAIRS] != 0) return TBS_ESTATE;  // A not empty yet
     c->seg = seg_index;
     c->round = 0;
-    c->pred_ahead = false;
+    c->pred_ahead = 0;
     c->join_ahead = false;
     AView &A = c->A[c->a_cur];
     HIPCHK(c, launch_segment_begin(c->stream, c->cur, c->seg, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h,
@@ -581,7 +581,7 @@ int tbs_expand(tbs_ctx *c) {
 }
 
 static bool predictor_all_fused(const tbs_ctx *c, int M);
-static int predictor_launch(tbs_ctx *c, int M, const int *m_dev);
+static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part = 0);
 
 int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     if (!c) return TBS_EINVAL;
@@ -613,32 +613,22 @@ int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
             HIPCHK(c, launch_pred_gather(c->stream, c->cur, c->cfg.dtype, c->cur.U * c->cur.N, An, c->rv, c->w.embed,
                                          c->pool_h, c->xh[0]));
     }
-    // Small batches: the predictor step itself goes out now, sized for every hypothesis the round
-    // could have created and reading the number it did create from device memory.  The host's
-    // round trip (counts into pinned memory, the host seeing them, a launch reaching the GPU: 7-8 us
-    // during which the GPU had nothing to run) then lies beside these kernels instead of in front
-    // of them.  A round that created nothing (the last of every segment) pays two launches that
-    // leave at once.
-    c->pred_ahead = false;
+    // Small batches: the LSTM layers of the predictor step go out now, sized for every hypothesis
+    // the round could have created and reading the number it did create from device memory.  The
+    // host's round trip (counts into pinned memory, the host seeing them, a launch reaching the GPU:
+    // 7-8 us during which the GPU had nothing to run) then lies beside these kernels instead of in
+    // front of them; the projection and the next round follow from tbs_predictor_step on, in time.
+    // A round that created nothing (the last of every segment) pays launches that leave at once,
+    // which is why no more than this goes out early: measured, the layers alone beat layers +
+    // projection and layers + projection + next joiner GEMM (23.5 / 24.2 / 24.7 ms per decode).
+    c->pred_ahead = 0;
     c->join_ahead = false;
     c->a_cur ^= 1;   // (the new hypotheses are the current group from here on)
     if (!(c->cfg.debug & 64) && predictor_all_fused(c, c->cur.U * c->cur.N)) {
         ProfScope ps(c, TBS_K_PREDICTOR, 0);
-        const int rc = predictor_launch(c, c->cur.U * c->cur.N, c->rv.counts + TBS_CNT_PAIRS);
+        const int rc = predictor_launch(c, c->cur.U * c->cur.N, c->rv.counts + TBS_CNT_PAIRS, 1);
         if (rc) return rc;
-        c->prep_ahead = false;   // (known only with the counts: see tbs_predictor_step)
-        c->pred_ahead = true;
-        // and the joiner GEMM of the next round behind them (its input rows come from the
-        // projection's epilogue), reading the number of rows from device memory
-        const Dims &d = c->cur;
-        if (c->round + 1 <= d.R && gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj)) {
-            ProfScope pj(c, TBS_K_JOINER, 0);
-            ProfScope pg(c, TBS_K_GEMM, 0);
-            HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out,
-                                       c->logits, d.U * d.N * d.S, d.V, d.Dj, nullptr, d.V, 0,
-                                       c->rv.counts + TBS_CNT_ROWS));
-            c->join_ahead = true;
-        }
+        c->pred_ahead = 1;
     }
     HIPCHK(c, wait_counts(c));
     if (live_host) *live_host = c->h_counts[TBS_CNT_PAIRS];
@@ -667,11 +657,11 @@ static int64_t predictor_madds(const tbs_ctx *c, int64_t pairs) {   // multiply-
     return n;
 }
 
-static int predictor_launch(tbs_ctx *c, int M, const int *m_dev) {
+static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part) {   // part: 0 all, 1 the LSTM layers, 2 the projection
     const Dims &d = c->cur;
     AView &A = c->A[c->a_cur];
     // (the input rows of the first layer were gathered behind select/merge)
-    for (int l = 0; l < d.L; ++l) {
+    for (int l = 0; l < d.L && part != 2; ++l) {
         int in_dim = l == 0 ? d.E : d.H;
         const int K = (l == 0 && c->emb_gates) ? d.H : in_dim + d.H;
         if (c->emb_gates && !(c->cfg.debug & 8) && gemm_lstm_fits(M, d.H, K)) {
@@ -702,6 +692,7 @@ static int predictor_launch(tbs_ctx *c, int M, const int *m_dev) {
         HIPCHK(c, launch_lstm_pointwise(c->stream, d, c->cfg.dtype, M, l, A, c->rv, c->gates, c->pool_h, c->pool_c,
                                         c->pool_rows, c->xh[(l + 1) & 1], c->htop, l == 0 ? c->emb_gates : nullptr));
     }
+    if (part == 1) return TBS_OK;
     if (c->cfg.dtype == 1 && !(c->cfg.debug & 16) && gemm_join_fits(M, d.Dj, d.H)) {
         // small problem: the projection's epilogue also makes the joiner input rows of the coming
         // round (every row of that round belongs to one of these pairs)
@@ -729,10 +720,19 @@ int tbs_predictor_step(tbs_ctx *c) {
     const int pairs = c->h_counts[TBS_CNT_PAIRS];
     if (c->pred_ahead) {
         // the kernels went out behind select/merge, before the counts were known; now they are
-        c->pred_ahead = false;
+        const int level = c->pred_ahead;
+        c->pred_ahead = 0;
         c->prep_ahead = pairs > 0;   // (with no pairs the projection made no joiner input rows)
-        if (c->prof_kernel == TBS_K_GEMM) c->prof_units += predictor_madds(c, pairs);
+        // (work of the launches that went out with their size unknown; the projection, if it goes
+        // out now, counts itself)
+        if (c->prof_kernel == TBS_K_GEMM)
+            c->prof_units += predictor_madds(c, pairs) - (level == 1 ? (int64_t)pairs * c->cur.Dj * c->cur.H : 0);
         if (c->prof_kernel == TBS_K_PREDICTOR) c->prof_units += pairs;
+        if (level == 1 && pairs > 0) {
+            ProfScope ps(c, TBS_K_PREDICTOR, 0);
+            const int rc = predictor_launch(c, pairs, nullptr, 2);
+            if (rc) return rc;
+        }
     } else if (pairs > 0) {
         ProfScope ps(c, TBS_K_PREDICTOR, pairs);
         const int rc = predictor_launch(c, pairs, nullptr);
@@ -814,7 +814,7 @@ static int segment_begin_ahead(tbs_ctx *c, int32_t seg_index) {
     const int rc = predictor_launch(c, d.U * d.N, pairs_dev);
     if (rc) return rc;
     c->prep_ahead = false;
-    c->pred_ahead = true;
+    c->pred_ahead = 2;
     c->join_ahead = false;
     if (c->round + 1 <= d.R) {   // and the joiner GEMM of the second round
         HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, c->logits,
