@@ -193,7 +193,9 @@ enum tbs_buffer {
  * current round's counts (TBS_BUF_COUNTS). */
 int tbs_debug_read(tbs_ctx *ctx, int32_t which, void *dst, size_t bytes);
 /* Overwrite A_COUNT / A_LOGS / A_DHAT / A_PRED from HOST memory (full arrays),
- * so that a test can put the joiner and expansion steps on chosen inputs. */
+ * so that a test can put the joiner and expansion steps on chosen inputs.  Not
+ * between tbs_select_merge and tbs_predictor_step: part of the predictor step
+ * may already have run on the state as it was. */
 int tbs_debug_write(tbs_ctx *ctx, int32_t which, const void *src, size_t bytes);
 /* After tbs_debug_write: rebuild the row list for segment seg_index without
  * touching A or B. */
