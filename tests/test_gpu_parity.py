@@ -417,11 +417,15 @@ def test_decode_step_by_step_matches_oracle_trace():
     tbs.close()
 
 
-def test_round_limit_matches_oracle():
-    shape = small_bf16_shape(n_utts=2, vocab=32, d=64, hidden=64)
+@pytest.mark.parametrize("d,limit", [(64, 2), (128, 2), (128, 1)])
+def test_round_limit_matches_oracle(d, limit):
+    """Hypotheses still emitting after `limit` rounds of a segment are dropped (Section 3.2 mentions
+    such a limit).  Width 128 takes the path on which a segment's head and first round are enqueued
+    in one go (with limit 1 the drop falls into that first round), width 64 the step-by-step one."""
+    shape = small_bf16_shape(n_utts=2, vocab=32, d=d, hidden=d)
     model, offsets, enc = build_case(shape, n_utts=2, lengths=np.array([9, 6]))
-    ref = _oracle_decode(shape, model, offsets, enc, 4, 3, max_rounds=2)
-    got, _ = _gpu_decode(shape, model, offsets, enc, 4, 3, max_rounds_per_segment=2)
+    ref = _oracle_decode(shape, model, offsets, enc, 4, 3, max_rounds=limit)
+    got, _ = _gpu_decode(shape, model, offsets, enc, 4, 3, max_rounds_per_segment=limit)
     same, amb, tot = compare_nbest(got, ref)
     assert same == tot
 
@@ -595,3 +599,16 @@ def test_errors_are_codes_not_crashes():
         tbs.decode(tbs.upload_frames(enc), offsets)
     assert e.value.code == -5
     tbs.close()
+    # the same at a width whose segments are enqueued head and first round in one go, and the
+    # context still decodes afterwards when given the room
+    shape = small_bf16_shape(n_utts=2, d=128, hidden=128)
+    model, offsets, enc = build_case(shape, n_utts=2, lengths=np.array([5, 6]))
+    tbs = make_tbs(shape, model, offsets, 2, 2, rounds_capacity=1)
+    with pytest.raises(TbsError) as e:
+        tbs.decode(tbs.upload_frames(enc), offsets)
+    assert e.value.code == -5
+    tbs.close()
+    ref = _oracle_decode(shape, model, offsets, enc, 2, 2)
+    got, _ = _gpu_decode(shape, model, offsets, enc, 2, 2)
+    same, amb, tot = compare_nbest(got, ref)
+    assert same + amb == tot
