@@ -417,6 +417,7 @@ k_select_merge(Dims d, int round, int drop, const float *logits, const float *ro
     __shared__ int s_sel[TBS_MAX_BEAM];      // candidate index by rank
     __shared__ int s_keep[TBS_MAX_BEAM];
     __shared__ double s_thr;
+    __shared__ float s_dnew[TBS_MAX_SEG * TBS_MAX_BEAM];   // frame distributions of the new hypotheses, [frame][hypothesis]
     const int u = blockIdx.x, lane = threadIdx.x;
     const int N = d.N;
     // everything that describes the utterance in one round of loads
@@ -572,17 +573,21 @@ k_select_merge(Dims d, int round, int drop, const float *logits, const float *ro
                 const int row0 = urow0 + h * sp;
                 // (kept as logarithms: over a long segment d spans more than the range of float, and
                 // the small entries matter to the next blank expansion)
+                // The S' values wait in LDS (frame-major, so the lanes' accesses fall into different
+                // banks) between the pass that reads the logits and the one that writes the normalised
+                // result: going through the result array itself cost two more memory round trips.
                 float *dh = An.dhat + an * d.S;
+                float *sd = s_dnew + lane;
                 float mx = -INFINITY;
                 for (int t = 0; t < sp; ++t) {
                     const float x = logits[(long)(row0 + t) * d.V + tok] + row_lc[row0 + t];
-                    dh[t] = x;
+                    sd[t * TBS_MAX_BEAM] = x;
                     mx = fmaxf(mx, x);
                 }
                 float sum = 0.f;
-                for (int t = 0; t < sp; ++t) sum += __expf(dh[t] - mx);
+                for (int t = 0; t < sp; ++t) sum += __expf(sd[t * TBS_MAX_BEAM] - mx);
                 const float lz = mx + __logf(sum);
-                for (int t = 0; t < sp; ++t) dh[t] -= lz;
+                for (int t = 0; t < sp; ++t) dh[t] = sd[t * TBS_MAX_BEAM] - lz;
                 for (int t = sp; t < d.S; ++t) dh[t] = -INFINITY;
             }
         }
