@@ -81,6 +81,8 @@ typedef struct tbs_config {
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */
+    int32_t max_result_len;   /* longest token sequence tbs_decode / tbs_result hand back (sizes the result
+                                 buffer at tbs_init); 0 = 256.  A larger max_len there is TBS_EINVAL */
     int32_t device_id;
     void *stream;             /* hipStream_t to enqueue on (0 = the null stream) */
 } tbs_config;
@@ -98,7 +100,9 @@ typedef struct tbs_weights {          /* DEVICE pointers, borrowed */
 } tbs_weights;
 
 /* Create a context: validates the configuration, allocates every workspace
- * once (no later call allocates), and prepares the predictor weights.
+ * once (no later call of the decode or streaming path allocates; the inspection
+ * and timing calls below make temporaries of their own), and prepares the
+ * predictor weights.  N * rounds capacity (the longest list B) may not exceed 2048.
  * Algorithm 1 inputs N and S are fixed per context. */
 int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out);
 void tbs_free(tbs_ctx *ctx);
@@ -138,7 +142,9 @@ int tbs_predictor_step(tbs_ctx *ctx);
 /* Algorithm 1 for U utterances in lock-step; equals running each alone.
  * Outputs (HOST): tokens [U, N, max_len], lens [U, N], logscores [U, N]
  * (natural log), nbest_count [U]; hypotheses in descending score order.
- * A hypothesis longer than max_len is truncated and TBS_EOVERFLOW returned. */
+ * A hypothesis longer than max_len is truncated to its first max_len tokens (lens
+ * still holds its true length) and TBS_EOVERFLOW returned; the other outputs are complete.
+ * max_len may not exceed the configuration's max_result_len. */
 int tbs_decode(tbs_ctx *ctx, const void *enc_proj, const int32_t *frame_offsets, int32_t U,
                int32_t *tokens, int32_t *lens, double *logscores, int32_t *nbest_count,
                int32_t max_len);

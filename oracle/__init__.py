@@ -57,6 +57,8 @@ def lib():
         L.orc_result_counters.argtypes = [C.c_void_p, C.POINTER(C.c_long), C.POINTER(C.c_long), C.POINTER(C.c_long)]
         L.orc_result_min_gap.argtypes = [C.c_void_p]
         L.orc_result_min_gap.restype = C.c_double
+        L.orc_result_final_gap.argtypes = [C.c_void_p]
+        L.orc_result_final_gap.restype = C.c_double
         L.orc_result_trace.argtypes = [C.c_void_p, C.POINTER(_ip), C.POINTER(C.c_long), C.POINTER(_dp), C.POINTER(C.c_long)]
         L.orc_result_trace.restype = C.c_long
         L.orc_decode_lstm_batch.argtypes = [C.POINTER(_LstmWeightsC), _dp, _ip, C.c_int, C.POINTER(_OptsC),
@@ -271,6 +273,8 @@ class Round:
     new_pairs: list         # (parent h, token)
     new_scores: list
     new_d: list
+    head_gap: float = math.inf   # gap of the ChooseNBest(B) that opened the segment of this round
+    gap: float = math.inf        # smallest gap of this round's own decisions
 
 
 @dataclass
@@ -280,7 +284,17 @@ class Decoded:
     joined_frames: int
     frames: int
     min_gap: float
+    final_gap: float = math.inf
     rounds: list = field(default_factory=list)
+
+    def first_ambiguous_segment(self, tol: float):
+        """Index of the first segment in which a decision (the ChooseNBest that opens it, or a
+        round's top-N cut or threshold test) had a gap of at most tol; None if there is none.
+        Needs a decode with trace=True."""
+        for r in self.rounds:
+            if r.head_gap <= tol or r.gap <= tol:
+                return r.seg
+        return None
 
 
 def _collect(res_ptr, want_trace) -> Decoded:
@@ -293,7 +307,8 @@ def _collect(res_ptr, want_trace) -> Decoded:
         nbest.append((tuple(int(tp[j]) for j in range(ln)), float(L.orc_result_logscore(res_ptr, i))))
     a, b, c = C.c_long(), C.c_long(), C.c_long()
     L.orc_result_counters(res_ptr, C.byref(a), C.byref(b), C.byref(c))
-    out = Decoded(nbest, a.value, b.value, c.value, float(L.orc_result_min_gap(res_ptr)))
+    out = Decoded(nbest, a.value, b.value, c.value, float(L.orc_result_min_gap(res_ptr)),
+                  float(L.orc_result_final_gap(res_ptr)))
     if want_trace:
         ip, dp_ = _ip(), _dp()
         ni, nd = C.c_long(), C.c_long()
@@ -332,8 +347,9 @@ def _parse_trace(it, dt):
         new_scores, new_d = [], []
         for _ in range(nA):
             new_scores.append(float(dt[d])); new_d.append(dt[d + 1:d + 1 + Sp].copy()); d += 1 + Sp
+        head_gap, gap = float(dt[d]), float(dt[d + 1]); d += 2
         rounds.append(Round(seg, rnd, Sp, a_tokens, a_scores, dphi, d_old, b_tokens, b_scores, thr,
-                            pairs, new_scores, new_d))
+                            pairs, new_scores, new_d, head_gap, gap))
     assert d == len(dt)
     return rounds
 

@@ -365,7 +365,8 @@ struct orc_result {
     int **tok;
     double *logs;
     long joiner_calls, joined_frames, frames;
-    double min_gap;
+    double min_gap;   /* smallest gap of any decision of the run */
+    double final_gap; /* gap of the last ChooseNBest(B) alone */
     int *it;
     long n_it, cap_it;
     double *dt;
@@ -422,17 +423,22 @@ static double score_gap(double a, double b, int raw) {
     return fabs(a - b);
 }
 
-static void note_gaps(orc_result *r, const rank_item *sorted, int n, int N, int raw) {
-    int last = N < n - 1 ? N : n - 1; /* pairs (0,1) .. (last-1,last) */
-    for (int i = 0; i < last; ++i) {
-        double g = score_gap(sorted[i].key, sorted[i + 1].key, raw);
-        if (g < r->min_gap) r->min_gap = g;
-    }
+/* A ranking that keeps the best N of n sorted entries decides one thing that
+ * rounding could change: which of the N-th and the (N+1)-th entry stays.  The
+ * distance between those two is the gap of the decision (infinite when
+ * nothing is cut).  The order inside the kept N changes no later score. */
+static double cut_gap(const rank_item *sorted, int n, int N, int raw) {
+    if (n <= N || N < 1) return INFINITY;
+    return score_gap(sorted[N - 1].key, sorted[N].key, raw);
+}
+
+static void note_gap(orc_result *r, double g) {
+    if (r && g < r->min_gap) r->min_gap = g;
 }
 
 /* ChooseNBest: the N highest-scoring hypotheses of src, moved into dst in
- * descending order; the rest are released. */
-static void choose_n_best(hlist *src, int N, hlist *dst, orc_result *r, int raw) {
+ * descending order; the rest are released.  Returns the gap of the cut. */
+static double choose_n_best(hlist *src, int N, hlist *dst, orc_result *r, int raw) {
     int n = src->n;
     rank_item *it = (rank_item *)malloc(sizeof(rank_item) * (size_t)(n > 0 ? n : 1));
     for (int i = 0; i < n; ++i) {
@@ -441,7 +447,8 @@ static void choose_n_best(hlist *src, int N, hlist *dst, orc_result *r, int raw)
         it[i].idx = i;
     }
     qsort(it, (size_t)n, sizeof(rank_item), rank_cmp);
-    if (r) note_gaps(r, it, n, N, raw);
+    const double gap = cut_gap(it, n, N, raw);
+    note_gap(r, gap);
     for (int i = 0; i < n; ++i) {
         hyp *h = &src->v[it[i].idx];
         if (i < N) {
@@ -456,6 +463,7 @@ static void choose_n_best(hlist *src, int N, hlist *dst, orc_result *r, int raw)
     }
     src->n = 0;
     free(it);
+    return gap;
 }
 
 /* AddAndMerge: append, or add the score to an entry with the same tokens. */
@@ -493,6 +501,7 @@ static double choose_nth_score(const hlist *B, int N) {
     double *s = (double *)malloc(sizeof(double) * (size_t)n);
     for (int i = 0; i < n; ++i) s[i] = B->v[i].s;
     /* selection by repeated maximum: plain and small */
+    if (g_mutant == 11 && N < n) N = N + 1; /* planted: one place too far down the list */
     double nth = 0.0;
     for (int r = 0; r < N; ++r) {
         int best = -1;
@@ -509,6 +518,144 @@ static double choose_nth_score(const hlist *B, int N) {
 /* Algorithm 1                                                         */
 /* ================================================================== */
 
+/* Scores of one round of the inner loop for the H hypotheses of A over the
+ * S' frames of the segment that starts at frame t0: the joiner on every
+ * (hypothesis, frame) pair, softmax, then Eq. 3-7 in the order of the paper. */
+typedef struct {
+    int H, Sp, V;
+    double *d_old; /* [H][S']     frame distributions the hypotheses came with */
+    double *d;     /* [H][V][S']  Eq. 4-5 */
+    double *dnb;   /* [H][V]      Eq. 6 */
+    double *dphi;  /* [H]         Eq. 7 */
+} round_scores;
+
+static void round_scores_free(round_scores *rs) {
+    free(rs->d_old);
+    free(rs->d);
+    free(rs->dnb);
+    free(rs->dphi);
+}
+
+static round_scores score_round(const orc_model *m, const hlist *A, int t0, int Sp) {
+    const int H = A->n, V = m->vocab, blank = m->blank_id;
+    round_scores rs;
+    rs.H = H;
+    rs.Sp = Sp;
+    rs.V = V;
+    double *logits = (double *)malloc(sizeof(double) * (size_t)H * Sp * V);
+    double *J = (double *)malloc(sizeof(double) * (size_t)H * Sp * V);
+    double *Bl = (double *)malloc(sizeof(double) * (size_t)H * (Sp + 1) * (Sp + 1));
+    rs.d_old = (double *)malloc(sizeof(double) * (size_t)H * Sp);
+    rs.d = (double *)malloc(sizeof(double) * (size_t)H * V * Sp);
+    rs.dnb = (double *)malloc(sizeof(double) * (size_t)H * V);
+    rs.dphi = (double *)malloc(sizeof(double) * (size_t)H);
+
+    /* the joiner sees every frame of the segment with every hypothesis' predictor output
+     * (Algorithm 1, first statement of the inner loop; Section 3.1) */
+    for (int h = 0; h < H; ++h)
+        for (int tau = 0; tau < Sp; ++tau)
+            m->joiner(m->user, t0 + tau, A->v[h].state, logits + ((size_t)h * Sp + tau) * V);
+    orc_softmax(logits, H * Sp, V, J);
+
+    for (int h = 0; h < H; ++h)
+        for (int tau = 0; tau < Sp; ++tau) rs.d_old[(size_t)h * Sp + tau] = A->v[h].d[tau];
+    if (g_mutant == 5) /* planted: forget where the last token was emitted */
+        for (int h = 0; h < H; ++h) {
+            double tot = 0.0;
+            for (int tau = 0; tau < Sp; ++tau) tot += rs.d_old[(size_t)h * Sp + tau];
+            for (int tau = 0; tau < Sp; ++tau) rs.d_old[(size_t)h * Sp + tau] = tau == 0 ? tot : 0.0;
+        }
+    orc_blank_product(J, H, Sp, V, blank, Bl);                         /* Eq. 3 */
+    orc_nonblank_expansion_t(J, Bl, rs.d_old, H, Sp, V, blank, rs.d);  /* Eq. 4-5 */
+    orc_nonblank_expansion(rs.d, H, Sp, V, rs.dnb);                    /* Eq. 6 */
+    orc_blank_expansion(Bl, rs.d_old, H, Sp, rs.dphi);                 /* Eq. 7 */
+    free(logits);
+    free(J);
+    free(Bl);
+    return rs;
+}
+
+/* Every hypothesis of A may stop emitting in this segment: its blank expansion
+ * (Eq. 7) goes into B, merged with an entry of equal tokens if there is one
+ * (Algorithm 1, the loop over AddAndMerge). */
+static void merge_blank_expansions(hlist *B, const hlist *A, const round_scores *rs, int raw, long *order_ctr) {
+    for (int h = 0; h < A->n; ++h) {
+        double sc = raw ? rs->dphi[h] : A->v[h].s + log(rs->dphi[h]);
+        add_and_merge(B, A->v[h].tok, A->v[h].len, sc, A->v[h].state, raw, order_ctr);
+    }
+}
+
+/* The next A: of all (hypothesis, non-blank token) pairs the N with the best
+ * non-blank expansion score (Eq. 6) are looked at, best first, and one becomes
+ * a hypothesis if B is still short of N entries or its score beats the N-th
+ * score of B (Algorithm 1: ChooseNthScore, ChooseNBestExpansions and the test
+ * inside the loop over them).  A new hypothesis takes the tokens of its parent
+ * plus the token, the expansion score, no predictor output yet, and the frame
+ * distribution of that token (Eq. 5).  new_pairs receives (parent, token) of
+ * each; *threshold_out the threshold (NaN when B is short); the return value
+ * is the smallest gap of the decisions taken here. */
+static double select_expansions(const hlist *A, const hlist *B, const round_scores *rs, int N, int blank, int raw,
+                                hlist *An, int *new_pairs, double *threshold_out) {
+    const int H = rs->H, V = rs->V, Sp = rs->Sp;
+    double gap = INFINITY;
+    const int have_thr = B->n >= N;
+    const double threshold = have_thr ? choose_nth_score(B, N) : NAN;
+    *threshold_out = threshold;
+
+    size_t ncand = 0;
+    rank_item *cand = (rank_item *)malloc(sizeof(rank_item) * (size_t)H * V);
+    for (int h = 0; h < H; ++h)
+        for (int k = 0; k < V; ++k) {
+            if (k == blank) continue;
+            double p = rs->dnb[(size_t)h * V + k];
+            if (!(p > 0.0)) continue;
+            cand[ncand].key = raw ? p : A->v[h].s + log(p);
+            cand[ncand].order = (long)h * V + k;
+            cand[ncand].idx = h * V + k;
+            ++ncand;
+        }
+    qsort(cand, ncand, sizeof(rank_item), rank_cmp);
+    int ntop = (int)ncand < N ? (int)ncand : N;
+    if (g_mutant == 10) { /* planted: the N best of every hypothesis instead of the N best of all */
+        size_t w = 0;
+        int *taken = (int *)calloc((size_t)H, sizeof(int));
+        for (size_t i = 0; i < ncand; ++i)
+            if (taken[cand[i].idx / V]++ < N) cand[w++] = cand[i];
+        free(taken);
+        ntop = (int)w;
+    } else if (ntop == N && (!have_thr || cand[N - 1].key > threshold)) {
+        /* the cut after the N-th pair matters only if that pair is kept */
+        double g = cut_gap(cand, (int)ncand, N, raw);
+        if (g < gap) gap = g;
+    }
+
+    hl_clear(An);
+    for (int i = 0; i < ntop; ++i) {
+        int h = cand[i].idx / V, k = cand[i].idx % V;
+        double key = cand[i].key;
+        if (have_thr) {
+            double g = score_gap(key, threshold, raw);
+            if (g < gap) gap = g;
+        }
+        int keep = (B->n < N) || (g_mutant == 9 ? key >= threshold /* planted: not strict */ : key > threshold);
+        if (!keep) continue;
+        hyp *nh = hl_push(An);
+        nh->tok = tok_copy(A->v[h].tok, A->v[h].len, 1);
+        nh->tok[A->v[h].len] = k;
+        nh->len = A->v[h].len + 1;
+        nh->s = key;
+        nh->state = A->v[h].state; /* the parent's, until the predictor has run */
+        nh->d = (double *)malloc(sizeof(double) * (size_t)Sp);
+        double norm = raw ? 1.0 : rs->dnb[(size_t)h * V + k];
+        for (int tau = 0; tau < Sp; ++tau) nh->d[tau] = rs->d[((size_t)h * V + k) * Sp + tau] / norm;
+        nh->order = An->n - 1;
+        new_pairs[2 * (An->n - 1)] = h;
+        new_pairs[2 * (An->n - 1) + 1] = k;
+    }
+    free(cand);
+    return gap;
+}
+
 /*
  * Trace layout (opts.trace = 1).  One record per round of the inner loop.
  *  int stream:    -1, segment, round, S', H, nB, nA_new,
@@ -520,11 +667,13 @@ static double choose_nth_score(const hlist *B, int N) {
  *                 threshold (NaN when B holds fewer than N)
  *                 scores of B after the merges (nB)
  *                 for each new hypothesis: score, then the S' entries of its d
+ *                 gap of the ChooseNBest that opened this segment, smallest gap of this round's decisions
  */
 orc_result *orc_decode(const orc_model *m, int T, const orc_search_opts *o) {
-    const int N = o->beam_n, S = o->seg_s, V = m->vocab, blank = m->blank_id, raw = o->raw_prob;
+    const int N = o->beam_n, S = o->seg_s, blank = m->blank_id, raw = o->raw_prob;
     orc_result *res = (orc_result *)calloc(1, sizeof(*res));
     res->min_gap = INFINITY;
+    res->final_gap = INFINITY;
     res->frames = T;
 
     hlist A, B, An;
@@ -533,7 +682,7 @@ orc_result *orc_decode(const orc_model *m, int T, const orc_search_opts *o) {
     hl_init(&An);
     long order_ctr = 0;
 
-    /* B = [([], 1, InitPredictor(), Null)] */
+    /* B starts as the empty hypothesis with score one and the initial predictor output */
     {
         hyp *h = hl_push(&B);
         h->tok = tok_copy(NULL, 0, 0);
@@ -545,11 +694,13 @@ orc_result *orc_decode(const orc_model *m, int T, const orc_search_opts *o) {
 
     int t = 0, seg_index = 0;
     while (t < T) {
-        const int Sp = (T - t) < S ? (T - t) : S; /* seg = enc[t : t+S] */
+        /* head of the outer loop: the next S frames (fewer at the end), A = the N best of B,
+         * B emptied, every d set to (score, 0, ..., 0) */
+        const int Sp = (T - t) < S ? (T - t) : S;
         hl_clear(&A);
-        choose_n_best(&B, N, &A, res, raw); /* A = ChooseNBest(B); B = [] */
+        const double head_gap = choose_n_best(&B, N, &A, res, raw);
         order_ctr = 0;
-        for (int h = 0; h < A.n; ++h) {     /* A_h.d = (A_h.s, 0, ..., 0) */
+        for (int h = 0; h < A.n; ++h) {
             free(A.v[h].d);
             A.v[h].d = (double *)calloc((size_t)Sp, sizeof(double));
             A.v[h].d[0] = raw ? A.v[h].s : 1.0;
@@ -558,35 +709,9 @@ orc_result *orc_decode(const orc_model *m, int T, const orc_search_opts *o) {
         while (A.n > 0) {
             ++round;
             const int H = A.n;
-            double *logits = (double *)malloc(sizeof(double) * (size_t)H * Sp * V);
-            double *J = (double *)malloc(sizeof(double) * (size_t)H * Sp * V);
-            double *Bl = (double *)malloc(sizeof(double) * (size_t)H * (Sp + 1) * (Sp + 1));
-            double *d_old = (double *)malloc(sizeof(double) * (size_t)H * Sp);
-            double *d = (double *)malloc(sizeof(double) * (size_t)H * V * Sp);
-            double *dnb = (double *)malloc(sizeof(double) * (size_t)H * V);
-            double *dphi = (double *)malloc(sizeof(double) * (size_t)H);
-
-            /* J = Softmax(Joiner(seg, pred)) */
-            for (int h = 0; h < H; ++h)
-                for (int tau = 0; tau < Sp; ++tau)
-                    m->joiner(m->user, t + tau, A.v[h].state, logits + ((size_t)h * Sp + tau) * V);
+            round_scores rs = score_round(m, &A, t, Sp);
             res->joiner_calls += 1;
             res->joined_frames += Sp;
-            orc_softmax(logits, H * Sp, V, J);
-
-            /* Eq. 3-7 */
-            for (int h = 0; h < H; ++h)
-                for (int tau = 0; tau < Sp; ++tau) d_old[(size_t)h * Sp + tau] = A.v[h].d[tau];
-            if (g_mutant == 5) /* planted: forget where the last token was emitted */
-                for (int h = 0; h < H; ++h) {
-                    double tot = 0.0;
-                    for (int tau = 0; tau < Sp; ++tau) tot += d_old[(size_t)h * Sp + tau];
-                    for (int tau = 0; tau < Sp; ++tau) d_old[(size_t)h * Sp + tau] = tau == 0 ? tot : 0.0;
-                }
-            orc_blank_product(J, H, Sp, V, blank, Bl);
-            orc_nonblank_expansion_t(J, Bl, d_old, H, Sp, V, blank, d);
-            orc_nonblank_expansion(d, H, Sp, V, dnb);
-            orc_blank_expansion(Bl, d_old, H, Sp, dphi);
 
             if (o->trace) {
                 tr_i(res, -1); tr_i(res, seg_index); tr_i(res, round); tr_i(res, Sp); tr_i(res, H);
@@ -597,64 +722,16 @@ orc_result *orc_decode(const orc_model *m, int T, const orc_search_opts *o) {
                 for (int h = 0; h < H; ++h) tr_tokens(res, &A.v[h]);
                 for (int h = 0; h < H; ++h) {
                     tr_d(res, A.v[h].s);
-                    tr_d(res, dphi[h]);
-                    for (int tau = 0; tau < Sp; ++tau) tr_d(res, d_old[(size_t)h * Sp + tau]);
+                    tr_d(res, rs.dphi[h]);
+                    for (int tau = 0; tau < Sp; ++tau) tr_d(res, rs.d_old[(size_t)h * Sp + tau]);
                 }
             }
-            int *new_pairs = (int *)malloc(sizeof(int) * (size_t)(2 * N + 2));
 
-            /* Add all blank expansions to B and merge if needed */
-            for (int h = 0; h < H; ++h) {
-                double sc = raw ? dphi[h] : A.v[h].s + log(dphi[h]);
-                add_and_merge(&B, A.v[h].tok, A.v[h].len, sc, A.v[h].state, raw, &order_ctr);
-            }
-
-            /* threshold = ChooseNthScore(B, N) */
-            int have_thr = B.n >= N;
-            double threshold = have_thr ? choose_nth_score(&B, N) : NAN;
-
-            /* ChooseNBestExpansions: joint top-N over (h, k != blank) */
-            size_t ncand = 0;
-            rank_item *cand = (rank_item *)malloc(sizeof(rank_item) * (size_t)H * V);
-            for (int h = 0; h < H; ++h)
-                for (int k = 0; k < V; ++k) {
-                    if (k == blank) continue;
-                    double p = dnb[(size_t)h * V + k];
-                    if (!(p > 0.0)) continue;
-                    cand[ncand].key = raw ? p : A.v[h].s + log(p);
-                    cand[ncand].order = (long)h * V + k;
-                    cand[ncand].idx = h * V + k;
-                    ++ncand;
-                }
-            qsort(cand, ncand, sizeof(rank_item), rank_cmp);
-            note_gaps(res, cand, (int)ncand, N, raw);
-
-            hl_clear(&An);
-            int ntop = (int)ncand < N ? (int)ncand : N;
-            for (int i = 0; i < ntop; ++i) {
-                int h = cand[i].idx / V, k = cand[i].idx % V;
-                double key = cand[i].key;
-                if (have_thr) {
-                    double g = score_gap(key, threshold, raw);
-                    if (g < res->min_gap) res->min_gap = g;
-                }
-                int keep = (B.n < N) || (key > threshold);
-                if (!keep) continue;
-                /* new_hypo = (A'_h.tok + k, delta_nb_h(k), Null, d_h(k)) */
-                hyp *nh = hl_push(&An);
-                nh->tok = tok_copy(A.v[h].tok, A.v[h].len, 1);
-                nh->tok[A.v[h].len] = k;
-                nh->len = A.v[h].len + 1;
-                nh->s = key;
-                nh->state = A.v[h].state; /* parent state until the predictor runs */
-                nh->d = (double *)malloc(sizeof(double) * (size_t)Sp);
-                double norm = raw ? 1.0 : dnb[(size_t)h * V + k];
-                for (int tau = 0; tau < Sp; ++tau)
-                    nh->d[tau] = d[((size_t)h * V + k) * Sp + tau] / norm;
-                nh->order = An.n - 1;
-                new_pairs[2 * (An.n - 1)] = h;
-                new_pairs[2 * (An.n - 1) + 1] = k;
-            }
+            merge_blank_expansions(&B, &A, &rs, raw, &order_ctr);
+            int *new_pairs = (int *)malloc(sizeof(int) * (size_t)(2 * (size_t)H * N + 2));
+            double threshold;
+            const double round_gap = select_expansions(&A, &B, &rs, N, blank, raw, &An, new_pairs, &threshold);
+            note_gap(res, round_gap);
 
             if (o->trace) {
                 res->it[trace_counts_at] = B.n;
@@ -667,21 +744,21 @@ orc_result *orc_decode(const orc_model *m, int T, const orc_search_opts *o) {
                     tr_d(res, An.v[i].s);
                     for (int tau = 0; tau < Sp; ++tau) tr_d(res, An.v[i].d[tau]);
                 }
+                tr_d(res, head_gap);
+                tr_d(res, round_gap);
             }
             free(new_pairs);
+            round_scores_free(&rs);
 
-            /* UpdatePredictorOutput(A) */
+            /* the predictor runs once for every new hypothesis (UpdatePredictorOutput) */
             for (int i = 0; i < An.n; ++i)
                 An.v[i].state = m->update_state(m->user, An.v[i].state, An.v[i].tok[An.v[i].len - 1]);
 
-            /* A = new list */
+            /* the new hypotheses are the A of the next round */
             hl_clear(&A);
             hlist tmp = A;
             A = An;
             An = tmp;
-
-            free(cand);
-            free(logits); free(J); free(Bl); free(d_old); free(d); free(dnb); free(dphi);
 
             if (o->max_rounds > 0 && round >= o->max_rounds) hl_clear(&A);
         }
@@ -689,10 +766,10 @@ orc_result *orc_decode(const orc_model *m, int T, const orc_search_opts *o) {
         ++seg_index;
     }
 
-    /* return ChooseNBest(B) */
+    /* the result is the N best of B */
     hlist out;
     hl_init(&out);
-    choose_n_best(&B, N, &out, res, raw);
+    res->final_gap = choose_n_best(&B, N, &out, res, raw);
     res->n = out.n;
     res->lens = (int *)malloc(sizeof(int) * (size_t)(out.n + 1));
     res->tok = (int **)malloc(sizeof(int *) * (size_t)(out.n + 1));
@@ -733,6 +810,7 @@ void orc_result_counters(const orc_result *r, long *joiner_calls, long *joined_f
 }
 
 double orc_result_min_gap(const orc_result *r) { return r->min_gap; }
+double orc_result_final_gap(const orc_result *r) { return r->final_gap; }
 
 long orc_result_trace(const orc_result *r, const int **itrace, long *n_i, const double **dtrace, long *n_d) {
     *itrace = r->it;

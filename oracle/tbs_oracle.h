@@ -135,8 +135,14 @@ const int *orc_result_tokens(const orc_result *r, int i);
 double orc_result_logscore(const orc_result *r, int i);
 /* counters: joiner calls, frames joined (summed over calls: rows / hypotheses), frames decoded */
 void orc_result_counters(const orc_result *r, long *joiner_calls, long *joined_frames, long *frames);
-/* smallest |log a - log b| seen between neighbours at any ranking or threshold decision */
+/* Smallest |log a - log b| over the decisions of the run that rounding could turn: the N-th
+ * against the (N+1)-th entry wherever a ranking keeps N (ChooseNBest at the head of a segment
+ * and at the end, ChooseNBestExpansions when its N-th pair is kept), and every expansion score
+ * against the threshold it is tested with.  A run whose smallest gap exceeds the tolerance of a
+ * comparison has one correct output; the trace holds the gap of every segment head and round. */
 double orc_result_min_gap(const orc_result *r);
+/* the same for the last ChooseNBest(B) alone (infinite if B held at most N entries) */
+double orc_result_final_gap(const orc_result *r);
 /* trace: flat int and double streams, layout documented in tbs_oracle.c */
 long orc_result_trace(const orc_result *r, const int **itrace, long *n_i, const double **dtrace, long *n_d);
 

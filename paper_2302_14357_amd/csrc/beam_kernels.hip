@@ -598,13 +598,23 @@ hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int dro
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes) {
     const size_t shm = (size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int));
+    // the longest B list the library accepts (2048 entries) needs 56 KB of dynamic LDS on top of
+    // the kernel's static arrays: more than the default limit, so the limit is raised once
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_select_merge),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 2048 * (int)(sizeof(double) + sizeof(u64) + 3 * sizeof(int)));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     hipLaunchKernelGGL(k_select_merge, dim3(d.U), dim3(WAVE), shm, st, d, round, drop, logits, row_lc, dphi,
                        cand_score, cand_tok, A, An, B, rv, nodes);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ results
-__device__ void write_tokens(const int2 *nodes, int node, int len, int max_len, int *out, int *ovf) {
+__device__ void write_tokens(const int2 *nodes, int node, int len, int max_len, int *out) {
     // walk from the last token to the first
     int pos = len - 1;
     while (node > 0 && pos >= 0) {
@@ -613,15 +623,21 @@ __device__ void write_tokens(const int2 *nodes, int node, int len, int max_len, 
         node = nd.x;
         --pos;
     }
-    if (len > max_len) atomicOr(ovf, 1);
 }
 
 // return ChooseNBest(B)   (Algorithm 1, last line)
-__global__ void k_finalize(Dims d, BView B, const int2 *nodes, int *res_count, int *res_len, double *res_logs,
-                           int *res_tok, int max_len, int *ovf) {
-    int u = blockIdx.x, lane = threadIdx.x;
-    int nB = B.count[u];
+// One wave per utterance writes every output entry of that utterance exactly once: ranks that
+// exist get their score, length and tokens, everything else (ranks beyond the list, positions
+// beyond a sequence) the neutral value, so the caller's buffers need no clearing beforehand.
+__global__ void __launch_bounds__(WAVE)
+k_finalize(Dims d, BView B, const int2 *nodes, int *res_count, int *res_len, double *res_logs,
+           int *res_tok, int max_len) {
+    __shared__ int s_len[TBS_MAX_BEAM];
+    const int u = blockIdx.x, lane = threadIdx.x;
+    const int nB = B.count[u];
     const double *bl = B.logs + (long)u * d.BCAP;
+    if (lane < d.N) s_len[lane] = 0;
+    __syncthreads();
     for (int i = lane; i < nB; i += WAVE) {
         double si = bl[i];
         int rank = 0;
@@ -634,16 +650,27 @@ __global__ void k_finalize(Dims d, BView B, const int2 *nodes, int *res_count, i
             int len = B.len[(long)u * d.BCAP + i];
             res_logs[o] = si;
             res_len[o] = len;
-            write_tokens(nodes, B.node[(long)u * d.BCAP + i], len, max_len, res_tok + o * max_len, ovf);
+            s_len[rank] = len;
+            write_tokens(nodes, B.node[(long)u * d.BCAP + i], len, max_len, res_tok + o * max_len);
         }
     }
-    if (lane == 0) res_count[u] = nB < d.N ? nB : d.N;
+    __syncthreads();
+    const int cnt = nB < d.N ? nB : d.N;
+    if (lane < d.N && lane >= cnt) {
+        res_logs[(long)u * d.N + lane] = 0.0;
+        res_len[(long)u * d.N + lane] = 0;
+    }
+    for (int idx = lane; idx < d.N * max_len; idx += WAVE) {
+        const int r = idx / max_len, p = idx - r * max_len;
+        if (p >= s_len[r]) res_tok[((long)u * d.N + r) * max_len + p] = -1;
+    }
+    if (lane == 0) res_count[u] = cnt;
 }
 
 hipError_t launch_finalize(hipStream_t st, const Dims &d, BView B, const int2 *nodes, int *res_count, int *res_len,
-                           double *res_logs, int *res_tok, int max_len, int *ovf) {
+                           double *res_logs, int *res_tok, int max_len) {
     hipLaunchKernelGGL(k_finalize, dim3(d.U), dim3(WAVE), 0, st, d, B, nodes, res_count, res_len, res_logs, res_tok,
-                       max_len, ovf);
+                       max_len);
     return hipGetLastError();
 }
 
@@ -653,14 +680,13 @@ __global__ void k_hyps_dump(Dims d, int group, AView A, BView B, const int2 *nod
     int n = group == 0 ? A.count[u] : B.count[u];
     int stride = group == 0 ? d.N : d.BCAP;
     if (n > cap) n = cap;
-    int dummy = 0;
     for (int i = lane; i < n; i += WAVE) {
         long s = (long)u * stride + i, o = (long)u * cap + i;
         int ln = group == 0 ? A.len[s] : B.len[s];
         int nd = group == 0 ? A.node[s] : B.node[s];
         logs[o] = group == 0 ? A.logs[s] : B.logs[s];
         len[o] = ln;
-        write_tokens(nodes, nd, ln, max_len, tok + o * max_len, &dummy);
+        write_tokens(nodes, nd, ln, max_len, tok + o * max_len);
     }
     if (lane == 0) count[u] = n;
 }

@@ -4,6 +4,7 @@
 // the other files; this file only sizes buffers, orders launches and moves
 // counts and results between device and host.
 #include <algorithm>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -78,7 +79,7 @@ struct tbs_ctx {
     float *gates;
 
     // results
-    int *res_count, *res_len, *res_tok, *res_ovf;
+    int *res_count, *res_len, *res_tok;
     double *res_logs;
     int res_max_len;
 
@@ -153,8 +154,14 @@ struct ProfScope {
 // Wait for the counts of the scan numbered c->seq without draining the stream: the kernel that
 // runs the scan writes them into pinned host memory and its number last, so the host can size
 // and enqueue the next launches while the kernels behind that scan are still running.
+// The wait is bounded on the host: a stream that ends without the number, a stream error, or
+// TBS_WAIT_LIMIT_S seconds without it (no kernel of this library runs anywhere near that long)
+// all come back as an error code instead of a call that never returns.
+#define TBS_WAIT_LIMIT_S 20
 hipError_t wait_counts(tbs_ctx *c) {
     const int want = c->seq;
+    std::chrono::steady_clock::time_point t0;
+    bool timing = false;
     for (unsigned spin = 1;; ++spin) {
         if (__atomic_load_n(&c->h_counts[TBS_CNT_SEQ], __ATOMIC_ACQUIRE) == want) return hipSuccess;
         if ((spin & 0x3FFFFF) == 0) {   // every few milliseconds (a query costs microseconds, during which the
@@ -164,6 +171,13 @@ hipError_t wait_counts(tbs_ctx *c) {
                 return __atomic_load_n(&c->h_counts[TBS_CNT_SEQ], __ATOMIC_ACQUIRE) == want ? hipSuccess
                                                                                               : hipErrorUnknown;
             if (e != hipErrorNotReady) return e;
+            const auto now = std::chrono::steady_clock::now();
+            if (!timing) {
+                t0 = now;
+                timing = true;
+            } else if (now - t0 > std::chrono::seconds(TBS_WAIT_LIMIT_S)) {
+                return hipErrorLaunchTimeOut;
+            }
         }
     }
 }
@@ -227,6 +241,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         return TBS_EINVAL;
     if (cfg->act < 0 || cfg->act > 1 || cfg->dtype < 0 || cfg->dtype > 1) return TBS_EINVAL;
     if (cfg->max_rounds_per_segment < 0 || cfg->rounds_capacity < 0 || cfg->max_nodes < 0) return TBS_EINVAL;
+    if (cfg->max_result_len < 0) return TBS_EINVAL;
     if (cfg->stream_buffer_frames < 0 || (cfg->stream_buffer_frames != 0 && cfg->stream_buffer_frames < cfg->seg_s))
         return TBS_EINVAL;
     if (cfg->vocab > 16000) return TBS_EINVAL;  // the expansion kernel keeps one row of scores in LDS
@@ -368,7 +383,8 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->res_count, U);
     rc |= dev_alloc(c, &c->res_len, UN);
     rc |= dev_alloc(c, &c->res_logs, UN);
-    rc |= dev_alloc(c, &c->res_ovf, 1);
+    c->res_max_len = cfg->max_result_len > 0 ? cfg->max_result_len : 256;
+    rc |= dev_alloc(c, &c->res_tok, (size_t)UN * c->res_max_len);
     if (rc) {
         tbs_free(c);
         return TBS_ENOMEM;
@@ -748,26 +764,18 @@ int tbs_result(tbs_ctx *c, int32_t *tokens, int32_t *lens, double *logscores, in
     if (c->state == ST_INIT) return TBS_ESTATE;
     const Dims &d = c->cur;
     const long UN = (long)d.U * d.N;
-    if (max_len > c->res_max_len) {  // grown on demand; the decode loop itself never allocates
-        int *p = nullptr;
-        if (dev_alloc(c, &p, (size_t)c->d.U * d.N * max_len) != TBS_OK) return TBS_ENOMEM;
-        c->res_tok = p;
-        c->res_max_len = max_len;
-    }
-    HIPCHK(c, hipMemsetAsync(c->res_ovf, 0, sizeof(int), c->stream));
-    HIPCHK(c, hipMemsetAsync(c->res_tok, 0xFF, sizeof(int) * UN * max_len, c->stream));
-    HIPCHK(c, hipMemsetAsync(c->res_len, 0, sizeof(int) * UN, c->stream));
-    HIPCHK(c, hipMemsetAsync(c->res_logs, 0, sizeof(double) * UN, c->stream));
+    if (max_len > c->res_max_len) return TBS_EINVAL;   // the result buffer was sized at tbs_init (max_result_len)
+    // (the kernel writes every entry of the four outputs: nothing is cleared beforehand)
     HIPCHK(c, launch_finalize(c->stream, d, c->B, c->nodes, c->res_count, c->res_len, c->res_logs, c->res_tok,
-                              max_len, c->res_ovf));
-    int ovf = 0;
+                              max_len));
     HIPCHK(c, hipMemcpyAsync(tokens, c->res_tok, sizeof(int) * UN * max_len, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(lens, c->res_len, sizeof(int) * UN, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(logscores, c->res_logs, sizeof(double) * UN, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(nbest_count, c->res_count, sizeof(int) * d.U, hipMemcpyDeviceToHost, c->stream));
-    HIPCHK(c, hipMemcpyAsync(&ovf, c->res_ovf, sizeof(int), hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    return ovf ? TBS_EOVERFLOW : TBS_OK;
+    for (long i = 0; i < UN; ++i)
+        if (lens[i] > max_len) return TBS_EOVERFLOW;   // truncated to max_len tokens; lens keeps the true length
+    return TBS_OK;
 }
 
 // Small batches: the head of a segment and its whole first round enqueued in one go, with one

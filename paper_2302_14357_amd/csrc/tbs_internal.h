@@ -144,7 +144,7 @@ hipError_t launch_lstm_pointwise(hipStream_t st, const Dims &d, int dtype, int p
                                  const float *gates, float *pool_h, float *pool_c, long pool_rows, void *xh_next,
                                  void *htop, const float *emb_gates);
 hipError_t launch_finalize(hipStream_t st, const Dims &d, BView B, const int2 *nodes, int *res_count, int *res_len,
-                           double *res_logs, int *res_tok, int max_len, int *ovf);
+                           double *res_logs, int *res_tok, int max_len);
 hipError_t launch_hyps_dump(hipStream_t st, const Dims &d, int group, AView A, BView B, const int2 *nodes, int cap,
                             int max_len, int *tok, int *len, double *logs, int *count);
 hipError_t launch_gather_pred(hipStream_t st, const Dims &d, AView A, const float *pool_p, float *out, int scatter);

@@ -59,7 +59,7 @@ def make_model(shape: TbsShape, seed: int = SEED_WEIGHTS) -> dict:
     m = {}
     m["w_enc"] = _xavier(rng, Dj, shape.d_enc)
     m["b_enc"] = _small(rng, Dj)
-    m["w_out"] = _xavier(rng, V, Dj)
+    m["w_out"] = _xavier(rng, V, Dj) * np.float32(shape.logit_scale)
     b_out = _small(rng, V)
     b_out[shape.blank_id] += np.float32(shape.blank_bias)
     m["b_out"] = b_out

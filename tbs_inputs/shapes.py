@@ -21,6 +21,8 @@ class TbsShape:
     dtype: str            # "f32" or "bf16": storage type of weights and projected frames
     act: str = "tanh"     # joiner activation: "tanh" or "relu"
     blank_bias: float = 3.0
+    logit_scale: float = 1.0   # multiplies the Xavier draw of the joiner output matrix: > 1 gives peaked output
+                               # distributions (as a trained model has), so that hypotheses grow to many tokens
 
     def with_utts(self, n_utts: int) -> "TbsShape":
         return replace(self, n_utts=n_utts)

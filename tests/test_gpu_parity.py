@@ -18,7 +18,8 @@ import pytest
 
 import oracle
 from tbs_inputs import SHAPES, TbsShape, make_model, make_utterances
-from helpers import build_case, oracle_weights, make_tbs, compare_nbest, small_bf16_shape
+from helpers import (build_case, oracle_weights, make_tbs, compare_nbest, small_bf16_shape, tolerance,
+                     strict_prefixes, assert_all_agree, nbest_agrees)
 
 pytestmark = pytest.mark.gpu
 
@@ -194,6 +195,7 @@ def test_joiner_expand_throughput_shape_sampled():
 
 def _oracle_decode(shape, model, offsets, enc, N, S, threads=16, **kw):
     W = oracle_weights(shape, model)
+    kw.setdefault("trace", True)   # the per-round decision gaps decide how strictly results are compared
     res, _ = oracle.decode_lstm_batch(W, enc, offsets, N, S, threads=min(threads, oracle.max_threads()), **kw)
     return res
 
@@ -206,15 +208,55 @@ def _gpu_decode(shape, model, offsets, enc, N, S, **kw):
     return out, st
 
 
+def _check_decode(shape, model, offsets, enc, N, S, max_rounds=0, report=None, **kw):
+    """tbs_decode against the oracle under the gap rule, in two steps.  (1) The whole batch:
+    utterances all of whose decisions were clear must agree.  (2) Every utterance cut back to the
+    whole segments before its first close decision, decoded again by both sides: now every
+    decision is clear, so every utterance must agree and the joiner-call counters must be equal.
+    Returns a dict of what was seen (for assertions on coverage, e.g. hypothesis lengths)."""
+    tol, score_tol = tolerance(shape, model)
+    okw = dict(max_rounds=max_rounds) if max_rounds else {}
+    gkw = dict(kw)
+    if max_rounds:
+        gkw["max_rounds_per_segment"] = max_rounds
+    ref = _oracle_decode(shape, model, offsets, enc, N, S, **okw)
+    U = len(offsets) - 1
+    tbs = make_tbs(shape, model, offsets, N, S, **gkw)
+    got = tbs.decode(tbs.upload_frames(enc), offsets)
+    st = tbs.stats()
+    same, amb, tot = compare_nbest(got, ref, score_tol=score_tol, gap_tol=tol)
+    clear = [u for u in range(U) if ref[u].first_ambiguous_segment(tol) is None]
+    info = {"same": same, "amb": amb, "tot": tot, "clear": len(clear),
+            "max_len_checked": max([len(y) for u in clear for y, _ in ref[u].nbest], default=0)}
+    if len(clear) == U:
+        assert same == tot
+        assert st["joiner_calls"] == sum(r.joiner_calls for r in ref)
+        assert st["joined_frames"] == sum(r.joined_frames for r in ref)
+    else:
+        off2, enc2, keep = strict_prefixes(ref, offsets, enc, S, tol)
+        ref2 = _oracle_decode(shape, model, off2, enc2, N, S, **okw)
+        got2 = tbs.decode(tbs.upload_frames(enc2), off2)
+        st2 = tbs.stats()
+        assert_all_agree(got2, ref2, score_tol, tol)
+        assert st2["joiner_calls"] == sum(r.joiner_calls for r in ref2)
+        assert st2["joined_frames"] == sum(r.joined_frames for r in ref2)
+        info["prefix_frames"] = int(keep.sum())
+        info["max_len_checked"] = max(info["max_len_checked"],
+                                      max([len(y) for r in ref2 for y, _ in r.nbest], default=0))
+    tbs.close()
+    if report:
+        print(f"{report}: identical {same}/{tot}, differing after a close decision {amb}, "
+              f"utterances with every decision clear {len(clear)}, "
+              f"frames checked strictly {info.get('prefix_frames', int(offsets[-1]))}/{int(offsets[-1])}, "
+              f"longest hypothesis checked {info['max_len_checked']}")
+    return info
+
+
 def test_decode_tiny_reference_config():
     shape = SHAPES["tiny"]
     model, offsets, enc = build_case(shape)
-    ref = _oracle_decode(shape, model, offsets, enc, 2, 3)
-    got, st = _gpu_decode(shape, model, offsets, enc, 2, 3)
-    same, amb, tot = compare_nbest(got, ref, score_tol=1e-3)
-    assert same == tot
-    assert st["joiner_calls"] == ref[0].joiner_calls and st["joined_frames"] == ref[0].joined_frames
-    assert st["frames"] == 50
+    info = _check_decode(shape, model, offsets, enc, 2, 3, report="tiny")
+    assert info["tot"] == 1
 
 
 @pytest.mark.parametrize("N,S", [(1, 1), (2, 2), (5, 3), (3, 7), (4, 30)])
@@ -224,12 +266,106 @@ def test_decode_small_bf16_and_edges(N, S):
     shape = small_bf16_shape(n_utts=6, vocab=64, d=64, hidden=64, layers=2)
     lengths = np.array([0, 1, 2, 7, 12, 23])
     model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, N, S)
-    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    got, _ = _gpu_decode(shape, model, offsets, enc, N, S)
     assert got[0] == [((), 0.0)]
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 1
-    assert st["joiner_calls"] == sum(r.joiner_calls for r in ref) or amb > 0
+    _check_decode(shape, model, offsets, enc, N, S)
+
+
+# ------------------------------------------------------------------ peaked models: long hypotheses
+
+def _peaked(shape, scale, blank_bias):
+    """A model with peaked output distributions (the output matrix scaled up, the blank bias with it):
+    hypotheses then grow to many tokens, which the benchmark models' flat distributions never
+    produce.  Such a model keeps emitting within a frame, so these runs cap the rounds of a
+    segment on both sides (Section 3.2 mentions such a cap)."""
+    import dataclasses
+    return dataclasses.replace(shape, logit_scale=scale, blank_bias=blank_bias)
+
+
+@pytest.mark.parametrize("dtype,N,S,cap,bb,min_len", [("f32", 5, 3, 8, 8.0, 5), ("bf16", 5, 3, 8, 8.0, 4),
+                                                     ("bf16", 4, 2, 6, 12.0, 5), ("f32", 8, 5, 8, 12.0, 5),
+                                                     ("bf16", 3, 1, 5, 10.0, 4)])
+def test_decode_peaked_model_long_hypotheses(dtype, N, S, cap, bb, min_len):
+    """Whole decodes whose N-best lists hold sequences of five and more tokens: deep walks of the
+    token trie in AddAndMerge, hash-and-walk matches between long sequences, token read-out.
+    (The list kernels are the same for both storage types; the fp32 models, whose tolerance is
+    ten times tighter, are the ones that stay comparable over whole utterances; bf16 models meet a
+    close decision sooner and are compared strictly on shorter prefixes.)"""
+    import dataclasses
+    shape = _peaked(dataclasses.replace(small_bf16_shape(n_utts=8, vocab=96, d=64, hidden=64), dtype=dtype), 8.0, bb)
+    lengths = np.array([23, 17, 30, 9, 41, 26, 12, 35])
+    model, offsets, enc = build_case(shape, n_utts=8, lengths=lengths)
+    info = _check_decode(shape, model, offsets, enc, N, S, max_rounds=cap, report=f"peaked {dtype} N={N} S={S}")
+    assert info["max_len_checked"] >= min_len, info
+
+
+def test_decode_peaked_model_librispeech_widths():
+    """The same at the headline widths (Dj=512, V=1024, LSTM 640, N=5, S=3)."""
+    import dataclasses
+    shape = _peaked(dataclasses.replace(SHAPES["librispeech"], n_utts=6), 16.0, 20.0)
+    lengths = np.array([60, 90, 45, 33, 75, 52])
+    model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
+    info = _check_decode(shape, model, offsets, enc, 5, 3, max_rounds=4, report="peaked, Librispeech widths")
+    assert info["max_len_checked"] >= 5, info
+
+
+def test_decode_truncation_and_capacity_codes():
+    """Results longer than max_len come back truncated to their first max_len tokens, with their
+    true lengths, and the call says TBS_EOVERFLOW; a list B or a token trie too small for the run
+    is reported as the same code, not as a crash or a wrong result."""
+    from paper_2302_14357_amd import TbsError
+    shape = _peaked(small_bf16_shape(n_utts=3, vocab=96, d=64, hidden=64), 8.0, 8.0)
+    lengths = np.array([23, 17, 30])
+    model, offsets, enc = build_case(shape, n_utts=3, lengths=lengths)
+    N, S, cap = 5, 3, 8
+    tol, score_tol = tolerance(shape, model)
+    ref = _oracle_decode(shape, model, offsets, enc, N, S, max_rounds=cap)
+    longest = max(len(y) for r in ref for y, _ in r.nbest)
+    assert longest >= 5
+    tbs = make_tbs(shape, model, offsets, N, S, max_rounds_per_segment=cap)
+    enc_dev = tbs.upload_frames(enc)
+    full = tbs.decode(enc_dev, offsets)
+    cut = 3
+    tok = np.full((3, N, cut), -7, np.int32)
+    lens = np.zeros((3, N), np.int32)
+    logs = np.zeros((3, N), np.float64)
+    cnt = np.zeros(3, np.int32)
+    rc = tbs.decode_raw(enc_dev, offsets, tok, lens, logs, cnt, cut)
+    assert rc == -5
+    for u in range(3):
+        assert cnt[u] == len(full[u])
+        for i, (y, sc) in enumerate(full[u]):
+            assert lens[u, i] == len(y) and logs[u, i] == sc
+            assert tok[u, i, :min(cut, len(y))].tolist() == list(y[:cut])
+            assert (tok[u, i, len(y):] == -1).all()
+    with pytest.raises(TbsError) as e:
+        tbs.result(max_len=257)          # beyond the configuration's max_result_len (256)
+    assert e.value.code == -1
+    tbs.close()
+    # a trie with room for a handful of sequences only
+    tbs = make_tbs(shape, model, offsets, N, S, max_rounds_per_segment=cap, max_nodes=40)
+    with pytest.raises(TbsError) as e:
+        tbs.decode(tbs.upload_frames(enc), offsets)
+    assert e.value.code == -5
+    tbs.close()
+    # a list B smaller than a segment's blank expansions: the rounds of a segment are not capped,
+    # the workspaces are sized for two
+    tbs = make_tbs(shape, model, offsets, N, S, rounds_capacity=2)
+    with pytest.raises(TbsError) as e:
+        tbs.decode(tbs.upload_frames(enc), offsets)
+    assert e.value.code == -5
+    tbs.close()
+
+
+def test_longest_list_b():
+    """N * rounds capacity = 2048 entries of B per utterance, the most the library accepts."""
+    shape = small_bf16_shape(n_utts=2, vocab=48, d=64, hidden=64)
+    model, offsets, enc = build_case(shape, n_utts=2, lengths=np.array([9, 14]))
+    _check_decode(shape, model, offsets, enc, 4, 3, rounds_capacity=512)
+    from paper_2302_14357_amd import TbsError
+    with pytest.raises(TbsError) as e:
+        make_tbs(shape, model, offsets, 4, 3, rounds_capacity=513)
+    assert e.value.code == -1
 
 
 @pytest.mark.parametrize("debug", [0, 8, 32, 64, 8 + 16 + 32])
@@ -242,10 +378,7 @@ def test_decode_cell_update_inside_and_outside_the_gate_gemm(debug):
     shape = small_bf16_shape(n_utts=5, vocab=96, d=128, hidden=128, layers=2)
     lengths = np.array([4, 9, 15, 22, 31])
     model, offsets, enc = build_case(shape, n_utts=5, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, 4, 3)
-    got, st = _gpu_decode(shape, model, offsets, enc, 4, 3, debug=debug)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 1
+    _check_decode(shape, model, offsets, enc, 4, 3, debug=debug)
 
 
 @pytest.mark.parametrize("d,hidden,N,S", [(128, 128, 4, 3), (144, 128, 5, 7), (80, 256, 8, 2)])
@@ -258,15 +391,14 @@ def test_decode_joiner_rows_from_the_projection_epilogue(d, hidden, N, S):
     shape = small_bf16_shape(n_utts=14, vocab=96, d=d, hidden=hidden, layers=1)
     lengths = np.array([0, 1, 3, 5, 8, 9, 11, 14, 15, 17, 20, 23, 26, 29])
     model, offsets, enc = build_case(shape, n_utts=14, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, N, S)
     got, st = _gpu_decode(shape, model, offsets, enc, N, S)
     own, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=16)
     for a, b in zip(got, own):
         assert [h[0] for h in a] == [h[0] for h in b]
         np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-6, atol=1e-6)
     assert st["joiner_calls"] == st2["joiner_calls"]
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 2
+    _check_decode(shape, model, offsets, enc, N, S)
+    _check_decode(shape, model, offsets, enc, N, S, debug=16)
 
 
 @pytest.mark.parametrize("base,N,S", [("tiny", 2, 3), ("small64", 4, 3), ("small128", 5, 4)])
@@ -282,10 +414,7 @@ def test_decode_relu_joiner(base, N, S):
         shape = dataclasses.replace(small_bf16_shape(n_utts=6, vocab=80, d=w, hidden=w), act="relu")
         kw = dict(n_utts=6, lengths=np.array([2, 5, 9, 14, 20, 27]))
     model, offsets, enc = build_case(shape, **kw)
-    ref = _oracle_decode(shape, model, offsets, enc, N, S)
-    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
-    same, amb, tot = compare_nbest(got, ref, score_tol=1e-3)
-    assert same + amb == tot and same >= tot - 1
+    _check_decode(shape, model, offsets, enc, N, S)
 
 
 # ------------------------------------------------------------------ streaming
@@ -315,7 +444,9 @@ def test_streaming_in_pieces_equals_decode(N, S, pieces):
     """Encoder frames arriving in pieces (frame by frame, in decoder-sized segments, in random
     sizes different per utterance, or some utterances much faster than others) and a flush at
     the end give what tbs_decode gives on the whole utterances (Section 3.2: the encoder's
-    segment size need not be the decoder's), and that agrees with the oracle."""
+    segment size need not be the decoder's): the segments of an utterance are the same either
+    way, so the results are required to be identical; tbs_decode itself is checked against the
+    oracle."""
     shape = small_bf16_shape(n_utts=7, vocab=64, d=128, hidden=128, layers=1)
     lengths = np.array([0, 1, 4, 9, 13, 22, 30])
     model, offsets, enc = build_case(shape, n_utts=7, lengths=lengths)
@@ -333,14 +464,12 @@ def test_streaming_in_pieces_equals_decode(N, S, pieces):
         assert [h[0] for h in a] == [h[0] for h in b]
         np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-5, atol=1e-5)
     assert st["frames"] == int(lengths.sum()) and st["joined_frames"] == st0["joined_frames"]
-    ref = _oracle_decode(shape, model, offsets, enc, N, S)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 1
+    _check_decode(shape, model, offsets, enc, N, S)
 
 
 def test_streaming_partial_results_and_limits():
     """Between pushes B holds the result for the frames decoded so far: with no flush, that is the
-    oracle's decode of each utterance's whole segments.  A push beyond the buffer is refused and
+    decode of each utterance's whole segments.  A push beyond the buffer is refused and
     changes nothing; step calls and pushes do not mix."""
     from paper_2302_14357_amd.tbs import TbsError
     shape = small_bf16_shape(n_utts=3, vocab=48, d=64, hidden=64)
@@ -355,9 +484,11 @@ def test_streaming_partial_results_and_limits():
     done = (lengths // S) * S
     off2 = np.concatenate([[0], np.cumsum(done)]).astype(np.int32)
     enc2 = np.concatenate([enc[offsets[u]: offsets[u] + done[u]] for u in range(3)])
-    ref = _oracle_decode(shape, model, off2, enc2, N, S)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 1
+    part, _ = _gpu_decode(shape, model, off2, enc2, N, S)
+    for a, b in zip(got, part):
+        assert [h[0] for h in a] == [h[0] for h in b]
+        np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-5, atol=1e-5)
+    _check_decode(shape, model, off2, enc2, N, S)
     # 2, 1, 2 frames are still buffered; 11 more do not fit into 12
     with pytest.raises(TbsError):
         tbs.push_segment(tbs.upload_frames(np.zeros((11, 64), np.float32)), np.array([0, 11, 11, 11], np.int32))
@@ -366,55 +497,105 @@ def test_streaming_partial_results_and_limits():
     assert tbs.result() == got
     # the rest of the stream still decodes: flush the leftovers
     tbs.push_segment(None, np.zeros(4, np.int32), flush=True)
-    full = _oracle_decode(shape, model, offsets, enc, N, S)
-    same, amb, tot = compare_nbest(tbs.result(), full)
-    assert same + amb == tot and same >= tot - 1
+    rest = tbs.result()
     tbs.close()
+    whole, _ = _gpu_decode(shape, model, offsets, enc, N, S)
+    for a, b in zip(rest, whole):
+        assert [h[0] for h in a] == [h[0] for h in b]
+        np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-5, atol=1e-5)
+    _check_decode(shape, model, offsets, enc, N, S)
 
 
-def test_decode_step_by_step_matches_oracle_trace():
-    """Drive the step entry points and compare A and B with the oracle after every round."""
-    shape = small_bf16_shape(n_utts=1, vocab=48, d=64, hidden=64)
-    N, S, T = 3, 4, 38
-    model, offsets, enc = build_case(shape, n_utts=1, lengths=np.array([T]))
-    W = oracle_weights(shape, model)
-    ref = oracle.decode(oracle.LstmModel(W, enc), T, N, S, trace=True)
-    # the run must exercise AddAndMerge: some round adds fewer entries to B than it has hypotheses
-    merges, prev = 0, {}
-    for r in ref.rounds:
-        before = prev.get(r.seg, 0)
-        merges += before + len(r.a_tokens) - len(r.b_tokens)
-        prev[r.seg] = len(r.b_tokens)
-    assert merges > 0
-    tbs = make_tbs(shape, model, offsets, N, S, debug=1)
+def _step_by_step(shape, model, offsets, enc, N, S, max_rounds=0, **kw):
+    """Drive the step entry points over a batch and compare A and B of every utterance with the
+    oracle's trace after every round, up to the utterance's first close decision (from there on its
+    run may legitimately differ and it is only followed).  Lists are compared as sets of token
+    sequences with their scores: the order inside A changes no score.  Returns what was covered."""
+    from paper_2302_14357_amd import BUF
+    tol, score_tol = tolerance(shape, model)
+    U = len(offsets) - 1
+    T = np.diff(offsets)
+    okw = dict(max_rounds=max_rounds) if max_rounds else {}
+    ref = _oracle_decode(shape, model, offsets, enc, N, S, **okw)
+    gkw = dict(kw)
+    if max_rounds:
+        gkw["max_rounds_per_segment"] = max_rounds
+    tbs = make_tbs(shape, model, offsets, N, S, debug=1, **gkw)
     tbs.begin(tbs.upload_frames(enc), offsets)
-    it = iter(ref.rounds)
-    nseg = (T + S - 1) // S
+    trace = [{(r.seg, r.round): r for r in ref[u].rounds} for u in range(U)]
+    stop = [ref[u].first_ambiguous_segment(tol) for u in range(U)]
+    cov = {"rounds": 0, "merges": 0, "max_len": 0, "deep_merges": 0}
+    nseg = (int(T.max()) + S - 1) // S if U else 0
     for seg in range(nseg):
         rows = tbs.segment_begin(seg)
+        rnd = 0
+        prev_nb = [0] * U
         while rows > 0:
-            r = next(it)
-            assert r.seg == seg
-            a_now = tbs.debug_hyps(0)[0]
-            assert [y for y, _ in a_now] == r.a_tokens
-            np.testing.assert_allclose([s for _, s in a_now], r.a_scores, atol=1e-3)
+            rnd += 1
+            a_now = tbs.debug_hyps(0)
             tbs.joiner_segment()
             tbs.expand()
             live = tbs.select_merge()
-            b_now = tbs.debug_hyps(1)[0]
-            assert [y for y, _ in b_now] == r.b_tokens
-            np.testing.assert_allclose([s for _, s in b_now], r.b_scores, atol=1e-3)
-            assert live == len(r.new_pairs)
-            from paper_2302_14357_amd import BUF
-            dh = tbs.debug_read(BUF.A_DHAT)[0]
-            for i, dref in enumerate(r.new_d):
-                np.testing.assert_allclose(dh[i, :r.S], dref, rtol=1e-3, atol=1e-7)
+            b_now = tbs.debug_hyps(1, cap=N * (max_rounds or 32))
+            a_new = tbs.debug_hyps(0)
+            dh = tbs.debug_read(BUF.A_DHAT)
+            for u in range(U):
+                if stop[u] is not None and seg >= stop[u]:
+                    continue
+                r = trace[u].get((seg, rnd))
+                if r is None:
+                    assert a_now[u] == [] or seg * S >= T[u], (u, seg, rnd)
+                    continue
+                cov["rounds"] += 1
+                assert {y for y, _ in a_now[u]} == set(r.a_tokens), (u, seg, rnd)
+                want = dict(zip(r.a_tokens, r.a_scores))
+                for y, sc in a_now[u]:
+                    assert abs(sc - want[y]) <= score_tol, (u, seg, rnd, y)
+                assert [y for y, _ in b_now[u]] == r.b_tokens, (u, seg, rnd)     # insertion order is unique
+                np.testing.assert_allclose([sc for _, sc in b_now[u]], r.b_scores, atol=score_tol)
+                new_tokens = [r.a_tokens[h] + (k,) for h, k in r.new_pairs]
+                assert {y for y, _ in a_new[u]} == set(new_tokens), (u, seg, rnd)
+                for i, (y, sc) in enumerate(a_new[u]):
+                    j = new_tokens.index(y)
+                    assert abs(sc - r.new_scores[j]) <= score_tol
+                    np.testing.assert_allclose(dh[u, i, :r.S], r.new_d[j], rtol=10 * tol, atol=1e-7)
+                merged = prev_nb[u] + len(r.a_tokens) - len(r.b_tokens)
+                cov["merges"] += merged
+                if merged:
+                    cov["deep_merges"] += sum(1 for y in r.a_tokens if len(y) >= 3 and y in r.b_tokens[:prev_nb[u]])
+                prev_nb[u] = len(r.b_tokens)
+                cov["max_len"] = max([cov["max_len"]] + [len(y) for y in r.b_tokens])
             tbs.predictor_step()
             rows = tbs.counts()["rows"]
-    assert next(it, None) is None
-    final = tbs.result()[0]
-    assert [y for y, _ in final] == [y for y, _ in ref.nbest]
+    final = tbs.result()
+    for u in range(U):
+        if stop[u] is None:
+            why = nbest_agrees(final[u], ref[u], score_tol, tol)
+            assert why is None, (u, why)
     tbs.close()
+    return cov
+
+
+def test_decode_step_by_step_matches_oracle_trace():
+    """One utterance at the benchmark models' scale: A and B after every round."""
+    shape = small_bf16_shape(n_utts=1, vocab=48, d=64, hidden=64)
+    model, offsets, enc = build_case(shape, n_utts=1, lengths=np.array([38]))
+    cov = _step_by_step(shape, model, offsets, enc, 3, 4)
+    assert cov["merges"] > 0 and cov["rounds"] > 10, cov
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_step_by_step_peaked_batch(dtype):
+    """A batch with a peaked model: A and B of every utterance after every round while the
+    hypotheses grow long, including merges between sequences of three and more tokens (a sequence
+    carried into a segment meeting the same sequence re-created in it)."""
+    import dataclasses
+    shape = _peaked(dataclasses.replace(small_bf16_shape(n_utts=5, vocab=24, d=64, hidden=64), dtype=dtype), 8.0, 8.0)
+    lengths = np.array([30, 21, 38, 14, 26])
+    model, offsets, enc = build_case(shape, n_utts=5, lengths=lengths)
+    cov = _step_by_step(shape, model, offsets, enc, 5, 3, max_rounds=6)
+    print(cov)
+    assert cov["max_len"] >= 5 and cov["merges"] > 0, cov
 
 
 @pytest.mark.parametrize("d,limit", [(64, 2), (128, 2), (128, 1)])
@@ -424,10 +605,7 @@ def test_round_limit_matches_oracle(d, limit):
     in one go (with limit 1 the drop falls into that first round), width 64 the step-by-step one."""
     shape = small_bf16_shape(n_utts=2, vocab=32, d=d, hidden=d)
     model, offsets, enc = build_case(shape, n_utts=2, lengths=np.array([9, 6]))
-    ref = _oracle_decode(shape, model, offsets, enc, 4, 3, max_rounds=limit)
-    got, _ = _gpu_decode(shape, model, offsets, enc, 4, 3, max_rounds_per_segment=limit)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same == tot
+    _check_decode(shape, model, offsets, enc, 4, 3, max_rounds=limit)
 
 
 def test_batch_equals_each_alone_and_is_deterministic():
@@ -443,21 +621,18 @@ def test_batch_equals_each_alone_and_is_deterministic():
         np.testing.assert_allclose([s for _, s in alone[0]], [s for _, s in together[u]], atol=1e-5)
 
 
-def test_decode_librispeech_like_subset():
-    """Headline shapes (Dj=512, V=1024, LSTM 640, N=5, S=3) on the first 8
-    utterances of the benchmark batch, whole decode against the oracle."""
+def test_decode_librispeech_headline_batch():
+    """The benchmark's own batch in the benchmark's launch configuration (64 utterances, 17983
+    frames, Dj=512, V=1024, LSTM 640, N=5, S=3): every utterance against the oracle, whole where
+    all its decisions were clear and up to its first close decision otherwise."""
     shape = SHAPES["librispeech"]
     model = make_model(shape)
-    offsets_all, _ = None, None
-    full_off, full_enc = make_utterances(shape, model)
-    U = 8
-    offsets = full_off[:U + 1].copy()
-    enc = full_enc[:offsets[-1]]
-    ref = _oracle_decode(shape, model, offsets, enc, 5, 3)
-    got, st = _gpu_decode(shape, model, offsets, enc, 5, 3)
-    same, amb, tot = compare_nbest(got, ref)
-    print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
-    assert same + amb == tot and same >= tot - 2
+    offsets, enc = make_utterances(shape, model)
+    info = _check_decode(shape, model, offsets, enc, 5, 3, report="Librispeech-like headline batch")
+    assert info["tot"] == 64
+    # flat synthetic distributions put thousands of expansion scores close together, so most
+    # utterances meet a close decision at some point; the strict part must still be substantial
+    assert info.get("prefix_frames", int(offsets[-1])) >= 2000, info
 
 
 @pytest.mark.parametrize("name,N,S", [("assistant", 10, 3), ("throughput", 10, 5)])
@@ -468,11 +643,7 @@ def test_decode_large_shapes_short_utterances(name, N, S):
     shape = dataclasses.replace(SHAPES[name], n_utts=4)
     lengths = np.array([7, 16, 23, 30])
     model, offsets, enc = build_case(shape, n_utts=4, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, N, S)
-    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
-    same, amb, tot = compare_nbest(got, ref)
-    print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
-    assert same + amb == tot and same >= tot - 1
+    _check_decode(shape, model, offsets, enc, N, S, report=name)
 
 
 @pytest.mark.parametrize("N,S", [(2, 1), (2, 5), (10, 1), (10, 2), (10, 5), (5, 2), (5, 5)])
@@ -483,11 +654,7 @@ def test_decode_librispeech_like_beam_and_segment_sweep(N, S):
     shape = dataclasses.replace(SHAPES["librispeech"], n_utts=3)
     lengths = np.array([31, 44, 60])
     model, offsets, enc = build_case(shape, n_utts=3, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, N, S)
-    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 1
-    assert st["joiner_calls"] == sum(r.joiner_calls for r in ref) or amb > 0
+    _check_decode(shape, model, offsets, enc, N, S)
 
 
 @pytest.mark.parametrize("S", [10, 20, 50])
@@ -498,14 +665,10 @@ def test_decode_long_segments(S):
     shape = dataclasses.replace(SHAPES["librispeech"], n_utts=2)
     lengths = np.array([75, 128])
     model, offsets, enc = build_case(shape, n_utts=2, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, 5, S)
     # a segment of S frames can take more rounds than the default workspace is sized for
-    got, st = _gpu_decode(shape, model, offsets, enc, 5, S, rounds_capacity=4 * S)
-    same, amb, tot = compare_nbest(got, ref)
-    print(f"identical {same}/{tot}, ambiguous-mismatch {amb}, min gaps {[f'{r.min_gap:.1e}' for r in ref]}")
     # (with blank probabilities of a few percent the blank products over such segments span ~1e-85:
     # this is the case that needs the forward variable and d carried with extended range)
-    assert same + amb == tot and same >= tot - 1
+    _check_decode(shape, model, offsets, enc, 5, S, rounds_capacity=4 * S, report=f"S={S}")
 
 
 def test_decode_largest_segment_and_smallest_vocabulary():
@@ -515,36 +678,38 @@ def test_decode_largest_segment_and_smallest_vocabulary():
     shape = small_bf16_shape(n_utts=2, vocab=24, d=64, hidden=64)
     lengths = np.array([140, 131])
     model, offsets, enc = build_case(shape, n_utts=2, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, 3, 128)
-    got, st = _gpu_decode(shape, model, offsets, enc, 3, 128, rounds_capacity=512)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 1
+    _check_decode(shape, model, offsets, enc, 3, 128, rounds_capacity=512)
     shape2 = small_bf16_shape(n_utts=3, vocab=2, d=64, hidden=64)
     model2, off2, enc2 = build_case(shape2, n_utts=3, lengths=np.array([5, 11, 2]))
     for N, S in ((1, 1), (3, 2), (4, 5)):
-        ref2 = _oracle_decode(shape2, model2, off2, enc2, N, S)
-        got2, _ = _gpu_decode(shape2, model2, off2, enc2, N, S)
-        same, amb, tot = compare_nbest(got2, ref2)
-        assert same + amb == tot and same >= tot - 1, (N, S)
+        _check_decode(shape2, model2, off2, enc2, N, S)
 
 
 @pytest.mark.parametrize("name,N,S,U", [("assistant", 10, 3, 300), ("throughput", 10, 5, 200)])
 def test_decode_large_batch_contains_the_small_one(name, N, S, U):
     """The large configurations' widths with enough utterances that every round runs on the kernels
     chosen at scale (256x256-tile joiner GEMM, 80- or 48-logit-per-thread expansion, LSTM cell
-    update as its own kernel behind a large gate GEMM): the first four utterances must decode
-    exactly as in the four-utterance batch, which is checked against the oracle above."""
+    update as its own kernel behind a large gate GEMM): the first eight utterances against the
+    oracle under the gap rule, decoded inside the large batch."""
     import dataclasses
     shape = dataclasses.replace(SHAPES[name], n_utts=U)
-    lengths = np.concatenate([np.array([7, 16, 23, 30]), np.full(U - 4, 12)])
+    lengths = np.concatenate([np.array([7, 16, 23, 30, 5, 11, 19, 26]), np.full(U - 8, 12)])
     model, offsets, enc = build_case(shape, n_utts=U, lengths=lengths)
+    tol, score_tol = tolerance(shape, model)
     full, st = _gpu_decode(shape, model, offsets, enc, N, S)
-    off4 = offsets[:5].copy()
-    part, _ = _gpu_decode(shape, model, off4, enc[:off4[-1]], N, S)
-    for u in range(4):
-        assert [y for y, _ in part[u]] == [y for y, _ in full[u]]
-        np.testing.assert_allclose([s for _, s in part[u]], [s for _, s in full[u]], atol=2e-3)
     assert st["frames"] == int(offsets[-1])
+    off8 = offsets[:9].copy()
+    ref = _oracle_decode(shape, model, off8, enc[:off8[-1]], N, S)
+    same, amb, tot = compare_nbest(full[:8], ref, score_tol=score_tol, gap_tol=tol)
+    # the same eight cut back to before their first close decision, again inside a large batch
+    offp, encp, keep = strict_prefixes(ref, off8, enc[:off8[-1]], S, tol)
+    lengths2 = np.concatenate([keep, np.full(U - 8, 12)])
+    off2 = np.concatenate([[0], np.cumsum(lengths2)]).astype(np.int32)
+    enc2 = np.concatenate([encp, enc[off8[-1]:]])
+    full2, _ = _gpu_decode(shape, model, off2, enc2, N, S)
+    ref2 = _oracle_decode(shape, model, offp, encp, N, S)
+    assert_all_agree(full2[:8], ref2, score_tol, tol)
+    print(f"{name}: identical {same}/{tot} whole, strict prefix frames {int(keep.sum())}/{int(off8[-1])}")
 
 
 @pytest.mark.parametrize("N,S", [(32, 2), (17, 3)])
@@ -554,26 +719,7 @@ def test_decode_wide_beams(N, S):
     shape = small_bf16_shape(n_utts=3, vocab=96, d=64, hidden=64)
     lengths = np.array([5, 11, 18])
     model, offsets, enc = build_case(shape, n_utts=3, lengths=lengths)
-    ref = _oracle_decode(shape, model, offsets, enc, N, S)
-    got, st = _gpu_decode(shape, model, offsets, enc, N, S)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot and same >= tot - 1
-
-
-def test_decode_full_batch_contains_the_subset():
-    """Full benchmark batch (64 utterances) in the benchmark's launch
-    configuration: the first utterances must decode exactly as they do in the
-    8-utterance batch that is checked against the oracle above."""
-    shape = SHAPES["librispeech"]
-    model = make_model(shape)
-    full_off, full_enc = make_utterances(shape, model)
-    full, st = _gpu_decode(shape, model, full_off, full_enc, 5, 3)
-    offsets = full_off[:9].copy()
-    part, _ = _gpu_decode(shape, model, offsets, full_enc[:offsets[-1]], 5, 3)
-    for u in range(8):
-        assert [y for y, _ in part[u]] == [y for y, _ in full[u]]
-    assert st["frames"] == int(full_off[-1])
-    assert 0.3 < st["joiner_calls"] / st["frames"] < 2.0
+    _check_decode(shape, model, offsets, enc, N, S)
 
 
 def test_errors_are_codes_not_crashes():
@@ -608,7 +754,4 @@ def test_errors_are_codes_not_crashes():
         tbs.decode(tbs.upload_frames(enc), offsets)
     assert e.value.code == -5
     tbs.close()
-    ref = _oracle_decode(shape, model, offsets, enc, 2, 2)
-    got, _ = _gpu_decode(shape, model, offsets, enc, 2, 2)
-    same, amb, tot = compare_nbest(got, ref)
-    assert same + amb == tot
+    _check_decode(shape, model, offsets, enc, 2, 2)

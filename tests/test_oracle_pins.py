@@ -164,39 +164,99 @@ def test_segment_one_equals_framewise_search(seed, N, V, T):
     np.testing.assert_allclose([math.exp(s) for _, s in got.nbest], [p for _, p in want], rtol=1e-11)
 
 
-# ------------------------------------------------------------------ hand-worked example (policy)
+# ------------------------------------------------------------------ hand-worked examples (policy)
 
 def _read_golden(name):
+    """{section: {key: value}}; lines before the first [section] go to section ''."""
     path = os.path.join(os.path.dirname(__file__), "golden", name)
-    rows = {}
+    out, cur = {"": {}}, ""
     with open(path) as f:
         for line in f:
             line = line.split("#")[0].strip()
-            if line:
-                k, v = line.split("=")
-                rows[k.strip()] = v.strip()
-    return rows
+            if not line:
+                continue
+            if line.startswith("[") and line.endswith("]"):
+                cur = line[1:-1]
+                out[cur] = {}
+                continue
+            k, v = line.split("=")
+            out[cur][k.strip()] = v.strip()
+    return out
 
 
-def test_hand_worked_example():
-    g = _read_golden("alg1_hand_example.txt")
+def _run_golden(g):
     probs = {}
     for k, v in g.items():
-        if k.startswith("J"):
+        if k.startswith("J("):
             frame, toks = k[2:-1].split("|")
             probs[(int(frame), tuple(int(x) for x in toks.split()))] = [float(x) for x in v.split()]
 
     def fn(frame, toks):
-        return np.log(np.array(probs[(frame, toks)]))
+        # (a table the file does not hold, asked for only by a run that has already gone wrong: blank only)
+        with np.errstate(divide="ignore"):
+            return np.log(np.array(probs.get((frame, toks), [1.0, 0.0, 0.0])))
 
     res = oracle.decode(oracle.TableModel(fn, 3), int(g["T"]), int(g["N"]), int(g["S"]), raw_prob=True, trace=True)
     want = []
     for item in g["nbest"].split(";"):
         toks, p = item.split(":")
         want.append((tuple(int(x) for x in toks.split()), float(p)))
+    return res, want
+
+
+def _check_golden(g):
+    res, want = _run_golden(g)
     assert [y for y, _ in res.nbest] == [y for y, _ in want]
     np.testing.assert_allclose([math.exp(s) for _, s in res.nbest], [p for _, p in want], rtol=1e-12)
     assert res.joiner_calls == int(g["joiner_calls"])
+    for k, v in g.items():   # (parent, token) of the hypotheses each round creates, rounds counted over the run
+        if k.startswith("new("):
+            pairs = [tuple(int(x) for x in it.split()) for it in v.split(";") if it.strip()]
+            assert res.rounds[int(k[4:-1]) - 1].new_pairs == pairs, k
+    return res
+
+
+def test_hand_worked_example():
+    _check_golden(_read_golden("alg1_hand_example.txt")[""])
+
+
+def test_hand_worked_decision_gaps():
+    """The gap bookkeeping that decides how strictly two decodes are compared: every head-of-segment
+    and per-round gap of the hand-worked run, from the values worked out beside it."""
+    g = _read_golden("alg1_hand_example.txt")[""]
+    res, _ = _run_golden(g)
+
+    def val(key):
+        v = g[key]
+        if v == "none":
+            return math.inf
+        a, b = (float(x) for x in v.split())
+        return abs(math.log(a) - math.log(b))
+
+    seen = set()
+    for r in res.rounds:
+        assert r.head_gap == pytest.approx(val(f"head({r.seg})"), rel=1e-12), (r.seg, r.round)
+        assert r.gap == pytest.approx(val(f"gap({r.seg},{r.round})"), rel=1e-12), (r.seg, r.round)
+        seen.add((r.seg, r.round))
+    assert seen == {(0, 1), (0, 2), (1, 1), (1, 2)}
+    assert res.final_gap == val("final")
+    assert res.min_gap == pytest.approx(abs(math.log(0.12) - math.log(0.1134)), rel=1e-12)
+    assert res.first_ambiguous_segment(0.05) is None
+    assert res.first_ambiguous_segment(0.06) == 1       # segment 1, round 1: 0.12 against 0.1134
+    assert res.first_ambiguous_segment(0.09) == 0       # segment 0, round 2: 0.174 against 0.189
+    # with N = 1 the final list of two entries is cut: its gap is that of the two results
+    res1 = oracle.decode(oracle.TableModel(lambda f, t: np.log(np.array([0.5, 0.3, 0.2])), 3), 1, 1, 1, raw_prob=True)
+    assert res1.nbest[0][0] == () and res1.final_gap == pytest.approx(math.inf)   # 0.3 <= threshold 0.5: B = {[]}
+    res2 = oracle.decode(oracle.TableModel(lambda f, t: np.log(np.array([0.3, 0.5, 0.2])), 3), 1, 1, 1, raw_prob=True)
+    # B = {[]:0.3}, threshold 0.3 < 0.5: [1] enters, takes its blank (0.15) into B; final cut: 0.3 vs 0.15
+    assert res2.nbest[0][0] == () and res2.final_gap == pytest.approx(math.log(2.0), rel=1e-12)
+
+
+@pytest.mark.parametrize("case", ["strict", "joint"])
+def test_policy_examples(case):
+    """Hand-worked runs in which a non-strict threshold test, or N expansions per hypothesis
+    instead of N in all, would give another result."""
+    _check_golden(_read_golden("alg1_policy_examples.txt")[case])
 
 
 # ------------------------------------------------------------------ library pins
@@ -294,7 +354,7 @@ def test_lstm_decode_runs_and_counts():
 
 # ------------------------------------------------------------------ planted mistakes are noticed
 
-def _pins_for_mutants():
+def _score_pins():
     test_brute_force_all_alignments(3, 3, 2, False)
     test_brute_force_all_alignments(4, 2, 2, False)
     test_brute_force_last_emission_distribution()
@@ -302,12 +362,34 @@ def _pins_for_mutants():
     test_mass_conservation(3, 3, 7)
 
 
-@pytest.mark.parametrize("mutant", [1, 2, 4, 5, 6, 8])
-def test_planted_mistake_is_caught(mutant):
+def _policy_pins():
+    test_hand_worked_example()
+    test_policy_examples("strict")
+    test_policy_examples("joint")
+
+
+# 1 blank product off by a frame, 2 no same-frame emission, 4 merge keeps the larger score, 5 the
+# frame of the last token forgotten, 6 blank expansion a frame short, 8 no merging at all: caught by
+# the score pins.  9 threshold test not strict, 10 N expansions per hypothesis, 11 threshold one
+# place too far down B: caught by the hand-worked runs of Algorithm 1.
+@pytest.mark.parametrize("mutant,pins", [(1, _score_pins), (2, _score_pins), (4, _score_pins), (5, _score_pins),
+                                         (6, _score_pins), (8, _score_pins), (9, _policy_pins),
+                                         (10, _policy_pins), (11, _policy_pins)])
+def test_planted_mistake_is_caught(mutant, pins):
     oracle.set_mutant(mutant)
     try:
         with pytest.raises(AssertionError):
-            _pins_for_mutants()
+            pins()
     finally:
         oracle.set_mutant(0)
-    _pins_for_mutants()
+    pins()
+
+
+@pytest.mark.parametrize("mutant,case", [(9, "strict"), (10, "joint")])
+def test_each_policy_example_catches_its_own_reading(mutant, case):
+    oracle.set_mutant(mutant)
+    try:
+        with pytest.raises(AssertionError):
+            test_policy_examples(case)
+    finally:
+        oracle.set_mutant(0)
