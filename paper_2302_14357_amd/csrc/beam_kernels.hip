@@ -674,19 +674,33 @@ hipError_t launch_finalize(hipStream_t st, const Dims &d, BView B, const int2 *n
     return hipGetLastError();
 }
 
-__global__ void k_hyps_dump(Dims d, int group, AView A, BView B, const int2 *nodes, int cap, int max_len, int *tok,
-                            int *len, double *logs, int *count) {
+// Every entry of the four outputs is written exactly once (entries past the list and positions
+// past a sequence get the neutral value), so the buffers need no clearing beforehand.
+__global__ void __launch_bounds__(WAVE)
+k_hyps_dump(Dims d, int group, AView A, BView B, const int2 *nodes, int cap, int max_len, int *tok,
+            int *len, double *logs, int *count) {
     int u = blockIdx.x, lane = threadIdx.x;
     int n = group == 0 ? A.count[u] : B.count[u];
     int stride = group == 0 ? d.N : d.BCAP;
     if (n > cap) n = cap;
-    for (int i = lane; i < n; i += WAVE) {
+    for (int i = lane; i < cap; i += WAVE) {
         long s = (long)u * stride + i, o = (long)u * cap + i;
-        int ln = group == 0 ? A.len[s] : B.len[s];
-        int nd = group == 0 ? A.node[s] : B.node[s];
-        logs[o] = group == 0 ? A.logs[s] : B.logs[s];
-        len[o] = ln;
-        write_tokens(nodes, nd, ln, max_len, tok + o * max_len);
+        if (i < n) {
+            int ln = group == 0 ? A.len[s] : B.len[s];
+            int nd = group == 0 ? A.node[s] : B.node[s];
+            logs[o] = group == 0 ? A.logs[s] : B.logs[s];
+            len[o] = ln;
+            write_tokens(nodes, nd, ln, max_len, tok + o * max_len);
+        } else {
+            logs[o] = 0.0;
+            len[o] = 0;
+        }
+    }
+    for (int idx = lane; idx < cap * max_len; idx += WAVE) {
+        const int i = idx / max_len, p = idx - i * max_len;
+        int ln = 0;
+        if (i < n) ln = group == 0 ? A.len[(long)u * stride + i] : B.len[(long)u * stride + i];
+        if (p >= ln) tok[((long)u * cap + i) * max_len + p] = -1;
     }
     if (lane == 0) count[u] = n;
 }

@@ -1072,10 +1072,7 @@ int tbs_debug_hyps(tbs_ctx *c, int32_t group, int32_t *tokens, int32_t *lens, do
     if (e == hipSuccess) e = hipMalloc((void **)&dlen, sizeof(int) * n);
     if (e == hipSuccess) e = hipMalloc((void **)&dlogs, sizeof(double) * n);
     if (e == hipSuccess) e = hipMalloc((void **)&dcnt, sizeof(int) * d.U);
-    if (e == hipSuccess) e = hipMemsetAsync(dtok, 0xFF, sizeof(int) * n * max_len, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(dlen, 0, sizeof(int) * n, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(dlogs, 0, sizeof(double) * n, c->stream);
-    if (e == hipSuccess)
+    if (e == hipSuccess)   // (the kernel writes every entry: nothing is cleared beforehand)
         e = launch_hyps_dump(c->stream, d, group, c->A[c->a_cur], c->B, c->nodes, cap, max_len, dtok, dlen, dlogs,
                              dcnt);
     if (e == hipSuccess) e = hipMemcpyAsync(tokens, dtok, sizeof(int) * n * max_len, hipMemcpyDeviceToHost, c->stream);
