@@ -41,6 +41,7 @@ extern "C" {
 #define TBS_ENOMEM (-3)    /* device or host allocation failed */
 #define TBS_EHIP (-4)      /* a HIP call failed; see tbs_last_hip_error */
 #define TBS_EOVERFLOW (-5) /* a capacity was exceeded (rounds, merged list, trie nodes, max_len) */
+#define TBS_ELIMIT (-6)    /* request larger than the fixed scratch of an entry point that does not allocate */
 
 #define TBS_MAX_BEAM 32
 #define TBS_MAX_SEG 128
@@ -210,6 +211,19 @@ int tbs_debug_rebuild(tbs_ctx *ctx, int32_t seg_index, int32_t *rows_host);
  * lens [U,cap], logscores [U,cap], counts [U], all HOST. */
 int tbs_debug_hyps(tbs_ctx *ctx, int32_t group, int32_t *tokens, int32_t *lens, double *logscores,
                    int32_t *counts, int32_t cap, int32_t max_len);
+
+/* tbs_debug_hyps for callers that cannot allocate device memory (a tight serving loop reading the
+ * running hypotheses after every push, a harness that forbids allocation, code that must not
+ * call the allocator between captures): the same outputs, but the kernel's staging area is a
+ * fixed 2 MiB array in the library's device image instead of four allocations per call, and the
+ * call makes no allocation of any kind.  U * cap * (max_len + 3) * 4 + U * 4 bytes (U = utterances
+ * of the current batch) must fit into it, otherwise TBS_ELIMIT and nothing is done.  Every GPU
+ * holds its own copy of the array from the moment the library is loaded until the process ends;
+ * all contexts on one GPU share it, so calls that overlap in time on one GPU (from different
+ * contexts or streams) race and must be serialised by the caller.  The array keeps what the last
+ * call left in it; the kernel overwrites every entry it hands back. */
+int tbs_debug_hyps_noalloc(tbs_ctx *ctx, int32_t group, int32_t *tokens, int32_t *lens, double *logscores,
+                           int32_t *counts, int32_t cap, int32_t max_len);
 
 /* ---- timing of one kernel family, for the benchmark ---- */
 enum tbs_kernel_id { TBS_K_JOINER = 0, TBS_K_EXPAND = 1, TBS_K_SELECT = 2, TBS_K_PREDICTOR = 3,

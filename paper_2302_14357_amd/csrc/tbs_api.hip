@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -92,6 +93,28 @@ struct tbs_ctx {
     size_t ev_used;
     int64_t prof_units;
 };
+
+// Scratch of tbs_debug_hyps_noalloc: one array per GPU the library is loaded on, held until the
+// process ends.  In host code the array's name is only a stand-in for the symbol, not a device
+// address: the address on a device is asked for once per device, with that device current (each GPU
+// has its own copy at its own address), and only that pointer is handed to kernels and copies.
+#define TBS_NOALLOC_BYTES (2u << 20)
+#define TBS_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[TBS_NOALLOC_BYTES];
+static void *g_scratch_ptr[TBS_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+// (the caller has made `device` current)
+static hipError_t scratch_resolve(int device) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = p;
+    return hipSuccess;
+}
 
 #define HIPCHK(ctx, expr)                       \
     do {                                        \
@@ -210,6 +233,7 @@ const char *tbs_strerror(int code) {
         case TBS_ENOMEM: return "allocation failed";
         case TBS_EHIP: return "HIP call failed";
         case TBS_EOVERFLOW: return "capacity exceeded (rounds per segment, merged list, trie nodes or max_len)";
+        case TBS_ELIMIT: return "request larger than the fixed scratch of an entry point that does not allocate";
         default: return "unknown error";
     }
 }
@@ -237,6 +261,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     if (cfg->beam_n < 1 || cfg->beam_n > TBS_MAX_BEAM || cfg->seg_s < 1 || cfg->seg_s > TBS_MAX_SEG)
         return TBS_EINVAL;
     if (cfg->max_utts < 1 || cfg->max_frames_total < 0) return TBS_EINVAL;
+    if (cfg->device_id < 0 || cfg->device_id >= TBS_MAX_DEVICES) return TBS_EINVAL;
     if (cfg->pred_layers < 1 || cfg->pred_layers > TBS_MAX_LAYERS || cfg->pred_hidden < 1 || cfg->pred_embed < 1)
         return TBS_EINVAL;
     if (cfg->act < 0 || cfg->act > 1 || cfg->dtype < 0 || cfg->dtype > 1) return TBS_EINVAL;
@@ -269,6 +294,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     c->ev_used = 0;
     c->prof_units = 0;
     hipError_t e = hipSetDevice(cfg->device_id);
+    if (e == hipSuccess) e = scratch_resolve(cfg->device_id);   // this device's address of the static scratch
     if (e != hipSuccess) {
         c->last_hip = (int)e;
         delete c;
@@ -1085,6 +1111,36 @@ int tbs_debug_hyps(tbs_ctx *c, int32_t group, int32_t *tokens, int32_t *lens, do
     (void)hipFree(dlogs);
     (void)hipFree(dcnt);
     HIPCHK(c, e);
+    return TBS_OK;
+}
+
+int tbs_debug_hyps_noalloc(tbs_ctx *c, int32_t group, int32_t *tokens, int32_t *lens, double *logscores,
+                           int32_t *counts, int32_t cap, int32_t max_len) {
+    if (!c || !tokens || !lens || !logscores || !counts || cap < 1 || max_len < 1 || group < 0 || group > 1)
+        return TBS_EINVAL;
+    if (c->state == ST_INIT) return TBS_ESTATE;
+    const Dims &d = c->cur;
+    // layout inside the scratch: scores (8-byte entries first), tokens, lengths, counts
+    const size_t n = (size_t)d.U * cap;
+    const size_t b_logs = sizeof(double) * n, b_tok = sizeof(int) * n * (size_t)max_len, b_len = sizeof(int) * n,
+                 b_cnt = sizeof(int) * (size_t)d.U;
+    if ((size_t)cap > TBS_NOALLOC_BYTES || (size_t)max_len > TBS_NOALLOC_BYTES ||
+        b_logs + b_tok + b_len + b_cnt > TBS_NOALLOC_BYTES)
+        return TBS_ELIMIT;
+    HIPCHK(c, hipSetDevice(c->cfg.device_id));
+    unsigned char *base = (unsigned char *)g_scratch_ptr[c->cfg.device_id];   // resolved in tbs_init on this device
+    if (!base) return TBS_ESTATE;
+    double *dlogs = (double *)base;
+    int *dtok = (int *)(base + b_logs), *dlen = (int *)(base + b_logs + b_tok),
+        *dcnt = (int *)(base + b_logs + b_tok + b_len);
+    // the kernel writes every entry of the four arrays, so what an earlier call left there does not matter
+    HIPCHK(c, launch_hyps_dump(c->stream, d, group, c->A[c->a_cur], c->B, c->nodes, cap, max_len, dtok, dlen, dlogs,
+                               dcnt));
+    HIPCHK(c, hipMemcpyAsync(tokens, dtok, b_tok, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(lens, dlen, b_len, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(logscores, dlogs, b_logs, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(counts, dcnt, b_cnt, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
     return TBS_OK;
 }
 

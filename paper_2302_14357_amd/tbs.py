@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "tbs_select_merge", "tbs_predictor_step", "tbs_decode", "tbs_result", "tbs_stats", "tbs_debug_read",
     "tbs_debug_write", "tbs_debug_rebuild", "tbs_debug_hyps", "tbs_profile_select", "tbs_profile_read",
     "tbs_strerror", "tbs_last_hip_error", "tbs_gemm_bf16", "tbs_stream_begin", "tbs_push_segment",
-    "tbs_profile_overhead",
+    "tbs_profile_overhead", "tbs_debug_hyps_noalloc",
 ]
 
 TBS_MAX_LAYERS = 4
@@ -86,6 +86,7 @@ def load_library():
     L.tbs_debug_write.argtypes = [vp, i32, vp, C.c_size_t]
     L.tbs_debug_rebuild.argtypes = [vp, i32, C.POINTER(i32)]
     L.tbs_debug_hyps.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32]
+    L.tbs_debug_hyps_noalloc.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32]
     L.tbs_profile_select.argtypes = [vp, i32]
     L.tbs_profile_read.argtypes = [vp, i64p, C.POINTER(C.c_double), i64p]
     L.tbs_profile_overhead.argtypes = [vp, i32, C.POINTER(C.c_double)]
@@ -294,15 +295,20 @@ class Tbs:
 
     def debug_hyps(self, group: int, cap: int = 0, max_len: int = 256):
         """group 0 = A, 1 = B; per utterance [(tokens, log score)] in stored order."""
+        tok, lens, logs, cnt = self.debug_hyps_raw(group, cap, max_len)
+        return self._nbest(tok, lens, logs, cnt)
+
+    def debug_hyps_raw(self, group: int, cap: int = 0, max_len: int = 256, noalloc: bool = False, fill: int = -1):
+        """The four output arrays of tbs_debug_hyps (or of tbs_debug_hyps_noalloc), pre-filled with `fill`."""
         cap = cap or (self.N if group == 0 else self.N * 64)
         U = self.U
-        tok = np.full((U, cap, max_len), -1, np.int32)
-        lens = np.zeros((U, cap), np.int32)
-        logs = np.zeros((U, cap), np.float64)
-        cnt = np.zeros(U, np.int32)
-        _check(self.L.tbs_debug_hyps(self.ctx, group, _hp(tok), _hp(lens), _hp(logs), _hp(cnt), cap, max_len),
-               self.ctx)
-        return self._nbest(tok, lens, logs, cnt)
+        tok = np.full((U, cap, max_len), fill, np.int32)
+        lens = np.full((U, cap), fill, np.int32)
+        logs = np.full((U, cap), float(fill), np.float64)
+        cnt = np.full(U, fill, np.int32)
+        fn = self.L.tbs_debug_hyps_noalloc if noalloc else self.L.tbs_debug_hyps
+        _check(fn(self.ctx, group, _hp(tok), _hp(lens), _hp(logs), _hp(cnt), cap, max_len), self.ctx)
+        return tok, lens, logs, cnt
 
     # ---- timing
     def profile_select(self, kernel_id: int):
