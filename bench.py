@@ -49,7 +49,7 @@ def read_traffic(kernel, workload):
     return None
 
 
-def measure_at_scale(iters=6):
+def measure_at_scale(iters=6, chunk_rows=0):
     """One joiner + expansion call on the shape of the largest configuration (1024 utterances,
     N=10, S=5, Dj=1024, V=4096: 51200 joiner rows, a full beam everywhere), where the two kernels
     are throughput-bound: the figures the roofline targets are stated for."""
@@ -61,7 +61,7 @@ def measure_at_scale(iters=6):
     model = make_model(shape)
     offsets, enc = make_utterances(shape, model)
     t = Tbs(model, blank_id=shape.blank_id, beam_n=N, seg_s=S, max_utts=U, max_frames_total=int(offsets[-1]),
-            dtype=shape.dtype, act=shape.act)
+            dtype=shape.dtype, act=shape.act, joiner_chunk_rows=chunk_rows)
     try:
         enc_dev = t.upload_frames(enc)
         rng = np.random.default_rng(0)
@@ -73,7 +73,7 @@ def measure_at_scale(iters=6):
         t.debug_write(BUF.A_DHAT, dh / dh.sum(-1, keepdims=True))
         out = {"workload": f"one joiner + expansion call, {U} utterances x {N} hypotheses x {S} frames, "
                            f"Dj={shape.d_joint}, V={shape.vocab}"}
-        for name, kid in (("joiner_gemm", KERNEL.JOINER), ("expand", KERNEL.EXPAND)):
+        for name, kid in (("joiner_gemm", KERNEL.JOINER), ("expand", KERNEL.EXPAND), ("joiner_prep", KERNEL.PREP)):
             t.profile_select(kid)
             rows = 0
             for _ in range(iters):
@@ -81,16 +81,23 @@ def measure_at_scale(iters=6):
                 t.joiner_segment()
                 t.expand()
             r = t.profile_read()
-            us = r["total_ms"] / max(r["launches"], 1) * 1e3
-            if name == "joiner_gemm":
-                ach = 2.0 * rows * shape.d_joint * shape.vocab / (us * 1e-6) / 1e12
+            # a call this large runs in pieces (one GEMM and one expansion launch per piece): the
+            # figures are per launch, work and time summed over all launches of the family
+            n, sec, units = max(r["launches"], 1), r["total_ms"] * 1e-3, r["units"]
+            us = sec / n * 1e6
+            if name == "joiner_prep":
+                out[name] = {"avg_us": us, "launches_per_call": n / iters, "us_per_call": sec / iters * 1e6}
+            elif name == "joiner_gemm":
+                ach = 2.0 * units * shape.d_joint * shape.vocab / sec / 1e12
                 out[name] = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                             "frac": ach / PEAK_BF16_TFLOPS, "avg_us": us, "rows": rows,
+                             "frac": ach / PEAK_BF16_TFLOPS, "avg_us": us, "rows_per_call": rows,
+                             "launches_per_call": n / iters, "us_per_call": sec / iters * 1e6,
                              "traffic": read_traffic("gemm", "at_scale")}
             else:
-                ach = rows * shape.vocab * 4.0 / (us * 1e-6) / 1e9
+                ach = units * shape.vocab * 4.0 / sec / 1e9
                 out[name] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                             "frac": ach / PEAK_HBM_GBS, "avg_us": us, "rows": rows,
+                             "frac": ach / PEAK_HBM_GBS, "avg_us": us, "rows_per_call": rows,
+                             "launches_per_call": n / iters, "us_per_call": sec / iters * 1e6,
                              "traffic": read_traffic("expand", "at_scale")}
         t.profile_select(-1)
         return out
@@ -114,6 +121,8 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--at-scale-only", action="store_true",
                     help="only the joiner + expansion call on the largest configuration's shape (for profiling)")
+    ap.add_argument("--chunk-rows", type=int, default=0,
+                    help="joiner_chunk_rows of the library (0 = joiner calls are not split)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one device copy of 256 MiB (the yardstick for the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -133,7 +142,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if args.at_scale_only:
-        print(json.dumps({"roofline_at_scale": measure_at_scale()}))
+        print(json.dumps({"roofline_at_scale": measure_at_scale(chunk_rows=args.chunk_rows)}))
         return
 
     shape_name, N, S, U, cpu_utts = WORKLOADS[args.workload]
@@ -149,7 +158,8 @@ def main():
 
     piece = args.stream_piece
     tbs = Tbs(model, blank_id=shape.blank_id, beam_n=N, seg_s=S, max_utts=U, max_frames_total=frames,
-              dtype=shape.dtype, act=shape.act, stream_buffer_frames=(piece + S) if piece else 0)
+              dtype=shape.dtype, act=shape.act, stream_buffer_frames=(piece + S) if piece else 0,
+              joiner_chunk_rows=args.chunk_rows)
     enc_dev = tbs.upload_frames(enc)           # inputs resident in HBM before the timed region
     max_len = 256
     tok = np.full((U, N, max_len), -1, np.int32)

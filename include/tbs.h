@@ -84,6 +84,10 @@ typedef struct tbs_config {
                                  push may bring an utterance up to this many minus seg_s - 1 frames */
     int32_t max_result_len;   /* longest token sequence tbs_decode / tbs_result hand back (sizes the result
                                  buffer at tbs_init); 0 = 256.  A larger max_len there is TBS_EINVAL */
+    int32_t joiner_chunk_rows; /* > 0: a joiner call with more rows than this is run in pieces of about that
+                                 many rows (whole hypotheses), each piece expanded right behind its GEMM
+                                 while its logits are still in the memory-side cache; 0: never split (the
+                                 default: splitting measured slower on this part, see tbs_joiner_segment) */
     int32_t device_id;
     void *stream;             /* hipStream_t to enqueue on (0 = the null stream) */
 } tbs_config;
@@ -123,7 +127,10 @@ int tbs_segment_begin(tbs_ctx *ctx, int32_t seg_index, int32_t *rows_host);
 /* J = Softmax(Joiner(seg, pred)) for all live (utterance, hypothesis, frame)
  * rows in one batched call (Algorithm 1, first line of the inner loop;
  * Section 3.1).  Logits are written once; softmax is kept as per-row
- * statistics, the probabilities are never stored. */
+ * statistics, the probabilities are never stored.  With joiner_chunk_rows set,
+ * a call larger than that is run in pieces and the expansion of each piece
+ * follows its GEMM at once, inside this call; tbs_expand, which must still be
+ * called next, then finds its work done. */
 int tbs_joiner_segment(tbs_ctx *ctx);
 
 /* BlankProduct, NonBlankExpansionT, NonBlankExpansion and BlankExpansion

@@ -123,12 +123,13 @@ template <bool VEC4>
 __global__ void __launch_bounds__(EXP_THREADS)
 k_expand(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
          float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
-         float *__restrict__ row_stats, float *__restrict__ delta_nb, const int *__restrict__ pairs_dev) {
+         float *__restrict__ row_stats, float *__restrict__ delta_nb, const int *__restrict__ pairs_dev,
+         int pair_base) {
     extern __shared__ float s_dnb[];  // [V]
     __shared__ float s_m[TBS_MAX_SEG], s_z[TBS_MAX_SEG], s_b[TBS_MAX_SEG], s_lc[TBS_MAX_SEG];
     __shared__ float s_rv[EXP_WAVES];
     __shared__ int s_rk[EXP_WAVES];
-    const int pair = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pair = pair_base + blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (pairs_dev && pair >= *pairs_dev) return;   // (enqueued on an upper-bound grid, see k_expand_reg)
     const int u = rv.pair_u[pair], h = rv.pair_h[pair];
     const int row0 = rv.pair_row0[pair], sp = rv.pair_len[pair];
@@ -395,37 +396,47 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
         if (lane == 0) sm.pz[t][wave] = z;
     }
     __syncthreads();
-    // ---- every thread: row sums, forward variable (Eq. 3 as a scan), Eq. 7, the row coefficients
-    float cf[SMAX];
+    // ---- every thread: row sums, forward variable (Eq. 3 as a scan), Eq. 7, the row coefficients.
+    // The scan runs on logarithms: la_t = log alpha_t = logaddexp(la_{t-1} + log b_{t-1}, log d_old[t]),
+    // which has the range the products of Eq. 3 need (see ScanAlpha) at four transcendentals and a
+    // dozen plain operations per frame; the values are the same in every lane.  What goes to memory
+    // is kept in registers until the scan is over and then stored by one thread in one go.
+    float cf[SMAX], lcrow[SMAX];
+    float lphi = -INFINITY;
     {
-        ScanAlpha al;
-        al.start();
-        float bprev = 0.f;
+        float la = -INFINITY, lbprev = 0.f;
 #pragma unroll
         for (int t = 0; t < SMAX; ++t) {
             cf[t] = 0.f;
-            if (t < pi.sp) {
+            lcrow[t] = 0.f;
+            if (t < pi.sp) {   // (uniform)
                 float z = sm.pz[t][0];
 #pragma unroll
                 for (int w = 1; w < EXP_WAVES; ++w) z += sm.pz[t][w];
                 __builtin_amdgcn_sched_barrier(0);
-                const float rz = __builtin_amdgcn_rcpf(z);
-                const float b = __builtin_amdgcn_exp2f((pi.lblank[t] - mrow[t]) * 1.44269504088896341f) * rz;
-                al.step(bprev, pi.dold[t]);
-                bprev = b;
-                const float c = al.value() * rz;
-                cf[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(c)));
-                if (tid == 0) {
-                    row_lc[pi.row0 + t] = al.log_value() - __logf(z) - mrow[t];   // log(alpha_t / Z_t) - m_t, no underflow
-                    if (row_stats) {
-                        row_stats[(long)(pi.row0 + t) * 3 + 0] = mrow[t];
-                        row_stats[(long)(pi.row0 + t) * 3 + 1] = z;
-                        row_stats[(long)(pi.row0 + t) * 3 + 2] = b;
-                    }
-                    if (t == pi.sp - 1) dphi[pi.pair] = al.log_times(b);
+                const float lz = __logf(z);
+                const float lb = (pi.lblank[t] - mrow[t]) - lz;       // log of the blank probability of frame t
+                const float x = la + lbprev, ld = pi.dold[t];
+                const float mx = fmaxf(x, ld), mn = fminf(x, ld);
+                la = mx > -INFINITY ? mx + __logf(1.f + __expf(mn - mx)) : -INFINITY;
+                lbprev = lb;
+                const float lc = la - lz;                              // log(alpha_t / Z_t)
+                cf[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(__expf(lc))));
+                lcrow[t] = lc - mrow[t];
+                if (t == pi.sp - 1) lphi = la + lb;                    // Eq. 7
+                if (row_stats && tid == 0) {
+                    row_stats[(long)(pi.row0 + t) * 3 + 0] = mrow[t];
+                    row_stats[(long)(pi.row0 + t) * 3 + 1] = z;
+                    row_stats[(long)(pi.row0 + t) * 3 + 2] = __expf(lb);
                 }
             }
         }
+    }
+    if (tid == 0) {
+#pragma unroll
+        for (int t = 0; t < SMAX; ++t)
+            if (t < pi.sp) row_lc[pi.row0 + t] = lcrow[t];   // log(alpha_t / Z_t) - m_t
+        dphi[pi.pair] = lphi;
     }
     // ---- Eq. 4-6 from registers
     float v[NC];
@@ -436,14 +447,20 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
         for (int t = 0; t < SMAX; ++t) acc += cf[t] * e[t][c];
         v[c] = acc;
     }
-    // blank is not a non-blank expansion; columns past V do not exist
+    // blank is not a non-blank expansion; columns past V do not exist.  (Blank in column 0 and a
+    // vocabulary that fills every thread's columns, the usual case, cost one select; anything
+    // else takes the general form.)
+    if (d.blank == 0 && V4 == EXP_THREADS * NV4) {   // (uniform)
+        if (tid == 0) v[0] = 0.f;
+    } else {
 #pragma unroll
-    for (int q = 0; q < NV4; ++q)
+        for (int q = 0; q < NV4; ++q)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int col = 4 * (tid + EXP_THREADS * q) + c;
-            if (col == d.blank || col >= V) v[4 * q + c] = 0.f;
-        }
+            for (int c = 0; c < 4; ++c) {
+                const int col = 4 * (tid + EXP_THREADS * q) + c;
+                if (col == d.blank || col >= V) v[4 * q + c] = 0.f;
+            }
+    }
     if (delta_nb) {   // debug output: its indices are made afresh, not kept in registers from the loads
         int t2 = threadIdx.x;
         asm volatile("" : "+v"(t2));
@@ -600,7 +617,8 @@ template <int NV4, int SMAX>
 __global__ void __launch_bounds__(EXP_THREADS, (NV4 * SMAX == 20 ? 5 : 1))   // 80 logits per thread: five waves per SIMD still fit
 k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, float *__restrict__ row_lc,
              float *__restrict__ dphi, float *__restrict__ cand_score, int *__restrict__ cand_tok,
-             float *__restrict__ row_stats, float *__restrict__ delta_nb, const int *__restrict__ pairs_dev) {
+             float *__restrict__ row_stats, float *__restrict__ delta_nb, const int *__restrict__ pairs_dev,
+             int pair_base) {
     __shared__ ExpandShared<SMAX> sm;
     // Workgroup b runs on XCD b % 8.  The joiner GEMM before this kernel gave XCD x the x-th eighth
     // of the rows, in increasing order; here XCD x walks the pairs of the same eighth backwards, so
@@ -610,6 +628,8 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
     // (eighth x holds as many pairs as there are workgroups with b % 8 == x: every pair gets one)
     // (pairs_dev not null: the launch went out before the host knew the number of pairs; the grid is
     // an upper bound and the workgroups beyond the count in device memory leave)
+    // (pair_base: the grid covers the pairs pair_base .. pair_base + gridDim.x - 1, one piece of a
+    // large call, joined by a GEMM launch of its own over exactly these pairs' rows)
     int pair = blockIdx.x;
     if (pairs_dev) {
         if (pair >= *pairs_dev) return;
@@ -618,6 +638,7 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
         const int first = x * q + min(x, r), count = q + (x < r);
         pair = first + count - 1 - (int)(blockIdx.x >> 3);
     }
+    pair += pair_base;
     ExpandPair<SMAX> pi;
     expand_pair_info(pi, pair, d, A, rv, logits);
     float e[SMAX][NV4 * 4];
@@ -628,21 +649,22 @@ k_expand_reg(Dims d, const float *__restrict__ logits, AView A, RowView rv, floa
 template <int NV4, int SMAX>
 static void expand_reg_launch(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                               float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
-                              float *delta_nb, const int *pairs_dev) {
+                              float *delta_nb, const int *pairs_dev, int pair_base) {
     hipLaunchKernelGGL((k_expand_reg<NV4, SMAX>), dim3(pairs), dim3(EXP_THREADS), 0, st, d, logits, A, rv, row_lc, dphi,
-                       cand_score, cand_tok, row_stats, delta_nb, pairs_dev);
+                       cand_score, cand_tok, row_stats, delta_nb, pairs_dev, pair_base);
 }
 
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
-                         float *delta_nb, int force_generic, const int *pairs_dev) {
+                         float *delta_nb, int force_generic, const int *pairs_dev, int pair_base) {
     if (pairs <= 0) return hipSuccess;
+    if (pairs_dev && pair_base) return hipErrorInvalidValue;   // (a piece is launched with its size known)
     size_t shm = (size_t)d.V * sizeof(float);
     if (d.V % 4 == 0 && !force_generic) {
 #define TBS_EXPAND_REG(NV4, SMAX)                                                                              \
     {                                                                                                          \
         expand_reg_launch<NV4, SMAX>(st, d, pairs, logits, A, rv, row_lc, dphi, cand_score, cand_tok, row_stats, \
-                                     delta_nb, pairs_dev);                                                     \
+                                     delta_nb, pairs_dev, pair_base);                                          \
         return hipGetLastError();                                                                              \
     }
         const int nv4 = (d.V / 4 + EXP_THREADS - 1) / EXP_THREADS;
@@ -656,9 +678,9 @@ hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *
     }
     if (d.V % 4 == 0)
         hipLaunchKernelGGL(k_expand<true>, dim3(pairs), dim3(EXP_THREADS), shm, st, d, logits, A, rv, row_lc, dphi,
-                           cand_score, cand_tok, row_stats, delta_nb, pairs_dev);
+                           cand_score, cand_tok, row_stats, delta_nb, pairs_dev, pair_base);
     else
         hipLaunchKernelGGL(k_expand<false>, dim3(pairs), dim3(EXP_THREADS), shm, st, d, logits, A, rv, row_lc, dphi,
-                           cand_score, cand_tok, row_stats, delta_nb, pairs_dev);
+                           cand_score, cand_tok, row_stats, delta_nb, pairs_dev, pair_base);
     return hipGetLastError();
 }

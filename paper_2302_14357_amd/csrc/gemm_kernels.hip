@@ -58,7 +58,7 @@ template <int TM, int TN, int WM, int WN, int BK, bool KGUARD>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
             float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
-            int tiles_n, int group_m) {
+            int tiles_n, int group_m, const int *__restrict__ m_begin, const int *__restrict__ m_end) {
     constexpr int NT = 64 * WM * WN;
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr int CH = BK / 8;                                       // 16-byte chunks per LDS row
@@ -70,6 +70,16 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
     const int wm = wave / WN, wn = wave % WN;
     const int xcd = blockIdx.x % GEMM_XCDS, jstride = gridDim.x / GEMM_XCDS;
     int idx = blockIdx.x / GEMM_XCDS;
+    if (m_begin) {
+        // a piece of a larger product: its rows [*m_begin, *m_end) are known on the device only (the
+        // launch was sized for the most the piece can hold); operands and result shift to the piece
+        const int mb = *m_begin, me = *m_end;
+        A += (long)mb * K;
+        C += (long)mb * ldc;
+        M = me - mb;
+        if (M <= 0) return;
+        tiles_m = (M + BM - 1) / BM;
+    }
     int tile_m, tile_n;
     if (!gemm_tile_of(xcd, idx, tiles_m, tiles_n, group_m, tile_m, tile_n)) return;
 
@@ -278,7 +288,8 @@ k_gemm_bf16(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const fl
 
 template <int TM, int TN, int WM, int WN, int BK, int OCC>
 static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                              int N, int K, const int *out_row, long ldc) {
+                              int N, int K, const int *out_row, long ldc, const int *m_begin = nullptr,
+                              const int *m_end = nullptr) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const size_t shm = 2u * (BM + BN) * BK * sizeof(bf16_t);
@@ -299,10 +310,10 @@ static hipError_t gemm_launch(hipStream_t st, const bf16_t *A, const bf16_t *B, 
     const dim3 grid((unsigned)g), block(64 * WM * WN);
     if (K % BK == 0)
         hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, BK, false>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
-                           ldc, tiles_m, tiles_n, GEMM_GROUP_M);
+                           ldc, tiles_m, tiles_n, GEMM_GROUP_M, m_begin, m_end);
     else
         hipLaunchKernelGGL((k_gemm_bf16<TM, TN, WM, WN, BK, true>), grid, block, shm, st, A, B, bias, C, M, N, K, out_row,
-                           ldc, tiles_m, tiles_n, GEMM_GROUP_M);
+                           ldc, tiles_m, tiles_n, GEMM_GROUP_M, m_begin, m_end);
     return hipGetLastError();
 }
 
@@ -681,4 +692,17 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
         case 3: return gemm_launch<4, 2, 2, 4, 64, 1>(st, A, B, bias, C, M, N, K, out_row, ldc);   // 256x256, 8 waves
         default: return hipErrorInvalidValue;
     }
+}
+
+// One piece of a large product: rows [*m_begin, *m_end) of A and C, the two bounds read from device
+// memory by the kernel; m_max (at least the piece's rows) sizes the launch.  Persistent kernel only.
+hipError_t launch_gemm_bf16_rows(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C,
+                                 int m_max, int N, int K, long ldc, const int *m_begin, const int *m_end) {
+    if (m_max <= 0) return hipSuccess;
+    if (!m_begin || !m_end) return hipErrorInvalidValue;
+    const long t256 = (long)((m_max + 255) / 256) * ((N + 255) / 256);
+    const long t128 = (long)((m_max + 127) / 128) * ((N + 127) / 128);
+    if (t256 >= 384) return gemm_launch<4, 2, 2, 4, 64, 1>(st, A, B, bias, C, m_max, N, K, nullptr, ldc, m_begin, m_end);
+    if (t128 >= 256) return gemm_launch<2, 2, 2, 2, 64, 2>(st, A, B, bias, C, m_max, N, K, nullptr, ldc, m_begin, m_end);
+    return gemm_launch<1, 1, 2, 2, 64, 4>(st, A, B, bias, C, m_max, N, K, nullptr, ldc, m_begin, m_end);
 }

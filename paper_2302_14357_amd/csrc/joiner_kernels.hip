@@ -28,10 +28,12 @@ __device__ __forceinline__ float joiner_act(float x, int act) { return act == 0 
 __global__ void k_joiner_prep_bf16(int rows, int Dj, int act, const bf16_t *__restrict__ enc,
                                    const float *__restrict__ pool_p, const int *__restrict__ row_enc,
                                    const int *__restrict__ row_slot, bf16_t *__restrict__ amat,
-                                   const int *__restrict__ rows_dev) {
+                                   const int *__restrict__ rows_dev, const int *__restrict__ row_begin) {
+    // (row_begin not null: the rows [*row_begin, *rows_dev) only, one piece of a large call)
+    const int r0 = row_begin ? *row_begin : 0;
     if (rows_dev) rows = *rows_dev;
     int chunks = Dj / 8;
-    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x + (long)r0 * chunks;
     if (idx >= (long)rows * chunks) return;
     int r = (int)(idx / chunks), c = (int)(idx % chunks);
     const uint4 ev = *reinterpret_cast<const uint4 *>(enc + (long)row_enc[r] * Dj + c * 8);
@@ -64,12 +66,13 @@ __global__ void k_joiner_prep_f32(int rows, int Dj, int act, const float *__rest
 }
 
 hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
-                              const float *pool_p, RowView rv, void *amat, const int *rows_dev) {
+                              const float *pool_p, RowView rv, void *amat, const int *rows_dev, const int *row_begin) {
     if (rows <= 0) return hipSuccess;
+    if (row_begin && (dtype != 1 || !rows_dev)) return hipErrorInvalidValue;
     if (dtype == 1) {
         long n = (long)rows * (d.Dj / 8);
         hipLaunchKernelGGL(k_joiner_prep_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rows, d.Dj, act,
-                           (const bf16_t *)enc, pool_p, rv.row_enc, rv.row_slot, (bf16_t *)amat, rows_dev);
+                           (const bf16_t *)enc, pool_p, rv.row_enc, rv.row_slot, (bf16_t *)amat, rows_dev, row_begin);
     } else {
         long n = (long)rows * d.Dj;
         hipLaunchKernelGGL(k_joiner_prep_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rows, d.Dj, act,

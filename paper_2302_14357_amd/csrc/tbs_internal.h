@@ -112,14 +112,18 @@ hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const in
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
                           int2 *nodes, int assign_nodes, int *host_counts, int seq, const float *gather_h = nullptr,
                           bf16_t *gather_xh = nullptr);
+// row_begin (bf16 only, with rows_dev): only the rows [*row_begin, *rows_dev), `rows` sizing the launch
 hipError_t launch_joiner_prep(hipStream_t st, const Dims &d, int dtype, int act, int rows, const void *enc,
-                              const float *pool_p, RowView rv, void *amat, const int *rows_dev = nullptr);
+                              const float *pool_p, RowView rv, void *amat, const int *rows_dev = nullptr,
+                              const int *row_begin = nullptr);
 hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const float *bias, float *C, int M, int N,
                            int K, const int *out_row, long ldc);
 // m_dev (launch_gemm_bf16 only where gemm_small_fits; the fused forms always): the launch is enqueued
 // before the host knows the row count; M is an upper bound and the count is read from *m_dev
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
                             int N, int K, const int *out_row, long ldc, int kernel = 0, const int *m_dev = nullptr);
+hipError_t launch_gemm_bf16_rows(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C,
+                                 int m_max, int N, int K, long ldc, const int *m_begin, const int *m_end);
 bool gemm_small_fits(int M, int N, int K);
 // true if launch_gemm_lstm can run this problem (small, K a multiple of 128 that fits the LDS stages)
 bool gemm_lstm_fits(int M, int H, int K);
@@ -132,7 +136,7 @@ hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, co
 hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
-                         float *delta_nb, int force_generic, const int *pairs_dev = nullptr);
+                         float *delta_nb, int force_generic, const int *pairs_dev = nullptr, int pair_base = 0);
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes);

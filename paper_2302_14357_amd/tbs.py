@@ -40,7 +40,7 @@ class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "d_joint", "vocab", "blank_id", "beam_n", "seg_s", "max_utts", "max_frames_total", "pred_layers",
         "pred_hidden", "pred_embed", "act", "dtype", "max_rounds_per_segment", "rounds_capacity", "max_nodes",
-        "debug", "stream_buffer_frames", "max_result_len", "device_id")] + [("stream", C.c_void_p)]
+        "debug", "stream_buffer_frames", "max_result_len", "joiner_chunk_rows", "device_id")] + [("stream", C.c_void_p)]
 
 
 class _Weights(C.Structure):
@@ -117,7 +117,7 @@ class Tbs:
     def __init__(self, model: dict, *, blank_id: int, beam_n: int, seg_s: int, max_utts: int,
                  max_frames_total: int, dtype: str = "bf16", act: str = "tanh", max_rounds_per_segment: int = 0,
                  rounds_capacity: int = 0, max_nodes: int = 0, debug: int = 0, stream_buffer_frames: int = 0,
-                 max_result_len: int = 0, device: int = 0, stream=None):
+                 max_result_len: int = 0, joiner_chunk_rows: int = 0, device: int = 0, stream=None):
         import torch
         self.torch = torch
         self.L = load_library()
@@ -153,7 +153,7 @@ class Tbs:
         self.stream = stream if stream is not None else torch.cuda.Stream(self.device)
         cfg = _Config(Dj, V, blank_id, beam_n, seg_s, max_utts, max_frames_total, L_, H, E,
                       {"tanh": 0, "relu": 1}[act], 1 if dtype == "bf16" else 0, max_rounds_per_segment,
-                      rounds_capacity, max_nodes, int(debug), int(stream_buffer_frames), int(max_result_len), device,
+                      rounds_capacity, max_nodes, int(debug), int(stream_buffer_frames), int(max_result_len), int(joiner_chunk_rows), device,
                       self.stream.cuda_stream)
         torch.cuda.synchronize(self.device)
         self.ctx = C.c_void_p()

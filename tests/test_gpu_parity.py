@@ -68,13 +68,13 @@ def _teacher_forced_state(rng, U, N, S, Dj):
 _EXPAND_DEBUG = {"auto": 1, "generic": 3}   # tbs_config.debug: statistics kept + kernel choice
 
 
-def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, kernel="auto", flat=False):
+def _check_joiner_expand(shape, U, N, S, seg, sample_pairs=None, tol=1e-3, kernel="auto", flat=False, **kw):
     model, offsets, enc = build_case(shape, n_utts=U)
     if flat:   # every logit equal: every expansion ties, the smallest tokens must win
         model["w_out"] = np.zeros_like(model["w_out"])
         model["b_out"] = np.zeros_like(model["b_out"])
     W = oracle_weights(shape, model)
-    tbs = make_tbs(shape, model, offsets, N, S, debug=_EXPAND_DEBUG[kernel])
+    tbs = make_tbs(shape, model, offsets, N, S, debug=_EXPAND_DEBUG[kernel], **kw)
     enc_dev = tbs.upload_frames(enc)
     rng = np.random.default_rng(11)
     counts, pred, dhat, logs = _teacher_forced_state(rng, U, N, S, shape.d_joint)
@@ -179,6 +179,24 @@ def test_joiner_expand_assistant_full_width_sampled():
     """Large-assistant widths (V=4096, Dj=1024, N=10, S=3) with a multi-tile row count."""
     _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=6)
     _check_joiner_expand(SHAPES["assistant"].with_utts(48), U=48, N=10, S=3, seg=5, sample_pairs=4, kernel="generic")
+
+
+@pytest.mark.parametrize("kernel", ["auto", "generic"])
+@pytest.mark.parametrize("N,S,chunk", [(5, 3, 16), (10, 5, 37), (3, 50, 60), (4, 12, 1), (6, 2, 7)])
+def test_joiner_expand_in_pieces(N, S, chunk, kernel):
+    """A joiner call run in pieces (input rows, GEMM and expansion of some hypotheses, then of the
+    next): piece sizes that are no multiple of the segment size, ragged last segments, a piece of a
+    single hypothesis, finished utterances in the batch."""
+    shape = small_bf16_shape(n_utts=5, vocab=200, d=128, hidden=64)
+    _check_joiner_expand(shape, U=5, N=N, S=S, seg=1 if S < 20 else 0, kernel=kernel, joiner_chunk_rows=chunk)
+
+
+def test_joiner_expand_throughput_shape_in_pieces():
+    """The largest configuration's widths with ~8000 rows in two pieces of 6144 rows at most: each
+    piece runs on the 256x256-tile persistent GEMM over a row range read from device memory."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES["throughput"], n_utts=320, len_lo=25, len_hi=25)
+    _check_joiner_expand(shape, U=320, N=10, S=5, seg=3, sample_pairs=10, joiner_chunk_rows=6144)
 
 
 def test_joiner_expand_throughput_shape_sampled():
@@ -716,6 +734,18 @@ def test_decode_large_batch_contains_the_small_one(name, N, S, U):
     ref2 = _oracle_decode(shape, model, offp, encp, N, S)
     assert_all_agree(full2[:8], ref2, score_tol, tol)
     print(f"{name}: identical {same}/{tot} whole, strict prefix frames {int(keep.sum())}/{int(off8[-1])}")
+
+
+@pytest.mark.parametrize("chunk", [1, 11, 40])
+def test_decode_with_joiner_calls_in_pieces(chunk):
+    """Whole decodes whose every joiner call of more than `chunk` rows runs in pieces."""
+    shape = small_bf16_shape(n_utts=6, vocab=64, d=64, hidden=64, layers=2)
+    lengths = np.array([0, 1, 2, 7, 12, 23])
+    model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
+    _check_decode(shape, model, offsets, enc, 5, 3, joiner_chunk_rows=chunk)
+    whole, _ = _gpu_decode(shape, model, offsets, enc, 5, 3, joiner_chunk_rows=0)
+    parts, _ = _gpu_decode(shape, model, offsets, enc, 5, 3, joiner_chunk_rows=chunk)
+    assert whole == parts      # the same arithmetic per row, whatever the pieces
 
 
 @pytest.mark.parametrize("N,S", [(32, 2), (17, 3)])
