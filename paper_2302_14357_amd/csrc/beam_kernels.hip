@@ -9,31 +9,7 @@
 // hypothesis carries its node, length and a 64-bit hash; two hypotheses are
 // "the same tokens" when hash and length agree and a walk up the trie agrees.
 #include "tbs_internal.h"
-
-#define WAVE 64
-
-// log(exp(a) + exp(b)); the correction term lies in [0, log 2] and is taken in fp32
-// (absolute error ~1e-7, far inside the score tolerance), the sum stays fp64
-__device__ __forceinline__ double log_add(double a, double b) {
-    double mx = a > b ? a : b, mn = a > b ? b : a;
-    if (isinf(mx)) return mx;
-    return mx + (double)log1pf(expf((float)(mn - mx)));
-}
-
-__device__ __forceinline__ u64 hash_append(u64 h, int token) {
-    return (h ^ (u64)(unsigned)(token + 1)) * 0x100000001B3ull + 0x9E3779B97F4A7C15ull;
-}
-
-__device__ bool same_sequence(const int2 *nodes, int a, int b) {
-    // both sequences have the same length, so the walks reach the root together
-    while (a != b) {
-        int2 na = nodes[a], nb = nodes[b];
-        if (na.y != nb.y) return false;
-        a = na.x;
-        b = nb.x;
-    }
-    return true;
-}
+#include "select_device.h"
 
 // Figures for the host go out as uncached system-scope stores into pinned host memory, which the
 // host polls while the stream runs on.
@@ -395,203 +371,20 @@ hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt
 // with one round of parallel loads, all list work happens there, and B and the
 // new A are written back once, so the kernel costs a handful of memory round
 // trips instead of one per list operation.
-#define CAND_MAX (TBS_MAX_BEAM * TBS_MAX_BEAM)
 
 __global__ void __launch_bounds__(WAVE)
 k_select_merge(Dims d, int round, int drop, const float *logits, const float *row_lc,
                const float *dphi, const float *cand_score, const int *cand_tok, AView A, AView An, BView B,
                RowView rv, const int2 *nodes) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // B list of this utterance
-    double *s_blogs = reinterpret_cast<double *>(s_dyn);
-    u64 *s_bhash = reinterpret_cast<u64 *>(s_blogs + d.BCAP);
-    int *s_bnode = reinterpret_cast<int *>(s_bhash + d.BCAP);
-    int *s_blen = s_bnode + d.BCAP;
-    int *s_bslot = s_blen + d.BCAP;
-    __shared__ double s_key[CAND_MAX];
-    __shared__ int s_ctok[CAND_MAX];
-    __shared__ double s_alogs[TBS_MAX_BEAM];
-    __shared__ u64 s_ahash[TBS_MAX_BEAM];
-    __shared__ int s_anode[TBS_MAX_BEAM], s_alen[TBS_MAX_BEAM], s_aslot[TBS_MAX_BEAM];
-    __shared__ double s_bkey[TBS_MAX_BEAM];
-    __shared__ int s_match[TBS_MAX_BEAM];
-    __shared__ int s_sel[TBS_MAX_BEAM];      // candidate index by rank
-    __shared__ int s_keep[TBS_MAX_BEAM];
-    __shared__ double s_thr;
-    __shared__ float s_dnew[TBS_MAX_SEG * TBS_MAX_BEAM];   // frame distributions of the new hypotheses, [frame][hypothesis]
-    const int u = blockIdx.x, lane = threadIdx.x;
-    const int N = d.N;
-    // everything that describes the utterance in one round of loads
-    const int sp = rv.utt_sp[u], cntA = A.count[u], pair0 = rv.utt_pair0[u], urow0 = rv.utt_row0[u];
-    const int nB0 = B.count[u], parity = rv.utt_par[u];
-    const int H = sp > 0 ? cntA : 0;
-    if (H == 0) {
-        if (lane == 0) An.count[u] = 0;
-    } else {
-        const long bbase = (long)u * d.BCAP;
-        int nB = nB0;
-        // --- stage B, A and the candidates
-        for (int i = lane; i < nB0; i += WAVE) {
-            s_blogs[i] = B.logs[bbase + i];
-            s_bhash[i] = B.hash[bbase + i];
-            s_bnode[i] = B.node[bbase + i];
-            s_blen[i] = B.len[bbase + i];
-            s_bslot[i] = B.slot[bbase + i];
-        }
-        if (lane < H) {
-            const long a = (long)u * N + lane;
-            const double al = A.logs[a];
-            s_alogs[lane] = al;
-            s_ahash[lane] = A.hash[a];
-            s_anode[lane] = A.node[a];
-            s_alen[lane] = A.len[a];
-            s_aslot[lane] = A.slot[a];
-            s_bkey[lane] = al + (double)dphi[pair0 + lane];   // score of the blank expansion (dphi holds log delta_blank)
-        }
-        if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
-        const int nc = H * N;
-        for (int c = lane; c < nc; c += WAVE) {
-            s_ctok[c] = cand_tok[(long)pair0 * N + c];
-            s_key[c] = (double)cand_score[(long)pair0 * N + c];
-        }
-        __syncthreads();
-        for (int c = lane; c < nc; c += WAVE) s_key[c] = s_ctok[c] >= 0 ? s_alogs[c / N] + s_key[c] : nan("");
-
-        // --- AddAndMerge of every blank expansion.  The hypotheses of A are distinct sequences and so
-        // are the entries of B, so each hypothesis matches at most one old entry and no entry added in
-        // this round: all (hypothesis, entry) pairs are tested at once, matched scores are summed in
-        // place, and the unmatched hypotheses are appended in hypothesis order.
-        if (lane < H) s_match[lane] = -1;
-        __syncthreads();
-        for (int c = lane; c < H * nB0; c += WAVE) {
-            const int h = c / nB0, i = c - h * nB0;
-            if (s_bhash[i] == s_ahash[h] && s_blen[i] == s_alen[h] && same_sequence(nodes, s_bnode[i], s_anode[h]))
-                s_match[h] = i;
-        }
-        __syncthreads();
-        {
-            const bool unmatched = lane < H && s_match[lane] < 0;
-            const u64 um = __ballot(unmatched);
-            const int n_new = __popcll(um);
-            if (lane < H) {
-                if (!unmatched) {
-                    const int f = s_match[lane];
-                    s_blogs[f] = log_add(s_blogs[f], s_bkey[lane]);
-                } else {
-                    const int pos = nB0 + __popcll(um & ((1ull << lane) - 1ull));
-                    if (pos < d.BCAP) {
-                        s_blogs[pos] = s_bkey[lane];
-                        s_bhash[pos] = s_ahash[lane];
-                        s_bnode[pos] = s_anode[lane];
-                        s_blen[pos] = s_alen[lane];
-                        s_bslot[pos] = s_aslot[lane];
-                    } else {
-                        atomicOr(&rv.counts[TBS_CNT_ERR], TBS_ERRF_BCAP);
-                    }
-                }
-            }
-            nB = min(nB0 + n_new, d.BCAP);
-        }
-        __syncthreads();
-        // --- B back to memory: merged scores of old entries, and the new entries
-        for (int i = lane; i < nB; i += WAVE) {
-            B.logs[bbase + i] = s_blogs[i];
-            if (i >= nB0) {
-                B.hash[bbase + i] = s_bhash[i];
-                B.node[bbase + i] = s_bnode[i];
-                B.len[bbase + i] = s_blen[i];
-                B.slot[bbase + i] = s_bslot[i];
-            }
-        }
-        if (lane == 0) B.count[u] = nB;
-
-        // --- threshold = ChooseNthScore(B, N), only defined when B holds N entries.  The rank of an
-        // entry is the number of entries that beat it (larger score, or equal score and earlier
-        // place); every lane counts for its own entries against the whole list, read from LDS at
-        // one address for all lanes.  (Ranking by one ballot per entry was measured at ~270 ns per
-        // entry on the single wave: readlane and ballot results are needed at once, so nothing
-        // overlaps.)
-        const bool have_thr = nB >= N;
-        if (have_thr) {
-            for (int i = lane; i < nB; i += WAVE) {
-                const double si = s_blogs[i];
-                int rank = 0;
-#pragma unroll 4
-                for (int j = 0; j < nB; ++j) {
-                    const double sj = s_blogs[j];
-                    rank += (sj > si) || (sj == si && j < i);
-                }
-                if (rank == N - 1) s_thr = si;
-            }
-        }
-        // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates, ranked the
-        // same way: larger score first, then the earlier hypothesis, then the smaller token.  The N
-        // candidates of a hypothesis arrive sorted by exactly that rule, hypotheses in order, so
-        // "earlier place" decides equal scores.
-        for (int c = lane; c < nc; c += WAVE) {
-            const double kc = s_key[c];
-            if (kc != kc) continue;  // no candidate in this place
-            int rank = 0;
-#pragma unroll 4
-            for (int j = 0; j < nc; ++j) {
-                const double kj = s_key[j];   // (a place without a candidate holds NaN and never compares as better)
-                rank += kj > kc || (kj == kc && j < c);
-            }
-            if (rank < N) s_sel[rank] = c;
-        }
-        __syncthreads();
-        // --- threshold test, in rank order: keep iff |B| < N or score > threshold (strict)
-        const double thr = have_thr ? s_thr : 0.0;
-        if (lane < N) {
-            const int c = s_sel[lane];
-            if (c >= 0) s_keep[lane] = (!have_thr) || (s_key[c] > thr);
-        }
-        __syncthreads();
-        if (drop) {
-            if (lane == 0) An.count[u] = 0;
-        } else {
-            int pos = 0, total = 0;
-            for (int r = 0; r < N; ++r) {
-                const int k = s_keep[r];
-                if (r < lane) pos += k;
-                total += k;
-            }
-            if (lane == 0) An.count[u] = total;
-            if (lane < N && s_keep[lane]) {
-                const int c = s_sel[lane];
-                const int h = c / N;
-                const int tok = s_ctok[c];
-                const long an = (long)u * N + pos;
-                An.logs[an] = s_key[c];
-                An.pnode[an] = s_anode[h];
-                An.node[an] = -1;
-                An.token[an] = tok;
-                An.hash[an] = hash_append(s_ahash[h], tok);
-                An.len[an] = s_alen[h] + 1;
-                An.pslot[an] = s_aslot[h];
-                An.slot[an] = tbs_slot_id(u, parity, round, pos, d.R, N);
-                // d of the new hypothesis (Eq. 5 for the chosen token), normalised by its sum (Eq. 6)
-                const int row0 = urow0 + h * sp;
-                // (kept as logarithms: over a long segment d spans more than the range of float, and
-                // the small entries matter to the next blank expansion)
-                // The S' values wait in LDS (frame-major, so the lanes' accesses fall into different
-                // banks) between the pass that reads the logits and the one that writes the normalised
-                // result: going through the result array itself cost two more memory round trips.
-                float *dh = An.dhat + an * d.S;
-                float *sd = s_dnew + lane;
-                float mx = -INFINITY;
-                for (int t = 0; t < sp; ++t) {
-                    const float x = logits[(long)(row0 + t) * d.V + tok] + row_lc[row0 + t];
-                    sd[t * TBS_MAX_BEAM] = x;
-                    mx = fmaxf(mx, x);
-                }
-                float sum = 0.f;
-                for (int t = 0; t < sp; ++t) sum += __expf(sd[t * TBS_MAX_BEAM] - mx);
-                const float lz = mx + __logf(sum);
-                for (int t = 0; t < sp; ++t) dh[t] = sd[t * TBS_MAX_BEAM] - lz;
-                for (int t = sp; t < d.S; ++t) dh[t] = -INFINITY;
-            }
-        }
-    }
+    const int u = blockIdx.x;
+    const int pair0 = rv.utt_pair0[u], urow0 = rv.utt_row0[u];
+    SelectIn in;
+    in.cand_score = cand_score + (long)pair0 * d.N;
+    in.cand_tok = cand_tok + (long)pair0 * d.N;
+    in.dphi = dphi + pair0;
+    in.lc = row_lc + urow0;
+    select_merge_utt(d, round, drop, u, (int)threadIdx.x, logits, in, A, An, B, rv, nodes, s_dyn);
 }
 
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int drop, const float *logits,
