@@ -77,7 +77,9 @@ typedef struct tbs_config {
                                  gather the first LSTM layer's input rows in a kernel of their own,
                                  also where the row list kernel would; bit 6: enqueue the predictor
                                  step only once the host knows how many hypotheses the round
-                                 created, also where it could go out ahead of that (tests cover
+                                 created, also where it could go out ahead of that; bit 7: keep
+                                 expansion and select/merge two kernels inside tbs_decode and
+                                 tbs_push_segment also where one kernel would run both (tests cover
                                  each pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
@@ -234,7 +236,10 @@ int tbs_debug_hyps_noalloc(tbs_ctx *ctx, int32_t group, int32_t *tokens, int32_t
 
 /* ---- timing of one kernel family, for the benchmark ---- */
 enum tbs_kernel_id { TBS_K_JOINER = 0, TBS_K_EXPAND = 1, TBS_K_SELECT = 2, TBS_K_PREDICTOR = 3,
-                     TBS_K_PREP = 4, TBS_K_GEMM = 5, TBS_K_COUNT = 6 };
+                     TBS_K_PREP = 4, TBS_K_GEMM = 5,
+                     TBS_K_ROUND = 6,   /* expansion + select/merge as one kernel (small shapes inside tbs_decode
+                                           and tbs_push_segment; timing TBS_K_EXPAND or TBS_K_SELECT keeps them apart) */
+                     TBS_K_COUNT = 7 };
 /* Bracket every launch of the chosen kernel family (-1: none) with HIP events
  * on the context's stream. */
 int tbs_profile_select(tbs_ctx *ctx, int32_t kernel_id);

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtbs.so")
-SOURCES = ["tbs_api.hip", "beam_kernels.hip", "expand_kernels.hip", "joiner_kernels.hip", "gemm_kernels.hip", "pred_kernels.hip"]
+SOURCES = ["tbs_api.hip", "beam_kernels.hip", "expand_kernels.hip", "joiner_kernels.hip", "gemm_kernels.hip", "pred_kernels.hip", "round_kernels.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-result"]

@@ -689,16 +689,35 @@ int tbs_expand(tbs_ctx *c) {
 static bool predictor_all_fused(const tbs_ctx *c, int M);
 static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part = 0);
 
+// Expansion and select/merge of a round in one kernel (small shapes, see round_kernels.hip)?  Not
+// when the generic expansion kernel is forced, the fusion switched off (debug bit 7), the expansion
+// already done piece by piece behind the joiner, or one of the two steps being timed on its own.
+static bool round_fused_ok(const tbs_ctx *c) {
+    return !(c->cfg.debug & (2 | 128)) && !c->expanded_ahead && c->prof_kernel != TBS_K_EXPAND &&
+           c->prof_kernel != TBS_K_SELECT && round_fits(c->cur);
+}
+
+static int select_merge_impl(tbs_ctx *c, int32_t *live_host, bool fused);
+
 int tbs_select_merge(tbs_ctx *c, int32_t *live_host) {
     if (!c) return TBS_EINVAL;
     if (c->state != ST_EXPANDED) return TBS_ESTATE;
+    return select_merge_impl(c, live_host, false);
+}
+
+// fused: the state is "joined"; one kernel runs the expansion and select/merge
+static int select_merge_impl(tbs_ctx *c, int32_t *live_host, bool fused) {
     AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];
     const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
     bool gathered = false;
     {
-        ProfScope ps(c, TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
-        HIPCHK(c, launch_select_merge(c->stream, c->cur, c->round, drop, c->logits, c->row_lc, c->dphi,
-                                      c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes));
+        ProfScope ps(c, fused ? TBS_K_ROUND : TBS_K_SELECT, c->h_counts[TBS_CNT_PAIRS]);
+        if (fused)
+            HIPCHK(c, launch_round(c->stream, c->cur, c->round, drop, c->logits, A, An, c->B, c->rv, c->nodes,
+                                   c->row_stats, c->delta_nb));
+        else
+            HIPCHK(c, launch_select_merge(c->stream, c->cur, c->round, drop, c->logits, c->row_lc, c->dphi,
+                                          c->cand_score, c->cand_tok, A, An, c->B, c->rv, c->nodes));
         // small batches: the row list kernel also writes the first LSTM layer's input rows
         const bool fused_gather = c->emb_gates && !(c->cfg.debug & 32) && (c->cur.H & 3) == 0 &&
                                   (long)c->cur.U * c->cur.N <= 1024;
@@ -898,11 +917,16 @@ static int segment_begin_ahead(tbs_ctx *c, int32_t seg_index) {
     HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, c->logits,
                                d.U * d.N * d.S, d.V, d.Dj, nullptr, d.V, 0, rows_dev));
     c->n_launches += 1;
-    HIPCHK(c, launch_expand(c->stream, d, d.U * d.N, c->logits, A, c->rv, c->row_lc, c->dphi, c->cand_score,
-                            c->cand_tok, c->row_stats, c->delta_nb, (c->cfg.debug & 2) != 0, pairs_dev));
     const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
-    HIPCHK(c, launch_select_merge(c->stream, d, c->round, drop, c->logits, c->row_lc, c->dphi, c->cand_score,
-                                  c->cand_tok, A, An, c->B, c->rv, c->nodes));
+    if (round_fused_ok(c)) {
+        HIPCHK(c, launch_round(c->stream, d, c->round, drop, c->logits, A, An, c->B, c->rv, c->nodes, c->row_stats,
+                               c->delta_nb));
+    } else {
+        HIPCHK(c, launch_expand(c->stream, d, d.U * d.N, c->logits, A, c->rv, c->row_lc, c->dphi, c->cand_score,
+                                c->cand_tok, c->row_stats, c->delta_nb, (c->cfg.debug & 2) != 0, pairs_dev));
+        HIPCHK(c, launch_select_merge(c->stream, d, c->round, drop, c->logits, c->row_lc, c->dphi, c->cand_score,
+                                      c->cand_tok, A, An, c->B, c->rv, c->nodes));
+    }
     const bool fused_gather = !(c->cfg.debug & 32) && (d.H & 3) == 0 && (long)d.U * d.N <= 1024;
     HIPCHK(c, launch_rowfill(c->stream, d, c->seg, c->utt_off, An, c->rv, c->nodes, 1, c->h_counts_dev, ++c->seq,
                              fused_gather ? c->pool_h : nullptr, fused_gather ? (bf16_t *)c->xh[0] : nullptr));
@@ -924,6 +948,14 @@ static int segment_begin_ahead(tbs_ctx *c, int32_t seg_index) {
     return check_err_flags(c);
 }
 
+// expansion and select/merge behind a joiner call: one kernel where the shape allows, else two
+static int expand_select(tbs_ctx *c, int32_t *live) {
+    if (c->state != ST_JOINED) return TBS_ESTATE;
+    if (round_fused_ok(c)) return select_merge_impl(c, live, true);
+    const int rc = tbs_expand(c);
+    return rc ? rc : tbs_select_merge(c, live);
+}
+
 // one segment: the head of the outer loop of Algorithm 1 and its inner loop (while Length(A) > 0)
 static int run_segment(tbs_ctx *c, int32_t seg_index) {
     int rc, rows = 0, live = 0;
@@ -933,15 +965,13 @@ static int run_segment(tbs_ctx *c, int32_t seg_index) {
         if ((rc = segment_begin(c, seg_index, &rows))) return rc;
         if (rows == 0) return TBS_OK;
         if ((rc = tbs_joiner_segment(c))) return rc;
-        if ((rc = tbs_expand(c))) return rc;
-        if ((rc = tbs_select_merge(c, &live))) return rc;
+        if ((rc = expand_select(c, &live))) return rc;
     }
     for (;;) {
         if ((rc = tbs_predictor_step(c))) return rc;
         if (c->h_counts[TBS_CNT_ROWS] == 0) return TBS_OK;
         if ((rc = tbs_joiner_segment(c))) return rc;
-        if ((rc = tbs_expand(c))) return rc;
-        if ((rc = tbs_select_merge(c, &live))) return rc;
+        if ((rc = expand_select(c, &live))) return rc;
     }
 }
 

@@ -140,6 +140,11 @@ hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int drop, const float *logits,
                                const float *row_lc, const float *dphi, const float *cand_score,
                                const int *cand_tok, AView A, AView An, BView B, RowView rv, const int2 *nodes);
+// expansion and select/merge of a round in one kernel, a workgroup per utterance (small shapes:
+// round_fits says whether the shape is served)
+bool round_fits(const Dims &d);
+hipError_t launch_round(hipStream_t st, const Dims &d, int round, int drop, const float *logits, AView A, AView An,
+                        BView B, RowView rv, const int2 *nodes, float *row_stats, float *delta_nb);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
                               const void *embed, const float *pool_h, void *xh);
 hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, const float *pool_h,

@@ -27,7 +27,7 @@ class BUF:
 
 
 class KERNEL:
-    JOINER, EXPAND, SELECT, PREDICTOR, PREP, GEMM = range(6)
+    JOINER, EXPAND, SELECT, PREDICTOR, PREP, GEMM, ROUND = range(7)
 
 
 class TbsError(RuntimeError):

@@ -736,6 +736,31 @@ def test_decode_large_batch_contains_the_small_one(name, N, S, U):
     print(f"{name}: identical {same}/{tot} whole, strict prefix frames {int(keep.sum())}/{int(off8[-1])}")
 
 
+@pytest.mark.parametrize("N,S,V,peaked", [(3, 3, 96, False), (4, 5, 1024, False), (5, 3, 1024, False), (8, 5, 512, True),
+                                          (10, 3, 1024, False), (16, 4, 200, True), (5, 3, 96, True), (2, 1, 64, True)])
+def test_round_in_one_kernel_equals_separate_kernels(N, S, V, peaked):
+    """Inside tbs_decode, expansion and select/merge of a round run as one kernel (a workgroup per
+    utterance) where the shape allows; debug bit 7 keeps them two kernels.  Beam widths and
+    vocabularies that take each of the kernel's team sizes (4, 2 and 1 waves per hypothesis), ragged
+    utterances, flat and peaked models: the two forms must give the same hypotheses, and the
+    one-kernel form is checked against the oracle."""
+    shape = small_bf16_shape(n_utts=6, vocab=V, d=128, hidden=128)
+    cap = 0
+    if peaked:
+        shape, cap = _peaked(shape, 8.0, 8.0), 5
+    lengths = np.array([0, 2, 7, 12, 23, 31])
+    model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
+    kw = dict(max_rounds_per_segment=cap) if cap else {}
+    one, st1 = _gpu_decode(shape, model, offsets, enc, N, S, **kw)
+    two, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=128, **kw)
+    for a, b in zip(one, two):
+        assert [h[0] for h in a] == [h[0] for h in b]
+        np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-6, atol=1e-5)
+    assert st1["joiner_calls"] == st2["joiner_calls"] and st1["joined_frames"] == st2["joined_frames"]
+    _check_decode(shape, model, offsets, enc, N, S, max_rounds=cap)
+    _check_decode(shape, model, offsets, enc, N, S, max_rounds=cap, debug=128)
+
+
 @pytest.mark.parametrize("chunk", [1, 11, 40])
 def test_decode_with_joiner_calls_in_pieces(chunk):
     """Whole decodes whose every joiner call of more than `chunk` rows runs in pieces."""
