@@ -79,8 +79,11 @@ typedef struct tbs_config {
                                  step only once the host knows how many hypotheses the round
                                  created, also where it could go out ahead of that; bit 7: keep
                                  expansion and select/merge two kernels inside tbs_decode and
-                                 tbs_push_segment also where one kernel would run both (tests cover
-                                 each pair of variants) */
+                                 tbs_push_segment also where one kernel would run both; bit 8: keep the
+                                 row lists (hypotheses and joiner rows compacted over the batch by a
+                                 kernel of its own every round) also where a small batch would run with
+                                 every hypothesis in a fixed place and no such kernel (tests cover each
+                                 pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

@@ -11,12 +11,6 @@
 #include "tbs_internal.h"
 #include "select_device.h"
 
-// Figures for the host go out as uncached system-scope stores into pinned host memory, which the
-// host polls while the stream runs on.
-__device__ __forceinline__ void store_host(int *p, int v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-}
-
 // ------------------------------------------------------------------ batch init
 __global__ void k_init_batch(Dims d, BView B, AView A0, AView A1, RowView rv, int2 *nodes, float *pool_p,
                              float *pool_h, float *pool_c, const float *pred_init, long pool_rows) {
@@ -76,7 +70,7 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 #define SEG_BATCH 5    // survivors whose rows a thread has in flight together in the state copy
 __global__ void __launch_bounds__(SEG_THREADS)
 k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv, float *pool_p,
-                float *pool_h, float *pool_c, long pool_rows) {
+                float *pool_h, float *pool_c, long pool_rows, FixedView fx) {
     __shared__ int s_src[TBS_MAX_BEAM], s_dst[TBS_MAX_BEAM];
     __shared__ int s_n;
     const int u = blockIdx.x, tid = threadIdx.x;
@@ -97,8 +91,17 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
         rv.utt_sp[u] = sp;
         s_n = 0;
     }
+    if (fx.on && tid == 0) {
+        rv.utt_pair0[u] = u * d.N;
+        rv.utt_row0[u] = u * d.N * d.S;
+        if (u == 0) fx.live_sum[(fx.seq + 1) & 1] = 0;   // the counter of the launch after this one
+    }
     if (sp == 0) {  // finished (or empty) utterance: B keeps the final list
         if (tid == 0) A.count[u] = 0;
+        if (fx.on) {
+            if (tid < d.N) pair_mark_dead(rv, u * d.N + tid, u, d.S);
+            if (tid == 0) store_host(fx.host_live + (fx.seq & 1) * d.U + u, fx.seq << 8);
+        }
         return;
     }
     const int parity = par_old ^ 1;   // the arena the survivors are not in
@@ -140,6 +143,28 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
     if (tid == 0) {   // (every thread has read the old values by now)
         rv.utt_par[u] = parity;
         B.count[u] = 0;
+    }
+    if (fx.on) {   // slot layout: this utterance's pair descriptors for the first round, its count to the host
+        const int cnt = s_n;
+        if (tid < d.N) {
+            const int j = u * d.N + tid;
+            if (tid < cnt) {
+                rv.pair_u[j] = u;
+                rv.pair_h[j] = tid;
+                rv.pair_row0[j] = j * d.S;
+                rv.pair_len[j] = sp;
+                rv.pair_slot[j] = s_dst[tid];
+                rv.pair_pslot[j] = s_src[tid];
+                rv.pair_frame0[j] = fx.utt_off[u] + seg * d.S;
+                rv.pair_tok[j] = -1;
+            } else {
+                pair_mark_dead(rv, j, u, d.S);
+            }
+        }
+        if (tid == 0) {
+            atomicAdd(fx.live_sum + (fx.seq & 1), cnt);
+            store_host(fx.host_live + (fx.seq & 1) * d.U + u, (fx.seq << 8) | cnt);
+        }
     }
     // The survivors' predictor outputs and LSTM states move to their new slots.  Thread j moves
     // element j (16 bytes where the widths allow) of every survivor's output row and of its h and c
@@ -184,9 +209,12 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
 }
 
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const int *utt_T, BView B,
-                                AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows) {
+                                AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows,
+                                const FixedView *fx) {
+    FixedView f{};
+    if (fx) f = *fx;
     hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(SEG_THREADS), 0, st, d, seg, utt_T, B, A, rv, pool_p,
-                       pool_h, pool_c, pool_rows);
+                       pool_h, pool_c, pool_rows, f);
     return hipGetLastError();
 }
 
@@ -384,6 +412,7 @@ k_select_merge(Dims d, int round, int drop, const float *logits, const float *ro
     in.cand_tok = cand_tok + (long)pair0 * d.N;
     in.dphi = dphi + pair0;
     in.lc = row_lc + urow0;
+    in.slot_rows = 0;
     select_merge_utt(d, round, drop, u, (int)threadIdx.x, logits, in, A, An, B, rv, nodes, s_dyn);
 }
 

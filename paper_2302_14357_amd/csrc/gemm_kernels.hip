@@ -355,7 +355,8 @@ template <int MODE>
 __global__ void __launch_bounds__(256)
 k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
              float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
-             int tiles_n, int ns, LstmEp ep, JoinEp jp, const int *__restrict__ m_dev) {
+             int tiles_n, int ns, LstmEp ep, JoinEp jp, const int *__restrict__ m_dev,
+             const int *__restrict__ any_dev) {
     constexpr bool LSTM = MODE == 1;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // ns stages
     const int tid = threadIdx.x, lane = tid & 63;
@@ -419,6 +420,9 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     asm volatile("" ::: "memory");
     const int m_live = m_dev ? min(*m_dev, M) : M;   // (the same in every lane: a scalar load)
     if (tile_m * 64 >= m_live) return;   // no row of this tile exists (before anything is on its way into LDS)
+    // (slot layout: rows that exist lie anywhere among the M, a dead row has state slot -1; the
+    // launch as a whole leaves when the round made no hypothesis at all)
+    if (any_dev && *any_dev == 0) return;
     const int first = min(ns, kt);
     for (int c = 0; c < first; ++c) fetch(c, c);
     floatx16 acc;
@@ -468,7 +472,7 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         float4 g4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) g4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
-        if (row < m_live && j0 < ep.H) {
+        if (row < m_live && j0 < ep.H && e_ns >= 0) {
             const int H = ep.H;
             // everything the update reads from memory is requested before any of it is used: the
             // parent's cell state, the parent's h of the next layer, the input half of the gates
@@ -540,7 +544,7 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         float4 p4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) p4[q] = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + q * 4);
-        if (row < m_live && c0 < N) {
+        if (row < m_live && c0 < N && e_ns >= 0) {
             const float p[16] = {p4[0].x, p4[0].y, p4[0].z, p4[0].w, p4[1].x, p4[1].y, p4[1].z, p4[1].w,
                                  p4[2].x, p4[2].y, p4[2].z, p4[2].w, p4[3].x, p4[3].y, p4[3].z, p4[3].w};
             for (int t0 = 0; t0 < len; t0 += 4) {
@@ -631,14 +635,14 @@ bool gemm_lstm_fits(int M, int H, int K) {
 }
 
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
-                            const LstmEp &ep, const int *m_dev) {
+                            const LstmEp &ep, const int *m_dev, const int *any_dev) {
     if (M <= 0) return hipSuccess;
     if (!gemm_lstm_fits(M, ep.H, K)) return hipErrorInvalidValue;
     const int N = 4 * ep.H, tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
     hipLaunchKernelGGL(k_gemm_small<1>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, Wp, biasp,
-                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep, JoinEp{}, m_dev);
+                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep, JoinEp{}, m_dev, any_dev);
     return hipGetLastError();
 }
 
@@ -649,14 +653,15 @@ bool gemm_join_fits(int M, int N, int K) {
 }
 
 hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev) {
+                            int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev,
+                            const int *any_dev) {
     if (M <= 0) return hipSuccess;
     if (!gemm_join_fits(M, N, K) || !out_row) return hipErrorInvalidValue;
     const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
     hipLaunchKernelGGL(k_gemm_small<2>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C, M,
-                       N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp, m_dev);
+                       N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp, m_dev, any_dev);
     return hipGetLastError();
 }
 
@@ -673,7 +678,7 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
             const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
             hipLaunchKernelGGL(k_gemm_small<0>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
-                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, m_dev);
+                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, m_dev, nullptr);
             return hipGetLastError();
         }
     }

@@ -54,6 +54,46 @@ __global__ void k_joiner_prep_bf16(int rows, int Dj, int act, const bf16_t *__re
     *reinterpret_cast<uint4 *>(amat + (long)r * Dj + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// The same in the slot layout (pair j owns the rows j*S .. j*S + S - 1 and uses the first
+// pair_len[j] of them): a row's frame and state slot come from its pair's descriptor.
+__global__ void k_joiner_prep_fixed(int rows, int Dj, int S, int act, const bf16_t *__restrict__ enc,
+                                    const float *__restrict__ pool_p, const int *__restrict__ pair_len,
+                                    const int *__restrict__ pair_frame0, const int *__restrict__ pair_slot,
+                                    bf16_t *__restrict__ amat) {
+    const int chunks = Dj / 8;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)rows * chunks) return;
+    const int r = (int)(idx / chunks), c = (int)(idx % chunks);
+    const int j = r / S, t = r - j * S;
+    if (t >= pair_len[j]) return;
+    const long fr = pair_frame0[j] + t, slot = pair_slot[j];
+    const uint4 ev = *reinterpret_cast<const uint4 *>(enc + fr * Dj + c * 8);
+    const float4 p0 = *reinterpret_cast<const float4 *>(pool_p + slot * Dj + c * 8);
+    const float4 p1 = *reinterpret_cast<const float4 *>(pool_p + slot * Dj + c * 8 + 4);
+    const float e[8] = {__uint_as_float(ev.x << 16), __uint_as_float(ev.x & 0xFFFF0000u),
+                        __uint_as_float(ev.y << 16), __uint_as_float(ev.y & 0xFFFF0000u),
+                        __uint_as_float(ev.z << 16), __uint_as_float(ev.z & 0xFFFF0000u),
+                        __uint_as_float(ev.w << 16), __uint_as_float(ev.w & 0xFFFF0000u)};
+    const float p[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+    unsigned o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const unsigned lo = f2bf(tbs_joiner_act(e[2 * i] + p[2 * i], act));
+        const unsigned hi = f2bf(tbs_joiner_act(e[2 * i + 1] + p[2 * i + 1], act));
+        o[i] = lo | (hi << 16);
+    }
+    *reinterpret_cast<uint4 *>(amat + (long)r * Dj + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+hipError_t launch_joiner_prep_fixed(hipStream_t st, const Dims &d, int act, const bf16_t *enc, const float *pool_p,
+                                    RowView rv, bf16_t *amat) {
+    const int rows = d.U * d.N * d.S;
+    const long n = (long)rows * (d.Dj / 8);
+    hipLaunchKernelGGL(k_joiner_prep_fixed, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rows, d.Dj, d.S, act,
+                       enc, pool_p, rv.pair_len, rv.pair_frame0, rv.pair_slot, amat);
+    return hipGetLastError();
+}
+
 __global__ void k_joiner_prep_f32(int rows, int Dj, int act, const float *__restrict__ enc,
                                   const float *__restrict__ pool_p, const int *__restrict__ row_enc,
                                   const int *__restrict__ row_slot, float *__restrict__ amat,

@@ -9,10 +9,16 @@
 #include "expand_device.h"
 #include "select_device.h"
 
+__device__ __forceinline__ unsigned round_bf16(float f) {   // nearest, ties to even
+    unsigned v = __float_as_uint(f);
+    v += 0x7FFFu + ((v >> 16) & 1u);
+    return v >> 16;
+}
+
 template <int TW, int NV4, int SMAX>
 __global__ void __launch_bounds__(1024)
 k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, AView An, BView B, RowView rv,
-        const int2 *nodes, float *__restrict__ row_stats, float *__restrict__ delta_nb) {
+        int2 *nodes, float *__restrict__ row_stats, float *__restrict__ delta_nb, FixedView fx) {
     constexpr int TT = TW * 64;
     typedef ExpandShared<SMAX, TW> TeamShared;
     extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
@@ -28,10 +34,20 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
 
     const int u = blockIdx.x;
     const int team = __builtin_amdgcn_readfirstlane((int)threadIdx.x / TT), tid = (int)threadIdx.x % TT;
+    __shared__ SelectOut s_out;
     const int sp = rv.utt_sp[u];
     const int H = sp > 0 ? A.count[u] : 0;
+    // (asked for now, needed at the end)
+    const int used0 = fx.on ? fx.utt_nodes[u] : 0, ncap = fx.on ? fx.node_cap[u] : 0, nbase = fx.on ? fx.node_base[u] : 0;
     if (H == 0) {   // (the same for the whole workgroup: nobody reaches a barrier)
         if (threadIdx.x == 0) An.count[u] = 0;
+        if (fx.on) {
+            if ((int)threadIdx.x < N) pair_mark_dead(rv, u * N + (int)threadIdx.x, u, d.S);
+            if (threadIdx.x == 0) {
+                if (u == 0) fx.live_sum[(fx.seq + 1) & 1] = 0;
+                store_host(fx.host_live + (fx.seq & 1) * d.U + u, fx.seq << 8);
+            }
+        }
         return;
     }
     const int pair0 = rv.utt_pair0[u];
@@ -60,7 +76,55 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
         in.cand_tok = s_ct;
         in.dphi = s_dphi;
         in.lc = s_lc;
-        select_merge_utt(d, round, drop, u, (int)threadIdx.x, logits, in, A, An, B, rv, nodes, s_raw);
+        in.slot_rows = fx.on;
+        select_merge_utt(d, round, drop, u, (int)threadIdx.x, logits, in, A, An, B, rv, nodes, s_raw, &s_out);
+        if (fx.on) {
+            // Slot layout: what a row list kernel would do for this utterance.  The new hypotheses
+            // take trie nodes from the utterance's own range, their pairs get their descriptors, the
+            // places of A beyond them are marked dead, and the host hears how many there are.
+            sel_sync();
+            const int lane = (int)threadIdx.x, total = s_out.total;
+            bool full = false;
+            if (lane < N) {
+                const int j = u * N + lane;
+                if (lane < total) {
+                    const int tok = s_out.tok[lane];
+                    full = used0 + lane >= ncap;
+                    const int node = full ? 0 : nbase + used0 + lane;
+                    if (!full) nodes[node] = make_int2(s_out.pnode[lane], tok);
+                    An.node[j] = node;
+                    rv.pair_u[j] = u;
+                    rv.pair_h[j] = lane;
+                    rv.pair_row0[j] = j * d.S;
+                    rv.pair_len[j] = sp;
+                    rv.pair_slot[j] = s_out.slot[lane];
+                    rv.pair_pslot[j] = s_out.pslot[lane];
+                    rv.pair_frame0[j] = fx.utt_off[u] + fx.seg * d.S;
+                    rv.pair_tok[j] = tok;
+                } else {
+                    pair_mark_dead(rv, j, u, d.S);
+                }
+            }
+            const bool any_full = __ballot(full) != 0;
+            if (lane == 0) {
+                fx.utt_nodes[u] = min(used0 + total, ncap);
+                if (total) atomicAdd(fx.live_sum + (fx.seq & 1), total);
+                if (u == 0) fx.live_sum[(fx.seq + 1) & 1] = 0;
+                store_host(fx.host_live + (fx.seq & 1) * d.U + u, (fx.seq << 8) | (any_full ? 64 : 0) | total);
+            }
+        }
+    }
+    if (fx.on && fx.xh) {
+        // input rows of the first LSTM layer for the new hypotheses: bf16 of their parents' h
+        __syncthreads();
+        const int total = s_out.total, H4 = d.H >> 2;
+        for (int idx = (int)threadIdx.x; idx < total * H4; idx += (int)blockDim.x) {
+            const int h = idx / H4, i = idx - h * H4;
+            const float4 v = reinterpret_cast<const float4 *>(fx.pool_h + (long)s_out.pslot[h] * d.H)[i];
+            reinterpret_cast<uint2 *>(fx.xh)[(long)(u * N + h) * H4 + i] =
+                make_uint2((unsigned)round_bf16(v.x) | ((unsigned)round_bf16(v.y) << 16),
+                           (unsigned)round_bf16(v.z) | ((unsigned)round_bf16(v.w) << 16));
+        }
     }
 }
 
@@ -78,7 +142,8 @@ bool round_fits(const Dims &d) { return round_variant(d) != 0; }
 
 template <int TW, int NV4, int SMAX>
 static hipError_t round_launch(hipStream_t st, const Dims &d, int round, int drop, const float *logits, AView A,
-                               AView An, BView B, RowView rv, const int2 *nodes, float *row_stats, float *delta_nb) {
+                               AView An, BView B, RowView rv, int2 *nodes, float *row_stats, float *delta_nb,
+                               const FixedView &fx) {
     const size_t b_list = ((size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int)) + 15) & ~(size_t)15;
     const size_t shm = b_list + (size_t)d.N * sizeof(ExpandShared<SMAX, TW>) +
                        sizeof(float) * ((size_t)d.N * SMAX + d.N + 2 * (size_t)d.N * d.N);
@@ -90,19 +155,22 @@ static hipError_t round_launch(hipStream_t st, const Dims &d, int round, int dro
         attr_for = shm;
     }
     hipLaunchKernelGGL((k_round<TW, NV4, SMAX>), dim3(d.U), dim3(d.N * TW * 64), shm, st, d, round, drop, logits, A, An,
-                       B, rv, nodes, row_stats, delta_nb);
+                       B, rv, nodes, row_stats, delta_nb, fx);
     return hipGetLastError();
 }
 
 hipError_t launch_round(hipStream_t st, const Dims &d, int round, int drop, const float *logits, AView A, AView An,
-                        BView B, RowView rv, const int2 *nodes, float *row_stats, float *delta_nb) {
+                        BView B, RowView rv, int2 *nodes, float *row_stats, float *delta_nb, const FixedView *fxp) {
+    FixedView fx{};
+    if (fxp) fx = *fxp;
+    if (fx.on && fx.xh && (d.H & 3)) return hipErrorInvalidValue;
     switch (round_variant(d)) {
-        case 43: return round_launch<4, 1, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb);
-        case 45: return round_launch<4, 1, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb);
-        case 23: return round_launch<2, 2, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb);
-        case 25: return round_launch<2, 2, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb);
-        case 13: return round_launch<1, 4, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb);
-        case 15: return round_launch<1, 4, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb);
+        case 43: return round_launch<4, 1, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 45: return round_launch<4, 1, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 23: return round_launch<2, 2, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 25: return round_launch<2, 2, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 13: return round_launch<1, 4, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 15: return round_launch<1, 4, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
         default: return hipErrorInvalidValue;
     }
 }

@@ -40,6 +40,30 @@ __device__ __forceinline__ void sel_sync() {
 
 #define CAND_MAX (TBS_MAX_BEAM * TBS_MAX_BEAM)
 
+// Figures for the host go out as uncached system-scope stores into pinned host memory, which the
+// host polls while the stream runs on.
+__device__ __forceinline__ void store_host(int *p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// What select_merge_utt leaves in LDS about the list A it made, for a caller that goes on with it.
+struct SelectOut {
+    int total;
+    int slot[TBS_MAX_BEAM], pslot[TBS_MAX_BEAM], tok[TBS_MAX_BEAM], pnode[TBS_MAX_BEAM];
+};
+
+// slot layout: descriptor of a pair that does not exist (every address made from it stays valid)
+__device__ __forceinline__ void pair_mark_dead(const RowView &rv, int j, int u, int S) {
+    rv.pair_u[j] = u;
+    rv.pair_h[j] = 0;
+    rv.pair_row0[j] = j * S;
+    rv.pair_len[j] = 0;
+    rv.pair_slot[j] = -1;
+    rv.pair_pslot[j] = 0;
+    rv.pair_frame0[j] = 0;
+    rv.pair_tok[j] = 0;
+}
+
 // What the expansion step left for this utterance: logarithms and tokens of the N best expansions
 // of each of its hypotheses [H, N], the logarithm of each blank expansion [H], and per frame of each
 // hypothesis log(alpha_t / Z_t) - m_t [H, S'] (any of them in LDS or in device memory).
@@ -48,12 +72,14 @@ struct SelectIn {
     const int *cand_tok;
     const float *dphi;
     const float *lc;
+    int slot_rows;   // 1: hypothesis h of the utterance owns the joiner rows h*S .. (slot layout); 0: rows h*S' ..
 };
 
 // s_dyn: LDS for the utterance's B list, BCAP * (8 + 8 + 3 * 4) bytes, 16-byte aligned
 __device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int drop, int u, int lane,
                                                  const float *logits, SelectIn in, AView A, AView An, BView B,
-                                                 RowView rv, const int2 *nodes, unsigned char *s_dyn) {
+                                                 RowView rv, const int2 *nodes, unsigned char *s_dyn,
+                                                 SelectOut *out = nullptr) {
     double *s_blogs = reinterpret_cast<double *>(s_dyn);
     u64 *s_bhash = reinterpret_cast<u64 *>(s_blogs + d.BCAP);
     int *s_bnode = reinterpret_cast<int *>(s_bhash + d.BCAP);
@@ -76,7 +102,10 @@ __device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int d
     const int nB0 = B.count[u], parity = rv.utt_par[u];
     const int H = sp > 0 ? cntA : 0;
     if (H == 0) {
-        if (lane == 0) An.count[u] = 0;
+        if (lane == 0) {
+            An.count[u] = 0;
+            if (out) out->total = 0;
+        }
     } else {
         const long bbase = (long)u * d.BCAP;
         int nB = nB0;
@@ -198,7 +227,10 @@ __device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int d
         }
         sel_sync();
         if (drop) {
-            if (lane == 0) An.count[u] = 0;
+            if (lane == 0) {
+                An.count[u] = 0;
+                if (out) out->total = 0;
+            }
         } else {
             int pos = 0, total = 0;
             for (int r = 0; r < N; ++r) {
@@ -206,7 +238,17 @@ __device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int d
                 if (r < lane) pos += k;
                 total += k;
             }
-            if (lane == 0) An.count[u] = total;
+            if (lane == 0) {
+                An.count[u] = total;
+                if (out) out->total = total;
+            }
+            if (out && lane < N && s_keep[lane]) {
+                const int c = s_sel[lane], h = c / N;
+                out->slot[pos] = tbs_slot_id(u, parity, round, pos, d.R, N);
+                out->pslot[pos] = s_aslot[h];
+                out->tok[pos] = s_ctok[c];
+                out->pnode[pos] = s_anode[h];
+            }
             if (lane < N && s_keep[lane]) {
                 const int c = s_sel[lane];
                 const int h = c / N;
@@ -214,14 +256,14 @@ __device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int d
                 const long an = (long)u * N + pos;
                 An.logs[an] = s_key[c];
                 An.pnode[an] = s_anode[h];
-                An.node[an] = -1;
+                if (!out) An.node[an] = -1;   // (a caller that takes `out` assigns the node itself)
                 An.token[an] = tok;
                 An.hash[an] = hash_append(s_ahash[h], tok);
                 An.len[an] = s_alen[h] + 1;
                 An.pslot[an] = s_aslot[h];
                 An.slot[an] = tbs_slot_id(u, parity, round, pos, d.R, N);
                 // d of the new hypothesis (Eq. 5 for the chosen token), normalised by its sum (Eq. 6)
-                const int row0 = urow0 + h * sp;
+                const int row0 = urow0 + h * (in.slot_rows ? d.S : sp);
                 // (kept as logarithms: over a long segment d spans more than the range of float, and
                 // the small entries matter to the next blank expansion)
                 // The S' values wait in LDS (frame-major, so the lanes' accesses fall into different

@@ -61,6 +61,15 @@ struct tbs_ctx {
     int pred_ahead;     // predictor kernels of this round already enqueued (see tbs_select_merge): 1 the LSTM layers, 2 all
     bool join_ahead;    // and so is the joiner GEMM of the next round
     bool expanded_ahead; // tbs_joiner_segment already ran the expansion, piece by piece behind the GEMM of each piece
+    // slot layout (small shapes inside tbs_decode / tbs_push_segment, see FixedView)
+    bool fixed;         // the current batch runs in the slot layout
+    int *utt_nodes;     // [U] trie nodes taken by each utterance from its own range
+    int *node_base, *node_cap;   // [U] the ranges
+    int *live_sum;      // [2] hypotheses made per launch, alternating
+    int *h_live;        // pinned [U]: what each utterance's workgroup tells the host
+    int *h_live_dev;    // device view of the same memory
+    std::vector<int> live_u;   // hypotheses each utterance takes into the coming round
+    int64_t fx_calls, fx_joined;   // joiner invocations and frames joined, counted on the host in this layout
     int2 *nodes;
     long pool_rows;
     float *pool_p, *pool_h, *pool_c;
@@ -247,6 +256,7 @@ void tbs_free(tbs_ctx *c) {
     (void)hipStreamSynchronize(c->stream);
     for (void *p : c->allocs) (void)hipFree(p);
     if (c->h_counts) (void)hipHostFree(c->h_counts);
+    if (c->h_live) (void)hipHostFree(c->h_live);
     if (c->h_desc) (void)hipHostFree(c->h_desc);
     for (auto &e : c->events) {
         (void)hipEventDestroy(e.a);
@@ -285,6 +295,8 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     c->state = ST_INIT;
     c->last_hip = 0;
     c->h_counts = nullptr;
+    c->h_live = nullptr;
+    c->fixed = false;
     c->h_desc = nullptr;
     c->d_desc = nullptr;
     c->stream_enc = c->stream_tmp = nullptr;
@@ -350,6 +362,10 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->rv.row_enc, M);
     rc |= dev_alloc(c, &c->rv.row_slot, M);
     rc |= dev_alloc(c, &c->rv.counts, TBS_CNT_SIZE);
+    rc |= dev_alloc(c, &c->utt_nodes, U);
+    rc |= dev_alloc(c, &c->node_base, U);
+    rc |= dev_alloc(c, &c->node_cap, U);
+    rc |= dev_alloc(c, &c->live_sum, 2);
     rc |= dev_alloc(c, &c->utt_T, U);
     rc |= dev_alloc(c, &c->utt_off, U + 1);
     rc |= dev_alloc(c, &c->nodes, (size_t)d.max_nodes);
@@ -438,6 +454,14 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         return TBS_ENOMEM;
     }
     memset(c->h_counts, 0, TBS_CNT_SIZE * sizeof(int));
+    e = hipHostMalloc((void **)&c->h_live, 2 * (size_t)U * sizeof(int), hipHostMallocMapped);
+    if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&c->h_live_dev, c->h_live, 0);
+    if (e != hipSuccess) {
+        c->last_hip = (int)e;
+        tbs_free(c);
+        return TBS_ENOMEM;
+    }
+    memset(c->h_live, 0, 2 * (size_t)U * sizeof(int));
     e = hipHostGetDevicePointer((void **)&c->h_counts_dev, c->h_counts, 0);
     if (e != hipSuccess) {
         c->last_hip = (int)e;
@@ -490,6 +514,21 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     return TBS_OK;
 }
 
+static bool predictor_all_fused(const tbs_ctx *c, int M);
+
+// The slot layout serves a batch when every kernel of a round has its small-shape form: the joiner
+// GEMM over all U*N*S rows in one wave of workgroups, the one-kernel expansion + select/merge, the
+// LSTM layers with the cell update and the projection with the joiner input rows in their GEMMs'
+// epilogues.  Debug bits that ask for any of the separate forms (or bit 8, for this layout itself)
+// keep the row lists.
+static bool fixed_layout_ok(const tbs_ctx *c) {
+    const Dims &d = c->cur;
+    if (c->cfg.dtype != 1 || (c->cfg.debug & (2 | 8 | 16 | 32 | 64 | 128 | 256)) || c->cfg.joiner_chunk_rows > 0)
+        return false;
+    if ((d.H & 3) || (long)d.max_nodes - 1 < (long)d.U) return false;
+    return round_fits(d) && gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj) && predictor_all_fused(c, d.U * d.N);
+}
+
 // B = [([], 1, InitPredictor(), Null)] for U utterances whose lengths and first frames are h_T / offsets
 static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int32_t U, int max_T, long frames) {
     HIPCHK(c, hipSetDevice(c->cfg.device_id));
@@ -501,7 +540,31 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     HIPCHK(c, hipMemcpyAsync(c->utt_off, offsets, sizeof(int) * (U + 1), hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, launch_init_batch(c->stream, c->cur, c->B, c->A[0], c->A[1], c->rv, c->nodes, c->pool_p, c->pool_h,
                                 c->pool_c, c->w.pred_init, c->pool_rows));
-    // the two host arrays above are read by the copies: finish them before returning
+    HIPCHK(c, hipMemsetAsync(c->utt_nodes, 0, sizeof(int) * U, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->live_sum, 0, sizeof(int) * 2, c->stream));
+    memset(c->h_live, 0, 2 * sizeof(int) * (size_t)c->d.U);
+    c->fx_calls = c->fx_joined = 0;
+    // Slot layout: every utterance takes trie nodes from a range of its own, sized in proportion to
+    // its length (a stream's utterances, whose lengths are not known, share equally); node 0 is the root.
+    std::vector<int> nb(U), nc(U);
+    {
+        const int S = c->cur.S;
+        double weight_all = 0.0;
+        for (int u = 0; u < U; ++u) weight_all += max_T > 0 ? (double)(c->h_T[u] + S) : 1.0;
+        const long pool = (long)c->cur.max_nodes - 1;
+        long at = 1;
+        for (int u = 0; u < U; ++u) {
+            const double w = max_T > 0 ? (double)(c->h_T[u] + S) : 1.0;
+            long n = (long)((double)pool * (w / weight_all));
+            if (at + n > (long)c->cur.max_nodes) n = (long)c->cur.max_nodes - at;
+            nb[u] = (int)at;
+            nc[u] = (int)(n < 0 ? 0 : n);
+            at += nc[u];
+        }
+    }
+    HIPCHK(c, hipMemcpyAsync(c->node_base, nb.data(), sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->node_cap, nc.data(), sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
+    // the host arrays above are read by the copies: finish them before returning
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->seg = -1;
     c->round = 0;
@@ -516,6 +579,7 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     c->n_launches = 0;
     c->n_frames = frames;
     c->state = ST_BEGUN;
+    c->fixed = fixed_layout_ok(c);
     return TBS_OK;
 }
 
@@ -686,8 +750,7 @@ int tbs_expand(tbs_ctx *c) {
     return TBS_OK;
 }
 
-static bool predictor_all_fused(const tbs_ctx *c, int M);
-static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part = 0);
+static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part = 0, const int *any_dev = nullptr);
 
 // Expansion and select/merge of a round in one kernel (small shapes, see round_kernels.hip)?  Not
 // when the generic expansion kernel is forced, the fusion switched off (debug bit 7), the expansion
@@ -782,7 +845,7 @@ static int64_t predictor_madds(const tbs_ctx *c, int64_t pairs) {   // multiply-
     return n;
 }
 
-static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part) {   // part: 0 all, 1 the LSTM layers, 2 the projection
+static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part, const int *any_dev) {   // part: 0 all, 1 the LSTM layers, 2 the projection
     const Dims &d = c->cur;
     AView &A = c->A[c->a_cur];
     // (the input rows of the first layer were gathered behind select/merge)
@@ -803,12 +866,12 @@ static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part) {   /
             ep.h_par_next = last ? nullptr : c->pool_h + (size_t)(l + 1) * c->pool_rows * d.H;
             ep.out16 = (bf16_t *)(last ? c->htop : c->xh[(l + 1) & 1]);
             ep.H = d.H;
-            ProfScope pg(c, TBS_K_GEMM, m_dev ? 0 : (int64_t)M * 4 * d.H * K);
+            ProfScope pg(c, TBS_K_GEMM, (m_dev || any_dev) ? 0 : (int64_t)M * 4 * d.H * K);
             HIPCHK(c, launch_gemm_lstm(c->stream, (const bf16_t *)c->xh[l & 1], (const bf16_t *)c->wperm[l], c->bperm[l],
-                                       M, K, ep, m_dev));
+                                       M, K, ep, m_dev, any_dev));
             continue;
         }
-        if (m_dev) return TBS_ESTATE;   // (predictor_all_fused was not asked)
+        if (m_dev || any_dev) return TBS_ESTATE;   // (predictor_all_fused was not asked)
         if (l == 0 && c->emb_gates)
             HIPCHK(c, gemm(c, c->xh[0], c->w.w_hh[0], nullptr, c->gates, M, 4 * d.H, d.H, nullptr, 4L * d.H));
         else
@@ -828,12 +891,12 @@ static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part) {   /
         jp.enc = (const bf16_t *)c->enc;
         jp.amat = (bf16_t *)c->amat;
         jp.act = c->cfg.act;
-        ProfScope pg(c, TBS_K_GEMM, m_dev ? 0 : (int64_t)M * d.Dj * d.H);
+        ProfScope pg(c, TBS_K_GEMM, (m_dev || any_dev) ? 0 : (int64_t)M * d.Dj * d.H);
         HIPCHK(c, launch_gemm_join(c->stream, (const bf16_t *)c->htop, (const bf16_t *)c->w.w_proj, c->w.b_proj,
-                                   c->pool_p, M, d.Dj, d.H, c->rv.pair_slot, d.Dj, jp, m_dev));
+                                   c->pool_p, M, d.Dj, d.H, c->rv.pair_slot, d.Dj, jp, m_dev, any_dev));
         c->prep_ahead = true;
     } else {
-        if (m_dev) return TBS_ESTATE;
+        if (m_dev || any_dev) return TBS_ESTATE;
         HIPCHK(c, gemm(c, c->htop, c->w.w_proj, c->w.b_proj, c->pool_p, M, d.Dj, d.H, c->rv.pair_slot, d.Dj));
     }
     return TBS_OK;
@@ -956,8 +1019,152 @@ static int expand_select(tbs_ctx *c, int32_t *live) {
     return rc ? rc : tbs_select_merge(c, live);
 }
 
+// Wait until every utterance's workgroup of launch `seq` has told the host its count (slot layout):
+// one word per utterance in pinned memory, in the half that launch writes to.  The counts go to
+// `out` [U].  Bounded like wait_counts.
+static int wait_live(tbs_ctx *c, int seq, int *out, int *total, bool *trie_full) {
+    const int U = c->cur.U;
+    const unsigned want = (unsigned)seq & 0xFFFFFFu;
+    const int *words = c->h_live + (seq & 1) * c->cur.U;
+    std::chrono::steady_clock::time_point t0;
+    bool timing = false;
+    int u = 0, sum = 0;
+    bool full = false;
+    for (unsigned spin = 1; u < U; ++spin) {
+        const int w = __atomic_load_n(&words[u], __ATOMIC_ACQUIRE);
+        if (((unsigned)w >> 8) == want) {
+            out[u] = w & 63;
+            sum += w & 63;
+            full = full || (w & 64);
+            ++u;
+            continue;
+        }
+        if ((spin & 0x3FFFFF) == 0) {
+            const hipError_t e = hipStreamQuery(c->stream);
+            if (e == hipSuccess) {
+                if (((unsigned)__atomic_load_n(&words[u], __ATOMIC_ACQUIRE) >> 8) == want) continue;
+                c->last_hip = (int)hipErrorUnknown;
+                return TBS_EHIP;
+            }
+            if (e != hipErrorNotReady) {
+                c->last_hip = (int)e;
+                return TBS_EHIP;
+            }
+            const auto now = std::chrono::steady_clock::now();
+            if (!timing) {
+                t0 = now;
+                timing = true;
+            } else if (now - t0 > std::chrono::seconds(TBS_WAIT_LIMIT_S)) {
+                c->last_hip = (int)hipErrorLaunchTimeOut;
+                return TBS_EHIP;
+            }
+        }
+    }
+    *total = sum;
+    *trie_full = full;
+    return TBS_OK;
+}
+
+// One segment in the slot layout: four kernels a round (joiner GEMM; expansion, select/merge and
+// the utterance's own bookkeeping; LSTM layers; projection), no row list kernel, and the host
+// reads one word per utterance instead of waiting for a scan over all of them.  The head of the
+// segment and its first round go out without a wait between them: every kernel finds what it
+// needs to know of an utterance in that utterance's descriptors.
+static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
+    if (c->state != ST_BEGUN && c->state != ST_READY && c->state != ST_SELECTED) return TBS_ESTATE;
+    const Dims &d = c->cur;
+    c->seg = seg_index;
+    c->round = 0;
+    c->live_u.assign(d.U, 0);
+    FixedView fx{};
+    fx.on = 1;
+    fx.seg = seg_index;
+    fx.utt_off = c->utt_off;
+    fx.utt_nodes = c->utt_nodes;
+    fx.node_base = c->node_base;
+    fx.node_cap = c->node_cap;
+    fx.live_sum = c->live_sum;
+    fx.host_live = c->h_live_dev;
+    fx.pool_h = c->pool_h;
+    fx.xh = (bf16_t *)c->xh[0];
+    // A = ChooseNBest(B), B = [], the first round's pair descriptors and joiner input rows
+    const int head_seq = fx.seq = ++c->seq;
+    HIPCHK(c, launch_segment_begin(c->stream, d, c->seg, c->utt_T, c->B, c->A[c->a_cur], c->rv, c->pool_p, c->pool_h,
+                                   c->pool_c, c->pool_rows, &fx));
+    {
+        ProfScope ps(c, TBS_K_PREP, 0);
+        HIPCHK(c, launch_joiner_prep_fixed(c->stream, d, c->cfg.act, (const bf16_t *)c->enc, c->pool_p, c->rv,
+                                           (bf16_t *)c->amat));
+    }
+    const int M = d.U * d.N * d.S;
+    std::vector<int> made(d.U, 0);
+    int total = 0, rc;
+    bool full = false, first = true;
+    for (;;) {   // while Length(A) > 0
+        if (c->round + 1 > d.R) return TBS_EOVERFLOW;
+        c->round += 1;
+        {
+            ProfScope ps(c, TBS_K_JOINER, 0);
+            ProfScope pg(c, TBS_K_GEMM, 0);
+            HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, c->logits,
+                                       M, d.V, d.Dj, nullptr, d.V));
+        }
+        AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];
+        const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
+        fx.seq = ++c->seq;
+        {
+            ProfScope ps(c, TBS_K_ROUND, 0);
+            HIPCHK(c, launch_round(c->stream, d, c->round, drop, c->logits, A, An, c->B, c->rv, c->nodes, c->row_stats,
+                                   c->delta_nb, &fx));
+        }
+        c->a_cur ^= 1;
+        // The LSTM layers go out before the host knows whether the round made anything (they leave at
+        // once if it did not): the host's wait then lies beside them, not in front of them.
+        const int *any = c->live_sum + (fx.seq & 1);
+        {
+            ProfScope ps(c, TBS_K_PREDICTOR, 0);
+            if ((rc = predictor_launch(c, d.U * d.N, nullptr, 1, any))) return rc;
+        }
+        if ((rc = wait_live(c, fx.seq, made.data(), &total, &full))) return rc;
+        if (first) {   // (what the head of the segment put into A: there for certain once the round's words are)
+            int t0 = 0;
+            bool f0 = false;
+            if ((rc = wait_live(c, head_seq, c->live_u.data(), &t0, &f0))) return rc;
+            first = false;
+        }
+        // the joiner call that just ran: counted per utterance that had hypotheses in it
+        int rows = 0, pairs = 0;
+        for (int u = 0; u < d.U; ++u)
+            if (c->live_u[u] > 0) {
+                const int left = c->h_T[u] - seg_index * d.S, sp = left < 0 ? 0 : (left > d.S ? d.S : left);
+                c->fx_calls += 1;
+                c->fx_joined += sp;
+                rows += c->live_u[u] * sp;
+                pairs += c->live_u[u];
+            }
+        if (rows > 0) c->n_launches += 1;
+        if (c->prof_kernel == TBS_K_JOINER) c->prof_units += rows;
+        if (c->prof_kernel == TBS_K_GEMM) c->prof_units += (int64_t)rows * d.V * d.Dj + predictor_madds(c, total);
+        if (c->prof_kernel == TBS_K_ROUND) c->prof_units += pairs;
+        if (c->prof_kernel == TBS_K_PREDICTOR) c->prof_units += total;
+        c->live_u = made;
+        c->h_counts[TBS_CNT_PAIRS] = total;
+        if (full) return TBS_EOVERFLOW;
+        if (total == 0) break;
+        {
+            ProfScope ps(c, TBS_K_PREDICTOR, 0);
+            if ((rc = predictor_launch(c, d.U * d.N, nullptr, 2, any))) return rc;
+        }
+    }
+    c->h_counts[TBS_CNT_ROWS] = 0;
+    c->prep_ahead = false;
+    c->state = ST_SELECTED;
+    return TBS_OK;
+}
+
 // one segment: the head of the outer loop of Algorithm 1 and its inner loop (while Length(A) > 0)
 static int run_segment(tbs_ctx *c, int32_t seg_index) {
+    if (c->fixed) return run_segment_fixed(c, seg_index);
     int rc, rows = 0, live = 0;
     if (segment_ahead_ok(c)) {
         if ((rc = segment_begin_ahead(c, seg_index))) return rc;
@@ -1020,6 +1227,7 @@ int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offs
             any = any || take[u] > 0;
         }
         if (!any) break;
+        for (int u = 0; u < U; ++u) c->h_T[u] = take[u];   // (the slot layout's host bookkeeping reads the step sizes)
         HIPCHK(c, hipMemcpyAsync(c->utt_T, take, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, hipMemcpyAsync(c->utt_off, first, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
         const int rc = run_segment(c, 0);   // (waits for counts: the two copies above are done by then)
@@ -1062,8 +1270,8 @@ int tbs_decode(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offsets, i
 int tbs_stats(const tbs_ctx *c, int64_t *joiner_calls, int64_t *joined_frames, int64_t *frames, int64_t *launches) {
     if (!c) return TBS_EINVAL;
     // (running sums kept by the row list kernel, as of the last counts the host waited for)
-    if (joiner_calls) *joiner_calls = c->h_counts[TBS_CNT_ACC_CALLS];
-    if (joined_frames) *joined_frames = c->h_counts[TBS_CNT_ACC_JOINED];
+    if (joiner_calls) *joiner_calls = c->fixed ? c->fx_calls : c->h_counts[TBS_CNT_ACC_CALLS];
+    if (joined_frames) *joined_frames = c->fixed ? c->fx_joined : c->h_counts[TBS_CNT_ACC_JOINED];
     if (frames) *frames = c->n_frames;
     if (launches) *launches = c->n_launches;
     return TBS_OK;

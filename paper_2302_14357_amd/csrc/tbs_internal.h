@@ -58,6 +58,25 @@ enum { TBS_CNT_PAIRS = 0, TBS_CNT_ROWS = 1, TBS_CNT_NODES = 2, TBS_CNT_ERR = 3, 
        TBS_CNT_SEQ = 6, TBS_CNT_NODE_BASE = 7, TBS_CNT_ACC_CALLS = 8, TBS_CNT_ACC_JOINED = 9, TBS_CNT_SIZE = 10 };
 enum { TBS_ERRF_BCAP = 1, TBS_ERRF_NODES = 2 };
 
+// Slot layout of small shapes: hypothesis i of utterance u is pair j = u*N + i whether or not it
+// exists, its frames are the joiner rows j*S .. j*S + S' - 1.  Nothing depends on the other utterances'
+// counts, so no kernel has to sum them: the kernel that makes a list A also writes the descriptors of
+// its pairs, takes trie nodes from the utterance's own range and tells the host its count.
+struct FixedView {
+    int on;
+    int seg;
+    const int *utt_off;   // [U] first frame row of each utterance
+    int *utt_nodes;       // [U] trie nodes each utterance has taken from its range
+    const int *node_base; // [U] first node of each utterance's range of the trie ...
+    const int *node_cap;  // [U] ... and its size (the ranges share the trie in proportion to the utterances' lengths)
+    int *live_sum;        // [2] hypotheses made by all utterances in launch seq (slot seq & 1): kernels queued
+                          //     behind it leave at once when it is zero
+    int *host_live;       // pinned [2, U], half seq & 1: (seq << 8) | (trie full << 6) | hypotheses made
+    int seq;
+    const float *pool_h;  // first LSTM layer's h by state slot, and where the new hypotheses' input rows go:
+    bf16_t *xh;           // xh[j, :] = bf16(h of the parent of pair j)   (null: not wanted)
+};
+
 struct Dims {
     int U, N, S, V, Dj, blank;
     int R;      // rounds capacity
@@ -107,7 +126,11 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
                              float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
                              long pool_rows);
 hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const int *utt_T, BView B,
-                                AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows);
+                                AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows,
+                                const FixedView *fx = nullptr);
+// joiner input rows in the slot layout: every row j*S + t with t < pair_len[j]
+hipError_t launch_joiner_prep_fixed(hipStream_t st, const Dims &d, int act, const bf16_t *enc, const float *pool_p,
+                                    RowView rv, bf16_t *amat);
 // gather_h / gather_xh not null: also writes gather_xh[pair, :] = bf16(gather_h[parent slot, :]) (H wide)
 hipError_t launch_rowfill(hipStream_t st, const Dims &d, int seg, const int *utt_off, AView A, RowView rv,
                           int2 *nodes, int assign_nodes, int *host_counts, int seq, const float *gather_h = nullptr,
@@ -127,12 +150,15 @@ hipError_t launch_gemm_bf16_rows(hipStream_t st, const bf16_t *A, const bf16_t *
 bool gemm_small_fits(int M, int N, int K);
 // true if launch_gemm_lstm can run this problem (small, K a multiple of 128 that fits the LDS stages)
 bool gemm_lstm_fits(int M, int H, int K);
+// any_dev (both fused forms): rows may be dead (state slot < 0) anywhere, and if *any_dev is zero
+// the whole launch leaves at once
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
-                            const LstmEp &ep, const int *m_dev = nullptr);
+                            const LstmEp &ep, const int *m_dev = nullptr, const int *any_dev = nullptr);
 // the same for the projection GEMM that also makes the next joiner call's input rows (bf16 models)
 bool gemm_join_fits(int M, int N, int K);
 hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev = nullptr);
+                            int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev = nullptr,
+                            const int *any_dev = nullptr);
 hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
@@ -144,7 +170,8 @@ hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int dro
 // round_fits says whether the shape is served)
 bool round_fits(const Dims &d);
 hipError_t launch_round(hipStream_t st, const Dims &d, int round, int drop, const float *logits, AView A, AView An,
-                        BView B, RowView rv, const int2 *nodes, float *row_stats, float *delta_nb);
+                        BView B, RowView rv, int2 *nodes, float *row_stats, float *delta_nb,
+                        const FixedView *fx = nullptr);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
                               const void *embed, const float *pool_h, void *xh);
 hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, const float *pool_h,

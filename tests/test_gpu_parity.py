@@ -366,6 +366,15 @@ def test_decode_truncation_and_capacity_codes():
         tbs.decode(tbs.upload_frames(enc), offsets)
     assert e.value.code == -5
     tbs.close()
+    # the same where every utterance takes nodes from a range of its own (width 128: the layout with
+    # every hypothesis in a fixed place)
+    shape128 = _peaked(small_bf16_shape(n_utts=3, vocab=96, d=128, hidden=128), 8.0, 8.0)
+    model128, off128, enc128 = build_case(shape128, n_utts=3, lengths=lengths)
+    tbs = make_tbs(shape128, model128, off128, N, S, max_rounds_per_segment=cap, max_nodes=40)
+    with pytest.raises(TbsError) as e:
+        tbs.decode(tbs.upload_frames(enc128), off128)
+    assert e.value.code == -5
+    tbs.close()
     # a list B smaller than a segment's blank expansions: the rounds of a segment are not capped,
     # the workspaces are sized for two
     tbs = make_tbs(shape, model, offsets, N, S, rounds_capacity=2)
@@ -751,13 +760,18 @@ def test_round_in_one_kernel_equals_separate_kernels(N, S, V, peaked):
     lengths = np.array([0, 2, 7, 12, 23, 31])
     model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
     kw = dict(max_rounds_per_segment=cap) if cap else {}
+    # default: every hypothesis in a fixed place, four kernels a round; 256: the one-kernel round with
+    # row lists made by a kernel of their own; 128: expansion and select/merge as two kernels as well
     one, st1 = _gpu_decode(shape, model, offsets, enc, N, S, **kw)
-    two, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=128, **kw)
-    for a, b in zip(one, two):
-        assert [h[0] for h in a] == [h[0] for h in b]
-        np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-6, atol=1e-5)
-    assert st1["joiner_calls"] == st2["joiner_calls"] and st1["joined_frames"] == st2["joined_frames"]
+    for dbg in (256, 128):
+        two, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=dbg, **kw)
+        for a, b in zip(one, two):
+            assert [h[0] for h in a] == [h[0] for h in b], dbg
+            np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=1e-6, atol=1e-5)
+        assert st1["joiner_calls"] == st2["joiner_calls"] and st1["joined_frames"] == st2["joined_frames"], dbg
+        assert st1["launches"] == st2["launches"] and st1["frames"] == st2["frames"], dbg
     _check_decode(shape, model, offsets, enc, N, S, max_rounds=cap)
+    _check_decode(shape, model, offsets, enc, N, S, max_rounds=cap, debug=256)
     _check_decode(shape, model, offsets, enc, N, S, max_rounds=cap, debug=128)
 
 
