@@ -406,14 +406,15 @@ k_select_merge(Dims d, int round, int drop, const float *logits, const float *ro
                RowView rv, const int2 *nodes) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // B list of this utterance
     const int u = blockIdx.x;
-    const int pair0 = rv.utt_pair0[u], urow0 = rv.utt_row0[u];
+    const int pair0 = rv.utt_pair0[u];
+    const SelectFigs fg = select_figs(u, A, B, rv);
     SelectIn in;
     in.cand_score = cand_score + (long)pair0 * d.N;
     in.cand_tok = cand_tok + (long)pair0 * d.N;
     in.dphi = dphi + pair0;
-    in.lc = row_lc + urow0;
+    in.lc = row_lc + fg.urow0;
     in.slot_rows = 0;
-    select_merge_utt(d, round, drop, u, (int)threadIdx.x, logits, in, A, An, B, rv, nodes, s_dyn);
+    select_merge_utt(0, d, round, drop, u, (int)threadIdx.x, logits, in, fg, A, An, B, rv, nodes, s_dyn);
 }
 
 hipError_t launch_select_merge(hipStream_t st, const Dims &d, int round, int drop, const float *logits,

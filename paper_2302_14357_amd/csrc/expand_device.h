@@ -149,6 +149,21 @@ struct ExpandPair {
 typedef const __attribute__((address_space(4))) int *cint_p;
 typedef const __attribute__((address_space(4))) float *cfloat_p;
 
+// (the caller knows the pair's rows and place: nothing is read from the pair list)
+template <int SMAX>
+__device__ __forceinline__ void expand_pair_info_at(ExpandPair<SMAX> &pi, int pair, int row0, int sp, int u, int h,
+                                                    const Dims &d, const AView &A, const float *logits) {
+    pi.pair = pair;
+    pi.row0 = row0;
+    pi.sp = sp;
+    cfloat_p dold = (cfloat_p)A.dhat + ((long)u * d.N + h) * d.S;
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) pi.dold[t] = t < pi.sp ? dold[t] : -INFINITY;
+    cfloat_p lb = (cfloat_p)logits + (long)pi.row0 * d.V + d.blank;
+#pragma unroll
+    for (int t = 0; t < SMAX; ++t) pi.lblank[t] = t < pi.sp ? lb[(long)t * d.V] : 0.f;
+}
+
 template <int SMAX>
 __device__ __forceinline__ void expand_pair_info(ExpandPair<SMAX> &pi, int pair, const Dims &d, const AView &A,
                                                  const RowView &rv, const float *logits) {
@@ -203,6 +218,10 @@ __device__ __forceinline__ float wave_max_ord(float f) {
     return ord2f(max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
                      max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48))));
 }
+
+// (expand_pair meets the other teams of its workgroup at this many barriers; a wave of the workgroup
+// that does something else meanwhile must meet them too)
+#define EXPAND_PAIR_BARRIERS 3
 
 // Everything after the load for one pair, by a team of TT threads (tid = 0 .. TT-1 within the team).
 // Results: lc_out[t] = log(alpha_t / Z_t) - m_t for the pair's frames, *dphi_out = log of the blank

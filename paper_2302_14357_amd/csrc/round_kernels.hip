@@ -34,9 +34,16 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
 
     const int u = blockIdx.x;
     const int team = __builtin_amdgcn_readfirstlane((int)threadIdx.x / TT), tid = (int)threadIdx.x % TT;
+    // Where the workgroup has room for one more wave, that wave belongs to the select step: it stages
+    // B and A in LDS while the teams expand, and goes on when they are done.  Otherwise the first
+    // wave does the select step after its share of the expansion.
+    const bool own_wave = (int)blockDim.x > N * TT;
+    const bool sel_wave = own_wave ? (int)threadIdx.x >= N * TT : (int)threadIdx.x < WAVE;
+    const int sel_lane = (int)threadIdx.x & 63;
     __shared__ SelectOut s_out;
-    const int sp = rv.utt_sp[u];
-    const int H = sp > 0 ? A.count[u] : 0;
+    const SelectFigs fg = select_figs(u, A, B, rv);
+    const int sp = fg.sp;
+    const int H = sp > 0 ? fg.cntA : 0;
     // (asked for now, needed at the end)
     const int used0 = fx.on ? fx.utt_nodes[u] : 0, ncap = fx.on ? fx.node_cap[u] : 0, nbase = fx.on ? fx.node_base[u] : 0;
     if (H == 0) {   // (the same for the whole workgroup: nobody reaches a barrier)
@@ -50,40 +57,64 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
         }
         return;
     }
-    const int pair0 = rv.utt_pair0[u];
+    // (the utterance's pairs and rows follow each other: nothing is read from the pair list)
+    const int pair0 = fx.on ? u * N : rv.utt_pair0[u], urow0 = fx.on ? u * N * d.S : fg.urow0;
     const bool live = team < H;
-    ExpandPair<SMAX> pi;
-    if (live) {
-        expand_pair_info(pi, pair0 + team, d, A, rv, logits);
-    } else {   // a team without a hypothesis reads the utterance's first row and scores nothing
-        pi.pair = pair0;
-        pi.row0 = rv.utt_row0[u];
-        pi.sp = 0;
+    SelectIn in;
+    in.cand_score = s_cs;
+    in.cand_tok = s_ct;
+    in.dphi = s_dphi;
+    in.lc = s_lc;
+    in.slot_rows = fx.on;
+    // Slot layout: the first LSTM layer's input rows of the hypotheses this round makes are bf16 copies
+    // of their parents' h.  The parents are among this utterance's H hypotheses, so every team asks for
+    // its own hypothesis' h now, beside the logits, and at the end writes it out once for every new
+    // hypothesis made from it: the end of the kernel then has no memory round trip of its own.
+    constexpr int HP = (160 + TT - 1) / TT;   // 16-byte pieces per thread for h up to 640 wide
+    const int H4 = d.H >> 2;
+    const bool pre_h = fx.on && fx.xh && H4 <= TT * HP;
+    float4 hpar[HP];
+    if (own_wave && sel_wave) {
+        select_merge_utt(1, d, round, drop, u, sel_lane, logits, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
 #pragma unroll
-        for (int t = 0; t < SMAX; ++t) {
-            pi.dold[t] = -INFINITY;
-            pi.lblank[t] = 0.f;
+        for (int b = 0; b < EXPAND_PAIR_BARRIERS; ++b) __syncthreads();
+    } else {
+        if (pre_h && live) {
+            const long slot = A.slot[(long)u * N + team];
+#pragma unroll
+            for (int q = 0; q < HP; ++q)
+                hpar[q] = reinterpret_cast<const float4 *>(fx.pool_h + slot * d.H)[min(tid + TT * q, H4 - 1)];
         }
+        ExpandPair<SMAX> pi;
+        if (live) {
+            expand_pair_info_at(pi, pair0 + team, urow0 + team * (fx.on ? d.S : sp), sp, u, team, d, A, logits);
+        } else {   // a team without a hypothesis reads the utterance's first row and scores nothing
+            pi.pair = pair0;
+            pi.row0 = urow0;
+            pi.sp = 0;
+#pragma unroll
+            for (int t = 0; t < SMAX; ++t) {
+                pi.dold[t] = -INFINITY;
+                pi.lblank[t] = 0.f;
+            }
+        }
+        float e[SMAX][NV4 * 4];
+        expand_load<NV4, SMAX, TT>(e, logits, pi.row0, pi.sp, d.V, tid);
+        expand_pair<NV4, SMAX, TT>(e, pi, teams[team], d, tid, live, s_lc + team * sp, s_dphi + team, s_cs + team * N,
+                                   s_ct + team * N, row_stats, delta_nb);
     }
-    float e[SMAX][NV4 * 4];
-    expand_load<NV4, SMAX, TT>(e, logits, pi.row0, pi.sp, d.V, tid);
-    expand_pair<NV4, SMAX, TT>(e, pi, teams[team], d, tid, live, s_lc + team * sp, s_dphi + team, s_cs + team * N,
-                               s_ct + team * N, row_stats, delta_nb);
     __syncthreads();
-    if (threadIdx.x < WAVE) {
-        SelectIn in;
-        in.cand_score = s_cs;
-        in.cand_tok = s_ct;
-        in.dphi = s_dphi;
-        in.lc = s_lc;
-        in.slot_rows = fx.on;
-        select_merge_utt(d, round, drop, u, (int)threadIdx.x, logits, in, A, An, B, rv, nodes, s_raw, &s_out);
+    if (sel_wave) {
+        if (own_wave)
+            select_merge_utt(2, d, round, drop, u, sel_lane, logits, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
+        else
+            select_merge_utt(0, d, round, drop, u, sel_lane, logits, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
         if (fx.on) {
             // Slot layout: what a row list kernel would do for this utterance.  The new hypotheses
             // take trie nodes from the utterance's own range, their pairs get their descriptors, the
             // places of A beyond them are marked dead, and the host hears how many there are.
             sel_sync();
-            const int lane = (int)threadIdx.x, total = s_out.total;
+            const int lane = sel_lane, total = s_out.total;
             bool full = false;
             if (lane < N) {
                 const int j = u * N + lane;
@@ -114,10 +145,26 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
             }
         }
     }
-    if (fx.on && fx.xh) {
-        // input rows of the first LSTM layer for the new hypotheses: bf16 of their parents' h
+    if (pre_h) {
         __syncthreads();
-        const int total = s_out.total, H4 = d.H >> 2;
+        const int total = s_out.total;
+        if (live) {
+            uint2 hb[HP];
+#pragma unroll
+            for (int q = 0; q < HP; ++q)
+                hb[q] = make_uint2((unsigned)round_bf16(hpar[q].x) | ((unsigned)round_bf16(hpar[q].y) << 16),
+                                   (unsigned)round_bf16(hpar[q].z) | ((unsigned)round_bf16(hpar[q].w) << 16));
+            for (int i = 0; i < total; ++i)
+                if (s_out.parent[i] == team) {
+#pragma unroll
+                    for (int q = 0; q < HP; ++q)
+                        if (tid + TT * q < H4) reinterpret_cast<uint2 *>(fx.xh)[(long)(u * N + i) * H4 + tid + TT * q] = hb[q];
+                }
+        }
+    } else if (fx.on && fx.xh) {
+        // (h too wide to wait in registers: read the parents' rows now)
+        __syncthreads();
+        const int total = s_out.total;
         for (int idx = (int)threadIdx.x; idx < total * H4; idx += (int)blockDim.x) {
             const int h = idx / H4, i = idx - h * H4;
             const float4 v = reinterpret_cast<const float4 *>(fx.pool_h + (long)s_out.pslot[h] * d.H)[i];
@@ -154,7 +201,9 @@ static hipError_t round_launch(hipStream_t st, const Dims &d, int round, int dro
         if (e != hipSuccess) return e;
         attr_for = shm;
     }
-    hipLaunchKernelGGL((k_round<TW, NV4, SMAX>), dim3(d.U), dim3(d.N * TW * 64), shm, st, d, round, drop, logits, A, An,
+    // (one wave more for the select step where 1024 threads allow it)
+    const int threads = d.N * TW * 64 + (d.N * TW * 64 + 64 <= 1024 ? 64 : 0);
+    hipLaunchKernelGGL((k_round<TW, NV4, SMAX>), dim3(d.U), dim3(threads), shm, st, d, round, drop, logits, A, An,
                        B, rv, nodes, row_stats, delta_nb, fx);
     return hipGetLastError();
 }

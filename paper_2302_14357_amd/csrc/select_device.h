@@ -50,6 +50,7 @@ __device__ __forceinline__ void store_host(int *p, int v) {
 struct SelectOut {
     int total;
     int slot[TBS_MAX_BEAM], pslot[TBS_MAX_BEAM], tok[TBS_MAX_BEAM], pnode[TBS_MAX_BEAM];
+    int parent[TBS_MAX_BEAM];   // index in A of the hypothesis each new one was made from
 };
 
 // slot layout: descriptor of a pair that does not exist (every address made from it stays valid)
@@ -75,11 +76,29 @@ struct SelectIn {
     int slot_rows;   // 1: hypothesis h of the utterance owns the joiner rows h*S .. (slot layout); 0: rows h*S' ..
 };
 
-// s_dyn: LDS for the utterance's B list, BCAP * (8 + 8 + 3 * 4) bytes, 16-byte aligned
-__device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int drop, int u, int lane,
-                                                 const float *logits, SelectIn in, AView A, AView An, BView B,
-                                                 RowView rv, const int2 *nodes, unsigned char *s_dyn,
-                                                 SelectOut *out = nullptr) {
+// What describes the utterance at the start of the step, in one round of loads.
+struct SelectFigs {
+    int sp, cntA, urow0, nB0, parity;
+};
+__device__ __forceinline__ SelectFigs select_figs(int u, const AView &A, const BView &B, const RowView &rv) {
+    SelectFigs f;
+    f.sp = rv.utt_sp[u];
+    f.cntA = A.count[u];
+    f.urow0 = rv.utt_row0[u];
+    f.nB0 = B.count[u];
+    f.parity = rv.utt_par[u];
+    return f;
+}
+
+// s_dyn: LDS for the utterance's B list, BCAP * (8 + 8 + 3 * 4) bytes, 16-byte aligned.
+// phase 0: the whole step.  phase 1: only what does not depend on the expansion (B and A staged in
+// LDS); phase 2: the rest, by the same wave: a caller whose expansion runs in the same kernel does
+// phase 1 beside it.  (The phase is an argument, not a template parameter: the LDS arrays below
+// belong to the function, and each instantiation of a template would have a set of its own.)
+__device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d, int round, int drop, int u, int lane,
+                                                 const float *logits, SelectIn in, const SelectFigs &fg, AView A,
+                                                 AView An, BView B, RowView rv, const int2 *nodes,
+                                                 unsigned char *s_dyn, SelectOut *out = nullptr) {
     double *s_blogs = reinterpret_cast<double *>(s_dyn);
     u64 *s_bhash = reinterpret_cast<u64 *>(s_blogs + d.BCAP);
     int *s_bnode = reinterpret_cast<int *>(s_bhash + d.BCAP);
@@ -97,37 +116,38 @@ __device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int d
     __shared__ double s_thr;
     __shared__ float s_dnew[TBS_MAX_SEG * TBS_MAX_BEAM];   // frame distributions of the new hypotheses, [frame][hypothesis]
     const int N = d.N;
-    // everything that describes the utterance in one round of loads
-    const int sp = rv.utt_sp[u], cntA = A.count[u], pair0 = rv.utt_pair0[u], urow0 = rv.utt_row0[u];
-    const int nB0 = B.count[u], parity = rv.utt_par[u];
+    const int sp = fg.sp, cntA = fg.cntA, urow0 = fg.urow0, nB0 = fg.nB0, parity = fg.parity;
     const int H = sp > 0 ? cntA : 0;
     if (H == 0) {
-        if (lane == 0) {
+        if (lane == 0 && PHASE != 1) {
             An.count[u] = 0;
             if (out) out->total = 0;
         }
     } else {
         const long bbase = (long)u * d.BCAP;
         int nB = nB0;
-        // --- stage B, A and the candidates
-        for (int i = lane; i < nB0; i += WAVE) {
-            s_blogs[i] = B.logs[bbase + i];
-            s_bhash[i] = B.hash[bbase + i];
-            s_bnode[i] = B.node[bbase + i];
-            s_blen[i] = B.len[bbase + i];
-            s_bslot[i] = B.slot[bbase + i];
+        // --- stage B and A
+        if (PHASE != 2) {
+            for (int i = lane; i < nB0; i += WAVE) {
+                s_blogs[i] = B.logs[bbase + i];
+                s_bhash[i] = B.hash[bbase + i];
+                s_bnode[i] = B.node[bbase + i];
+                s_blen[i] = B.len[bbase + i];
+                s_bslot[i] = B.slot[bbase + i];
+            }
+            if (lane < H) {
+                const long a = (long)u * N + lane;
+                s_alogs[lane] = A.logs[a];
+                s_ahash[lane] = A.hash[a];
+                s_anode[lane] = A.node[a];
+                s_alen[lane] = A.len[a];
+                s_aslot[lane] = A.slot[a];
+            }
+            if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
         }
-        if (lane < H) {
-            const long a = (long)u * N + lane;
-            const double al = A.logs[a];
-            s_alogs[lane] = al;
-            s_ahash[lane] = A.hash[a];
-            s_anode[lane] = A.node[a];
-            s_alen[lane] = A.len[a];
-            s_aslot[lane] = A.slot[a];
-            s_bkey[lane] = al + (double)in.dphi[lane];   // score of the blank expansion (dphi holds log delta_blank)
-        }
-        if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
+        if (PHASE == 1) return;
+        // --- the candidates and the blank expansions (dphi holds log delta_blank)
+        if (lane < H) s_bkey[lane] = s_alogs[lane] + (double)in.dphi[lane];
         const int nc = H * N;
         for (int c = lane; c < nc; c += WAVE) {
             s_ctok[c] = in.cand_tok[c];
@@ -248,6 +268,7 @@ __device__ __forceinline__ void select_merge_utt(const Dims &d, int round, int d
                 out->pslot[pos] = s_aslot[h];
                 out->tok[pos] = s_ctok[c];
                 out->pnode[pos] = s_anode[h];
+                out->parent[pos] = h;
             }
             if (lane < N && s_keep[lane]) {
                 const int c = s_sel[lane];
