@@ -293,10 +293,17 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
                 float *dh = An.dhat + an * d.S;
                 float *sd = s_dnew + lane;
                 float mx = -INFINITY;
-                for (int t = 0; t < sp; ++t) {
-                    const float x = logits[(long)(row0 + t) * d.V + tok] + in.lc[h * sp + t];
-                    sd[t * TBS_MAX_BEAM] = x;
-                    mx = fmaxf(mx, x);
+                for (int t0 = 0; t0 < sp; t0 += 8) {   // (eight logits asked for before the first is used)
+                    float xv[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) xv[q] = logits[(long)(row0 + min(t0 + q, sp - 1)) * d.V + tok];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (t0 + q < sp) {
+                            const float x = xv[q] + in.lc[h * sp + t0 + q];
+                            sd[(t0 + q) * TBS_MAX_BEAM] = x;
+                            mx = fmaxf(mx, x);
+                        }
                 }
                 float sum = 0.f;
                 for (int t = 0; t < sp; ++t) sum += __expf(sd[t * TBS_MAX_BEAM] - mx);
