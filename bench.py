@@ -49,6 +49,45 @@ def read_traffic(kernel, workload):
     return None
 
 
+def quick_decode(workload, steps=2, warmup=1, seg=0, beam=0, debug=0):
+    """frames/s of another configuration's whole decode (tbs_decode, inputs resident in HBM), timed
+    like the headline but over a couple of steps: reported beside the headline, not as `value`."""
+    import torch
+    from tbs_inputs import SHAPES, make_model, make_utterances
+    from paper_2302_14357_amd import Tbs
+    shape_name, N, S, _, _ = WORKLOADS[workload]
+    N, S = beam or N, seg or S
+    shape = SHAPES[shape_name]
+    model = make_model(shape)
+    offsets, enc = make_utterances(shape, model)
+    U, frames = len(offsets) - 1, int(offsets[-1])
+    t = Tbs(model, blank_id=shape.blank_id, beam_n=N, seg_s=S, max_utts=U, max_frames_total=frames,
+            dtype=shape.dtype, act=shape.act, debug=debug)
+    try:
+        enc_dev = t.upload_frames(enc)
+        max_len = 256
+        tok = np.full((U, N, max_len), -1, np.int32)
+        lens, logs, cnt = np.zeros((U, N), np.int32), np.zeros((U, N), np.float64), np.zeros(U, np.int32)
+        for _ in range(warmup):
+            if t.decode_raw(enc_dev, offsets, tok, lens, logs, cnt, max_len):
+                raise RuntimeError("decode failed")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            if t.decode_raw(enc_dev, offsets, tok, lens, logs, cnt, max_len):
+                raise RuntimeError("decode failed")
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        st = t.stats()
+        return {"workload": f"{shape.name}-like: {U} utterances, {frames} frames, Dj={shape.d_joint}, V={shape.vocab}, "
+                            f"LSTM {shape.pred_layers}x{shape.pred_hidden}, N={N}, S={S}",
+                "frames_per_sec": frames / (ms / 1e3), "ms_per_step": ms, "steps": steps,
+                "calls_per_frame": st["joiner_calls"] / max(frames, 1),
+                "joins_per_frame": st["joined_frames"] / max(frames, 1), "joiner_launches_per_step": st["launches"]}
+    finally:
+        t.close()
+
+
 def measure_at_scale(iters=6, chunk_rows=0):
     """One joiner + expansion call on the shape of the largest configuration (1024 utterances,
     N=10, S=5, Dj=1024, V=4096: 51200 joiner rows, a full beam everywhere), where the two kernels
@@ -118,6 +157,9 @@ def main():
                     help="decode through tbs_push_segment, every utterance receiving this many frames per "
                          "push (0 = tbs_decode on whole utterances, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short decodes of the other configurations reported beside the headline")
+    ap.add_argument("--debug", type=int, default=0, help="tbs_config.debug of the timed context (kernel variants)")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--at-scale-only", action="store_true",
                     help="only the joiner + expansion call on the largest configuration's shape (for profiling)")
@@ -159,7 +201,7 @@ def main():
     piece = args.stream_piece
     tbs = Tbs(model, blank_id=shape.blank_id, beam_n=N, seg_s=S, max_utts=U, max_frames_total=frames,
               dtype=shape.dtype, act=shape.act, stream_buffer_frames=(piece + S) if piece else 0,
-              joiner_chunk_rows=args.chunk_rows)
+              joiner_chunk_rows=args.chunk_rows, debug=args.debug)
     enc_dev = tbs.upload_frames(enc)           # inputs resident in HBM before the timed region
     max_len = 256
     tok = np.full((U, N, max_len), -1, np.int32)
@@ -208,11 +250,16 @@ def main():
     if not args.no_kernel_timing:
         H, E, Dj, V, L = shape.pred_hidden, shape.pred_embed, shape.d_joint, shape.vocab, shape.pred_layers
         bf16 = shape.dtype == "bf16"
+        # (small batches run expansion + select/merge as one kernel, "round"; timing "expand" or
+        # "select_merge" there reads nothing, or the two-kernel form where the batch keeps row lists)
         for name, kid in (("gemm", KERNEL.GEMM), ("joiner_gemm", KERNEL.JOINER), ("joiner_prep", KERNEL.PREP),
-                          ("expand", KERNEL.EXPAND), ("select_merge", KERNEL.SELECT), ("predictor", KERNEL.PREDICTOR)):
+                          ("round", KERNEL.ROUND), ("expand", KERNEL.EXPAND), ("select_merge", KERNEL.SELECT),
+                          ("predictor", KERNEL.PREDICTOR)):
             tbs.profile_select(kid)
             step()
-            kernels[name] = tbs.profile_read()
+            r = tbs.profile_read()
+            if r["launches"]:
+                kernels[name] = r
         tbs.profile_select(-1)
         event_cost = tbs.profile_overhead(200)
         for name, r in kernels.items():
@@ -235,12 +282,17 @@ def main():
             r["frac"] = r["achieved"] / r["peak"] if r["peak"] else None
         # the dominant single kernel of this workload: the GEMM kernel (three launches a round) or
         # the expansion kernel, whichever took longer in total
-        dom = max(("gemm", "expand"), key=lambda k: kernels[k]["total_ms"])
+        dom = max((k for k in ("gemm", "expand") if k in kernels), key=lambda k: kernels[k]["total_ms"])
         d = kernels[dom]
         roofline = {"kernel": {"gemm": "k_gemm_small / k_gemm_bf16 (all launches)", "expand": "k_expand_reg"}[dom],
                     "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
                     "frac": d["frac"], "traffic": read_traffic(dom, args.workload), "avg_us": d["avg_us"],
                     "launches": d["launches"],
+                    "note": "achieved = summed algorithmic work / summed HIP-event durations over every launch of "
+                            "the kernel in one decode; an event pair reads event_pair_around_empty_kernel_us around "
+                            "a kernel that does nothing, so microsecond kernels read long (profiles/ has the "
+                            "kernels' own durations); a problem of at most 1 GFLOP per launch is latency-bound: "
+                            "the throughput-bound figures are roofline_at_scale",
                     # the same event pair around a kernel that does nothing: what events add to every
                     # launch of a microsecond-scale kernel (a kernel trace shows that kernel's own time)
                     "event_pair_around_empty_kernel_us": event_cost}
@@ -270,6 +322,15 @@ def main():
         cpu["single_core"] = {"value": float(one_off[-1]) / c1, "unit": "frames/s", "cores": 1,
                               "sample": f"first {n1} utterances ({int(one_off[-1])} frames), {c1:.1f} s"}
 
+    # ---- the other configurations, briefly (not `value`): the large-assistant and throughput shapes,
+    # and the headline shapes at S = 1, i.e. the standard breadth-first search the method generalises
+    others = None
+    if not args.no_other_workloads and not piece and args.workload == "librispeech":
+        tbs.close()
+        others = {"librispeech_s1_standard_search": quick_decode("librispeech", steps=4, warmup=1, seg=1),
+                  "assistant_n10_s3": quick_decode("assistant", steps=2, warmup=1),
+                  "throughput_n10_s5": quick_decode("throughput", steps=2, warmup=1)}
+
     out = {
         "metric": "decoded_frames_per_sec",
         "value": value,
@@ -292,6 +353,7 @@ def main():
         "joiner_launches_per_step": stats["launches"],
         "roofline": roofline,
         "roofline_at_scale": at_scale,
+        "other_workloads": others,
         "cpu_baseline": cpu,
         "kernels": kernels,
     }
