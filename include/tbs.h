@@ -82,8 +82,11 @@ typedef struct tbs_config {
                                  tbs_push_segment also where one kernel would run both; bit 8: keep the
                                  row lists (hypotheses and joiner rows compacted over the batch by a
                                  kernel of its own every round) also where a small batch would run with
-                                 every hypothesis in a fixed place and no such kernel (tests cover each
-                                 pair of variants) */
+                                 every hypothesis in a fixed place and no such kernel; bit 9: with
+                                 seg_s = 1 (the standard breadth-first search, Eq. 1) store the logits and
+                                 expand from them as for longer segments, also where the joiner GEMM
+                                 would keep only each row's softmax sums and best tokens (tests cover
+                                 each pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */
@@ -188,6 +191,12 @@ int tbs_result(tbs_ctx *ctx, int32_t *tokens, int32_t *lens, double *logscores,
  * it), and frames decoded; plus the number of batched joiner launches. */
 int tbs_stats(const tbs_ctx *ctx, int64_t *joiner_calls, int64_t *joined_frames, int64_t *frames,
               int64_t *launches);
+
+/* Which forms of the kernels the batch begun last runs in (they give the same results; tests and
+ * benchmarks use this to say which one they exercised): bit 0 = every hypothesis in a fixed place,
+ * four kernels a round; bit 1 = seg_s = 1 without logits (the standard search of Eq. 1 with the
+ * row softmax sums and best tokens made in the joiner GEMM).  Negative: an error code. */
+int tbs_path(const tbs_ctx *ctx);
 
 /* ---- inspection, for tests ---- */
 enum tbs_buffer {

@@ -356,7 +356,7 @@ __global__ void __launch_bounds__(256)
 k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const float *__restrict__ bias,
              float *__restrict__ C, int M, int N, int K, const int *__restrict__ out_row, long ldc, int tiles_m,
              int tiles_n, int ns, LstmEp ep, JoinEp jp, const int *__restrict__ m_dev,
-             const int *__restrict__ any_dev) {
+             const int *__restrict__ any_dev, PartEp pe) {
     constexpr bool LSTM = MODE == 1;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];   // ns stages
     const int tid = threadIdx.x, lane = tid & 63;
@@ -514,6 +514,97 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         }
         return;
     }
+    if (MODE == 3) {
+        // One-frame segments: no logits leave the kernel.  The tile goes through LDS as above (lane l
+        // gets row l/2 of the wave's 32 and 16 consecutive columns), every lane reduces its 16 logits
+        // to their maximum, the sum of their exponentials, the blank logit if it is among them and its
+        // NP largest non-blank logits, and one thread per row merges the four 16-column pieces of the
+        // row into the tile's partial.
+        gs_barrier();
+        float *sacc = reinterpret_cast<float *>(smem) + wave * (32 * 36);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            sacc[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * 36 + (lane & 31)] = acc[r] + bv;
+        const int rowb = lane >> 1, half = lane & 1, np = pe.np, pw2 = 3 + 2 * np;
+        float q[16];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float4 v = *reinterpret_cast<const float4 *>(sacc + rowb * 36 + half * 16 + k * 4);
+            q[4 * k] = v.x; q[4 * k + 1] = v.y; q[4 * k + 2] = v.z; q[4 * k + 3] = v.w;
+        }
+        const int c0 = tile_n * 64 + wn * 32 + half * 16;
+        float mx = -INFINITY, lb = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (c0 + i < N) mx = fmaxf(mx, q[i]);
+        float z = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (c0 + i < N) z += __expf(q[i] - mx);
+            if (c0 + i == pe.blank) lb = q[i];
+            if (c0 + i >= N || c0 + i == pe.blank) q[i] = -INFINITY;   // not a candidate
+        }
+        float *spart = reinterpret_cast<float *>(smem) + 4 * (32 * 36);   // [64 rows][4 pieces][3 + 2 NP]
+        float *dst = spart + ((wm * 32 + rowb) * 4 + wn * 2 + half) * pw2;
+        dst[0] = mx;
+        dst[1] = z;
+        dst[2] = lb;
+        for (int n = 0; n < np; ++n) {
+            float best = -INFINITY;
+            int bi = -1;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (q[i] > best) { best = q[i]; bi = i; }   // (ascending columns: the smaller token wins a tie)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (i == bi) q[i] = -INFINITY;
+            dst[3 + n] = best;
+            dst[3 + np + n] = __int_as_float(bi >= 0 ? c0 + bi : -1);
+        }
+        gs_barrier();
+        if (tid < 64) {
+            const int row = tile_m * 64 + tid;
+            if (row < M) {
+                const float *src = spart + tid * 4 * pw2;
+                float m = -INFINITY, lbm = -INFINITY;
+#pragma unroll
+                for (int sgm = 0; sgm < 4; ++sgm) {
+                    m = fmaxf(m, src[sgm * pw2]);
+                    lbm = fmaxf(lbm, src[sgm * pw2 + 2]);
+                }
+                float zt = 0.f;
+#pragma unroll
+                for (int sgm = 0; sgm < 4; ++sgm) {
+                    const float ms = src[sgm * pw2];
+                    if (ms > -INFINITY) zt += src[sgm * pw2 + 1] * __expf(ms - m);
+                }
+                float *out = pe.part + ((long)row * tiles_n + tile_n) * part_width(np);
+                out[0] = m;
+                out[1] = zt;
+                out[2] = lbm;
+                out[3] = 0.f;
+                int i0 = 0, i1 = 0, i2 = 0, i3 = 0;   // heads of the four pieces' lists
+                for (int n = 0; n < np; ++n) {
+                    const float v0 = i0 < np ? src[0 * pw2 + 3 + i0] : -INFINITY;
+                    const float v1 = i1 < np ? src[1 * pw2 + 3 + i1] : -INFINITY;
+                    const float v2 = i2 < np ? src[2 * pw2 + 3 + i2] : -INFINITY;
+                    const float v3 = i3 < np ? src[3 * pw2 + 3 + i3] : -INFINITY;
+                    float best = v0;
+                    int bs = 0;
+                    if (v1 > best) { best = v1; bs = 1; }   // (pieces in column order: the smaller token wins a tie)
+                    if (v2 > best) { best = v2; bs = 2; }
+                    if (v3 > best) { best = v3; bs = 3; }
+                    const int bidx = bs == 0 ? i0 : (bs == 1 ? i1 : (bs == 2 ? i2 : i3));
+                    out[4 + n] = best;
+                    out[4 + np + n] = best > -INFINITY ? src[bs * pw2 + 3 + np + bidx] : __int_as_float(-1);
+                    if (best > -INFINITY) {
+                        i0 += bs == 0; i1 += bs == 1; i2 += bs == 2; i3 += bs == 3;
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (MODE == 2) {
         // Same passage through LDS: lane l takes row l/2 and 16 consecutive columns, stores them
         // as the projection and, for each frame of the pair, adds the encoder row and activates.
@@ -614,6 +705,9 @@ static int gemm_small_stages() {
                                     (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess &&
                 hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess &&
+                hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_small<3>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)(ns * GS_STAGE * sizeof(bf16_t))) == hipSuccess) {
                 stages = ns;
                 break;
@@ -642,7 +736,28 @@ hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, c
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
     hipLaunchKernelGGL(k_gemm_small<1>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, Wp, biasp,
-                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep, JoinEp{}, m_dev, any_dev);
+                       nullptr, M, N, K, nullptr, 0L, tiles_m, tiles_n, ns, ep, JoinEp{}, m_dev, any_dev, PartEp{});
+    return hipGetLastError();
+}
+
+bool gemm_part_fits(int M, int N, int K, int np) {
+    const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
+    // (the epilogue's LDS: four 32 x 36 blocks and 64 x 4 lists of 3 + 2 NP values, inside two stages)
+    const size_t lds = sizeof(float) * (4 * 32 * 36 + 64 * 4 * (size_t)(3 + 2 * np));
+    return K % GS_BK == 0 && gemm_small_stages() >= 2 && tiles <= 320 && np >= 1 && np <= 16 &&
+           lds <= 2 * GS_STAGE * sizeof(bf16_t);
+}
+
+hipError_t launch_gemm_part(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, int M, int N, int K,
+                            const PartEp &pe) {
+    if (M <= 0) return hipSuccess;
+    if (!gemm_part_fits(M, N, K, pe.np) || !pe.part) return hipErrorInvalidValue;
+    const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
+    const int ns_max = gemm_small_stages();
+    const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
+    const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
+    hipLaunchKernelGGL(k_gemm_small<3>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, nullptr, M,
+                       N, K, nullptr, 0L, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, nullptr, nullptr, pe);
     return hipGetLastError();
 }
 
@@ -661,7 +776,7 @@ hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, co
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
     hipLaunchKernelGGL(k_gemm_small<2>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C, M,
-                       N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp, m_dev, any_dev);
+                       N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp, m_dev, any_dev, PartEp{});
     return hipGetLastError();
 }
 
@@ -678,7 +793,7 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
             const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
             hipLaunchKernelGGL(k_gemm_small<0>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
-                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, m_dev, nullptr);
+                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, m_dev, nullptr, PartEp{});
             return hipGetLastError();
         }
     }

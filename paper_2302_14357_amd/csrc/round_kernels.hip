@@ -15,10 +15,14 @@ __device__ __forceinline__ unsigned round_bf16(float f) {   // nearest, ties to 
     return v >> 16;
 }
 
-template <int TW, int NV4, int SMAX>
+// S1NP > 0: segments of one frame (the standard breadth-first search, Eq. 1) in the slot layout.  The
+// joiner GEMM kept no logits: `logits` points at its row partials (see PartEp), tiles_n per row, and
+// the expansion of a hypothesis is the merge of its row's partials by one wave (TW = 1, SMAX = 1),
+// lane l taking tile l with a list of up to S1NP candidates in registers.
+template <int TW, int NV4, int SMAX, int S1NP>
 __global__ void __launch_bounds__(1024)
 k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, AView An, BView B, RowView rv,
-        int2 *nodes, float *__restrict__ row_stats, float *__restrict__ delta_nb, FixedView fx) {
+        int2 *nodes, float *__restrict__ row_stats, float *__restrict__ delta_nb, FixedView fx, int tiles_n) {
     constexpr int TT = TW * 64;
     typedef ExpandShared<SMAX, TW> TeamShared;
     extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
@@ -27,7 +31,7 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     const int N = d.N;
     const size_t b_list = ((size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int)) + 15) & ~(size_t)15;
     TeamShared *teams = reinterpret_cast<TeamShared *>(s_raw + b_list);
-    float *s_lc = reinterpret_cast<float *>(teams + N);   // [H, S']
+    float *s_lc = reinterpret_cast<float *>(teams + (S1NP > 0 ? 0 : N));   // [H, S']
     float *s_dphi = s_lc + N * SMAX;                       // [H]
     float *s_cs = s_dphi + N;                              // [H, N]
     int *s_ct = reinterpret_cast<int *>(s_cs + N * N);     // [H, N]
@@ -76,8 +80,67 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     float4 hpar[HP];
     if (own_wave && sel_wave) {
         select_merge_utt(1, d, round, drop, u, sel_lane, logits, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
+        if constexpr (S1NP == 0) {
 #pragma unroll
-        for (int b = 0; b < EXPAND_PAIR_BARRIERS; ++b) __syncthreads();
+            for (int b = 0; b < EXPAND_PAIR_BARRIERS; ++b) __syncthreads();
+        }
+    } else if constexpr (S1NP > 0) {
+        if (pre_h && live) {
+            const long slot = A.slot[(long)u * N + team];
+#pragma unroll
+            for (int q = 0; q < HP; ++q)
+                hpar[q] = reinterpret_cast<const float4 *>(fx.pool_h + slot * d.H)[min(tid + TT * q, H4 - 1)];
+        }
+        // Every request is made whatever the lane's tile and the team's hypothesis are (addresses
+        // clamped to ones that exist); what does not exist is masked afterwards.
+        const int pw = part_width(N), hyp = live ? team : 0;
+        const float *p = logits + ((long)(pair0 + hyp) * tiles_n + min(tid, tiles_n - 1)) * pw;   // (S = 1: a pair's row is its place)
+        const float la = A.dhat[((long)u * N + hyp) * d.S];   // log d_old[1]: alpha_1 of Eq. 3
+        const float4 hd = *reinterpret_cast<const float4 *>(p);
+        float lv[S1NP];
+        int lk[S1NP];
+#pragma unroll
+        for (int n = 0; n < S1NP; ++n) {
+            lv[n] = p[4 + min(n, N - 1)];
+            lk[n] = __float_as_int(p[4 + N + min(n, N - 1)]);
+        }
+        const bool have = live && tid < tiles_n;
+#pragma unroll
+        for (int n = 0; n < S1NP; ++n)
+            if (!have || n >= N || lk[n] < 0) {
+                lv[n] = -INFINITY;
+                lk[n] = 0x7fffffff;
+            }
+        const float mt = have ? hd.x : -INFINITY;
+        const float m = wave_max_ord(mt);
+        const float z = wave_sum(mt > -INFINITY ? hd.y * __expf(mt - m) : 0.f);
+        const float lb = wave_max_ord(have ? hd.z : -INFINITY);
+        // Eq. 1: an expansion's score relative to the hypothesis is the token's (or blank's) log
+        // probability at the frame (plus log alpha_1 = log d_old[1], which is 0 for a normalised d)
+        const float base = la - m - __logf(z);
+        if (tid == 0 && live) {
+            s_dphi[team] = base + lb;
+            s_lc[team] = base;
+        }
+        for (int n = 0; n < N; ++n) {   // the N best of the row: N rounds of arg-max over the lists' heads
+            float bv = lv[0];
+            int bk = lk[0];
+            wave_argmax(bv, bk);
+            const bool ok = bv > -INFINITY;
+            if (tid == 0 && live) {
+                s_cs[team * N + n] = ok ? base + bv : -INFINITY;
+                s_ct[team * N + n] = ok ? bk : -1;
+            }
+            if (ok && lk[0] == bk) {   // (a token lies in one tile: one lane's list moves up)
+#pragma unroll
+                for (int i = 0; i + 1 < S1NP; ++i) {
+                    lv[i] = lv[i + 1];
+                    lk[i] = lk[i + 1];
+                }
+                lv[S1NP - 1] = -INFINITY;
+                lk[S1NP - 1] = 0x7fffffff;
+            }
+        }
     } else {
         if (pre_h && live) {
             const long slot = A.slot[(long)u * N + team];
@@ -105,10 +168,11 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     }
     __syncthreads();
     if (sel_wave) {
+        const float *lg = S1NP > 0 ? nullptr : logits;   // (no logits: d of a new hypothesis over one frame is (1))
         if (own_wave)
-            select_merge_utt(2, d, round, drop, u, sel_lane, logits, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
+            select_merge_utt(2, d, round, drop, u, sel_lane, lg, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
         else
-            select_merge_utt(0, d, round, drop, u, sel_lane, logits, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
+            select_merge_utt(0, d, round, drop, u, sel_lane, lg, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
         if (fx.on) {
             // Slot layout: what a row list kernel would do for this utterance.  The new hypotheses
             // take trie nodes from the utterance's own range, their pairs get their descriptors, the
@@ -187,24 +251,24 @@ static int round_variant(const Dims &d) {
 
 bool round_fits(const Dims &d) { return round_variant(d) != 0; }
 
-template <int TW, int NV4, int SMAX>
+template <int TW, int NV4, int SMAX, int S1NP = 0>
 static hipError_t round_launch(hipStream_t st, const Dims &d, int round, int drop, const float *logits, AView A,
                                AView An, BView B, RowView rv, int2 *nodes, float *row_stats, float *delta_nb,
-                               const FixedView &fx) {
+                               const FixedView &fx, int tiles_n = 0) {
     const size_t b_list = ((size_t)d.BCAP * (sizeof(double) + sizeof(u64) + 3 * sizeof(int)) + 15) & ~(size_t)15;
-    const size_t shm = b_list + (size_t)d.N * sizeof(ExpandShared<SMAX, TW>) +
+    const size_t shm = b_list + (S1NP > 0 ? 0 : (size_t)d.N * sizeof(ExpandShared<SMAX, TW>)) +
                        sizeof(float) * ((size_t)d.N * SMAX + d.N + 2 * (size_t)d.N * d.N);
     static size_t attr_for = 0;
     if (shm > attr_for) {   // (static LDS of the select step comes on top: raise the limit to what the launch needs)
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_round<TW, NV4, SMAX>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_round<TW, NV4, SMAX, S1NP>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e != hipSuccess) return e;
         attr_for = shm;
     }
     // (one wave more for the select step where 1024 threads allow it)
     const int threads = d.N * TW * 64 + (d.N * TW * 64 + 64 <= 1024 ? 64 : 0);
-    hipLaunchKernelGGL((k_round<TW, NV4, SMAX>), dim3(d.U), dim3(threads), shm, st, d, round, drop, logits, A, An,
-                       B, rv, nodes, row_stats, delta_nb, fx);
+    hipLaunchKernelGGL((k_round<TW, NV4, SMAX, S1NP>), dim3(d.U), dim3(threads), shm, st, d, round, drop, logits, A, An,
+                       B, rv, nodes, row_stats, delta_nb, fx, tiles_n);
     return hipGetLastError();
 }
 
@@ -222,4 +286,14 @@ hipError_t launch_round(hipStream_t st, const Dims &d, int round, int drop, cons
         case 15: return round_launch<1, 4, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
         default: return hipErrorInvalidValue;
     }
+}
+
+bool round_s1_fits(const Dims &d) { return d.S == 1 && d.N >= 1 && d.N <= 16 && (d.V + 63) / 64 <= 64 && (d.H & 3) == 0; }
+
+hipError_t launch_round_s1(hipStream_t st, const Dims &d, int round, int drop, const float *part, int tiles_n, AView A,
+                           AView An, BView B, RowView rv, int2 *nodes, const FixedView *fxp) {
+    if (!fxp || !fxp->on || !part || !round_s1_fits(d) || tiles_n != (d.V + 63) / 64) return hipErrorInvalidValue;
+    if (d.N <= 4) return round_launch<1, 1, 1, 4>(st, d, round, drop, part, A, An, B, rv, nodes, nullptr, nullptr, *fxp, tiles_n);
+    if (d.N <= 8) return round_launch<1, 1, 1, 8>(st, d, round, drop, part, A, An, B, rv, nodes, nullptr, nullptr, *fxp, tiles_n);
+    return round_launch<1, 1, 1, 16>(st, d, round, drop, part, A, An, B, rv, nodes, nullptr, nullptr, *fxp, tiles_n);
 }

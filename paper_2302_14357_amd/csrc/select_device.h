@@ -291,25 +291,31 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
                 // banks) between the pass that reads the logits and the one that writes the normalised
                 // result: going through the result array itself cost two more memory round trips.
                 float *dh = An.dhat + an * d.S;
-                float *sd = s_dnew + lane;
-                float mx = -INFINITY;
-                for (int t0 = 0; t0 < sp; t0 += 8) {   // (eight logits asked for before the first is used)
-                    float xv[8];
+                if (logits) {
+                    float *sd = s_dnew + lane;
+                    float mx = -INFINITY;
+                    for (int t0 = 0; t0 < sp; t0 += 8) {   // (eight logits asked for before the first is used)
+                        float xv[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) xv[q] = logits[(long)(row0 + min(t0 + q, sp - 1)) * d.V + tok];
+                        for (int q = 0; q < 8; ++q) xv[q] = logits[(long)(row0 + min(t0 + q, sp - 1)) * d.V + tok];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        if (t0 + q < sp) {
-                            const float x = xv[q] + in.lc[h * sp + t0 + q];
-                            sd[(t0 + q) * TBS_MAX_BEAM] = x;
-                            mx = fmaxf(mx, x);
-                        }
+                        for (int q = 0; q < 8; ++q)
+                            if (t0 + q < sp) {
+                                const float x = xv[q] + in.lc[h * sp + t0 + q];
+                                sd[(t0 + q) * TBS_MAX_BEAM] = x;
+                                mx = fmaxf(mx, x);
+                            }
+                    }
+                    float sum = 0.f;
+                    for (int t = 0; t < sp; ++t) sum += __expf(sd[t * TBS_MAX_BEAM] - mx);
+                    const float lz = mx + __logf(sum);
+                    for (int t = 0; t < sp; ++t) dh[t] = sd[t * TBS_MAX_BEAM] - lz;
+                    for (int t = sp; t < d.S; ++t) dh[t] = -INFINITY;
+                } else {
+                    // (a caller without logits has segments of one frame: d normalised over one frame is (1))
+                    dh[0] = 0.f;
+                    for (int t = 1; t < d.S; ++t) dh[t] = -INFINITY;
                 }
-                float sum = 0.f;
-                for (int t = 0; t < sp; ++t) sum += __expf(sd[t * TBS_MAX_BEAM] - mx);
-                const float lz = mx + __logf(sum);
-                for (int t = 0; t < sp; ++t) dh[t] = sd[t * TBS_MAX_BEAM] - lz;
-                for (int t = sp; t < d.S; ++t) dh[t] = -INFINITY;
             }
         }
     }

@@ -63,6 +63,8 @@ struct tbs_ctx {
     bool expanded_ahead; // tbs_joiner_segment already ran the expansion, piece by piece behind the GEMM of each piece
     // slot layout (small shapes inside tbs_decode / tbs_push_segment, see FixedView)
     bool fixed;         // the current batch runs in the slot layout
+    bool s1;            // ... with segments of one frame and no logits (the joiner GEMM keeps row partials)
+    float *part;        // [U*N, tiles of 64 columns, part_width(N)] row partials (seg_s = 1 only)
     int *utt_nodes;     // [U] trie nodes taken by each utterance from its own range
     int *node_base, *node_cap;   // [U] the ranges
     int *live_sum;      // [2] hypotheses made per launch, alternating
@@ -379,6 +381,8 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         c->amat = p;
     }
     rc |= dev_alloc(c, &c->logits, (size_t)M * d.V);
+    c->part = nullptr;
+    if (d.S == 1 && cfg->dtype == 1) rc |= dev_alloc(c, &c->part, UN * (size_t)((d.V + 63) / 64) * part_width(d.N));
     rc |= dev_alloc(c, &c->row_lc, M);
     rc |= dev_alloc(c, &c->dphi, UN);
     rc |= dev_alloc(c, &c->cand_score, UN * d.N);
@@ -521,12 +525,21 @@ static bool predictor_all_fused(const tbs_ctx *c, int M);
 // LSTM layers with the cell update and the projection with the joiner input rows in their GEMMs'
 // epilogues.  Debug bits that ask for any of the separate forms (or bit 8, for this layout itself)
 // keep the row lists.
+// Segments of one frame: the joiner GEMM can keep row partials instead of logits (unless debug output
+// that needs the logits, or debug bit 9, asks for them), and the round kernel then has no limit on
+// the vocabulary from its registers.
+static bool one_frame_ok(const tbs_ctx *c) {
+    const Dims &d = c->cur;
+    return c->part && !(c->cfg.debug & (1 | 512)) && round_s1_fits(d) && gemm_part_fits(d.U * d.N, d.V, d.Dj, d.N);
+}
+
 static bool fixed_layout_ok(const tbs_ctx *c) {
     const Dims &d = c->cur;
     if (c->cfg.dtype != 1 || (c->cfg.debug & (2 | 8 | 16 | 32 | 64 | 128 | 256)) || c->cfg.joiner_chunk_rows > 0)
         return false;
     if ((d.H & 3) || (long)d.max_nodes - 1 < (long)d.U) return false;
-    return round_fits(d) && gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj) && predictor_all_fused(c, d.U * d.N);
+    return (round_fits(d) || one_frame_ok(c)) && gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj) &&
+           predictor_all_fused(c, d.U * d.N);
 }
 
 // B = [([], 1, InitPredictor(), Null)] for U utterances whose lengths and first frames are h_T / offsets
@@ -580,6 +593,7 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     c->n_frames = frames;
     c->state = ST_BEGUN;
     c->fixed = fixed_layout_ok(c);
+    c->s1 = c->fixed && one_frame_ok(c);
     return TBS_OK;
 }
 
@@ -1106,16 +1120,27 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
         {
             ProfScope ps(c, TBS_K_JOINER, 0);
             ProfScope pg(c, TBS_K_GEMM, 0);
-            HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, c->logits,
-                                       M, d.V, d.Dj, nullptr, d.V));
+            if (c->s1) {
+                const PartEp pe{c->part, d.N, d.blank};
+                HIPCHK(c, launch_gemm_part(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, M, d.V,
+                                           d.Dj, pe));
+            } else {
+                HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out,
+                                           c->logits, M, d.V, d.Dj, nullptr, d.V));
+            }
         }
         AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];
         const int drop = c->cfg.max_rounds_per_segment > 0 && c->round >= c->cfg.max_rounds_per_segment;
         fx.seq = ++c->seq;
         {
             ProfScope ps(c, TBS_K_ROUND, 0);
-            HIPCHK(c, launch_round(c->stream, d, c->round, drop, c->logits, A, An, c->B, c->rv, c->nodes, c->row_stats,
-                                   c->delta_nb, &fx));
+            if (c->s1) {
+                HIPCHK(c, launch_round_s1(c->stream, d, c->round, drop, c->part, (d.V + 63) / 64, A, An, c->B, c->rv,
+                                          c->nodes, &fx));
+            } else {
+                HIPCHK(c, launch_round(c->stream, d, c->round, drop, c->logits, A, An, c->B, c->rv, c->nodes,
+                                       c->row_stats, c->delta_nb, &fx));
+            }
         }
         c->a_cur ^= 1;
         // The LSTM layers go out before the host knows whether the round made anything (they leave at
@@ -1275,6 +1300,12 @@ int tbs_stats(const tbs_ctx *c, int64_t *joiner_calls, int64_t *joined_frames, i
     if (frames) *frames = c->n_frames;
     if (launches) *launches = c->n_launches;
     return TBS_OK;
+}
+
+int tbs_path(const tbs_ctx *c) {
+    if (!c) return TBS_EINVAL;
+    if (c->state == ST_INIT) return TBS_ESTATE;
+    return (c->fixed ? 1 : 0) | (c->s1 ? 2 : 0);
 }
 
 // ------------------------------------------------------------------ inspection

@@ -121,6 +121,18 @@ struct JoinEp {
     int act;             // 0 tanh, 1 relu
 };
 
+// Segments of one frame (the standard breadth-first search, Eq. 1): the joiner GEMM keeps no logits.
+// Its epilogue leaves, per row and per tile of 64 columns, what the expansion of a one-frame segment
+// needs of them: part[(row * tiles_n + tile) * PW ..] = maximum, sum of exp(l - maximum), the blank
+// logit (-inf if blank is in another tile), a spare, then the NP largest non-blank logits in
+// descending order (-inf where there are fewer) and their tokens (as integer bit patterns, -1).
+struct PartEp {
+    float *part;
+    int np;      // NP = beam size
+    int blank;
+};
+__host__ __device__ inline int part_width(int np) { return (4 + 2 * np + 3) & ~3; }   // (whole 16-byte pieces)
+
 // ---- launchers (each enqueues on `st` and returns the HIP status) ----
 hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, AView A1, RowView rv, int2 *nodes,
                              float *pool_p, float *pool_h, float *pool_c, const float *pred_init,
@@ -159,6 +171,10 @@ bool gemm_join_fits(int M, int N, int K);
 hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
                             int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev = nullptr,
                             const int *any_dev = nullptr);
+// joiner GEMM of one-frame segments: row partials instead of logits (see PartEp)
+bool gemm_part_fits(int M, int N, int K, int np);
+hipError_t launch_gemm_part(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, int M, int N, int K,
+                            const PartEp &pe);
 hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);
 hipError_t launch_expand(hipStream_t st, const Dims &d, int pairs, const float *logits, AView A, RowView rv,
                          float *row_lc, float *dphi, float *cand_score, int *cand_tok, float *row_stats,
@@ -172,6 +188,10 @@ bool round_fits(const Dims &d);
 hipError_t launch_round(hipStream_t st, const Dims &d, int round, int drop, const float *logits, AView A, AView An,
                         BView B, RowView rv, int2 *nodes, float *row_stats, float *delta_nb,
                         const FixedView *fx = nullptr);
+// the same for one-frame segments in the slot layout, from the joiner GEMM's row partials
+bool round_s1_fits(const Dims &d);
+hipError_t launch_round_s1(hipStream_t st, const Dims &d, int round, int drop, const float *part, int tiles_n, AView A,
+                           AView An, BView B, RowView rv, int2 *nodes, const FixedView *fx);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,
                               const void *embed, const float *pool_h, void *xh);
 hipError_t launch_pred_gather_h(hipStream_t st, const Dims &d, int pairs, AView A, RowView rv, const float *pool_h,

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "tbs_select_merge", "tbs_predictor_step", "tbs_decode", "tbs_result", "tbs_stats", "tbs_debug_read",
     "tbs_debug_write", "tbs_debug_rebuild", "tbs_debug_hyps", "tbs_profile_select", "tbs_profile_read",
     "tbs_strerror", "tbs_last_hip_error", "tbs_gemm_bf16", "tbs_stream_begin", "tbs_push_segment",
-    "tbs_profile_overhead", "tbs_debug_hyps_noalloc",
+    "tbs_profile_overhead", "tbs_debug_hyps_noalloc", "tbs_path",
 ]
 
 TBS_MAX_LAYERS = 4
@@ -82,6 +82,7 @@ def load_library():
     L.tbs_stream_begin.argtypes = [vp, i32]
     L.tbs_push_segment.argtypes = [vp, vp, vp, i32]
     L.tbs_stats.argtypes = [vp, i64p, i64p, i64p, i64p]
+    L.tbs_path.argtypes = [vp]
     L.tbs_debug_read.argtypes = [vp, i32, vp, C.c_size_t]
     L.tbs_debug_write.argtypes = [vp, i32, vp, C.c_size_t]
     L.tbs_debug_rebuild.argtypes = [vp, i32, C.POINTER(i32)]
@@ -257,6 +258,12 @@ class Tbs:
         a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
         _check(self.L.tbs_stats(self.ctx, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
         return {"joiner_calls": a.value, "joined_frames": b.value, "frames": c.value, "launches": d.value}
+
+    def path(self):
+        v = self.L.tbs_path(self.ctx)
+        if v < 0:
+            _check(v, self.ctx)
+        return {"fixed_places": bool(v & 1), "one_frame_no_logits": bool(v & 2)}
 
     # ---- inspection
     def counts(self):
