@@ -79,8 +79,12 @@ def quick_decode(workload, steps=2, warmup=1, seg=0, beam=0, debug=0):
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / steps * 1e3
         st = t.stats()
+        path = t.path()
         return {"workload": f"{shape.name}-like: {U} utterances, {frames} frames, Dj={shape.d_joint}, V={shape.vocab}, "
                             f"LSTM {shape.pred_layers}x{shape.pred_hidden}, N={N}, S={S}",
+                "kernels": ("four kernels a round, hypotheses in fixed places" if path["fixed_places"] else
+                            "row lists, kernels sized by the round's rows") +
+                           ("; joiner GEMM keeps row softmax sums and best tokens, no logits" if path["one_frame_no_logits"] else ""),
                 "frames_per_sec": frames / (ms / 1e3), "ms_per_step": ms, "steps": steps,
                 "calls_per_frame": st["joiner_calls"] / max(frames, 1),
                 "joins_per_frame": st["joined_frames"] / max(frames, 1), "joiner_launches_per_step": st["launches"]}
@@ -201,7 +205,8 @@ def main():
     piece = args.stream_piece
     tbs = Tbs(model, blank_id=shape.blank_id, beam_n=N, seg_s=S, max_utts=U, max_frames_total=frames,
               dtype=shape.dtype, act=shape.act, stream_buffer_frames=(piece + S) if piece else 0,
-              joiner_chunk_rows=args.chunk_rows, debug=args.debug)
+              joiner_chunk_rows=args.chunk_rows, debug=args.debug,
+              rounds_capacity=(4 * S if S > 16 else 0))   # (a long segment can take more rounds than the default 32)
     enc_dev = tbs.upload_frames(enc)           # inputs resident in HBM before the timed region
     max_len = 256
     tok = np.full((U, N, max_len), -1, np.int32)
@@ -328,6 +333,8 @@ def main():
     if not args.no_other_workloads and not piece and args.workload == "librispeech":
         tbs.close()
         others = {"librispeech_s1_standard_search": quick_decode("librispeech", steps=4, warmup=1, seg=1),
+                  "librispeech_s1_standard_search_logits_stored": quick_decode("librispeech", steps=4, warmup=1, seg=1,
+                                                                               debug=512),
                   "assistant_n10_s3": quick_decode("assistant", steps=2, warmup=1),
                   "throughput_n10_s5": quick_decode("throughput", steps=2, warmup=1)}
 
