@@ -99,6 +99,11 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
     if (sp == 0) {  // finished (or empty) utterance: B keeps the final list
         if (tid == 0) A.count[u] = 0;
         if (fx.on) {
+            if (tid == 0) {
+                int *fig = fx.fig + u * TBS_FIG_SIZE;
+                fig[TBS_FIG_SP] = 0;
+                fig[TBS_FIG_CNT] = 0;
+            }
             if (tid < d.N) pair_mark_dead(rv, u * d.N + tid, u, d.S);
             if (tid == 0) store_host(fx.host_live + (fx.seq & 1) * d.U + u, fx.seq << 8);
         }
@@ -162,6 +167,11 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
             }
         }
         if (tid == 0) {
+            int *fig = fx.fig + u * TBS_FIG_SIZE;
+            fig[TBS_FIG_SP] = sp;
+            fig[TBS_FIG_CNT] = cnt;
+            fig[TBS_FIG_NB] = 0;
+            fig[TBS_FIG_PAR] = parity;
             atomicAdd(fx.live_sum + (fx.seq & 1), cnt);
             store_host(fx.host_live + (fx.seq & 1) * d.U + u, (fx.seq << 8) | cnt);
         }

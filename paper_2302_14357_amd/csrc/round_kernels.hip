@@ -45,14 +45,39 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     const bool sel_wave = own_wave ? (int)threadIdx.x >= N * TT : (int)threadIdx.x < WAVE;
     const int sel_lane = (int)threadIdx.x & 63;
     __shared__ SelectOut s_out;
-    const SelectFigs fg = select_figs(u, A, B, rv);
+    // Slot layout: everything the round has to know of the utterance lies side by side and comes
+    // with one request.
+    SelectFigs fg;
+    int used0 = 0, ncap = 0, nbase = 0;
+    if (fx.on) {
+        cint_p f = (cint_p)(fx.fig + u * TBS_FIG_SIZE);
+        fg.sp = f[TBS_FIG_SP];
+        fg.cntA = f[TBS_FIG_CNT];
+        fg.nB0 = f[TBS_FIG_NB];
+        fg.parity = f[TBS_FIG_PAR];
+        fg.urow0 = u * N * d.S;
+        used0 = f[TBS_FIG_USED];
+        ncap = f[TBS_FIG_CAP];
+        nbase = f[TBS_FIG_BASE];
+    } else {
+        fg = select_figs(u, A, B, rv);
+    }
+    // Slot layout: where a hypothesis' logits lie follows from its place alone, so the teams ask for
+    // them before anything is known about the utterance (all S rows of the place, or of the
+    // utterance's first place for a team beyond N: memory that exists whatever it holds); what turns
+    // out not to be a frame of a live hypothesis is cleared below.  The utterance's figures and the
+    // logits then take one memory round trip together instead of two in a row.
+    const bool early = S1NP == 0 && fx.on && !(own_wave && sel_wave);
+    const int hslot = fx.on && fx.xh ? A.slot[(long)u * N + (team < N ? team : 0)] : 0;   // (of a hypothesis that may not exist)
+    float e[SMAX][NV4 * 4];
+    if (S1NP == 0 && early)
+        expand_load<NV4, SMAX, TT>(e, logits, (u * N + (team < N ? team : 0)) * d.S, d.S, d.V, tid);
     const int sp = fg.sp;
     const int H = sp > 0 ? fg.cntA : 0;
-    // (asked for now, needed at the end)
-    const int used0 = fx.on ? fx.utt_nodes[u] : 0, ncap = fx.on ? fx.node_cap[u] : 0, nbase = fx.on ? fx.node_base[u] : 0;
     if (H == 0) {   // (the same for the whole workgroup: nobody reaches a barrier)
         if (threadIdx.x == 0) An.count[u] = 0;
         if (fx.on) {
+            if (threadIdx.x == 0) fx.fig[u * TBS_FIG_SIZE + TBS_FIG_CNT] = 0;
             if ((int)threadIdx.x < N) pair_mark_dead(rv, u * N + (int)threadIdx.x, u, d.S);
             if (threadIdx.x == 0) {
                 if (u == 0) fx.live_sum[(fx.seq + 1) & 1] = 0;
@@ -62,7 +87,7 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
         return;
     }
     // (the utterance's pairs and rows follow each other: nothing is read from the pair list)
-    const int pair0 = fx.on ? u * N : rv.utt_pair0[u], urow0 = fx.on ? u * N * d.S : fg.urow0;
+    const int pair0 = fx.on ? u * N : rv.utt_pair0[u], urow0 = fg.urow0;
     const bool live = team < H;
     SelectIn in;
     in.cand_score = s_cs;
@@ -142,12 +167,6 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
             }
         }
     } else {
-        if (pre_h && live) {
-            const long slot = A.slot[(long)u * N + team];
-#pragma unroll
-            for (int q = 0; q < HP; ++q)
-                hpar[q] = reinterpret_cast<const float4 *>(fx.pool_h + slot * d.H)[min(tid + TT * q, H4 - 1)];
-        }
         ExpandPair<SMAX> pi;
         if (live) {
             expand_pair_info_at(pi, pair0 + team, urow0 + team * (fx.on ? d.S : sp), sp, u, team, d, A, logits);
@@ -161,10 +180,27 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
                 pi.lblank[t] = 0.f;
             }
         }
-        float e[SMAX][NV4 * 4];
-        expand_load<NV4, SMAX, TT>(e, logits, pi.row0, pi.sp, d.V, tid);
+        if (!early) {
+            expand_load<NV4, SMAX, TT>(e, logits, pi.row0, pi.sp, d.V, tid);
+        } else {
+#pragma unroll
+            for (int t = 0; t < SMAX; ++t)
+                if (t >= pi.sp) {   // (uniform) not a frame: whatever was read, it must be a number
+#pragma unroll
+                    for (int c = 0; c < NV4 * 4; ++c) e[t][c] = 0.f;
+                }
+        }
         expand_pair<NV4, SMAX, TT>(e, pi, teams[team], d, tid, live, s_lc + team * sp, s_dphi + team, s_cs + team * N,
                                    s_ct + team * N, row_stats, delta_nb);
+        // (the parent's h is asked for only now, by the state slot asked for at the start: requests
+        // made beside those for the logits would have to be waited for with them, two round trips
+        // in a row; here the row's trip runs while the select step works)
+        if (pre_h && live) {
+            const long slot = hslot;
+#pragma unroll
+            for (int q = 0; q < HP; ++q)
+                hpar[q] = reinterpret_cast<const float4 *>(fx.pool_h + slot * d.H)[min(tid + TT * q, H4 - 1)];
+        }
     }
     __syncthreads();
     if (sel_wave) {
@@ -202,7 +238,10 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
             }
             const bool any_full = __ballot(full) != 0;
             if (lane == 0) {
-                fx.utt_nodes[u] = min(used0 + total, ncap);
+                int *fig = fx.fig + u * TBS_FIG_SIZE;
+                fig[TBS_FIG_CNT] = total;
+                fig[TBS_FIG_NB] = s_out.nB;
+                fig[TBS_FIG_USED] = min(used0 + total, ncap);
                 if (total) atomicAdd(fx.live_sum + (fx.seq & 1), total);
                 if (u == 0) fx.live_sum[(fx.seq + 1) & 1] = 0;
                 store_host(fx.host_live + (fx.seq & 1) * d.U + u, (fx.seq << 8) | (any_full ? 64 : 0) | total);

@@ -49,6 +49,7 @@ __device__ __forceinline__ void store_host(int *p, int v) {
 // What select_merge_utt leaves in LDS about the list A it made, for a caller that goes on with it.
 struct SelectOut {
     int total;
+    int nB;   // entries of B after the merge
     int slot[TBS_MAX_BEAM], pslot[TBS_MAX_BEAM], tok[TBS_MAX_BEAM], pnode[TBS_MAX_BEAM];
     int parent[TBS_MAX_BEAM];   // index in A of the hypothesis each new one was made from
 };
@@ -68,6 +69,8 @@ __device__ __forceinline__ void pair_mark_dead(const RowView &rv, int j, int u, 
 // What the expansion step left for this utterance: logarithms and tokens of the N best expansions
 // of each of its hypotheses [H, N], the logarithm of each blank expansion [H], and per frame of each
 // hypothesis log(alpha_t / Z_t) - m_t [H, S'] (any of them in LDS or in device memory).
+#define SEL_PRE_FRAMES 8   // segments up to this long have their candidates' logits asked for ahead of the ranking
+
 struct SelectIn {
     const float *cand_score;
     const int *cand_tok;
@@ -115,6 +118,7 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
     __shared__ int s_keep[TBS_MAX_BEAM];
     __shared__ double s_thr;
     __shared__ float s_dnew[TBS_MAX_SEG * TBS_MAX_BEAM];   // frame distributions of the new hypotheses, [frame][hypothesis]
+    __shared__ float s_xpre[SEL_PRE_FRAMES * WAVE];        // logits of the candidates' tokens, [frame][candidate]
     const int N = d.N;
     const int sp = fg.sp, cntA = fg.cntA, urow0 = fg.urow0, nB0 = fg.nB0, parity = fg.parity;
     const int H = sp > 0 ? cntA : 0;
@@ -155,6 +159,18 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         }
         sel_sync();
         for (int c = lane; c < nc; c += WAVE) s_key[c] = s_ctok[c] >= 0 ? s_alogs[c / N] + s_key[c] : nan("");
+        // The d of a new hypothesis (below) needs the logits of its token at the S' frames.  Which
+        // candidates become hypotheses is known only after the ranking, so where a lane per candidate
+        // suffices the logits of every candidate's token are asked for now and wait in registers: their
+        // round trip runs beside the merge and the ranking instead of behind them.
+        const bool pre_x = logits != nullptr && nc <= WAVE && sp <= SEL_PRE_FRAMES && !drop;
+        float xpre[SEL_PRE_FRAMES];
+        if (pre_x) {
+            const int c = min(lane, nc - 1), tokc = max(s_ctok[c], 0);
+            const float *lrow = logits + (long)(urow0 + (c / N) * (in.slot_rows ? d.S : sp)) * d.V + tokc;
+#pragma unroll
+            for (int q = 0; q < SEL_PRE_FRAMES; ++q) xpre[q] = lrow[(long)min(q, sp - 1) * d.V];
+        }
 
         // --- AddAndMerge of every blank expansion.  The hypotheses of A are distinct sequences and so
         // are the entries of B, so each hypothesis matches at most one old entry and no entry added in
@@ -202,7 +218,10 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
                 B.slot[bbase + i] = s_bslot[i];
             }
         }
-        if (lane == 0) B.count[u] = nB;
+        if (lane == 0) {
+            B.count[u] = nB;
+            if (out) out->nB = nB;
+        }
 
         // --- threshold = ChooseNthScore(B, N), only defined when B holds N entries.  The rank of an
         // entry is the number of entries that beat it (larger score, or equal score and earlier
@@ -244,6 +263,10 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         if (lane < N) {
             const int c = s_sel[lane];
             if (c >= 0) s_keep[lane] = (!have_thr) || (s_key[c] > thr);
+        }
+        if (pre_x) {
+#pragma unroll
+            for (int q = 0; q < SEL_PRE_FRAMES; ++q) s_xpre[q * WAVE + lane] = xpre[q];
         }
         sel_sync();
         if (drop) {
@@ -296,8 +319,13 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
                     float mx = -INFINITY;
                     for (int t0 = 0; t0 < sp; t0 += 8) {   // (eight logits asked for before the first is used)
                         float xv[8];
+                        if (pre_x) {
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) xv[q] = logits[(long)(row0 + min(t0 + q, sp - 1)) * d.V + tok];
+                            for (int q = 0; q < 8; ++q) xv[q] = q < SEL_PRE_FRAMES ? s_xpre[q * WAVE + c] : 0.f;
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) xv[q] = logits[(long)(row0 + min(t0 + q, sp - 1)) * d.V + tok];
+                        }
 #pragma unroll
                         for (int q = 0; q < 8; ++q)
                             if (t0 + q < sp) {

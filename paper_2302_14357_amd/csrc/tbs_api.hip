@@ -65,8 +65,7 @@ struct tbs_ctx {
     bool fixed;         // the current batch runs in the slot layout
     bool s1;            // ... with segments of one frame and no logits (the joiner GEMM keeps row partials)
     float *part;        // [U*N, tiles of 64 columns, part_width(N)] row partials (seg_s = 1 only)
-    int *utt_nodes;     // [U] trie nodes taken by each utterance from its own range
-    int *node_base, *node_cap;   // [U] the ranges
+    int *utt_fig;       // [U, TBS_FIG_SIZE] each utterance's figures for the round kernel, among them its range of the trie
     int *live_sum;      // [2] hypotheses made per launch, alternating
     int *h_live;        // pinned [U]: what each utterance's workgroup tells the host
     int *h_live_dev;    // device view of the same memory
@@ -364,9 +363,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->rv.row_enc, M);
     rc |= dev_alloc(c, &c->rv.row_slot, M);
     rc |= dev_alloc(c, &c->rv.counts, TBS_CNT_SIZE);
-    rc |= dev_alloc(c, &c->utt_nodes, U);
-    rc |= dev_alloc(c, &c->node_base, U);
-    rc |= dev_alloc(c, &c->node_cap, U);
+    rc |= dev_alloc(c, &c->utt_fig, U * TBS_FIG_SIZE);
     rc |= dev_alloc(c, &c->live_sum, 2);
     rc |= dev_alloc(c, &c->utt_T, U);
     rc |= dev_alloc(c, &c->utt_off, U + 1);
@@ -553,13 +550,12 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
     HIPCHK(c, hipMemcpyAsync(c->utt_off, offsets, sizeof(int) * (U + 1), hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, launch_init_batch(c->stream, c->cur, c->B, c->A[0], c->A[1], c->rv, c->nodes, c->pool_p, c->pool_h,
                                 c->pool_c, c->w.pred_init, c->pool_rows));
-    HIPCHK(c, hipMemsetAsync(c->utt_nodes, 0, sizeof(int) * U, c->stream));
     HIPCHK(c, hipMemsetAsync(c->live_sum, 0, sizeof(int) * 2, c->stream));
     memset(c->h_live, 0, 2 * sizeof(int) * (size_t)c->d.U);
     c->fx_calls = c->fx_joined = 0;
     // Slot layout: every utterance takes trie nodes from a range of its own, sized in proportion to
     // its length (a stream's utterances, whose lengths are not known, share equally); node 0 is the root.
-    std::vector<int> nb(U), nc(U);
+    std::vector<int> fig((size_t)U * TBS_FIG_SIZE, 0);
     {
         const int S = c->cur.S;
         double weight_all = 0.0;
@@ -570,13 +566,12 @@ static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int3
             const double w = max_T > 0 ? (double)(c->h_T[u] + S) : 1.0;
             long n = (long)((double)pool * (w / weight_all));
             if (at + n > (long)c->cur.max_nodes) n = (long)c->cur.max_nodes - at;
-            nb[u] = (int)at;
-            nc[u] = (int)(n < 0 ? 0 : n);
-            at += nc[u];
+            fig[(size_t)u * TBS_FIG_SIZE + TBS_FIG_BASE] = (int)at;
+            fig[(size_t)u * TBS_FIG_SIZE + TBS_FIG_CAP] = (int)(n < 0 ? 0 : n);
+            at += n < 0 ? 0 : n;
         }
     }
-    HIPCHK(c, hipMemcpyAsync(c->node_base, nb.data(), sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
-    HIPCHK(c, hipMemcpyAsync(c->node_cap, nc.data(), sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->utt_fig, fig.data(), sizeof(int) * fig.size(), hipMemcpyHostToDevice, c->stream));
     // the host arrays above are read by the copies: finish them before returning
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->seg = -1;
@@ -1094,9 +1089,7 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
     fx.on = 1;
     fx.seg = seg_index;
     fx.utt_off = c->utt_off;
-    fx.utt_nodes = c->utt_nodes;
-    fx.node_base = c->node_base;
-    fx.node_cap = c->node_cap;
+    fx.fig = c->utt_fig;
     fx.live_sum = c->live_sum;
     fx.host_live = c->h_live_dev;
     fx.pool_h = c->pool_h;

@@ -66,9 +66,11 @@ struct FixedView {
     int on;
     int seg;
     const int *utt_off;   // [U] first frame row of each utterance
-    int *utt_nodes;       // [U] trie nodes each utterance has taken from its range
-    const int *node_base; // [U] first node of each utterance's range of the trie ...
-    const int *node_cap;  // [U] ... and its size (the ranges share the trie in proportion to the utterances' lengths)
+    int *fig;             // [U, 8] what a round needs to know of an utterance before it can start, side by side so
+                          //        that one request brings all of it (indices TBS_FIG_*): S' of the segment, the
+                          //        hypotheses in A, the entries of B, the state arena, then the trie nodes the
+                          //        utterance has taken from its range, the range's size and its first node (the
+                          //        ranges share the trie in proportion to the utterances' lengths)
     int *live_sum;        // [2] hypotheses made by all utterances in launch seq (slot seq & 1): kernels queued
                           //     behind it leave at once when it is zero
     int *host_live;       // pinned [2, U], half seq & 1: (seq << 8) | (trie full << 6) | hypotheses made
@@ -76,6 +78,9 @@ struct FixedView {
     const float *pool_h;  // first LSTM layer's h by state slot, and where the new hypotheses' input rows go:
     bf16_t *xh;           // xh[j, :] = bf16(h of the parent of pair j)   (null: not wanted)
 };
+
+enum { TBS_FIG_SP = 0, TBS_FIG_CNT = 1, TBS_FIG_NB = 2, TBS_FIG_PAR = 3, TBS_FIG_USED = 4, TBS_FIG_CAP = 5,
+       TBS_FIG_BASE = 6, TBS_FIG_SIZE = 8 };
 
 struct Dims {
     int U, N, S, V, Dj, blank;
