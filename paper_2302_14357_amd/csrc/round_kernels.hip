@@ -192,17 +192,17 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
         }
         expand_pair<NV4, SMAX, TT>(e, pi, teams[team], d, tid, live, s_lc + team * sp, s_dphi + team, s_cs + team * N,
                                    s_ct + team * N, row_stats, delta_nb);
-        // (the parent's h is asked for only now, by the state slot asked for at the start: requests
-        // made beside those for the logits would have to be waited for with them, two round trips
-        // in a row; here the row's trip runs while the select step works)
-        if (pre_h && live) {
-            const long slot = hslot;
-#pragma unroll
-            for (int q = 0; q < HP; ++q)
-                hpar[q] = reinterpret_cast<const float4 *>(fx.pool_h + slot * d.H)[min(tid + TT * q, H4 - 1)];
-        }
     }
     __syncthreads();
+    // (the parent's h is asked for only now, by the state slot asked for at the start: requests made
+    // beside those for the logits would have to be waited for with them, two round trips in a row;
+    // here the row's trip runs while the select step works)
+    if (S1NP == 0 && pre_h && live && !(own_wave && sel_wave)) {
+        const long slot = hslot;
+#pragma unroll
+        for (int q = 0; q < HP; ++q)
+            hpar[q] = reinterpret_cast<const float4 *>(fx.pool_h + slot * d.H)[min(tid + TT * q, H4 - 1)];
+    }
     if (sel_wave) {
         const float *lg = S1NP > 0 ? nullptr : logits;   // (no logits: d of a new hypothesis over one frame is (1))
         if (own_wave)

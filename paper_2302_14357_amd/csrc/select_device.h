@@ -115,7 +115,6 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
     __shared__ double s_bkey[TBS_MAX_BEAM];
     __shared__ int s_match[TBS_MAX_BEAM];
     __shared__ int s_sel[TBS_MAX_BEAM];      // candidate index by rank
-    __shared__ int s_keep[TBS_MAX_BEAM];
     __shared__ double s_thr;
     __shared__ float s_dnew[TBS_MAX_SEG * TBS_MAX_BEAM];   // frame distributions of the new hypotheses, [frame][hypothesis]
     __shared__ float s_xpre[SEL_PRE_FRAMES * WAVE];        // logits of the candidates' tokens, [frame][candidate]
@@ -147,18 +146,21 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
                 s_alen[lane] = A.len[a];
                 s_aslot[lane] = A.slot[a];
             }
-            if (lane < N) { s_sel[lane] = -1; s_keep[lane] = 0; }
+            if (lane < N) s_sel[lane] = -1;
         }
         if (PHASE == 1) return;
         // --- the candidates and the blank expansions (dphi holds log delta_blank)
+        if (PHASE == 0) sel_sync();   // (A's scores, staged just above, are read by other lanes below)
         if (lane < H) s_bkey[lane] = s_alogs[lane] + (double)in.dphi[lane];
         const int nc = H * N;
+        const float rcp_n = __builtin_amdgcn_rcpf((float)N);   // c / N as (c + 0.5) * (1 / N): exact for c < 1024
+        int tok_mine = -1;   // (token of candidate `lane`)
         for (int c = lane; c < nc; c += WAVE) {
-            s_ctok[c] = in.cand_tok[c];
-            s_key[c] = (double)in.cand_score[c];
+            const int tok = in.cand_tok[c];
+            if (c == lane) tok_mine = tok;
+            s_ctok[c] = tok;
+            s_key[c] = tok >= 0 ? s_alogs[(int)(((float)c + 0.5f) * rcp_n)] + (double)in.cand_score[c] : nan("");
         }
-        sel_sync();
-        for (int c = lane; c < nc; c += WAVE) s_key[c] = s_ctok[c] >= 0 ? s_alogs[c / N] + s_key[c] : nan("");
         // The d of a new hypothesis (below) needs the logits of its token at the S' frames.  Which
         // candidates become hypotheses is known only after the ranking, so where a lane per candidate
         // suffices the logits of every candidate's token are asked for now and wait in registers: their
@@ -166,8 +168,8 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         const bool pre_x = logits != nullptr && nc <= WAVE && sp <= SEL_PRE_FRAMES && !drop;
         float xpre[SEL_PRE_FRAMES];
         if (pre_x) {
-            const int c = min(lane, nc - 1), tokc = max(s_ctok[c], 0);
-            const float *lrow = logits + (long)(urow0 + (c / N) * (in.slot_rows ? d.S : sp)) * d.V + tokc;
+            const int c = min(lane, nc - 1), tokc = max(tok_mine, 0);
+            const float *lrow = logits + (long)(urow0 + (int)(((float)c + 0.5f) * rcp_n) * (in.slot_rows ? d.S : sp)) * d.V + tokc;
 #pragma unroll
             for (int q = 0; q < SEL_PRE_FRAMES; ++q) xpre[q] = lrow[(long)min(q, sp - 1) * d.V];
         }
@@ -178,8 +180,9 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         // place, and the unmatched hypotheses are appended in hypothesis order.
         if (lane < H) s_match[lane] = -1;
         sel_sync();
+        const float rcp_b = __builtin_amdgcn_rcpf((float)max(nB0, 1));   // (exact quotients up to 32 x 2048 pairs)
         for (int c = lane; c < H * nB0; c += WAVE) {
-            const int h = c / nB0, i = c - h * nB0;
+            const int h = (int)(((float)c + 0.5f) * rcp_b), i = c - h * nB0;
             if (s_bhash[i] == s_ahash[h] && s_blen[i] == s_alen[h] && same_sequence(nodes, s_bnode[i], s_anode[h]))
                 s_match[h] = i;
         }
@@ -245,14 +248,15 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates, ranked the
         // same way: larger score first, then the earlier hypothesis, then the smaller token.  The N
         // candidates of a hypothesis arrive sorted by exactly that rule, hypotheses in order, so
-        // "earlier place" decides equal scores.
+        // "earlier place" decides equal scores.  (A place without a candidate holds NaN and never
+        // compares as better.)
         for (int c = lane; c < nc; c += WAVE) {
             const double kc = s_key[c];
             if (kc != kc) continue;  // no candidate in this place
             int rank = 0;
 #pragma unroll 4
             for (int j = 0; j < nc; ++j) {
-                const double kj = s_key[j];   // (a place without a candidate holds NaN and never compares as better)
+                const double kj = s_key[j];
                 rank += kj > kc || (kj == kc && j < c);
             }
             if (rank < N) s_sel[rank] = c;
@@ -260,9 +264,10 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         sel_sync();
         // --- threshold test, in rank order: keep iff |B| < N or score > threshold (strict)
         const double thr = have_thr ? s_thr : 0.0;
+        bool keep = false;   // lane r: the candidate of rank r becomes a hypothesis
         if (lane < N) {
             const int c = s_sel[lane];
-            if (c >= 0) s_keep[lane] = (!have_thr) || (s_key[c] > thr);
+            if (c >= 0) keep = (!have_thr) || (s_key[c] > thr);
         }
         if (pre_x) {
 #pragma unroll
@@ -275,37 +280,35 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
                 if (out) out->total = 0;
             }
         } else {
-            int pos = 0, total = 0;
-            for (int r = 0; r < N; ++r) {
-                const int k = s_keep[r];
-                if (r < lane) pos += k;
-                total += k;
-            }
+            // the kept candidates move up in rank order: place = kept candidates of better rank
+            const u64 km = __ballot(keep);
+            const int pos = __popcll(km & ((1ull << lane) - 1ull)), total = __popcll(km);
             if (lane == 0) {
                 An.count[u] = total;
                 if (out) out->total = total;
             }
-            if (out && lane < N && s_keep[lane]) {
-                const int c = s_sel[lane], h = c / N;
-                out->slot[pos] = tbs_slot_id(u, parity, round, pos, d.R, N);
-                out->pslot[pos] = s_aslot[h];
-                out->tok[pos] = s_ctok[c];
-                out->pnode[pos] = s_anode[h];
-                out->parent[pos] = h;
-            }
-            if (lane < N && s_keep[lane]) {
+            if (keep) {
                 const int c = s_sel[lane];
-                const int h = c / N;
+                const int h = (int)(((float)c + 0.5f) * __builtin_amdgcn_rcpf((float)N));   // c / N for c < 256
                 const int tok = s_ctok[c];
+                const int slot_new = tbs_slot_id(u, parity, round, pos, d.R, N);
+                const int pslot = s_aslot[h], pnode = s_anode[h];
+                if (out) {
+                    out->slot[pos] = slot_new;
+                    out->pslot[pos] = pslot;
+                    out->tok[pos] = tok;
+                    out->pnode[pos] = pnode;
+                    out->parent[pos] = h;
+                }
                 const long an = (long)u * N + pos;
                 An.logs[an] = s_key[c];
-                An.pnode[an] = s_anode[h];
+                An.pnode[an] = pnode;
                 if (!out) An.node[an] = -1;   // (a caller that takes `out` assigns the node itself)
                 An.token[an] = tok;
                 An.hash[an] = hash_append(s_ahash[h], tok);
                 An.len[an] = s_alen[h] + 1;
-                An.pslot[an] = s_aslot[h];
-                An.slot[an] = tbs_slot_id(u, parity, round, pos, d.R, N);
+                An.pslot[an] = pslot;
+                An.slot[an] = slot_new;
                 // d of the new hypothesis (Eq. 5 for the chosen token), normalised by its sum (Eq. 6)
                 const int row0 = urow0 + h * (in.slot_rows ? d.S : sp);
                 // (kept as logarithms: over a long segment d spans more than the range of float, and
@@ -314,18 +317,31 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
                 // banks) between the pass that reads the logits and the one that writes the normalised
                 // result: going through the result array itself cost two more memory round trips.
                 float *dh = An.dhat + an * d.S;
-                if (logits) {
+                if (pre_x) {
+                    // (the S' <= 8 values stay in registers)
+                    float x[SEL_PRE_FRAMES];
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int q = 0; q < SEL_PRE_FRAMES; ++q) {
+                        x[q] = s_xpre[q * WAVE + c] + in.lc[h * sp + min(q, sp - 1)];
+                        if (q < sp) mx = fmaxf(mx, x[q]);
+                    }
+                    float sum = 0.f;
+#pragma unroll
+                    for (int q = 0; q < SEL_PRE_FRAMES; ++q)
+                        if (q < sp) sum += __expf(x[q] - mx);
+                    const float lz = mx + __logf(sum);
+#pragma unroll
+                    for (int q = 0; q < SEL_PRE_FRAMES; ++q)
+                        if (q < d.S) dh[q] = q < sp ? x[q] - lz : -INFINITY;
+                    for (int t = SEL_PRE_FRAMES; t < d.S; ++t) dh[t] = -INFINITY;
+                } else if (logits) {
                     float *sd = s_dnew + lane;
                     float mx = -INFINITY;
                     for (int t0 = 0; t0 < sp; t0 += 8) {   // (eight logits asked for before the first is used)
                         float xv[8];
-                        if (pre_x) {
 #pragma unroll
-                            for (int q = 0; q < 8; ++q) xv[q] = q < SEL_PRE_FRAMES ? s_xpre[q * WAVE + c] : 0.f;
-                        } else {
-#pragma unroll
-                            for (int q = 0; q < 8; ++q) xv[q] = logits[(long)(row0 + min(t0 + q, sp - 1)) * d.V + tok];
-                        }
+                        for (int q = 0; q < 8; ++q) xv[q] = logits[(long)(row0 + min(t0 + q, sp - 1)) * d.V + tok];
 #pragma unroll
                         for (int q = 0; q < 8; ++q)
                             if (t0 + q < sp) {
