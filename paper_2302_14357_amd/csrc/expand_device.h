@@ -260,7 +260,7 @@ __device__ __forceinline__ void expand_pair(float (&e)[SMAX][NV4 * 4], const Exp
         float m = sm.pm[t][0];
 #pragma unroll
         for (int w = 1; w < TW; ++w) m = fmaxf(m, sm.pm[t][w]);
-        __builtin_amdgcn_sched_barrier(0);   // one row at a time: the partial results of all rows at once cost registers
+        if (SMAX * TW > 8) __builtin_amdgcn_sched_barrier(0);   // one row at a time: the partial results of many rows at once cost registers
         mrow[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(m)));   // uniform: a scalar register
     }
     // ---- e = exp(l - m_t), once per logit; row sums across the workgroup

@@ -46,19 +46,25 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     const int sel_lane = (int)threadIdx.x & 63;
     __shared__ SelectOut s_out;
     // Slot layout: everything the round has to know of the utterance lies side by side and comes
-    // with one request.
+    // with one request.  What the kernel before this one wrote is asked for by the vector unit, a lane
+    // per value, and handed to the scalar registers by lane reads: a request of the scalar unit for
+    // memory that was written a moment ago was measured at ~1 us, one of the vector unit at a
+    // quarter of that.
     SelectFigs fg;
     int used0 = 0, ncap = 0, nbase = 0;
+    const int lane_w = (int)threadIdx.x & 63;
+    const int team_c = team < N ? team : 0;   // (a team beyond N keeps its requests inside the utterance)
+    int figv = 0;
+    float doldv = 0.f, lbv = 0.f;
     if (fx.on) {
-        cint_p f = (cint_p)(fx.fig + u * TBS_FIG_SIZE);
-        fg.sp = f[TBS_FIG_SP];
-        fg.cntA = f[TBS_FIG_CNT];
-        fg.nB0 = f[TBS_FIG_NB];
-        fg.parity = f[TBS_FIG_PAR];
-        fg.urow0 = u * N * d.S;
-        used0 = f[TBS_FIG_USED];
-        ncap = f[TBS_FIG_CAP];
-        nbase = f[TBS_FIG_BASE];
+        figv = fx.fig[u * TBS_FIG_SIZE + (lane_w & (TBS_FIG_SIZE - 1))];
+        if (S1NP == 0) {
+            // (and, lane t, the hypothesis' d_old[t] and the blank logit of its frame t: rows that exist
+            // whatever they hold)
+            const int t = min(lane_w, d.S - 1);
+            doldv = A.dhat[((long)u * N + team_c) * d.S + t];
+            lbv = logits[((long)(u * N + team_c) * d.S + t) * d.V + d.blank];
+        }
     } else {
         fg = select_figs(u, A, B, rv);
     }
@@ -68,10 +74,19 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     // out not to be a frame of a live hypothesis is cleared below.  The utterance's figures and the
     // logits then take one memory round trip together instead of two in a row.
     const bool early = S1NP == 0 && fx.on && !(own_wave && sel_wave);
-    const int hslot = fx.on && fx.xh ? A.slot[(long)u * N + (team < N ? team : 0)] : 0;   // (of a hypothesis that may not exist)
+    const int hslot = fx.on && fx.xh ? A.slot[(long)u * N + team_c] : 0;   // (of a hypothesis that may not exist)
     float e[SMAX][NV4 * 4];
-    if (S1NP == 0 && early)
-        expand_load<NV4, SMAX, TT>(e, logits, (u * N + (team < N ? team : 0)) * d.S, d.S, d.V, tid);
+    if (S1NP == 0 && early) expand_load<NV4, SMAX, TT>(e, logits, (u * N + team_c) * d.S, d.S, d.V, tid);
+    if (fx.on) {
+        fg.sp = __builtin_amdgcn_readlane(figv, TBS_FIG_SP);
+        fg.cntA = __builtin_amdgcn_readlane(figv, TBS_FIG_CNT);
+        fg.nB0 = __builtin_amdgcn_readlane(figv, TBS_FIG_NB);
+        fg.parity = __builtin_amdgcn_readlane(figv, TBS_FIG_PAR);
+        fg.urow0 = u * N * d.S;
+        used0 = __builtin_amdgcn_readlane(figv, TBS_FIG_USED);
+        ncap = __builtin_amdgcn_readlane(figv, TBS_FIG_CAP);
+        nbase = __builtin_amdgcn_readlane(figv, TBS_FIG_BASE);
+    }
     const int sp = fg.sp;
     const int H = sp > 0 ? fg.cntA : 0;
     if (H == 0) {   // (the same for the whole workgroup: nobody reaches a barrier)
@@ -168,7 +183,16 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
         }
     } else {
         ExpandPair<SMAX> pi;
-        if (live) {
+        if (live && early) {
+            pi.pair = pair0 + team;
+            pi.row0 = urow0 + team * d.S;
+            pi.sp = sp;
+#pragma unroll
+            for (int t = 0; t < SMAX; ++t) {
+                pi.dold[t] = t < sp ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(doldv), t)) : -INFINITY;
+                pi.lblank[t] = t < sp ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lbv), t)) : 0.f;
+            }
+        } else if (live) {
             expand_pair_info_at(pi, pair0 + team, urow0 + team * (fx.on ? d.S : sp), sp, u, team, d, A, logits);
         } else {   // a team without a hypothesis reads the utterance's first row and scores nothing
             pi.pair = pair0;

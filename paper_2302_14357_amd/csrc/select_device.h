@@ -69,6 +69,41 @@ __device__ __forceinline__ void pair_mark_dead(const RowView &rv, int j, int u, 
 // What the expansion step left for this utterance: logarithms and tokens of the N best expansions
 // of each of its hypotheses [H, N], the logarithm of each blank expansion [H], and per frame of each
 // hypothesis log(alpha_t / Z_t) - m_t [H, S'] (any of them in LDS or in device memory).
+// Ranks by counting: the rank of entry i of v[0..n) is the number of entries that beat it (larger
+// value, or equal value and earlier place; NaN beats nothing).  Every entry is read from LDS by all
+// lanes that need it.  Up to 32 entries the wave's lanes share an entry's count (two lanes each up to
+// 32, four up to 16), each counting over a part of the list, and add their counts up.
+// fn(i, rank, value) is called once per entry, by one lane.
+template <class F>
+__device__ __forceinline__ void sel_rank(const double *v, int n, int lane, F fn) {
+    if (n <= 32) {
+        const int parts = n <= 16 ? 4 : 2, width = WAVE / parts;   // lanes per part
+        const int i = lane & (width - 1), part = lane / width;
+        const int per = (n + parts - 1) / parts, j0 = part * per, j1 = min(j0 + per, n);
+        const double mine = v[min(i, n - 1)];
+        int rank = 0;
+#pragma unroll 4
+        for (int j = j0; j < j1; ++j) {
+            const double o = v[j];
+            rank += (o > mine) || (o == mine && j < i);
+        }
+        rank += __shfl_xor(rank, 32);
+        if (parts == 4) rank += __shfl_xor(rank, 16);
+        if (part == 0 && i < n) fn(i, rank, mine);
+    } else {
+        for (int i = lane; i < n; i += WAVE) {
+            const double mine = v[i];
+            int rank = 0;
+#pragma unroll 4
+            for (int j = 0; j < n; ++j) {
+                const double o = v[j];
+                rank += (o > mine) || (o == mine && j < i);
+            }
+            fn(i, rank, mine);
+        }
+    }
+}
+
 #define SEL_PRE_FRAMES 8   // segments up to this long have their candidates' logits asked for ahead of the ranking
 
 struct SelectIn {
@@ -233,34 +268,17 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         // entry on the single wave: readlane and ballot results are needed at once, so nothing
         // overlaps.)
         const bool have_thr = nB >= N;
-        if (have_thr) {
-            for (int i = lane; i < nB; i += WAVE) {
-                const double si = s_blogs[i];
-                int rank = 0;
-#pragma unroll 4
-                for (int j = 0; j < nB; ++j) {
-                    const double sj = s_blogs[j];
-                    rank += (sj > si) || (sj == si && j < i);
-                }
-                if (rank == N - 1) s_thr = si;
-            }
-        }
+        if (have_thr) sel_rank(s_blogs, nB, lane, [&](int i, int rank, double si) {
+            if (rank == N - 1) s_thr = si;
+        });
         // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates, ranked the
         // same way: larger score first, then the earlier hypothesis, then the smaller token.  The N
         // candidates of a hypothesis arrive sorted by exactly that rule, hypotheses in order, so
         // "earlier place" decides equal scores.  (A place without a candidate holds NaN and never
         // compares as better.)
-        for (int c = lane; c < nc; c += WAVE) {
-            const double kc = s_key[c];
-            if (kc != kc) continue;  // no candidate in this place
-            int rank = 0;
-#pragma unroll 4
-            for (int j = 0; j < nc; ++j) {
-                const double kj = s_key[j];
-                rank += kj > kc || (kj == kc && j < c);
-            }
-            if (rank < N) s_sel[rank] = c;
-        }
+        sel_rank(s_key, nc, lane, [&](int c, int rank, double kc) {
+            if (kc == kc && rank < N) s_sel[rank] = c;
+        });
         sel_sync();
         // --- threshold test, in rank order: keep iff |B| < N or score > threshold (strict)
         const double thr = have_thr ? s_thr : 0.0;
