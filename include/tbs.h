@@ -85,8 +85,10 @@ typedef struct tbs_config {
                                  every hypothesis in a fixed place and no such kernel; bit 9: with
                                  seg_s = 1 (the standard breadth-first search, Eq. 1) store the logits and
                                  expand from them as for longer segments, also where the joiner GEMM
-                                 would keep only each row's softmax sums and best tokens (tests cover
-                                 each pair of variants) */
+                                 would keep only each row's softmax sums and best tokens; bit 10: form the
+                                 joiner input rows of a segment's first round in a kernel of their own,
+                                 also where the kernel that starts the segment would (tests cover each
+                                 pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

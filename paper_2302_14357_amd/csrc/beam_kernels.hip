@@ -63,17 +63,33 @@ hipError_t launch_init_batch(hipStream_t st, const Dims &d, BView B, AView A0, A
 
 // ------------------------------------------------------------------ segment head
 // A = ChooseNBest(B); B = []; d = (s, 0, ..., 0)   (Algorithm 1, head of the outer loop)
-// The first wave ranks B and writes A; then the whole workgroup moves the survivors' predictor
-// state into this segment's arena (slot r=0): the arena of the segment before last is reused,
-// and a survivor may have been carried, untouched, from there.
+// The workgroup ranks B and writes A; then it moves the survivors' predictor state into this
+// segment's arena (slot r=0): the arena of the segment before last is reused, and a survivor may have
+// been carried, untouched, from there.  In the slot layout it also forms the joiner input rows of the
+// segment's first round, act(e_t + p) as bf16 (Section 3.1), from the p values it is moving.
+// A SIMD issues an instruction of one of its waves every few cycles, so what counts in a kernel of
+// this size is the number of instructions per SIMD: a workgroup is four waves, one per SIMD, and in
+// the slot layout, where a small batch leaves most of the chip idle, `parts` workgroups share an
+// utterance: each ranks B for itself (a few hundred instructions) and moves its share of the
+// survivors' rows, a 16-byte piece of one row per thread; the first also writes A and the
+// descriptors.  With parts > 1 nothing that the other workgroups of the utterance still have to read
+// is changed here: B's count and the arena flag are left to the round kernel that follows.
+__device__ __forceinline__ unsigned seg_bf16(float f) {   // nearest, ties to even
+    unsigned v = __float_as_uint(f);
+    v += 0x7FFFu + ((v >> 16) & 1u);
+    return v >> 16;
+}
 #define SEG_THREADS 256
-#define SEG_BATCH 5    // survivors whose rows a thread has in flight together in the state copy
+#define SEG_ENC_LOADS ((TBS_FIXED_SMAX * 1024 / 4 + SEG_THREADS - 1) / SEG_THREADS)   // 8-byte pieces of S rows of up to 1024 columns, per thread
 __global__ void __launch_bounds__(SEG_THREADS)
 k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv, float *pool_p,
                 float *pool_h, float *pool_c, long pool_rows, FixedView fx) {
     __shared__ int s_src[TBS_MAX_BEAM], s_dst[TBS_MAX_BEAM];
     __shared__ int s_n;
-    const int u = blockIdx.x, tid = threadIdx.x;
+    __shared__ uint2 s_enc[TBS_FIXED_SMAX * 1024 / 4];   // the segment's frames, [frame][4 columns]
+    const int parts = fx.parts > 1 ? fx.parts : 1;
+    const int u = blockIdx.x / parts, part = blockIdx.x - u * parts, tid = threadIdx.x;
+    const bool first = part == 0;
     // Everything the head of the kernel needs is requested at once, before anything is known:
     // the utterance's figures and, per thread, one entry of B (the first SEG_THREADS entries
     // cover every list but the very longest), so that the ranking below starts after one memory
@@ -87,16 +103,32 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
     const u64 my_hash = B.hash[bb + e0];
     int left = T_u - seg * d.S;
     int sp = left < 0 ? 0 : (left > d.S ? d.S : left);
+    // The frames of the segment come from memory nobody has touched yet, the slowest request of the
+    // kernel: they are asked for now, behind the entries of B (requests come back in order), and wait
+    // in registers until the ranking is done.  Asked for whether wanted or not, from an address that
+    // exists in either case: a request behind a condition would make every later wait a wait for all.
+    const bool rows_here = fx.on && fx.amat != nullptr && sp > 0;
+    const int cp = d.Dj >> 2;   // pieces of four columns in a row
+    uint2 ev[SEG_ENC_LOADS];
+    {
+        const bf16_t *ebase = rows_here ? fx.enc + ((long)fx.utt_off[u] + (long)seg * d.S) * d.Dj
+                                        : reinterpret_cast<const bf16_t *>(pool_p);
+        const int pieces = rows_here ? sp * cp : 1;
+#pragma unroll
+        for (int q = 0; q < SEG_ENC_LOADS; ++q)
+            ev[q] = reinterpret_cast<const uint2 *>(ebase)[min(tid + q * SEG_THREADS, pieces - 1)];   // (rows follow each other)
+    }
     if (tid == 0) {
-        rv.utt_sp[u] = sp;
+        if (first) rv.utt_sp[u] = sp;
         s_n = 0;
     }
-    if (fx.on && tid == 0) {
+    if (fx.on && tid == 0 && first) {
         rv.utt_pair0[u] = u * d.N;
         rv.utt_row0[u] = u * d.N * d.S;
         if (u == 0) fx.live_sum[(fx.seq + 1) & 1] = 0;   // the counter of the launch after this one
     }
     if (sp == 0) {  // finished (or empty) utterance: B keeps the final list
+        if (!first) return;
         if (tid == 0) A.count[u] = 0;
         if (fx.on) {
             if (tid == 0) {
@@ -125,31 +157,38 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
             const long a = (long)u * d.N + rank, b = bb + i;
             const bool mine = i == tid;
             const int src = mine ? my_slot : B.slot[b], dst = tbs_slot_id(u, parity, 0, rank, d.R, d.N);
-            A.logs[a] = si;
-            A.node[a] = mine ? my_node : B.node[b];
-            A.hash[a] = mine ? my_hash : B.hash[b];
-            A.len[a] = mine ? my_len : B.len[b];
-            A.pslot[a] = src;
-            A.slot[a] = dst;
-            A.pnode[a] = -1;
-            A.token[a] = -1;
-            float *dh = A.dhat + a * d.S;
-            dh[0] = 0.f;   // d = (s, 0, ..., 0), normalised and as logarithms
-            for (int t = 1; t < d.S; ++t) dh[t] = -INFINITY;
             s_src[rank] = src;
             s_dst[rank] = dst;
+            if (first) {
+                A.logs[a] = si;
+                A.node[a] = mine ? my_node : B.node[b];
+                A.hash[a] = mine ? my_hash : B.hash[b];
+                A.len[a] = mine ? my_len : B.len[b];
+                A.pslot[a] = src;
+                A.slot[a] = dst;
+                A.pnode[a] = -1;
+                A.token[a] = -1;
+                float *dh = A.dhat + a * d.S;
+                dh[0] = 0.f;   // d = (s, 0, ..., 0), normalised and as logarithms
+                for (int t = 1; t < d.S; ++t) dh[t] = -INFINITY;
+            }
         }
     }
     if (tid == 0) {
-        A.count[u] = nB < d.N ? nB : d.N;
+        if (first) A.count[u] = nB < d.N ? nB : d.N;
         s_n = nB < d.N ? nB : d.N;
     }
+    if (rows_here) {
+#pragma unroll
+        for (int q = 0; q < SEG_ENC_LOADS; ++q)
+            if (tid + q * SEG_THREADS < sp * cp) s_enc[tid + q * SEG_THREADS] = ev[q];
+    }
     __syncthreads();
-    if (tid == 0) {   // (every thread has read the old values by now)
+    if (tid == 0 && parts == 1) {   // (every thread has read the old values by now)
         rv.utt_par[u] = parity;
         B.count[u] = 0;
     }
-    if (fx.on) {   // slot layout: this utterance's pair descriptors for the first round, its count to the host
+    if (fx.on && first) {   // slot layout: this utterance's pair descriptors for the first round, its count to the host
         const int cnt = s_n;
         if (tid < d.N) {
             const int j = u * d.N + tid;
@@ -176,42 +215,51 @@ k_segment_begin(Dims d, int seg, const int *utt_T, BView B, AView A, RowView rv,
             store_host(fx.host_live + (fx.seq & 1) * d.U + u, (fx.seq << 8) | cnt);
         }
     }
-    // The survivors' predictor outputs and LSTM states move to their new slots.  Thread j moves
-    // element j (16 bytes where the widths allow) of every survivor's output row and of its h and c
-    // rows of one layer: up to 3 x SEG_BATCH values requested before the first is stored, so the
-    // copy costs a memory round trip per layer, not one per value.
+    // The survivors' predictor outputs and LSTM states move to their new slots: item (survivor k,
+    // piece j) moves piece j (16 bytes where the widths allow) of the survivor's output row and of
+    // its h and c rows of every layer, all requested before the first is stored.
     const int n = s_n;
     auto copy_all = [&](auto unit_tag, int w) {   // w = floats per unit
         using UNIT = decltype(unit_tag);
         const int up = d.Dj / w, uh = d.H / w, widest = max(up, uh);
-        for (int j = tid; j < widest; j += SEG_THREADS) {
+        const float rcp_w = __builtin_amdgcn_rcpf((float)widest);   // (item / widest exactly, items < 2^16)
+        for (int it = part * SEG_THREADS + tid; it < n * widest; it += parts * SEG_THREADS) {
+            const int k = (int)(((float)it + 0.5f) * rcp_w), j = it - k * widest;
+            const long src = s_src[k], dst = s_dst[k];
             const int jp = min(j, up - 1), jh = min(j, uh - 1);
-            for (int i0 = 0; i0 < n; i0 += SEG_BATCH)
-                for (int l = 0; l < d.L; ++l) {
-                    UNIT vp[SEG_BATCH], vh[SEG_BATCH], vc[SEG_BATCH];
-                    long src[SEG_BATCH], dst[SEG_BATCH];
+            const UNIT vp = reinterpret_cast<const UNIT *>(pool_p + src * d.Dj)[jp];
+            UNIT vh[TBS_MAX_LAYERS], vc[TBS_MAX_LAYERS];
 #pragma unroll
-                    for (int k = 0; k < SEG_BATCH; ++k) {
-                        const int i = min(i0 + k, n - 1);
-                        src[k] = __builtin_amdgcn_readfirstlane(s_src[i]);   // the same in every lane: scalar
-                        dst[k] = __builtin_amdgcn_readfirstlane(s_dst[i]);   // address arithmetic below
+            for (int l = 0; l < TBS_MAX_LAYERS; ++l)
+                if (l < d.L) {   // (uniform)
+                    vh[l] = reinterpret_cast<const UNIT *>(pool_h + ((long)l * pool_rows + src) * d.H)[jh];
+                    vc[l] = reinterpret_cast<const UNIT *>(pool_c + ((long)l * pool_rows + src) * d.H)[jh];
+                }
+            if (j < up) reinterpret_cast<UNIT *>(pool_p + dst * d.Dj)[j] = vp;
+            if (j < uh) {
+#pragma unroll
+                for (int l = 0; l < TBS_MAX_LAYERS; ++l)
+                    if (l < d.L) {
+                        reinterpret_cast<UNIT *>(pool_h + ((long)l * pool_rows + dst) * d.H)[j] = vh[l];
+                        reinterpret_cast<UNIT *>(pool_c + ((long)l * pool_rows + dst) * d.H)[j] = vc[l];
                     }
+            }
+            if constexpr (sizeof(UNIT) == 16) {
+                if (rows_here && j < up) {
+                    // (hypothesis k of the utterance is pair u*N + k: rows from pair * S)
+                    const float p4[4] = {vp.x, vp.y, vp.z, vp.w};
+                    uint2 *arow = reinterpret_cast<uint2 *>(fx.amat + (long)(u * d.N + k) * d.S * d.Dj) + j;
+                    for (int t = 0; t < sp; ++t) {
+                        const uint2 e2 = s_enc[t * cp + j];
+                        const float e4[4] = {__uint_as_float(e2.x << 16), __uint_as_float(e2.x & 0xFFFF0000u),
+                                             __uint_as_float(e2.y << 16), __uint_as_float(e2.y & 0xFFFF0000u)};
+                        unsigned o[4];
 #pragma unroll
-                    for (int k = 0; k < SEG_BATCH; ++k) {
-                        if (l == 0) vp[k] = reinterpret_cast<const UNIT *>(pool_p + src[k] * d.Dj)[jp];
-                        vh[k] = reinterpret_cast<const UNIT *>(pool_h + ((long)l * pool_rows + src[k]) * d.H)[jh];
-                        vc[k] = reinterpret_cast<const UNIT *>(pool_c + ((long)l * pool_rows + src[k]) * d.H)[jh];
-                    }
-#pragma unroll
-                    for (int k = 0; k < SEG_BATCH; ++k) {
-                        if (i0 + k >= n) continue;
-                        if (l == 0 && j < up) reinterpret_cast<UNIT *>(pool_p + dst[k] * d.Dj)[j] = vp[k];
-                        if (j < uh) {
-                            reinterpret_cast<UNIT *>(pool_h + ((long)l * pool_rows + dst[k]) * d.H)[j] = vh[k];
-                            reinterpret_cast<UNIT *>(pool_c + ((long)l * pool_rows + dst[k]) * d.H)[j] = vc[k];
-                        }
+                        for (int q = 0; q < 4; ++q) o[q] = seg_bf16(tbs_joiner_act(e4[q] + p4[q], fx.act));
+                        arow[(long)t * cp] = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
                     }
                 }
+            }
         }
     };
     if (((d.Dj | d.H) & 3) == 0) copy_all(float4{}, 4);
@@ -223,7 +271,8 @@ hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const in
                                 const FixedView *fx) {
     FixedView f{};
     if (fx) f = *fx;
-    hipLaunchKernelGGL(k_segment_begin, dim3(d.U), dim3(SEG_THREADS), 0, st, d, seg, utt_T, B, A, rv, pool_p,
+    if (f.parts > 1 && !f.on) return hipErrorInvalidValue;   // (only the slot layout's round kernel finishes what the parts leave)
+    hipLaunchKernelGGL(k_segment_begin, dim3(d.U * (f.parts > 1 ? f.parts : 1)), dim3(SEG_THREADS), 0, st, d, seg, utt_T, B, A, rv, pool_p,
                        pool_h, pool_c, pool_rows, f);
     return hipGetLastError();
 }

@@ -262,6 +262,7 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
             }
             const bool any_full = __ballot(full) != 0;
             if (lane == 0) {
+                rv.utt_par[u] = fg.parity;   // (the kernel that started the segment may have left this to the round)
                 int *fig = fx.fig + u * TBS_FIG_SIZE;
                 fig[TBS_FIG_CNT] = total;
                 fig[TBS_FIG_NB] = s_out.nB;

@@ -1096,13 +1096,23 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
     fx.xh = (bf16_t *)c->xh[0];
     // A = ChooseNBest(B), B = [], the first round's pair descriptors and joiner input rows
     const int head_seq = fx.seq = ++c->seq;
+    // (the head kernel also forms the first round's joiner input rows where it moves p in 16-byte pieces
+    // and the segment's frames fit the LDS it keeps for them; a kernel of their own makes them otherwise,
+    // or where debug bit 10 asks for it)
+    const bool rows_in_head = ((d.Dj | d.H) & 3) == 0 && d.Dj <= 1024 && d.S <= TBS_FIXED_SMAX &&
+                              !(c->cfg.debug & 1024);
+    fx.amat = rows_in_head ? (bf16_t *)c->amat : nullptr;
+    fx.enc = (const bf16_t *)c->enc;
+    fx.act = c->cfg.act;
+    fx.parts = d.U >= 128 ? 1 : (d.U > 64 ? 2 : 4);   // (a small batch leaves most CUs idle: several workgroups share an utterance)
     HIPCHK(c, launch_segment_begin(c->stream, d, c->seg, c->utt_T, c->B, c->A[c->a_cur], c->rv, c->pool_p, c->pool_h,
                                    c->pool_c, c->pool_rows, &fx));
-    {
+    if (!rows_in_head) {
         ProfScope ps(c, TBS_K_PREP, 0);
         HIPCHK(c, launch_joiner_prep_fixed(c->stream, d, c->cfg.act, (const bf16_t *)c->enc, c->pool_p, c->rv,
                                            (bf16_t *)c->amat));
     }
+    fx.amat = nullptr;
     const int M = d.U * d.N * d.S;
     std::vector<int> made(d.U, 0);
     int total = 0, rc;

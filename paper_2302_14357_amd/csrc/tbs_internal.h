@@ -77,7 +77,14 @@ struct FixedView {
     int seq;
     const float *pool_h;  // first LSTM layer's h by state slot, and where the new hypotheses' input rows go:
     bf16_t *xh;           // xh[j, :] = bf16(h of the parent of pair j)   (null: not wanted)
+    // head of a segment only: where the joiner input rows of the survivors go (null: a kernel of its own
+    // makes them), the projected encoder frames and the joiner activation
+    bf16_t *amat;
+    const bf16_t *enc;
+    int act;
+    int parts;            // workgroups per utterance of the kernel that starts a segment (0 = 1)
 };
+#define TBS_FIXED_SMAX 5   // longest segment the slot layout serves
 
 enum { TBS_FIG_SP = 0, TBS_FIG_CNT = 1, TBS_FIG_NB = 2, TBS_FIG_PAR = 3, TBS_FIG_USED = 4, TBS_FIG_CAP = 5,
        TBS_FIG_BASE = 6, TBS_FIG_SIZE = 8 };

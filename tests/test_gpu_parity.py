@@ -822,6 +822,25 @@ def test_standard_search_without_logits_librispeech_batch():
     assert info["tot"] == 64
 
 
+@pytest.mark.parametrize("N,S,U", [(5, 3, 6), (4, 5, 6), (10, 2, 70), (3, 1, 130)])
+def test_first_round_rows_from_the_segment_head_equal_those_of_their_own_kernel(N, S, U):
+    """In the layout with fixed places the kernel that starts a segment also forms the joiner input
+    rows of the segment's first round, with one, two or four workgroups per utterance depending on the
+    batch; debug bit 10 forms them in a kernel of their own.  Ragged and empty utterances, batches of
+    every workgroup count: identical hypotheses, and the oracle on the first utterances."""
+    shape = small_bf16_shape(n_utts=U, vocab=128, d=128, hidden=128)
+    rng = np.random.default_rng(7)
+    lengths = rng.integers(0, 20, size=U)
+    lengths[:6] = [0, 1, 7, 12, 23, 31]
+    model, offsets, enc = build_case(shape, n_utts=U, lengths=lengths)
+    one, st1 = _gpu_decode(shape, model, offsets, enc, N, S)
+    two, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=1024)
+    assert st1["path"]["fixed_places"] and st2["path"]["fixed_places"]
+    assert one == two
+    assert st1["joiner_calls"] == st2["joiner_calls"] and st1["joined_frames"] == st2["joined_frames"]
+    _check_decode(shape, model, offsets[:7], enc[:offsets[6]], N, S)
+
+
 @pytest.mark.parametrize("chunk", [1, 11, 40])
 def test_decode_with_joiner_calls_in_pieces(chunk):
     """Whole decodes whose every joiner call of more than `chunk` rows runs in pieces."""
