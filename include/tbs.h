@@ -87,8 +87,10 @@ typedef struct tbs_config {
                                  expand from them as for longer segments, also where the joiner GEMM
                                  would keep only each row's softmax sums and best tokens; bit 10: form the
                                  joiner input rows of a segment's first round in a kernel of their own,
-                                 also where the kernel that starts the segment would (tests cover each
-                                 pair of variants) */
+                                 also where the kernel that starts the segment would; bit 11: one
+                                 workgroup per tile of the predictor projection forms the joiner input rows
+                                 of all of a pair's frames, also where a small problem would run one
+                                 workgroup per tile and frame (tests cover each pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

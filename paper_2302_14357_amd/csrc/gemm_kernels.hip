@@ -364,8 +364,13 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     const int wm = wave >> 1, wn = wave & 1;
     // The 8 XCDs (workgroup id modulo 8) form a 2 x 4 grid over the tiles, so that each XCD's L2
     // fetches half of A and a quarter of B instead of all of both.
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    // (MODE 2 may run several workgroups per tile, see JoinEp: the grid is then that many copies of the
+    // tile grid, one behind the other)
     const int tmx = (tiles_m + 1) >> 1, tnx = (tiles_n + 3) >> 2;
+    const int base_grid = 8 * tmx * tnx;
+    const int fgroup = MODE == 2 ? (int)blockIdx.x / base_grid : 0;
+    const int bid = MODE == 2 ? (int)blockIdx.x - fgroup * base_grid : (int)blockIdx.x;
+    const int xcd = bid & 7, j = bid >> 3;
     const int tile_m = (xcd >> 2) * tmx + j % tmx, tile_n = (xcd & 3) * tnx + j / tmx;
     if (tile_m >= tiles_m || tile_n >= tiles_n) return;   // before any barrier
     const int kt = K / GS_BK;
@@ -615,13 +620,14 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         const int row = tile_m * 64 + wm * 32 + rowb;
         const int c0 = tile_n * 64 + wn * 32 + half * 16;
         const int len = e_tok;
+        const int fgs = jp.fgroups > 1 ? jp.fgroups : 1;   // this workgroup's frames: fgroup, fgroup + fgs, ...
         uint4 ev0[4][2];
         {
             const int c0c = min(c0, N - 16);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 // (a row that does not exist has no descriptor: frame 0 keeps the address valid)
-                const long fr = row < m_live ? (long)e_f0 + max(min(q, len - 1), 0) : 0;
+                const long fr = row < m_live ? (long)e_f0 + max(min(fgroup + q * fgs, len - 1), 0) : 0;
                 const uint4 *src = reinterpret_cast<const uint4 *>(jp.enc + fr * N + c0c);
                 ev0[q][0] = src[0];
                 ev0[q][1] = src[1];
@@ -638,23 +644,24 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
         if (row < m_live && c0 < N && e_ns >= 0) {
             const float p[16] = {p4[0].x, p4[0].y, p4[0].z, p4[0].w, p4[1].x, p4[1].y, p4[1].z, p4[1].w,
                                  p4[2].x, p4[2].y, p4[2].z, p4[2].w, p4[3].x, p4[3].y, p4[3].z, p4[3].w};
-            for (int t0 = 0; t0 < len; t0 += 4) {
+            for (int i0 = 0; fgroup + i0 * fgs < len; i0 += 4) {
                 uint4 ev[4][2];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if (t0 == 0) {
+                    if (i0 == 0) {
                         ev[q][0] = ev0[q][0];
                         ev[q][1] = ev0[q][1];
                     } else {
-                        const uint4 *src =
-                            reinterpret_cast<const uint4 *>(jp.enc + (long)(e_f0 + min(t0 + q, len - 1)) * N + c0);
+                        const uint4 *src = reinterpret_cast<const uint4 *>(
+                            jp.enc + (long)(e_f0 + min(fgroup + (i0 + q) * fgs, len - 1)) * N + c0);
                         ev[q][0] = src[0];
                         ev[q][1] = src[1];
                     }
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if (t0 + q < len) {
+                    const int t = fgroup + (i0 + q) * fgs;
+                    if (t < len) {
                         const unsigned w[8] = {ev[q][0].x, ev[q][0].y, ev[q][0].z, ev[q][0].w,
                                                ev[q][1].x, ev[q][1].y, ev[q][1].z, ev[q][1].w};
                         unsigned o[8];
@@ -664,15 +671,17 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
                             const float hi = tbs_joiner_act(__uint_as_float(w[i] & 0xFFFF0000u) + p[2 * i + 1], jp.act);
                             o[i] = (unsigned)gs_bf16(lo) | ((unsigned)gs_bf16(hi) << 16);
                         }
-                        uint4 *dstp = reinterpret_cast<uint4 *>(jp.amat + (long)(e_ps + t0 + q) * N + c0);
+                        uint4 *dstp = reinterpret_cast<uint4 *>(jp.amat + (long)(e_ps + t) * N + c0);
                         dstp[0] = make_uint4(o[0], o[1], o[2], o[3]);
                         dstp[1] = make_uint4(o[4], o[5], o[6], o[7]);
                     }
                 }
             }
-            float4 *crow = reinterpret_cast<float4 *>(C + (long)e_ns * ldc + c0);
+            if (fgroup == 0) {
+                float4 *crow = reinterpret_cast<float4 *>(C + (long)e_ns * ldc + c0);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) crow[q] = p4[q];
+                for (int q = 0; q < 4; ++q) crow[q] = p4[q];
+            }
         }
         return;
     }
@@ -774,7 +783,7 @@ hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, co
     if (!gemm_join_fits(M, N, K) || !out_row) return hipErrorInvalidValue;
     const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
-    const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
+    const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4) * (jp.fgroups > 1 ? jp.fgroups : 1);
     hipLaunchKernelGGL(k_gemm_small<2>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C, M,
                        N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, jp, m_dev, any_dev, PartEp{});
     return hipGetLastError();

@@ -900,6 +900,12 @@ static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part, const
         jp.enc = (const bf16_t *)c->enc;
         jp.amat = (bf16_t *)c->amat;
         jp.act = c->cfg.act;
+        // (a small problem leaves most CUs idle: as many workgroups per tile as the segment has frames,
+        // each forming the joiner input rows of one frame, while they fit one wave of workgroups)
+        {
+            const long tiles = (long)((M + 63) / 64) * ((d.Dj + 63) / 64);
+            jp.fgroups = (c->cfg.debug & 2048) ? 1 : (int)std::max(1L, std::min((long)d.S, 256 / std::max(tiles, 1L)));
+        }
         ProfScope pg(c, TBS_K_GEMM, (m_dev || any_dev) ? 0 : (int64_t)M * d.Dj * d.H);
         HIPCHK(c, launch_gemm_join(c->stream, (const bf16_t *)c->htop, (const bf16_t *)c->w.w_proj, c->w.b_proj,
                                    c->pool_p, M, d.Dj, d.H, c->rv.pair_slot, d.Dj, jp, m_dev, any_dev));

@@ -131,6 +131,8 @@ struct JoinEp {
     const bf16_t *enc;   // [frames, Dj]
     bf16_t *amat;        // [rows, Dj]
     int act;             // 0 tanh, 1 relu
+    int fgroups;         // workgroups per tile (0 = 1): each computes the tile and forms the joiner input rows of
+                         // the frames t = its number, + fgroups, ...; the first also stores the projection
 };
 
 // Segments of one frame (the standard breadth-first search, Eq. 1): the joiner GEMM keeps no logits.
