@@ -227,12 +227,19 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
         for (int q = 0; q < HP; ++q)
             hpar[q] = reinterpret_cast<const float4 *>(fx.pool_h + slot * d.H)[min(tid + TT * q, H4 - 1)];
     }
+    // Behind the expansion the select step has two parts that need nothing of each other: the select
+    // wave merges the blank expansions into B and finds the threshold while the workgroup's first wave,
+    // idle by now, ranks the candidates; the select wave goes on when both are done.
+    const float *lg = S1NP > 0 ? nullptr : logits;   // (no logits: d of a new hypothesis over one frame is (1))
+    if (own_wave) {
+        if (sel_wave)
+            select_merge_utt(4, d, round, drop, u, sel_lane, lg, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
+        else if ((int)threadIdx.x < WAVE)
+            select_merge_utt(3, d, round, drop, u, sel_lane, lg, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
+        __syncthreads();
+    }
     if (sel_wave) {
-        const float *lg = S1NP > 0 ? nullptr : logits;   // (no logits: d of a new hypothesis over one frame is (1))
-        if (own_wave)
-            select_merge_utt(2, d, round, drop, u, sel_lane, lg, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
-        else
-            select_merge_utt(0, d, round, drop, u, sel_lane, lg, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
+        select_merge_utt(own_wave ? 5 : 0, d, round, drop, u, sel_lane, lg, in, fg, A, An, B, rv, nodes, s_raw, &s_out);
         if (fx.on) {
             // Slot layout: what a row list kernel would do for this utterance.  The new hypotheses
             // take trie nodes from the utterance's own range, their pairs get their descriptors, the

@@ -131,8 +131,10 @@ __device__ __forceinline__ SelectFigs select_figs(int u, const AView &A, const B
 // s_dyn: LDS for the utterance's B list, BCAP * (8 + 8 + 3 * 4) bytes, 16-byte aligned.
 // phase 0: the whole step.  phase 1: only what does not depend on the expansion (B and A staged in
 // LDS); phase 2: the rest, by the same wave: a caller whose expansion runs in the same kernel does
-// phase 1 beside it.  (The phase is an argument, not a template parameter: the LDS arrays below
-// belong to the function, and each instantiation of a template would have a set of its own.)
+// phase 1 beside it.  Phases 3, 4 and 5 are the parts of phase 2 (see below), for a caller that has two
+// waves for them; the wave of phase 5 is the one that did phase 1 and 4 (`out->nB` is its).  (The phase is
+// an argument, not a template parameter: the LDS arrays below belong to the function, and each
+// instantiation of a template would have a set of its own.)
 __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d, int round, int drop, int u, int lane,
                                                  const float *logits, SelectIn in, const SelectFigs &fg, AView A,
                                                  AView An, BView B, RowView rv, const int2 *nodes,
@@ -151,13 +153,14 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
     __shared__ int s_match[TBS_MAX_BEAM];
     __shared__ int s_sel[TBS_MAX_BEAM];      // candidate index by rank
     __shared__ double s_thr;
+    __shared__ int s_have_thr;
     __shared__ float s_dnew[TBS_MAX_SEG * TBS_MAX_BEAM];   // frame distributions of the new hypotheses, [frame][hypothesis]
     __shared__ float s_xpre[SEL_PRE_FRAMES * WAVE];        // logits of the candidates' tokens, [frame][candidate]
     const int N = d.N;
     const int sp = fg.sp, cntA = fg.cntA, urow0 = fg.urow0, nB0 = fg.nB0, parity = fg.parity;
     const int H = sp > 0 ? cntA : 0;
     if (H == 0) {
-        if (lane == 0 && PHASE != 1) {
+        if (lane == 0 && (PHASE == 0 || PHASE == 2 || PHASE == 5)) {
             An.count[u] = 0;
             if (out) out->total = 0;
         }
@@ -165,7 +168,7 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
         const long bbase = (long)u * d.BCAP;
         int nB = nB0;
         // --- stage B and A
-        if (PHASE != 2) {
+        if (PHASE == 0 || PHASE == 1) {
             for (int i = lane; i < nB0; i += WAVE) {
                 s_blogs[i] = B.logs[bbase + i];
                 s_bhash[i] = B.hash[bbase + i];
@@ -184,114 +187,129 @@ __device__ __forceinline__ void select_merge_utt(const int PHASE, const Dims &d,
             if (lane < N) s_sel[lane] = -1;
         }
         if (PHASE == 1) return;
-        // --- the candidates and the blank expansions (dphi holds log delta_blank)
+        // The rest falls into three parts.  "Candidates" (keys of the per-hypothesis candidates, their
+        // joint ranking, the logits of their tokens) and "merge" (AddAndMerge, the threshold) need
+        // nothing of each other; "finish" needs both.  phase 0 and 2: one wave does all three; phase 3:
+        // candidates only, phase 4: merge only, phase 5: finish only: a caller with a second wave to
+        // spare runs 3 and 4 side by side and 5 behind a barrier.
+        const bool do_cand = PHASE == 0 || PHASE == 2 || PHASE == 3;
+        const bool do_merge = PHASE == 0 || PHASE == 2 || PHASE == 4;
+        const bool do_finish = PHASE == 0 || PHASE == 2 || PHASE == 5;
         if (PHASE == 0) sel_sync();   // (A's scores, staged just above, are read by other lanes below)
-        if (lane < H) s_bkey[lane] = s_alogs[lane] + (double)in.dphi[lane];
         const int nc = H * N;
         const float rcp_n = __builtin_amdgcn_rcpf((float)N);   // c / N as (c + 0.5) * (1 / N): exact for c < 1024
-        int tok_mine = -1;   // (token of candidate `lane`)
-        for (int c = lane; c < nc; c += WAVE) {
-            const int tok = in.cand_tok[c];
-            if (c == lane) tok_mine = tok;
-            s_ctok[c] = tok;
-            s_key[c] = tok >= 0 ? s_alogs[(int)(((float)c + 0.5f) * rcp_n)] + (double)in.cand_score[c] : nan("");
-        }
-        // The d of a new hypothesis (below) needs the logits of its token at the S' frames.  Which
-        // candidates become hypotheses is known only after the ranking, so where a lane per candidate
-        // suffices the logits of every candidate's token are asked for now and wait in registers: their
-        // round trip runs beside the merge and the ranking instead of behind them.
         const bool pre_x = logits != nullptr && nc <= WAVE && sp <= SEL_PRE_FRAMES && !drop;
         float xpre[SEL_PRE_FRAMES];
-        if (pre_x) {
-            const int c = min(lane, nc - 1), tokc = max(tok_mine, 0);
-            const float *lrow = logits + (long)(urow0 + (int)(((float)c + 0.5f) * rcp_n) * (in.slot_rows ? d.S : sp)) * d.V + tokc;
+        if (do_cand) {
+            int tok_mine = -1;   // (token of candidate `lane`)
+            for (int c = lane; c < nc; c += WAVE) {
+                const int tok = in.cand_tok[c];
+                if (c == lane) tok_mine = tok;
+                s_ctok[c] = tok;
+                s_key[c] = tok >= 0 ? s_alogs[(int)(((float)c + 0.5f) * rcp_n)] + (double)in.cand_score[c] : nan("");
+            }
+            // The d of a new hypothesis (below) needs the logits of its token at the S' frames.  Which
+            // candidates become hypotheses is known only after the ranking, so where a lane per candidate
+            // suffices the logits of every candidate's token are asked for now and wait in registers: their
+            // round trip runs beside the merge and the ranking instead of behind them.
+            if (pre_x) {
+                const int c = min(lane, nc - 1), tokc = max(tok_mine, 0);
+                const float *lrow = logits + (long)(urow0 + (int)(((float)c + 0.5f) * rcp_n) * (in.slot_rows ? d.S : sp)) * d.V + tokc;
 #pragma unroll
-            for (int q = 0; q < SEL_PRE_FRAMES; ++q) xpre[q] = lrow[(long)min(q, sp - 1) * d.V];
+                for (int q = 0; q < SEL_PRE_FRAMES; ++q) xpre[q] = lrow[(long)min(q, sp - 1) * d.V];
+            }
         }
-
-        // --- AddAndMerge of every blank expansion.  The hypotheses of A are distinct sequences and so
-        // are the entries of B, so each hypothesis matches at most one old entry and no entry added in
-        // this round: all (hypothesis, entry) pairs are tested at once, matched scores are summed in
-        // place, and the unmatched hypotheses are appended in hypothesis order.
-        if (lane < H) s_match[lane] = -1;
-        sel_sync();
-        const float rcp_b = __builtin_amdgcn_rcpf((float)max(nB0, 1));   // (exact quotients up to 32 x 2048 pairs)
-        for (int c = lane; c < H * nB0; c += WAVE) {
-            const int h = (int)(((float)c + 0.5f) * rcp_b), i = c - h * nB0;
-            if (s_bhash[i] == s_ahash[h] && s_blen[i] == s_alen[h] && same_sequence(nodes, s_bnode[i], s_anode[h]))
-                s_match[h] = i;
-        }
-        sel_sync();
-        {
-            const bool unmatched = lane < H && s_match[lane] < 0;
-            const u64 um = __ballot(unmatched);
-            const int n_new = __popcll(um);
-            if (lane < H) {
-                if (!unmatched) {
-                    const int f = s_match[lane];
-                    s_blogs[f] = log_add(s_blogs[f], s_bkey[lane]);
-                } else {
-                    const int pos = nB0 + __popcll(um & ((1ull << lane) - 1ull));
-                    if (pos < d.BCAP) {
-                        s_blogs[pos] = s_bkey[lane];
-                        s_bhash[pos] = s_ahash[lane];
-                        s_bnode[pos] = s_anode[lane];
-                        s_blen[pos] = s_alen[lane];
-                        s_bslot[pos] = s_aslot[lane];
+        if (do_merge) {
+            // (dphi holds log delta_blank)
+            if (lane < H) s_bkey[lane] = s_alogs[lane] + (double)in.dphi[lane];
+            // --- AddAndMerge of every blank expansion.  The hypotheses of A are distinct sequences and so
+            // are the entries of B, so each hypothesis matches at most one old entry and no entry added in
+            // this round: all (hypothesis, entry) pairs are tested at once, matched scores are summed in
+            // place, and the unmatched hypotheses are appended in hypothesis order.
+            if (lane < H) s_match[lane] = -1;
+            sel_sync();
+            const float rcp_b = __builtin_amdgcn_rcpf((float)max(nB0, 1));   // (exact quotients up to 32 x 2048 pairs)
+            for (int c = lane; c < H * nB0; c += WAVE) {
+                const int h = (int)(((float)c + 0.5f) * rcp_b), i = c - h * nB0;
+                if (s_bhash[i] == s_ahash[h] && s_blen[i] == s_alen[h] && same_sequence(nodes, s_bnode[i], s_anode[h]))
+                    s_match[h] = i;
+            }
+            sel_sync();
+            {
+                const bool unmatched = lane < H && s_match[lane] < 0;
+                const u64 um = __ballot(unmatched);
+                const int n_new = __popcll(um);
+                if (lane < H) {
+                    if (!unmatched) {
+                        const int f = s_match[lane];
+                        s_blogs[f] = log_add(s_blogs[f], s_bkey[lane]);
                     } else {
-                        atomicOr(&rv.counts[TBS_CNT_ERR], TBS_ERRF_BCAP);
+                        const int pos = nB0 + __popcll(um & ((1ull << lane) - 1ull));
+                        if (pos < d.BCAP) {
+                            s_blogs[pos] = s_bkey[lane];
+                            s_bhash[pos] = s_ahash[lane];
+                            s_bnode[pos] = s_anode[lane];
+                            s_blen[pos] = s_alen[lane];
+                            s_bslot[pos] = s_aslot[lane];
+                        } else {
+                            atomicOr(&rv.counts[TBS_CNT_ERR], TBS_ERRF_BCAP);
+                        }
                     }
                 }
+                nB = min(nB0 + n_new, d.BCAP);
             }
-            nB = min(nB0 + n_new, d.BCAP);
-        }
-        sel_sync();
-        // --- B back to memory: merged scores of old entries, and the new entries
-        for (int i = lane; i < nB; i += WAVE) {
-            B.logs[bbase + i] = s_blogs[i];
-            if (i >= nB0) {
-                B.hash[bbase + i] = s_bhash[i];
-                B.node[bbase + i] = s_bnode[i];
-                B.len[bbase + i] = s_blen[i];
-                B.slot[bbase + i] = s_bslot[i];
+            sel_sync();
+            // --- B back to memory: merged scores of old entries, and the new entries
+            for (int i = lane; i < nB; i += WAVE) {
+                B.logs[bbase + i] = s_blogs[i];
+                if (i >= nB0) {
+                    B.hash[bbase + i] = s_bhash[i];
+                    B.node[bbase + i] = s_bnode[i];
+                    B.len[bbase + i] = s_blen[i];
+                    B.slot[bbase + i] = s_bslot[i];
+                }
             }
-        }
-        if (lane == 0) {
-            B.count[u] = nB;
-            if (out) out->nB = nB;
-        }
+            if (lane == 0) {
+                B.count[u] = nB;
+                if (out) out->nB = nB;
+            }
 
-        // --- threshold = ChooseNthScore(B, N), only defined when B holds N entries.  The rank of an
-        // entry is the number of entries that beat it (larger score, or equal score and earlier
-        // place); every lane counts for its own entries against the whole list, read from LDS at
-        // one address for all lanes.  (Ranking by one ballot per entry was measured at ~270 ns per
-        // entry on the single wave: readlane and ballot results are needed at once, so nothing
-        // overlaps.)
-        const bool have_thr = nB >= N;
-        if (have_thr) sel_rank(s_blogs, nB, lane, [&](int i, int rank, double si) {
-            if (rank == N - 1) s_thr = si;
-        });
-        // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates, ranked the
-        // same way: larger score first, then the earlier hypothesis, then the smaller token.  The N
-        // candidates of a hypothesis arrive sorted by exactly that rule, hypotheses in order, so
-        // "earlier place" decides equal scores.  (A place without a candidate holds NaN and never
-        // compares as better.)
-        sel_rank(s_key, nc, lane, [&](int c, int rank, double kc) {
-            if (kc == kc && rank < N) s_sel[rank] = c;
-        });
+            // --- threshold = ChooseNthScore(B, N), only defined when B holds N entries.  The rank of an
+            // entry is the number of entries that beat it (larger score, or equal score and earlier
+            // place); every lane counts for its own entries against the whole list, read from LDS at
+            // one address for all lanes.  (Ranking by one ballot per entry was measured at ~270 ns per
+            // entry on the single wave: readlane and ballot results are needed at once, so nothing
+            // overlaps.)
+            const bool have_thr_m = nB >= N;
+            if (lane == 0) s_have_thr = have_thr_m;
+            if (have_thr_m) sel_rank(s_blogs, nB, lane, [&](int i, int rank, double si) {
+                if (rank == N - 1) s_thr = si;
+            });
+        }
+        if (do_cand) {
+            // --- ChooseNBestExpansions: joint top-N over the H*N per-hypothesis candidates, ranked the
+            // same way: larger score first, then the earlier hypothesis, then the smaller token.  The N
+            // candidates of a hypothesis arrive sorted by exactly that rule, hypotheses in order, so
+            // "earlier place" decides equal scores.  (A place without a candidate holds NaN and never
+            // compares as better.)
+            sel_rank(s_key, nc, lane, [&](int c, int rank, double kc) {
+                if (kc == kc && rank < N) s_sel[rank] = c;
+            });
+            if (pre_x) {
+#pragma unroll
+                for (int q = 0; q < SEL_PRE_FRAMES; ++q) s_xpre[q * WAVE + lane] = xpre[q];
+            }
+        }
+        if (!do_finish) return;   // (the caller's barrier stands between the parts)
         sel_sync();
         // --- threshold test, in rank order: keep iff |B| < N or score > threshold (strict)
+        const bool have_thr = s_have_thr != 0;
         const double thr = have_thr ? s_thr : 0.0;
         bool keep = false;   // lane r: the candidate of rank r becomes a hypothesis
         if (lane < N) {
             const int c = s_sel[lane];
             if (c >= 0) keep = (!have_thr) || (s_key[c] > thr);
         }
-        if (pre_x) {
-#pragma unroll
-            for (int q = 0; q < SEL_PRE_FRAMES; ++q) s_xpre[q * WAVE + lane] = xpre[q];
-        }
-        sel_sync();
         if (drop) {
             if (lane == 0) {
                 An.count[u] = 0;
