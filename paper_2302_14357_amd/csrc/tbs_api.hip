@@ -1160,6 +1160,12 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
             if ((rc = predictor_launch(c, d.U * d.N, nullptr, 1, any))) return rc;
         }
         if ((rc = wait_live(c, fx.seq, made.data(), &total, &full))) return rc;
+        // (the projection goes out the moment the host knows that the round made something: the LSTM
+        // layers in front of it take about as long as seeing the words and making this call)
+        if (!full && total > 0) {
+            ProfScope ps(c, TBS_K_PREDICTOR, 0);
+            if ((rc = predictor_launch(c, d.U * d.N, nullptr, 2, any))) return rc;
+        }
         if (first) {   // (what the head of the segment put into A: there for certain once the round's words are)
             int t0 = 0;
             bool f0 = false;
@@ -1185,10 +1191,6 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
         c->h_counts[TBS_CNT_PAIRS] = total;
         if (full) return TBS_EOVERFLOW;
         if (total == 0) break;
-        {
-            ProfScope ps(c, TBS_K_PREDICTOR, 0);
-            if ((rc = predictor_launch(c, d.U * d.N, nullptr, 2, any))) return rc;
-        }
     }
     c->h_counts[TBS_CNT_ROWS] = 0;
     c->prep_ahead = false;
