@@ -90,7 +90,9 @@ typedef struct tbs_config {
                                  also where the kernel that starts the segment would; bit 11: one
                                  workgroup per tile of the predictor projection forms the joiner input rows
                                  of all of a pair's frames, also where a small problem would run one
-                                 workgroup per tile and frame (tests cover each pair of variants) */
+                                 workgroup per tile and frame; bit 12: the joiner GEMM of a small batch spreads
+                                 its tiles over the XCDs as the other GEMMs do, also where it would give every
+                                 XCD a range of rows of its own (tests cover each pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

@@ -371,7 +371,12 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
     const int fgroup = MODE == 2 ? (int)blockIdx.x / base_grid : 0;
     const int bid = MODE == 2 ? (int)blockIdx.x - fgroup * base_grid : (int)blockIdx.x;
     const int xcd = bid & 7, j = bid >> 3;
-    const int tile_m = (xcd >> 2) * tmx + j % tmx, tile_n = (xcd & 3) * tnx + j / tmx;
+    int tile_m = (xcd >> 2) * tmx + j % tmx, tile_n = (xcd & 3) * tnx + j / tmx;
+    if ((MODE == 0 || MODE == 3) && pe.xcd_rows != 0) {   // a row range per XCD, all its columns
+        const int tpx = (tiles_m + 7) >> 3;
+        tile_m = xcd * tpx + j % tpx;
+        tile_n = j / tpx;
+    }
     if (tile_m >= tiles_m || tile_n >= tiles_n) return;   // before any barrier
     const int kt = K / GS_BK;
 
@@ -764,7 +769,7 @@ hipError_t launch_gemm_part(hipStream_t st, const bf16_t *A, const bf16_t *B, co
     const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns_max = gemm_small_stages();
     const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
-    const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
+    const int grid = pe.xcd_rows ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
     hipLaunchKernelGGL(k_gemm_small<3>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, nullptr, M,
                        N, K, nullptr, 0L, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, nullptr, nullptr, pe);
     return hipGetLastError();
@@ -792,7 +797,7 @@ hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, co
 // kernel: 0 = by size (what the decode uses); 1..4 force one (tests run every kernel on every shape):
 // 1 = 64x64 tiles, 2 = 128x128, 3 = 256x256 (all k_gemm_bf16), 4 = k_gemm_small
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, int kernel, const int *m_dev) {
+                            int N, int K, const int *out_row, long ldc, int kernel, const int *m_dev, bool xcd_rows) {
     if (M <= 0) return hipSuccess;
     if (m_dev && !gemm_small_fits(M, N, K)) return hipErrorInvalidValue;   // only k_gemm_small reads its row count
     if ((kernel == 0 || kernel == 4) && K % GS_BK == 0) {
@@ -800,9 +805,11 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
         const int ns_max = gemm_small_stages();
         if (ns_max >= 2 && ((long)tiles_m * tiles_n <= 320 || kernel == 4)) {
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
-            const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
+            const int grid = xcd_rows ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
+            PartEp pe{};
+            pe.xcd_rows = xcd_rows ? 1 : 0;
             hipLaunchKernelGGL(k_gemm_small<0>, dim3(grid), dim3(256), ns * GS_STAGE * sizeof(bf16_t), st, A, B, bias, C,
-                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, m_dev, nullptr, PartEp{});
+                               M, N, K, out_row, ldc, tiles_m, tiles_n, ns, LstmEp{}, JoinEp{}, m_dev, nullptr, pe);
             return hipGetLastError();
         }
     }

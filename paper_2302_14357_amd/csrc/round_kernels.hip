@@ -36,7 +36,16 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     float *s_cs = s_dphi + N;                              // [H, N]
     int *s_ct = reinterpret_cast<int *>(s_cs + N * N);     // [H, N]
 
-    const int u = blockIdx.x;
+    // Slot layout with a row range per XCD in the joiner GEMM: workgroup b runs on XCD b % 8 (workgroups
+    // go to the XCDs in turn) and takes the (b / 8)-th utterance whose first joiner row lies in that
+    // XCD's range, so that it finds the utterance's logits in its own XCD's L2.
+    int u = blockIdx.x;
+    if (fx.on && fx.xcd_rows > 0) {
+        const int x = (int)blockIdx.x & 7, R = N * d.S;
+        const int u0 = (x * fx.xcd_rows + R - 1) / R, u1 = ((x + 1) * fx.xcd_rows + R - 1) / R;
+        u = u0 + ((int)blockIdx.x >> 3);
+        if (u >= u1 || u >= d.U) return;   // (the whole workgroup, before any barrier)
+    }
     const int team = __builtin_amdgcn_readfirstlane((int)threadIdx.x / TT), tid = (int)threadIdx.x % TT;
     // Where the workgroup has room for one more wave, that wave belongs to the select step: it stages
     // B and A in LDS while the teams expand, and goes on when they are done.  Otherwise the first
@@ -338,7 +347,9 @@ static hipError_t round_launch(hipStream_t st, const Dims &d, int round, int dro
     }
     // (one wave more for the select step where 1024 threads allow it)
     const int threads = d.N * TW * 64 + (d.N * TW * 64 + 64 <= 1024 ? 64 : 0);
-    hipLaunchKernelGGL((k_round<TW, NV4, SMAX, S1NP>), dim3(d.U), dim3(threads), shm, st, d, round, drop, logits, A, An,
+    // (with a row range per XCD: eight workgroups, one per XCD, for each place in the longest XCD's list)
+    const int grid = fx.on && fx.xcd_rows > 0 ? 8 * (fx.xcd_rows / (d.N * d.S) + 1) : d.U;
+    hipLaunchKernelGGL((k_round<TW, NV4, SMAX, S1NP>), dim3(grid), dim3(threads), shm, st, d, round, drop, logits, A, An,
                        B, rv, nodes, row_stats, delta_nb, fx, tiles_n);
     return hipGetLastError();
 }

@@ -1120,6 +1120,13 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
     }
     fx.amat = nullptr;
     const int M = d.U * d.N * d.S;
+    // (a row range per XCD in the joiner GEMM, the round kernel's workgroups on the XCD of their
+    // utterance's rows, where an XCD's range holds whole utterances and its tiles fit its 32 CUs)
+    {
+        const int rpx = gemm_small_xcd_rows(M);
+        const long wgs = (long)(rpx / 64) * ((d.V + 63) / 64);
+        fx.xcd_rows = (!(c->cfg.debug & 4096) && d.N * d.S <= rpx && wgs <= 32) ? rpx : 0;
+    }
     std::vector<int> made(d.U, 0);
     int total = 0, rc;
     bool full = false, first = true;
@@ -1130,12 +1137,12 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
             ProfScope ps(c, TBS_K_JOINER, 0);
             ProfScope pg(c, TBS_K_GEMM, 0);
             if (c->s1) {
-                const PartEp pe{c->part, d.N, d.blank};
+                const PartEp pe{c->part, d.N, d.blank, fx.xcd_rows};
                 HIPCHK(c, launch_gemm_part(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, M, d.V,
                                            d.Dj, pe));
             } else {
                 HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out,
-                                           c->logits, M, d.V, d.Dj, nullptr, d.V));
+                                           c->logits, M, d.V, d.Dj, nullptr, d.V, 0, nullptr, fx.xcd_rows != 0));
             }
         }
         AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];

@@ -83,6 +83,8 @@ struct FixedView {
     const bf16_t *enc;
     int act;
     int parts;            // workgroups per utterance of the kernel that starts a segment (0 = 1)
+    int xcd_rows;         // round kernel: not 0 = joiner rows per XCD (workgroup b runs on XCD b % 8 and takes an
+                          // utterance whose first row lies in that XCD's range; see PartEp)
 };
 #define TBS_FIXED_SMAX 5   // longest segment the slot layout serves
 
@@ -144,6 +146,9 @@ struct PartEp {
     float *part;
     int np;      // NP = beam size
     int blank;
+    int xcd_rows;   // (also for the joiner GEMM that stores logits) not 0: every XCD computes a range of rows
+                    // of its own, all their columns, so that the logits or partials of an utterance lie in
+                    // the L2 of the XCD whose workgroup of the round kernel reads them (see FixedView)
 };
 __host__ __device__ inline int part_width(int np) { return (4 + 2 * np + 3) & ~3; }   // (whole 16-byte pieces)
 
@@ -170,7 +175,10 @@ hipError_t launch_gemm_f32(hipStream_t st, const float *A, const float *B, const
 // m_dev (launch_gemm_bf16 only where gemm_small_fits; the fused forms always): the launch is enqueued
 // before the host knows the row count; M is an upper bound and the count is read from *m_dev
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
-                            int N, int K, const int *out_row, long ldc, int kernel = 0, const int *m_dev = nullptr);
+                            int N, int K, const int *out_row, long ldc, int kernel = 0, const int *m_dev = nullptr,
+                            bool xcd_rows = false);
+// rows per XCD when k_gemm_small gives every XCD a row range of its own (PartEp::xcd_rows)
+inline int gemm_small_xcd_rows(int M) { return 64 * ((((M + 63) / 64) + 7) / 8); }
 hipError_t launch_gemm_bf16_rows(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C,
                                  int m_max, int N, int K, long ldc, const int *m_begin, const int *m_end);
 bool gemm_small_fits(int M, int N, int K);

@@ -836,7 +836,9 @@ def test_first_round_rows_from_the_segment_head_equal_those_of_their_own_kernel(
     one, st1 = _gpu_decode(shape, model, offsets, enc, N, S)
     # (bit 11: the later rounds' rows, from the projection's epilogue, by one workgroup per tile instead of
     # one per tile and frame)
-    for dbg in (1024, 2048, 1024 + 2048):
+    # (bit 12: the joiner GEMM's tiles spread over the XCDs as the other GEMMs' are, instead of a range of
+    # rows per XCD with the round kernel's workgroups placed to match)
+    for dbg in (1024, 2048, 4096, 1024 + 2048 + 4096):
         two, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=dbg)
         assert st1["path"]["fixed_places"] and st2["path"]["fixed_places"]
         assert one == two, dbg
