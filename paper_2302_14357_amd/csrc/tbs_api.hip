@@ -1121,11 +1121,12 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
     fx.amat = nullptr;
     const int M = d.U * d.N * d.S;
     // (a row range per XCD in the joiner GEMM, the round kernel's workgroups on the XCD of their
-    // utterance's rows, where an XCD's range holds whole utterances and its tiles fit its 32 CUs)
+    // utterance's rows, where every XCD gets rows, its range holds whole utterances and its tiles fit
+    // its 32 CUs)
     {
         const int rpx = gemm_small_xcd_rows(M);
         const long wgs = (long)(rpx / 64) * ((d.V + 63) / 64);
-        fx.xcd_rows = (!(c->cfg.debug & 4096) && d.N * d.S <= rpx && wgs <= 32) ? rpx : 0;
+        fx.xcd_rows = (!(c->cfg.debug & 4096) && (M + 63) / 64 >= 8 && d.N * d.S <= rpx && wgs <= 32) ? rpx : 0;
     }
     std::vector<int> made(d.U, 0);
     int total = 0, rc;
