@@ -1,11 +1,16 @@
 // One round of the inner loop of Algorithm 1 behind the joiner, for small shapes, as one kernel:
 // a workgroup per utterance expands all of the utterance's live hypotheses at once (Eq. 3-7 and the
 // N best expansions of each, one team of 64 to 256 threads per hypothesis), hands the results to
-// its first wave through LDS, and that wave does AddAndMerge, ChooseNthScore, the joint
-// ChooseNBestExpansions with the threshold test and the new list A.  Where the logits of one
-// utterance's hypotheses (at most N * S' * V values) fit the registers of one workgroup this saves a
-// kernel boundary and the trip of the candidates through memory in every round of a decode whose
-// time is the length of its chain of dependent kernels.
+// the select step through LDS, and that step does AddAndMerge, ChooseNthScore, the joint
+// ChooseNBestExpansions with the threshold test and the new list A.  Where the workgroup has room for
+// it the select step has a wave of its own, which stages B and A while the teams expand; behind the
+// expansion it merges and finds the threshold while the workgroup's first wave ranks the candidates.
+// Where the logits of one utterance's hypotheses (at most N * S' * V values) fit the registers of one
+// workgroup this saves a kernel boundary and the trip of the candidates through memory in every
+// round of a decode whose time is the length of its chain of dependent kernels.  What counts inside
+// is the number of instructions per SIMD (a wave issues one every few cycles, the waves of a SIMD
+// take turns) and the order of the requests to memory (they come back in order, and a wait behind a
+// branch is a wait for all of them).
 #include "expand_device.h"
 #include "select_device.h"
 
