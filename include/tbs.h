@@ -92,7 +92,9 @@ typedef struct tbs_config {
                                  of all of a pair's frames, also where a small problem would run one
                                  workgroup per tile and frame; bit 12: the joiner GEMM of a small batch spreads
                                  its tiles over the XCDs as the other GEMMs do, also where it would give every
-                                 XCD a range of rows of its own (tests cover each pair of variants) */
+                                 XCD a range of rows of its own; bit 13: the kernel that forms joiner input
+                                 rows takes a thread per row, also where it would take a thread per pair
+                                 (tests cover each pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

@@ -54,6 +54,52 @@ __global__ void k_joiner_prep_bf16(int rows, int Dj, int act, const bf16_t *__re
     *reinterpret_cast<uint4 *>(amat + (long)r * Dj + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// The same by pairs: a thread takes 8 columns of all frames of one (utterance, hypothesis) pair, so the
+// pair's p values are read once and its S' frame values are all requested before the first is used.
+// (pairs_dev: the number of pairs, in device memory; the grid is sized for the most there can be)
+#define PREP_FRAMES 8
+__global__ void k_joiner_prep_pairs(int Dj, int act, const bf16_t *__restrict__ enc, const float *__restrict__ pool_p,
+                                    const int *__restrict__ pair_row0, const int *__restrict__ pair_len,
+                                    const int *__restrict__ pair_frame0, const int *__restrict__ pair_slot,
+                                    bf16_t *__restrict__ amat, const int *__restrict__ pairs_dev) {
+    const int chunks = Dj / 8;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int j = (int)(idx / chunks), c = (int)(idx - (long)j * chunks);
+    if (j >= *pairs_dev) return;
+    const int len = pair_len[j];
+    const long r0 = pair_row0[j], f0 = pair_frame0[j], slot = pair_slot[j];
+    const float4 p0 = *reinterpret_cast<const float4 *>(pool_p + slot * Dj + c * 8);
+    const float4 p1 = *reinterpret_cast<const float4 *>(pool_p + slot * Dj + c * 8 + 4);
+    const float p[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+    for (int t0 = 0; t0 < len; t0 += PREP_FRAMES) {
+        uint4 ev[PREP_FRAMES];
+#pragma unroll
+        for (int q = 0; q < PREP_FRAMES; ++q)
+            ev[q] = *reinterpret_cast<const uint4 *>(enc + (f0 + min(t0 + q, len - 1)) * Dj + c * 8);
+#pragma unroll
+        for (int q = 0; q < PREP_FRAMES; ++q) {
+            if (t0 + q >= len) continue;
+            const unsigned w[4] = {ev[q].x, ev[q].y, ev[q].z, ev[q].w};
+            unsigned o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned lo = f2bf(tbs_joiner_act(__uint_as_float(w[i] << 16) + p[2 * i], act));
+                const unsigned hi = f2bf(tbs_joiner_act(__uint_as_float(w[i] & 0xFFFF0000u) + p[2 * i + 1], act));
+                o[i] = lo | (hi << 16);
+            }
+            *reinterpret_cast<uint4 *>(amat + (r0 + t0 + q) * Dj + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
+hipError_t launch_joiner_prep_pairs(hipStream_t st, const Dims &d, int act, const bf16_t *enc, const float *pool_p,
+                                    RowView rv, bf16_t *amat) {
+    const long n = (long)d.U * d.N * (d.Dj / 8);
+    hipLaunchKernelGGL(k_joiner_prep_pairs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d.Dj, act, enc, pool_p,
+                       rv.pair_row0, rv.pair_len, rv.pair_frame0, rv.pair_slot, amat, rv.counts + TBS_CNT_PAIRS);
+    return hipGetLastError();
+}
+
 // The same in the slot layout (pair j owns the rows j*S .. j*S + S - 1 and uses the first
 // pair_len[j] of them): a row's frame and state slot come from its pair's descriptor.
 __global__ void k_joiner_prep_fixed(int rows, int Dj, int S, int act, const bf16_t *__restrict__ enc,

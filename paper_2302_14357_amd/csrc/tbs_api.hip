@@ -539,6 +539,19 @@ static bool fixed_layout_ok(const tbs_ctx *c) {
            predictor_all_fused(c, d.U * d.N);
 }
 
+// The joiner input rows act(e + p) of the current row lists (Section 3.1), as a kernel of its own.  rows =
+// their number, or with rows_dev the most there can be (the launch goes out before the host knows).
+// bf16 and segments of several frames: a thread per pair and 8 columns, the pair's p read once and
+// all its frames requested together (the pair count comes from the row lists' counts in device
+// memory either way); otherwise a thread per row and 8 columns.
+static hipError_t joiner_rows(tbs_ctx *c, int rows, const int *rows_dev) {
+    if (c->cfg.dtype == 1 && c->cur.S >= 2 && !(c->cfg.debug & 8192))
+        return launch_joiner_prep_pairs(c->stream, c->cur, c->cfg.act, (const bf16_t *)c->enc, c->pool_p, c->rv,
+                                        (bf16_t *)c->amat);
+    return launch_joiner_prep(c->stream, c->cur, c->cfg.dtype, c->cfg.act, rows, c->enc, c->pool_p, c->rv, c->amat,
+                              rows_dev);
+}
+
 // B = [([], 1, InitPredictor(), Null)] for U utterances whose lengths and first frames are h_T / offsets
 static int begin_batch(tbs_ctx *c, const void *enc, const int32_t *offsets, int32_t U, int max_T, long frames) {
     HIPCHK(c, hipSetDevice(c->cfg.device_id));
@@ -644,8 +657,7 @@ static int segment_begin(tbs_ctx *c, int32_t seg_index, int32_t *rows_host) {
     {
         const Dims &d = c->cur;
         ProfScope ps(c, TBS_K_PREP, 0);
-        HIPCHK(c, launch_joiner_prep(c->stream, d, c->cfg.dtype, c->cfg.act, d.U * d.N * d.S, c->enc, c->pool_p, c->rv,
-                                     c->amat, c->rv.counts + TBS_CNT_ROWS));
+        HIPCHK(c, joiner_rows(c, d.U * d.N * d.S, c->rv.counts + TBS_CNT_ROWS));
         c->prep_ahead = true;
     }
     HIPCHK(c, wait_counts(c));
@@ -727,8 +739,7 @@ int tbs_joiner_segment(tbs_ctx *c) {
     }
     if (!c->prep_ahead) {
         ProfScope ps(c, TBS_K_PREP, rows);
-        HIPCHK(c, launch_joiner_prep(c->stream, c->cur, c->cfg.dtype, c->cfg.act, rows, c->enc, c->pool_p, c->rv,
-                                     c->amat));
+        HIPCHK(c, joiner_rows(c, rows, nullptr));
     }
     c->prep_ahead = false;
     {
@@ -989,8 +1000,7 @@ static int segment_begin_ahead(tbs_ctx *c, int32_t seg_index) {
     HIPCHK(c, launch_segment_begin(c->stream, d, c->seg, c->utt_T, c->B, A, c->rv, c->pool_p, c->pool_h, c->pool_c,
                                    c->pool_rows));
     HIPCHK(c, launch_rowfill(c->stream, d, c->seg, c->utt_off, A, c->rv, c->nodes, 0, c->h_counts_dev, ++c->seq));
-    HIPCHK(c, launch_joiner_prep(c->stream, d, c->cfg.dtype, c->cfg.act, d.U * d.N * d.S, c->enc, c->pool_p, c->rv,
-                                 c->amat, rows_dev));
+    HIPCHK(c, joiner_rows(c, d.U * d.N * d.S, rows_dev));
     // first round: joiner, expansion, select/merge, row list, predictor step
     HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, c->logits,
                                d.U * d.N * d.S, d.V, d.Dj, nullptr, d.V, 0, rows_dev));

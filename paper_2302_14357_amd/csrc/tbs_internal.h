@@ -160,6 +160,9 @@ hipError_t launch_segment_begin(hipStream_t st, const Dims &d, int seg, const in
                                 AView A, RowView rv, float *pool_p, float *pool_h, float *pool_c, long pool_rows,
                                 const FixedView *fx = nullptr);
 // joiner input rows in the slot layout: every row j*S + t with t < pair_len[j]
+// the same by pairs (bf16; the pair count is read from the row lists' counts in device memory)
+hipError_t launch_joiner_prep_pairs(hipStream_t st, const Dims &d, int act, const bf16_t *enc, const float *pool_p,
+                                    RowView rv, bf16_t *amat);
 hipError_t launch_joiner_prep_fixed(hipStream_t st, const Dims &d, int act, const bf16_t *enc, const float *pool_p,
                                     RowView rv, bf16_t *amat);
 // gather_h / gather_xh not null: also writes gather_xh[pair, :] = bf16(gather_h[parent slot, :]) (H wide)

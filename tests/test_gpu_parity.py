@@ -846,6 +846,23 @@ def test_first_round_rows_from_the_segment_head_equal_those_of_their_own_kernel(
     _check_decode(shape, model, offsets[:7], enc[:offsets[6]], N, S)
 
 
+@pytest.mark.parametrize("N,S,d", [(5, 3, 64), (3, 12, 64), (10, 2, 128), (4, 5, 144)])
+def test_joiner_rows_by_pair_equal_those_by_row(N, S, d):
+    """With row lists the joiner input rows act(e + p) come from a kernel of their own: a thread per
+    pair and 8 columns (all frames of the pair), or with debug bit 13 a thread per row and 8 columns.
+    Identical hypotheses required, and the oracle's on the default form."""
+    shape = small_bf16_shape(n_utts=6, vocab=96, d=d, hidden=64)
+    lengths = np.array([0, 1, 7, 12, 23, 31])
+    model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
+    kw = dict(rounds_capacity=4 * S) if S > 8 else {}
+    one, st1 = _gpu_decode(shape, model, offsets, enc, N, S, debug=256, **kw)
+    two, st2 = _gpu_decode(shape, model, offsets, enc, N, S, debug=256 + 8192, **kw)
+    assert not st1["path"]["fixed_places"]
+    assert one == two
+    assert st1["joiner_calls"] == st2["joiner_calls"] and st1["joined_frames"] == st2["joined_frames"]
+    _check_decode(shape, model, offsets, enc, N, S, debug=256, **kw)
+
+
 @pytest.mark.parametrize("chunk", [1, 11, 40])
 def test_decode_with_joiner_calls_in_pieces(chunk):
     """Whole decodes whose every joiner call of more than `chunk` rows runs in pieces."""
