@@ -333,8 +333,8 @@ def main():
     if not args.no_other_workloads and not piece and args.workload == "librispeech":
         tbs.close()
         others = {"librispeech_s1_standard_search": quick_decode("librispeech", steps=4, warmup=1, seg=1),
-                  "librispeech_s1_standard_search_logits_stored": quick_decode("librispeech", steps=4, warmup=1, seg=1,
-                                                                               debug=512),
+                  "librispeech_s1_standard_search_no_logits": quick_decode("librispeech", steps=4, warmup=1, seg=1,
+                                                                           debug=32768),
                   "assistant_n10_s3": quick_decode("assistant", steps=2, warmup=1),
                   "throughput_n10_s5": quick_decode("throughput", steps=2, warmup=1)}
 

@@ -85,7 +85,7 @@ typedef struct tbs_config {
                                  every hypothesis in a fixed place and no such kernel; bit 9: with
                                  seg_s = 1 (the standard breadth-first search, Eq. 1) store the logits and
                                  expand from them as for longer segments, also where the joiner GEMM
-                                 would keep only each row's softmax sums and best tokens; bit 10: form the
+                                 would keep only each row's softmax sums and best tokens (see bit 15); bit 10: form the
                                  joiner input rows of a segment's first round in a kernel of their own,
                                  also where the kernel that starts the segment would; bit 11: one
                                  workgroup per tile of the predictor projection forms the joiner input rows
@@ -93,8 +93,12 @@ typedef struct tbs_config {
                                  workgroup per tile and frame; bit 12: the joiner GEMM of a small batch spreads
                                  its tiles over the XCDs as the other GEMMs do, also where it would give every
                                  XCD a range of rows of its own; bit 13: the kernel that forms joiner input
-                                 rows takes a thread per row, also where it would take a thread per pair
-                                 (tests cover each pair of variants) */
+                                 rows takes a thread per row, also where it would take a thread per pair; bit 14:
+                                 seg_s = 1 without logits: the joiner GEMM merges the partials of a tile's four
+                                 16-column pieces itself, also where it would hand them to the round kernel
+                                 as they are; bit 15: seg_s = 1 without logits also where the form with
+                                 logits would run (beams above 4 with a vocabulary it can hold, where it was
+                                 measured faster; tests cover each pair of variants) */
     int32_t stream_buffer_frames; /* per-utterance capacity, in frames, of the buffer tbs_push_segment
                                  collects encoder frames in; 0 = no streaming.  At least seg_s; one
                                  push may bring an utterance up to this many minus seg_s - 1 frames */

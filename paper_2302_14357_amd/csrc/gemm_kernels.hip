@@ -554,6 +554,27 @@ k_gemm_small(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B, const f
             if (c0 + i == pe.blank) lb = q[i];
             if (c0 + i >= N || c0 + i == pe.blank) q[i] = -INFINITY;   // not a candidate
         }
+        if (pe.pieces) {
+            // (no second stage: the piece's partial goes out as it is; the reader merges four per tile)
+            const int row = tile_m * 64 + wm * 32 + rowb;
+            if (row < M) {
+                float *out = pe.part + (((long)row * tiles_n + tile_n) * 4 + wn * 2 + half) * part_width(np);
+                *reinterpret_cast<float4 *>(out) = make_float4(mx, z, lb, 0.f);
+                for (int n = 0; n < np; ++n) {
+                    float best = -INFINITY;
+                    int bi = -1;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (q[i] > best) { best = q[i]; bi = i; }   // (ascending columns: the smaller token wins a tie)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (i == bi) q[i] = -INFINITY;
+                    out[4 + n] = best;
+                    out[4 + np + n] = __int_as_float(bi >= 0 ? c0 + bi : -1);
+                }
+            }
+            return;
+        }
         float *spart = reinterpret_cast<float *>(smem) + 4 * (32 * 36);   // [64 rows][4 pieces][3 + 2 NP]
         float *dst = spart + ((wm * 32 + rowb) * 4 + wn * 2 + half) * pw2;
         dst[0] = mx;

@@ -379,7 +379,7 @@ bool round_s1_fits(const Dims &d) { return d.S == 1 && d.N >= 1 && d.N <= 16 && 
 
 hipError_t launch_round_s1(hipStream_t st, const Dims &d, int round, int drop, const float *part, int tiles_n, AView A,
                            AView An, BView B, RowView rv, int2 *nodes, const FixedView *fxp) {
-    if (!fxp || !fxp->on || !part || !round_s1_fits(d) || tiles_n != (d.V + 63) / 64) return hipErrorInvalidValue;
+    if (!fxp || !fxp->on || !part || !round_s1_fits(d) || tiles_n < 1 || tiles_n > 64) return hipErrorInvalidValue;
     if (d.N <= 4) return round_launch<1, 1, 1, 4>(st, d, round, drop, part, A, An, B, rv, nodes, nullptr, nullptr, *fxp, tiles_n);
     if (d.N <= 8) return round_launch<1, 1, 1, 8>(st, d, round, drop, part, A, An, B, rv, nodes, nullptr, nullptr, *fxp, tiles_n);
     return round_launch<1, 1, 1, 16>(st, d, round, drop, part, A, An, B, rv, nodes, nullptr, nullptr, *fxp, tiles_n);

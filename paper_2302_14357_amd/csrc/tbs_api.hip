@@ -379,7 +379,9 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     }
     rc |= dev_alloc(c, &c->logits, (size_t)M * d.V);
     c->part = nullptr;
-    if (d.S == 1 && cfg->dtype == 1) rc |= dev_alloc(c, &c->part, UN * (size_t)((d.V + 63) / 64) * part_width(d.N));
+    // (room for a partial per 16-column piece where the round kernel has a lane for each, else per 64-column tile)
+    if (d.S == 1 && cfg->dtype == 1)
+        rc |= dev_alloc(c, &c->part, UN * (size_t)((d.V + 63) / 64) * ((d.V + 63) / 64 <= 16 ? 4 : 1) * part_width(d.N));
     rc |= dev_alloc(c, &c->row_lc, M);
     rc |= dev_alloc(c, &c->dphi, UN);
     rc |= dev_alloc(c, &c->cand_score, UN * d.N);
@@ -524,10 +526,16 @@ static bool predictor_all_fused(const tbs_ctx *c, int M);
 // keep the row lists.
 // Segments of one frame: the joiner GEMM can keep row partials instead of logits (unless debug output
 // that needs the logits, or debug bit 9, asks for them), and the round kernel then has no limit on
-// the vocabulary from its registers.
+// the vocabulary from its registers.  Measured on the Librispeech-like batch (ms per decode, with
+// logits / without): N = 2: 26.1 / 24.4, N = 3: 27.1 / 26.0, N = 4: 30.1 / 26.8, N = 5: 28.8 / 29.5, N = 8:
+// 36.5 / 36.8, N = 10: 47.4 / 47.5.  The logits of a small batch never leave the cache, and picking the N
+// best of every 16 logits costs the GEMM N rounds of a 16-way arg-max: the partials serve beams up to 4,
+// the vocabularies the form with logits cannot hold, and debug bit 15.
 static bool one_frame_ok(const tbs_ctx *c) {
     const Dims &d = c->cur;
-    return c->part && !(c->cfg.debug & (1 | 512)) && round_s1_fits(d) && gemm_part_fits(d.U * d.N, d.V, d.Dj, d.N);
+    if (!c->part || (c->cfg.debug & (1 | 512)) || !round_s1_fits(d) || !gemm_part_fits(d.U * d.N, d.V, d.Dj, d.N))
+        return false;
+    return !round_fits(d) || d.N <= 4 || (c->cfg.debug & 32768);
 }
 
 static bool fixed_layout_ok(const tbs_ctx *c) {
@@ -1138,6 +1146,9 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
         const long wgs = (long)(rpx / 64) * ((d.V + 63) / 64);
         fx.xcd_rows = (!(c->cfg.debug & 4096) && (M + 63) / 64 >= 8 && d.N * d.S <= rpx && wgs <= 32) ? rpx : 0;
     }
+    // (S = 1 without logits: the GEMM's partials go out per 16-column piece where the round kernel's wave
+    // has a lane for each of them, which spares the GEMM the merge of a tile's four)
+    const int s1_pieces = (d.V + 63) / 64 <= 16 && !(c->cfg.debug & 16384) ? 1 : 0;
     std::vector<int> made(d.U, 0);
     int total = 0, rc;
     bool full = false, first = true;
@@ -1148,7 +1159,7 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
             ProfScope ps(c, TBS_K_JOINER, 0);
             ProfScope pg(c, TBS_K_GEMM, 0);
             if (c->s1) {
-                const PartEp pe{c->part, d.N, d.blank, fx.xcd_rows};
+                const PartEp pe{c->part, d.N, d.blank, s1_pieces, fx.xcd_rows};
                 HIPCHK(c, launch_gemm_part(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out, M, d.V,
                                            d.Dj, pe));
             } else {
@@ -1162,7 +1173,7 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
         {
             ProfScope ps(c, TBS_K_ROUND, 0);
             if (c->s1) {
-                HIPCHK(c, launch_round_s1(c->stream, d, c->round, drop, c->part, (d.V + 63) / 64, A, An, c->B, c->rv,
+                HIPCHK(c, launch_round_s1(c->stream, d, c->round, drop, c->part, ((d.V + 63) / 64) * (s1_pieces ? 4 : 1), A, An, c->B, c->rv,
                                           c->nodes, &fx));
             } else {
                 HIPCHK(c, launch_round(c->stream, d, c->round, drop, c->logits, A, An, c->B, c->rv, c->nodes,

@@ -146,6 +146,8 @@ struct PartEp {
     float *part;
     int np;      // NP = beam size
     int blank;
+    int pieces;     // 1: the partials of a tile's four 16-column pieces go out as they are (four partials per
+                    // tile, in column order), for a reader that has a lane for each; 0: merged into one
     int xcd_rows;   // (also for the joiner GEMM that stores logits) not 0: every XCD computes a range of rows
                     // of its own, all their columns, so that the logits or partials of an utterance lie in
                     // the L2 of the XCD whose workgroup of the round kernel reads them (see FixedView)
@@ -215,6 +217,7 @@ hipError_t launch_round(hipStream_t st, const Dims &d, int round, int drop, cons
                         const FixedView *fx = nullptr);
 // the same for one-frame segments in the slot layout, from the joiner GEMM's row partials
 bool round_s1_fits(const Dims &d);
+// (tiles_n: partials per row, in column order: the vocabulary's 64-column tiles, or their 16-column pieces)
 hipError_t launch_round_s1(hipStream_t st, const Dims &d, int round, int drop, const float *part, int tiles_n, AView A,
                            AView An, BView B, RowView rv, int2 *nodes, const FixedView *fx);
 hipError_t launch_pred_gather(hipStream_t st, const Dims &d, int dtype, int pairs, AView A, RowView rv,

@@ -780,13 +780,14 @@ def test_round_in_one_kernel_equals_separate_kernels(N, S, V, peaked):
                                               (5, 200, 7, True), (8, 512, 511, True), (10, 4096, 0, False),
                                               (16, 100, 64, True), (3, 68, 67, False)])
 def test_standard_search_without_logits_equals_the_one_with(N, V, blank, peaked):
-    """S = 1 is the standard breadth-first search (Eq. 1).  Where the shape allows, the joiner GEMM
-    then keeps no logits: its epilogue leaves each row's softmax sums, blank logit and N best tokens
-    per tile of 64 columns and the round kernel merges them; debug bit 9 stores the logits and expands
-    from them as for longer segments.  Vocabularies of one tile, of many and with a ragged last tile,
-    blank first, last, at a tile edge and inside a tile, every list length the round kernel has (4, 8,
-    16), flat and peaked models, ragged and empty utterances: the two forms give the same hypotheses,
-    and each is checked against the oracle."""
+    """S = 1 is the standard breadth-first search (Eq. 1).  The joiner GEMM can then keep no logits: its
+    epilogue leaves each row's softmax sums, blank logit and N best tokens per 16-column piece (or, debug
+    bit 14, merged per tile of 64 columns) and the round kernel merges them.  That form runs by default
+    for beams up to 4 and where the vocabulary is too large for the form with logits, and with debug bit
+    15 everywhere; debug bit 9 asks for the logits.  Vocabularies of one tile, of many and with a ragged last tile, blank
+    first, last, at a tile edge and inside a tile, every list length the round kernel has (4, 8, 16),
+    flat and peaked models, ragged and empty utterances: the forms give the same hypotheses, and each is
+    checked against the oracle."""
     import dataclasses
     shape = dataclasses.replace(small_bf16_shape(n_utts=6, vocab=V, d=128, hidden=128), blank_id=blank)
     cap = 0
@@ -795,30 +796,41 @@ def test_standard_search_without_logits_equals_the_one_with(N, V, blank, peaked)
     lengths = np.array([0, 1, 7, 12, 23, 31])
     model, offsets, enc = build_case(shape, n_utts=6, lengths=lengths)
     kw = dict(max_rounds_per_segment=cap) if cap else {}
-    one, st1 = _gpu_decode(shape, model, offsets, enc, N, 1, **kw)
+    dflt, st0 = _gpu_decode(shape, model, offsets, enc, N, 1, **kw)
+    one, st1 = _gpu_decode(shape, model, offsets, enc, N, 1, debug=32768, **kw)
     two, st2 = _gpu_decode(shape, model, offsets, enc, N, 1, debug=512, **kw)
-    assert st1["path"] == {"fixed_places": True, "one_frame_no_logits": True}
     # (the form with logits keeps a hypothesis' logits in registers: vocabularies up to 1024 entries)
+    # (by default the form without logits serves beams up to 4 and the vocabularies the other cannot hold)
+    assert st0["path"] == {"fixed_places": True, "one_frame_no_logits": V > 1024 or N <= 4}
+    assert st1["path"] == {"fixed_places": True, "one_frame_no_logits": True}
     assert st2["path"] == {"fixed_places": V <= 1024, "one_frame_no_logits": False}
+    assert dflt == (one if (V > 1024 or N <= 4) else two)
     tol, score_tol = tolerance(shape, model)
-    for a, b in zip(one, two):
-        # (the two forms round differently: log(exp(l - m) / Z) against (l - m) - log Z)
-        assert [h[0] for h in a] == [h[0] for h in b]
-        np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=0, atol=score_tol)
+    # (bit 14: the partials of a tile's four 16-column pieces merged by the GEMM instead of the round kernel:
+    # the same arithmetic in another order of the sums)
+    three, st3 = _gpu_decode(shape, model, offsets, enc, N, 1, debug=32768 + 16384, **kw)
+    assert st3["path"] == st1["path"]
+    for other in (two, three):
+        for a, b in zip(one, other):
+            # (the forms round differently: log(exp(l - m) / Z) against (l - m) - log Z)
+            assert [h[0] for h in a] == [h[0] for h in b]
+            np.testing.assert_allclose([h[1] for h in a], [h[1] for h in b], rtol=0, atol=score_tol)
     assert st1["joiner_calls"] == st2["joiner_calls"] and st1["joined_frames"] == st2["joined_frames"]
     assert st1["launches"] == st2["launches"] and st1["frames"] == st2["frames"]
-    _check_decode(shape, model, offsets, enc, N, 1, max_rounds=cap)
+    _check_decode(shape, model, offsets, enc, N, 1, max_rounds=cap, debug=32768)
     _check_decode(shape, model, offsets, enc, N, 1, max_rounds=cap, debug=512)
+    _check_decode(shape, model, offsets, enc, N, 1, max_rounds=cap, debug=32768 + 16384)
 
 
 def test_standard_search_without_logits_librispeech_batch():
-    """The in-house baseline of the benchmark (64 Librispeech-like utterances, N = 5, S = 1) runs in the
-    form without logits and agrees with the oracle under the gap rule."""
+    """The in-house baseline of the benchmark (64 Librispeech-like utterances, N = 5, S = 1) in the form
+    without logits agrees with the oracle under the gap rule."""
     shape = SHAPES["librispeech"]
     model, offsets, enc = build_case(shape)
-    _, st = _gpu_decode(shape, model, offsets[:3], enc[:offsets[2]], 5, 1)
+    _, st = _gpu_decode(shape, model, offsets[:3], enc[:offsets[2]], 5, 1, debug=32768)
     assert st["path"]["one_frame_no_logits"]
-    info = _check_decode(shape, model, offsets, enc, 5, 1, report="Librispeech-like, standard search (S=1)")
+    info = _check_decode(shape, model, offsets, enc, 5, 1, report="Librispeech-like, standard search (S=1)",
+                         debug=32768)
     assert info["tot"] == 64
 
 
