@@ -324,14 +324,18 @@ k_round(Dims d, int round, int drop, const float *__restrict__ logits, AView A, 
     }
 }
 
-// which instantiation serves the shape (0 = none): hypotheses per workgroup x threads per hypothesis
-// stay within 1024 threads, a hypothesis' S x V logits within its team's registers
+// which instantiation serves the shape (0 = none): a hypothesis' S x V logits stay within the
+// registers of its team.  A team is one wave whatever the beam (measured, ms per decode of the
+// Librispeech-like batch at S = 3 with teams of 4 / 2 / 1 waves: N = 2: 16.6 / 16.9 / 16.6, N = 4:
+// 19.1 / 17.6 / 17.4, N = 5: - / 18.2 / 18.0, N = 8: - / 28.3 / 26.4): what a wave more per hypothesis saves in
+// values per thread it costs in reductions, candidate lists and their merge, and the waves of a
+// workgroup share four SIMDs.  The template keeps teams of several waves.
 static int round_variant(const Dims &d) {
     if (d.V % 4 || d.S > 5 || d.N > 16) return 0;
-    const int tw = d.N <= 4 ? 4 : (d.N <= 8 ? 2 : 1);
-    const int nv4 = tw == 4 ? 1 : (tw == 2 ? 2 : 4);
-    if (d.V / 4 > tw * 64 * nv4) return 0;
-    return tw * 10 + (d.S <= 3 ? 3 : 5);
+    const int v4 = d.V / 4;
+    const int nv4 = v4 <= 64 ? 1 : (v4 <= 128 ? 2 : 4);
+    if (v4 > 64 * nv4) return 0;
+    return nv4 * 10 + (d.S <= 3 ? 3 : 5);
 }
 
 bool round_fits(const Dims &d) { return round_variant(d) != 0; }
@@ -365,12 +369,12 @@ hipError_t launch_round(hipStream_t st, const Dims &d, int round, int drop, cons
     if (fxp) fx = *fxp;
     if (fx.on && fx.xh && (d.H & 3)) return hipErrorInvalidValue;
     switch (round_variant(d)) {
-        case 43: return round_launch<4, 1, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
-        case 45: return round_launch<4, 1, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
-        case 23: return round_launch<2, 2, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
-        case 25: return round_launch<2, 2, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
-        case 13: return round_launch<1, 4, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
-        case 15: return round_launch<1, 4, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 13: return round_launch<1, 1, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 15: return round_launch<1, 1, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 23: return round_launch<1, 2, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 25: return round_launch<1, 2, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 43: return round_launch<1, 4, 3>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
+        case 45: return round_launch<1, 4, 5>(st, d, round, drop, logits, A, An, B, rv, nodes, row_stats, delta_nb, fx);
         default: return hipErrorInvalidValue;
     }
 }

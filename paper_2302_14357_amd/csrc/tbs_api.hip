@@ -527,8 +527,8 @@ static bool predictor_all_fused(const tbs_ctx *c, int M);
 // Segments of one frame: the joiner GEMM can keep row partials instead of logits (unless debug output
 // that needs the logits, or debug bit 9, asks for them), and the round kernel then has no limit on
 // the vocabulary from its registers.  Measured on the Librispeech-like batch (ms per decode, with
-// logits / without): N = 2: 26.1 / 24.4, N = 3: 27.1 / 26.0, N = 4: 30.1 / 26.8, N = 5: 28.8 / 29.5, N = 8:
-// 36.5 / 36.8, N = 10: 47.4 / 47.5.  The logits of a small batch never leave the cache, and picking the N
+// logits / without): N = 2: 25.7 / 24.6, N = 3: 26.7 / 25.6, N = 4: 27.2 / 26.7, N = 5: 28.4 / 29.0, N = 8:
+// 34.0 / 37.0, N = 10: 47.0 / 47.3.  The logits of a small batch never leave the cache, and picking the N
 // best of every 16 logits costs the GEMM N rounds of a 16-way arg-max: the partials serve beams up to 4,
 // the vocabularies the form with logits cannot hold, and debug bit 15.
 static bool one_frame_ok(const tbs_ctx *c) {

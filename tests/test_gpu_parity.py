@@ -751,8 +751,8 @@ def test_decode_large_batch_contains_the_small_one(name, N, S, U):
 def test_round_in_one_kernel_equals_separate_kernels(N, S, V, peaked):
     """Inside tbs_decode, expansion and select/merge of a round run as one kernel (a workgroup per
     utterance) where the shape allows; debug bit 7 keeps them two kernels.  Beam widths and
-    vocabularies that take each of the kernel's team sizes (4, 2 and 1 waves per hypothesis), ragged
-    utterances, flat and peaked models: the two forms must give the same hypotheses, and the
+    vocabularies that take each of the kernel's forms (4, 8 or 16 columns per thread, with and without
+    a wave of its own for the select step), ragged utterances, flat and peaked models: the two forms must give the same hypotheses, and the
     one-kernel form is checked against the oracle."""
     shape = small_bf16_shape(n_utts=6, vocab=V, d=128, hidden=128)
     cap = 0
