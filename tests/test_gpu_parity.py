@@ -669,6 +669,21 @@ def test_decode_librispeech_headline_batch():
     assert info.get("prefix_frames", int(offsets[-1])) >= 500, info
 
 
+@pytest.mark.parametrize("index,N,S", [(11, 5, 3), (23, 5, 3), (37, 4, 5), (41, 10, 2)])
+def test_decode_librispeech_widths_other_draws(index, N, S):
+    """The headline widths (Dj=512, V=1024, LSTM 640) with other draws of the model and of the frames
+    than the benchmark's, and utterance lengths around the segment size and its multiples (empty,
+    shorter than a segment, a ragged last segment, one frame more or less than whole segments):
+    the fixed-place form against the oracle."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES["librispeech"], index=index, n_utts=12)
+    lengths = np.array([0, 1, 2, S, S + 1, 2 * S - 1, 40, 77, 30 * S, 30 * S + 1, 30 * S - 1, 211])
+    model, offsets, enc = build_case(shape, n_utts=12, lengths=lengths)
+    _, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    assert st["path"]["fixed_places"]
+    _check_decode(shape, model, offsets, enc, N, S)
+
+
 @pytest.mark.parametrize("name,N,S", [("assistant", 10, 3), ("throughput", 10, 5)])
 def test_decode_large_shapes_short_utterances(name, N, S):
     """Whole decodes at the widths of the two large configurations (V=4096, Dj=1024, LSTM 2x1024 /
