@@ -365,8 +365,13 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     rc |= dev_alloc(c, &c->rv.counts, TBS_CNT_SIZE);
     rc |= dev_alloc(c, &c->utt_fig, U * TBS_FIG_SIZE);
     rc |= dev_alloc(c, &c->live_sum, 2);
-    rc |= dev_alloc(c, &c->utt_T, U);
-    rc |= dev_alloc(c, &c->utt_off, U + 1);
+    // (utterance lengths, first frames and the frame-copy descriptors of a push side by side, so that
+    // one copy from pinned memory brings all a push has to tell the kernels)
+    rc |= dev_alloc(c, &c->utt_T, 5 * (size_t)U + 1);
+    if (rc == 0) {
+        c->utt_off = c->utt_T + U;
+        c->d_desc = c->utt_off + U + 1;
+    }
     rc |= dev_alloc(c, &c->nodes, (size_t)d.max_nodes);
     c->pool_rows = U * 2 * (d.R + 1) * d.N;
     rc |= dev_alloc(c, &c->pool_p, (size_t)c->pool_rows * d.Dj);
@@ -441,10 +446,9 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
         char *p = nullptr, *q = nullptr;
         rc = dev_alloc(c, &p, (size_t)U * c->stream_cap * d.Dj * elem_bytes(c));
         rc |= dev_alloc(c, &q, (size_t)U * d.S * d.Dj * elem_bytes(c));
-        rc |= dev_alloc(c, &c->d_desc, 3 * U);
         c->stream_enc = p;
         c->stream_tmp = q;
-        if (rc == 0 && hipHostMalloc((void **)&c->h_desc, 11 * U * sizeof(int), hipHostMallocDefault) != hipSuccess) rc = 1;
+        if (rc == 0 && hipHostMalloc((void **)&c->h_desc, (11 * (size_t)U + 1) * sizeof(int), hipHostMallocDefault) != hipSuccess) rc = 1;
         if (rc) {
             tbs_free(c);
             return TBS_ENOMEM;
@@ -1264,26 +1268,27 @@ int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offs
     const long row_bytes = (long)d.Dj * elem_bytes(c);
     // Pinned descriptor areas, one per use within a call (the stream reads them later than the host
     // writes them); the call ends with the stream drained, so the next call may write them again.
+    // The first area mirrors the device's: step sizes, first frames, then the descriptors of the copy that
+    // appends the new frames, so that the first decode step of a push needs one copy for all three.
     const int Um = c->d.U;
-    int *src = c->h_desc, *dst = src + U, *cnt = src + 2 * U;           // appending the new frames
-    int *take = c->h_desc + 3 * Um, *first = take + Um;                  // a decode step
-    int *src1 = c->h_desc + 5 * Um, *dst1 = src1 + U, *cnt1 = src1 + 2 * U;   // leftovers to the spare area
-    int *src2 = c->h_desc + 8 * Um, *dst2 = src2 + U, *cnt2 = src2 + 2 * U;   // and back to the front
-    if (frame_offsets[U] > 0) {
+    int *take = c->h_desc, *first = take + Um;                           // a decode step
+    int *src = first + Um + 1, *dst = src + U, *cnt = src + 2 * U;       // appending the new frames
+    int *src1 = c->h_desc + 5 * Um + 1, *dst1 = src1 + U, *cnt1 = src1 + 2 * U;   // leftovers to the spare area
+    int *src2 = c->h_desc + 8 * Um + 1, *dst2 = src2 + U, *cnt2 = src2 + 2 * U;   // and back to the front
+    const bool append = frame_offsets[U] > 0;
+    if (append) {
         for (int u = 0; u < U; ++u) {
             src[u] = frame_offsets[u];
             dst[u] = u * cap + c->s_fill[u];
             cnt[u] = frame_offsets[u + 1] - frame_offsets[u];
             c->s_fill[u] += cnt[u];
         }
-        HIPCHK(c, hipMemcpyAsync(c->d_desc, src, sizeof(int) * 3 * U, hipMemcpyHostToDevice, c->stream));
-        HIPCHK(c, launch_stream_copy(c->stream, U, enc_proj, c->stream_enc, c->d_desc, row_bytes));
         c->n_frames += frame_offsets[U];
     }
     // decode: every utterance with a whole segment buffered (or, at a flush, with anything
     // buffered) takes one step; utterances advance independently of each other
     std::vector<int> pos(U, 0);
-    for (;;) {
+    for (int step = 0;; ++step) {
         bool any = false;
         for (int u = 0; u < U; ++u) {
             const int avail = c->s_fill[u] - pos[u];
@@ -1291,11 +1296,16 @@ int tbs_push_segment(tbs_ctx *c, const void *enc_proj, const int32_t *frame_offs
             first[u] = u * cap + pos[u];
             any = any || take[u] > 0;
         }
+        if (step == 0 && append) {
+            HIPCHK(c, hipMemcpyAsync(c->utt_T, take, sizeof(int) * (2 * (size_t)Um + 1 + 3 * (size_t)U), hipMemcpyHostToDevice,
+                                     c->stream));
+            HIPCHK(c, launch_stream_copy(c->stream, U, enc_proj, c->stream_enc, c->d_desc, row_bytes));
+        } else if (any) {
+            HIPCHK(c, hipMemcpyAsync(c->utt_T, take, sizeof(int) * (2 * (size_t)Um), hipMemcpyHostToDevice, c->stream));
+        }
         if (!any) break;
         for (int u = 0; u < U; ++u) c->h_T[u] = take[u];   // (the slot layout's host bookkeeping reads the step sizes)
-        HIPCHK(c, hipMemcpyAsync(c->utt_T, take, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
-        HIPCHK(c, hipMemcpyAsync(c->utt_off, first, sizeof(int) * U, hipMemcpyHostToDevice, c->stream));
-        const int rc = run_segment(c, 0);   // (waits for counts: the two copies above are done by then)
+        const int rc = run_segment(c, 0);   // (waits for counts: the copy above is done by then)
         if (rc) return rc;
         for (int u = 0; u < U; ++u) pos[u] += take[u];
     }
