@@ -14,6 +14,7 @@
 // workgroups resident on one XCD (ids equal modulo 8) work on a compact block of
 // tiles and share their operand rows in that XCD's L2.
 #include "tbs_internal.h"
+#include <climits>
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
@@ -752,21 +753,26 @@ static int gemm_small_stages() {
     return stages;
 }
 
-bool gemm_small_fits(int M, int N, int K) {   // what launch_gemm_bf16 sends to k_gemm_small by itself
-    const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
-    return K % GS_BK == 0 && gemm_small_stages() >= 2 && tiles <= 320;
+// The *_fits functions say whether the kernel can run the problem and has at most max_tiles tiles of
+// 64 x 64: GS_TILES by default (what pays where kernels are sized by the round's rows: beyond one turn
+// and a quarter of workgroups on the 256 CUs the persistent kernel's larger tiles do better), more
+// where the caller has measured otherwise (the slot layout, whose other savings outweigh a second
+// turn).  The launchers themselves take any number of tiles.
+static long gs_tiles(int M, int N) { return (long)((M + 63) / 64) * ((N + 63) / 64); }
+
+bool gemm_small_fits(int M, int N, int K, int max_tiles) {   // what launch_gemm_bf16 sends to k_gemm_small by itself
+    return K % GS_BK == 0 && gemm_small_stages() >= 2 && gs_tiles(M, N) <= max_tiles;
 }
 
-bool gemm_lstm_fits(int M, int H, int K) {
+bool gemm_lstm_fits(int M, int H, int K, int max_tiles) {
     const int ns_max = gemm_small_stages();
-    const long tiles = (long)((M + 63) / 64) * ((4 * H + 63) / 64);
-    return ns_max >= 2 && H % 4 == 0 && K % GS_BK == 0 && K / GS_BK <= ns_max && tiles <= 320;
+    return ns_max >= 2 && H % 4 == 0 && K % GS_BK == 0 && K / GS_BK <= ns_max && gs_tiles(M, 4 * H) <= max_tiles;
 }
 
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
                             const LstmEp &ep, const int *m_dev, const int *any_dev) {
     if (M <= 0) return hipSuccess;
-    if (!gemm_lstm_fits(M, ep.H, K)) return hipErrorInvalidValue;
+    if (!gemm_lstm_fits(M, ep.H, K, INT_MAX)) return hipErrorInvalidValue;
     const int N = 4 * ep.H, tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
@@ -775,18 +781,17 @@ hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, c
     return hipGetLastError();
 }
 
-bool gemm_part_fits(int M, int N, int K, int np) {
-    const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
+bool gemm_part_fits(int M, int N, int K, int np, int max_tiles) {
     // (the epilogue's LDS: four 32 x 36 blocks and 64 x 4 lists of 3 + 2 NP values, inside two stages)
     const size_t lds = sizeof(float) * (4 * 32 * 36 + 64 * 4 * (size_t)(3 + 2 * np));
-    return K % GS_BK == 0 && gemm_small_stages() >= 2 && tiles <= 320 && np >= 1 && np <= 16 &&
+    return K % GS_BK == 0 && gemm_small_stages() >= 2 && gs_tiles(M, N) <= max_tiles && np >= 1 && np <= 16 &&
            lds <= 2 * GS_STAGE * sizeof(bf16_t);
 }
 
 hipError_t launch_gemm_part(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, int M, int N, int K,
                             const PartEp &pe) {
     if (M <= 0) return hipSuccess;
-    if (!gemm_part_fits(M, N, K, pe.np) || !pe.part) return hipErrorInvalidValue;
+    if (!gemm_part_fits(M, N, K, pe.np, INT_MAX) || !pe.part) return hipErrorInvalidValue;
     const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns_max = gemm_small_stages();
     const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
@@ -796,17 +801,16 @@ hipError_t launch_gemm_part(hipStream_t st, const bf16_t *A, const bf16_t *B, co
     return hipGetLastError();
 }
 
-bool gemm_join_fits(int M, int N, int K) {
+bool gemm_join_fits(int M, int N, int K, int max_tiles) {
     const int ns_max = gemm_small_stages();
-    const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
-    return ns_max >= 2 && N % 16 == 0 && K % GS_BK == 0 && K / GS_BK <= ns_max && tiles <= 320;
+    return ns_max >= 2 && N % 16 == 0 && K % GS_BK == 0 && K / GS_BK <= ns_max && gs_tiles(M, N) <= max_tiles;
 }
 
 hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
                             int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev,
                             const int *any_dev) {
     if (M <= 0) return hipSuccess;
-    if (!gemm_join_fits(M, N, K) || !out_row) return hipErrorInvalidValue;
+    if (!gemm_join_fits(M, N, K, INT_MAX) || !out_row) return hipErrorInvalidValue;
     const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
     const int ns = K / GS_BK < 2 ? 2 : K / GS_BK;
     const int grid = 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4) * (jp.fgroups > 1 ? jp.fgroups : 1);
@@ -820,11 +824,11 @@ hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, co
 hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
                             int N, int K, const int *out_row, long ldc, int kernel, const int *m_dev, bool xcd_rows) {
     if (M <= 0) return hipSuccess;
-    if (m_dev && !gemm_small_fits(M, N, K)) return hipErrorInvalidValue;   // only k_gemm_small reads its row count
+    if (m_dev && !gemm_small_fits(M, N, K, INT_MAX)) return hipErrorInvalidValue;   // only k_gemm_small reads its row count
     if ((kernel == 0 || kernel == 4) && K % GS_BK == 0) {
         const int tiles_m = (M + 63) / 64, tiles_n = (N + 63) / 64;
         const int ns_max = gemm_small_stages();
-        if (ns_max >= 2 && ((long)tiles_m * tiles_n <= 320 || kernel == 4)) {
+        if (ns_max >= 2 && ((long)tiles_m * tiles_n <= GS_TILES || kernel == 4 || m_dev)) {
             const int ns = K / GS_BK < ns_max ? (K / GS_BK < 2 ? 2 : K / GS_BK) : ns_max;
             const int grid = xcd_rows ? 8 * ((tiles_m + 7) / 8) * tiles_n : 8 * ((tiles_m + 1) / 2) * ((tiles_n + 3) / 4);
             PartEp pe{};

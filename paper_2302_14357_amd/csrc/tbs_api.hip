@@ -521,7 +521,7 @@ int tbs_init(const tbs_config *cfg, const tbs_weights *w, tbs_ctx **out) {
     return TBS_OK;
 }
 
-static bool predictor_all_fused(const tbs_ctx *c, int M);
+static bool predictor_all_fused(const tbs_ctx *c, int M, int max_tiles = GS_TILES);
 
 // The slot layout serves a batch when every kernel of a round has its small-shape form: the joiner
 // GEMM over all U*N*S rows in one wave of workgroups, the one-kernel expansion + select/merge, the
@@ -537,7 +537,7 @@ static bool predictor_all_fused(const tbs_ctx *c, int M);
 // the vocabularies the form with logits cannot hold, and debug bit 15.
 static bool one_frame_ok(const tbs_ctx *c) {
     const Dims &d = c->cur;
-    if (!c->part || (c->cfg.debug & (1 | 512)) || !round_s1_fits(d) || !gemm_part_fits(d.U * d.N, d.V, d.Dj, d.N))
+    if (!c->part || (c->cfg.debug & (1 | 512)) || !round_s1_fits(d) || !gemm_part_fits(d.U * d.N, d.V, d.Dj, d.N, GS_TILES_FIXED))
         return false;
     return !round_fits(d) || d.N <= 4 || (c->cfg.debug & 32768);
 }
@@ -547,8 +547,8 @@ static bool fixed_layout_ok(const tbs_ctx *c) {
     if (c->cfg.dtype != 1 || (c->cfg.debug & (2 | 8 | 16 | 32 | 64 | 128 | 256)) || c->cfg.joiner_chunk_rows > 0)
         return false;
     if ((d.H & 3) || (long)d.max_nodes - 1 < (long)d.U) return false;
-    return (round_fits(d) || one_frame_ok(c)) && gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj) &&
-           predictor_all_fused(c, d.U * d.N);
+    return (round_fits(d) || one_frame_ok(c)) && gemm_small_fits(d.U * d.N * d.S, d.V, d.Dj, GS_TILES_FIXED) &&
+           predictor_all_fused(c, d.U * d.N, GS_TILES_FIXED);
 }
 
 // The joiner input rows act(e + p) of the current row lists (Section 3.1), as a kernel of its own.  rows =
@@ -859,12 +859,12 @@ static int select_merge_impl(tbs_ctx *c, int32_t *live_host, bool fused) {
 // UpdatePredictorOutput for the first M pairs (or, with m_dev, for as many as *m_dev says once the
 // kernels run: then M is the upper bound the launches are sized for, and only the forms that can
 // read their row count from device memory may be used: see predictor_all_fused).
-static bool predictor_all_fused(const tbs_ctx *c, int M) {
+static bool predictor_all_fused(const tbs_ctx *c, int M, int max_tiles) {
     const Dims &d = c->cur;
     if (c->cfg.dtype != 1 || !c->emb_gates || (c->cfg.debug & (8 | 16))) return false;
     for (int l = 0; l < d.L; ++l)
-        if (!gemm_lstm_fits(M, d.H, l == 0 ? d.H : 2 * d.H)) return false;
-    return gemm_join_fits(M, d.Dj, d.H);
+        if (!gemm_lstm_fits(M, d.H, l == 0 ? d.H : 2 * d.H, max_tiles)) return false;
+    return gemm_join_fits(M, d.Dj, d.H, max_tiles);
 }
 
 static int64_t predictor_madds(const tbs_ctx *c, int64_t pairs) {   // multiply-adds of its GEMMs
@@ -884,7 +884,7 @@ static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part, const
     for (int l = 0; l < d.L && part != 2; ++l) {
         int in_dim = l == 0 ? d.E : d.H;
         const int K = (l == 0 && c->emb_gates) ? d.H : in_dim + d.H;
-        if (c->emb_gates && !(c->cfg.debug & 8) && gemm_lstm_fits(M, d.H, K)) {
+        if (c->emb_gates && !(c->cfg.debug & 8) && gemm_lstm_fits(M, d.H, K, c->fixed ? GS_TILES_FIXED : GS_TILES)) {
             // small problem: the cell update runs in the epilogue of the gate GEMM
             const bool last = l + 1 == d.L;
             LstmEp ep;
@@ -913,7 +913,7 @@ static int predictor_launch(tbs_ctx *c, int M, const int *m_dev, int part, const
                                         c->pool_rows, c->xh[(l + 1) & 1], c->htop, l == 0 ? c->emb_gates : nullptr));
     }
     if (part == 1) return TBS_OK;
-    if (c->cfg.dtype == 1 && !(c->cfg.debug & 16) && gemm_join_fits(M, d.Dj, d.H)) {
+    if (c->cfg.dtype == 1 && !(c->cfg.debug & 16) && gemm_join_fits(M, d.Dj, d.H, c->fixed ? GS_TILES_FIXED : GS_TILES)) {
         // small problem: the projection's epilogue also makes the joiner input rows of the coming
         // round (every row of that round belongs to one of these pairs)
         JoinEp jp;
@@ -1168,7 +1168,7 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
                                            d.Dj, pe));
             } else {
                 HIPCHK(c, launch_gemm_bf16(c->stream, (const bf16_t *)c->amat, (const bf16_t *)c->w.w_out, c->w.b_out,
-                                           c->logits, M, d.V, d.Dj, nullptr, d.V, 0, nullptr, fx.xcd_rows != 0));
+                                           c->logits, M, d.V, d.Dj, nullptr, d.V, 4, nullptr, fx.xcd_rows != 0));
             }
         }
         AView &A = c->A[c->a_cur], &An = c->A[c->a_cur ^ 1];

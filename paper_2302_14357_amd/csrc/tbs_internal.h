@@ -186,20 +186,23 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
 inline int gemm_small_xcd_rows(int M) { return 64 * ((((M + 63) / 64) + 7) / 8); }
 hipError_t launch_gemm_bf16_rows(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C,
                                  int m_max, int N, int K, long ldc, const int *m_begin, const int *m_end);
-bool gemm_small_fits(int M, int N, int K);
+#define GS_TILES 320         // tiles of 64 x 64 up to which the small-problem GEMM kernel is chosen by size
+#define GS_TILES_FIXED 512   // the same for the slot layout (measured: 96 to 128 utterances of the Librispeech-like
+                             // shape decode 4-5 % faster in it than with row lists, 160 slower)
+bool gemm_small_fits(int M, int N, int K, int max_tiles = GS_TILES);
 // true if launch_gemm_lstm can run this problem (small, K a multiple of 128 that fits the LDS stages)
-bool gemm_lstm_fits(int M, int H, int K);
+bool gemm_lstm_fits(int M, int H, int K, int max_tiles = GS_TILES);
 // any_dev (both fused forms): rows may be dead (state slot < 0) anywhere, and if *any_dev is zero
 // the whole launch leaves at once
 hipError_t launch_gemm_lstm(hipStream_t st, const bf16_t *A, const bf16_t *Wp, const float *biasp, int M, int K,
                             const LstmEp &ep, const int *m_dev = nullptr, const int *any_dev = nullptr);
 // the same for the projection GEMM that also makes the next joiner call's input rows (bf16 models)
-bool gemm_join_fits(int M, int N, int K);
+bool gemm_join_fits(int M, int N, int K, int max_tiles = GS_TILES);
 hipError_t launch_gemm_join(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C, int M,
                             int N, int K, const int *out_row, long ldc, const JoinEp &jp, const int *m_dev = nullptr,
                             const int *any_dev = nullptr);
 // joiner GEMM of one-frame segments: row partials instead of logits (see PartEp)
-bool gemm_part_fits(int M, int N, int K, int np);
+bool gemm_part_fits(int M, int N, int K, int np, int max_tiles = GS_TILES);
 hipError_t launch_gemm_part(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, int M, int N, int K,
                             const PartEp &pe);
 hipError_t launch_permute_gate_rows(hipStream_t st, const void *src, void *dst, int H, long row_bytes);

@@ -684,6 +684,22 @@ def test_decode_librispeech_widths_other_draws(index, N, S):
     _check_decode(shape, model, offsets, enc, N, S)
 
 
+@pytest.mark.parametrize("U,N,S", [(100, 5, 3), (136, 5, 3), (137, 5, 3)])
+def test_decode_fixed_places_with_more_tiles_than_cus(U, N, S):
+    """The headline widths with so many utterances that the GEMMs of a round have more 64x64 tiles
+    than the chip has CUs (384 and 512 joiner tiles: the fixed-place form still runs, its GEMMs in two
+    turns of workgroups), and one utterance more (the row-list form): short utterances, all against
+    the oracle."""
+    import dataclasses
+    shape = dataclasses.replace(SHAPES["librispeech"], index=53, n_utts=U)
+    rng = np.random.default_rng(U)
+    lengths = rng.integers(0, 14, size=U)
+    model, offsets, enc = build_case(shape, n_utts=U, lengths=lengths)
+    _, st = _gpu_decode(shape, model, offsets, enc, N, S)
+    assert st["path"]["fixed_places"] == (U <= 136)
+    _check_decode(shape, model, offsets, enc, N, S)
+
+
 @pytest.mark.parametrize("name,N,S", [("assistant", 10, 3), ("throughput", 10, 5)])
 def test_decode_large_shapes_short_utterances(name, N, S):
     """Whole decodes at the widths of the two large configurations (V=4096, Dj=1024, LSTM 2x1024 /
