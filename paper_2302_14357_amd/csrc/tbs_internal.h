@@ -186,9 +186,9 @@ hipError_t launch_gemm_bf16(hipStream_t st, const bf16_t *A, const bf16_t *B, co
 inline int gemm_small_xcd_rows(int M) { return 64 * ((((M + 63) / 64) + 7) / 8); }
 hipError_t launch_gemm_bf16_rows(hipStream_t st, const bf16_t *A, const bf16_t *B, const float *bias, float *C,
                                  int m_max, int N, int K, long ldc, const int *m_begin, const int *m_end);
-#define GS_TILES 320         // tiles of 64 x 64 up to which the small-problem GEMM kernel is chosen by size
-#define GS_TILES_FIXED 512   // the same for the slot layout (measured: 96 to 128 utterances of the Librispeech-like
-                             // shape decode 4-5 % faster in it than with row lists, 160 slower)
+#define GS_TILES 320          // tiles of 64 x 64 up to which the small-problem GEMM kernel is chosen by size
+#define GS_TILES_FIXED 1024   // the same for the slot layout (measured on the Librispeech-like shape: 96 to 256
+                              // utterances decode 5-16 % faster in it than with row lists, 320 the same)
 bool gemm_small_fits(int M, int N, int K, int max_tiles = GS_TILES);
 // true if launch_gemm_lstm can run this problem (small, K a multiple of 128 that fits the LDS stages)
 bool gemm_lstm_fits(int M, int H, int K, int max_tiles = GS_TILES);
