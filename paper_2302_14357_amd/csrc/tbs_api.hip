@@ -1132,7 +1132,7 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
     fx.amat = rows_in_head ? (bf16_t *)c->amat : nullptr;
     fx.enc = (const bf16_t *)c->enc;
     fx.act = c->cfg.act;
-    fx.parts = d.U >= 128 ? 1 : (d.U > 64 ? 2 : 4);   // (a small batch leaves most CUs idle: several workgroups share an utterance)
+    fx.parts = d.U > 256 ? 1 : (d.U > 128 ? 2 : 4);   // (a small batch leaves most CUs idle: several workgroups share an utterance)
     HIPCHK(c, launch_segment_begin(c->stream, d, c->seg, c->utt_T, c->B, c->A[c->a_cur], c->rv, c->pool_p, c->pool_h,
                                    c->pool_c, c->pool_rows, &fx));
     if (!rows_in_head) {
