@@ -1144,11 +1144,11 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
     const int M = d.U * d.N * d.S;
     // (a row range per XCD in the joiner GEMM, the round kernel's workgroups on the XCD of their
     // utterance's rows, where every XCD gets rows, its range holds whole utterances and its tiles fit
-    // its 32 CUs)
+    // its 32 CUs, two workgroups each)
     {
         const int rpx = gemm_small_xcd_rows(M);
         const long wgs = (long)(rpx / 64) * ((d.V + 63) / 64);
-        fx.xcd_rows = (!(c->cfg.debug & 4096) && (M + 63) / 64 >= 8 && d.N * d.S <= rpx && wgs <= 32) ? rpx : 0;
+        fx.xcd_rows = (!(c->cfg.debug & 4096) && (M + 63) / 64 >= 8 && d.N * d.S <= rpx && wgs <= 64) ? rpx : 0;
     }
     // (S = 1 without logits: the GEMM's partials go out per 16-column piece where the round kernel's wave
     // has a lane for each of them, which spares the GEMM the merge of a tile's four)
