@@ -1148,7 +1148,8 @@ static int run_segment_fixed(tbs_ctx *c, int32_t seg_index) {
     {
         const int rpx = gemm_small_xcd_rows(M);
         const long wgs = (long)(rpx / 64) * ((d.V + 63) / 64);
-        fx.xcd_rows = (!(c->cfg.debug & 4096) && (M + 63) / 64 >= 8 && d.N * d.S <= rpx && wgs <= 64) ? rpx : 0;
+        const long tiles = (long)((M + 63) / 64) * ((d.V + 63) / 64);   // (more than 256: two workgroups share a CU)
+        fx.xcd_rows = (!(c->cfg.debug & 4096) && (M + 63) / 64 >= 8 && d.N * d.S <= rpx && wgs <= (tiles > 256 ? 64 : 32)) ? rpx : 0;
     }
     // (S = 1 without logits: the GEMM's partials go out per 16-column piece where the round kernel's wave
     // has a lane for each of them, which spares the GEMM the merge of a tile's four)
